@@ -1,0 +1,403 @@
+"""CPU oracle, part 2: the community-based ADMM sweep.  TEST INFRASTRUCTURE ONLY.
+
+Plain numpy in fp64, written step by step from the paper (Section 3 and Appendix A)
+in its notation: first-order messages p, second-order messages s, the subproblem
+objectives phi (W) and psi (Z), their quadratic models P and Q with backtracking on
+tau_l and theta_{l,m}, FISTA for the last layer, the dual step.  It shares no code
+with the HIP library and must never be imported by the product path.
+
+Everything is held in the community-contiguous node order of ``OracleGraph``; a
+"block" Z_{l,m} is the row range ``graph.rows(m)``.
+
+Readings taken where the paper is silent (all are definitions of this build, so the
+constants eta, tau0, theta0, J and the FISTA step are "parity unpinned" by the paper;
+only oracle <-> GPU agreement and the invariants in the tests hold them):
+  * initial point: W given, Z_l = forward pass, U = 0;
+  * backtracking: start from the last accepted value (tau0 / theta0 at k = 0), multiply
+    by eta until  model >= objective  holds (equality accepts), at most max_backtrack
+    multiplications (then the step is taken anyway and a status bit is raised);
+  * a step below resolution is not taken: if the first candidate would move the block by
+    less than 1e-12 of its own norm, i.e. ||grad||^2 <= (1e-12 * tau)^2 * ||block||^2, the
+    block keeps its value and its step parameter and no trial is counted (at the
+    forward-pass initial point every hidden-layer gradient is zero up to rounding, and a
+    search decided by rounding noise would inflate tau / theta arbitrarily);
+  * ReLU'(0) = 0;
+  * R = softmax cross-entropy summed over labelled rows (risk 0) or
+    1/2 ||Z_L - Y||^2 over labelled rows (risk 1); unlabelled rows contribute nothing;
+  * last layer: J FISTA steps of size 1/(rho + c_R) from the current Z_L
+    (c_R = 1/2 for cross-entropy, 1 for least squares bounds the Hessian of R);
+    a row without label has the exact minimiser  b = c - U/rho  of its quadratic;
+  * dual step with the superscripts as printed (Eq. 2): Z_L^k and p^k (p uses W^{k+1});
+  * updates are Jacobi: W^{k+1} from (W^k, Z^k, U^k); every Z^{k+1}_{l,m} from
+    (W^{k+1}, Z^k, U^k).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from .graph import OracleGraph
+
+
+def relu(x):
+    return np.maximum(x, 0.0)
+
+
+def relu_grad(x):
+    return (x > 0.0).astype(np.float64)
+
+
+def inner(a, b):
+    return float(np.sum(a * b))
+
+
+def sqnorm(a):
+    return float(np.sum(a * a))
+
+
+class AdmmOracle:
+    STATUS_BACKTRACK_CAP = 1
+    STATUS_NONFINITE = 2
+    STEP_FLOOR = 1e-12
+
+    def __init__(self, graph: OracleGraph, dims, *, nu, rho, tau0, theta0, eta, max_backtrack,
+                 fista_iters, risk=0, dual_form=0):
+        self.g = graph
+        self.M = graph.M
+        self.N = graph.N
+        self.dims = [int(c) for c in dims]
+        self.L = len(self.dims) - 1
+        if self.L < 2:
+            raise ValueError("need at least two layers")
+        # hyper-parameters travel as fp32 at the library boundary; take exactly those values
+        f32 = lambda v: float(np.float32(v))
+        self.nu, self.rho, self.eta = f32(nu), f32(rho), f32(eta)
+        self.tau = [None] + [f32(tau0)] * self.L                          # tau[l], l = 1..L
+        self.theta = [None] + [[f32(theta0)] * self.M for _ in range(self.L - 1)]   # theta[l][m], l = 1..L-1
+        self.max_backtrack = int(max_backtrack)
+        self.J = int(fista_iters)
+        self.risk = int(risk)
+        self.dual_form = int(dual_form)
+        if self.dual_form != 0:
+            raise NotImplementedError("only the dual step as printed (Eq. 2) is built")
+        self.k = 0
+        self.status = 0
+        self.trials_W = [0] * (self.L + 1)
+        self.trials_Z = [None] + [[0] * self.M for _ in range(self.L - 1)]
+        self.TL_prev = None
+
+    # ------------------------------------------------------------------ data / init
+    def set_data(self, X_old, labels_old):
+        self.Z = [None] * (self.L + 1)
+        self.Z[0] = self.g.to_new(np.asarray(X_old, dtype=np.float64))
+        self.labels = self.g.to_new(np.asarray(labels_old, dtype=np.int64))
+        CL = self.dims[-1]
+        if self.labels.max(initial=-1) >= CL:
+            raise ValueError("label out of range")
+        self.Y = np.zeros((self.N, CL))
+        lab = self.labels >= 0
+        self.Y[np.flatnonzero(lab), self.labels[lab]] = 1.0
+        self.labelled = lab
+
+    def init(self, W0):
+        """W given; Z_l = f_l(A~ Z_{l-1} W_l), Z_L = A~ Z_{L-1} W_L (constraints of Problem 1); U = 0."""
+        self.W = [None] + [np.asarray(w, dtype=np.float64).copy() for w in W0]
+        for l in range(1, self.L + 1):
+            assert self.W[l].shape == (self.dims[l - 1], self.dims[l])
+            T = np.vstack([self.g.aggregate_block(m, self.Z[l - 1]) @ self.W[l] for m in range(self.M)])
+            self.Z[l] = relu(T) if l < self.L else T
+        self.U = np.zeros((self.N, self.dims[-1]))
+        self.k = 0
+        self.TL_prev = None
+
+    def blk(self, X, m):
+        return X[self.g.rows(m)]
+
+    # ------------------------------------------------------------------ risk R(Z_L, Y)
+    def risk_value(self, ZL_rows, Y_rows, lab_rows):
+        """R restricted to some rows (it is a sum over labelled rows)."""
+        z = ZL_rows[lab_rows]
+        y = Y_rows[lab_rows]
+        if z.shape[0] == 0:
+            return 0.0
+        if self.risk == 0:
+            zmax = z.max(axis=1, keepdims=True)
+            lse = zmax[:, 0] + np.log(np.sum(np.exp(z - zmax), axis=1))
+            return float(np.sum(lse - np.sum(y * z, axis=1)))
+        return 0.5 * sqnorm(z - y)
+
+    def risk_grad(self, z, y):
+        """dR/dz for labelled rows."""
+        if self.risk == 0:
+            e = np.exp(z - z.max(axis=1, keepdims=True))
+            return e / e.sum(axis=1, keepdims=True) - y
+        return z - y
+
+    # ------------------------------------------------------------------ phi  (Section 3, definitions of phi)
+    def phi(self, l, Wl, Zprev, Zl, U=None):
+        """phi(W_l, Z_{l-1}, Z_l) for l < L, phi(W_L, Z_{L-1}, Z_L, U) for l = L, in the blocked form."""
+        tot = 0.0
+        for m in range(self.M):
+            T = self.g.aggregate_block(m, Zprev) @ Wl
+            if l < self.L:
+                tot += 0.5 * self.nu * sqnorm(self.blk(Zl, m) - relu(T))
+            else:
+                r = self.blk(Zl, m) - T
+                tot += inner(self.blk(U, m), r) + 0.5 * self.rho * sqnorm(r)
+        return tot
+
+    def grad_phi_W(self, l, Wl, Zprev, Zl, U=None):
+        """Gradient of phi with respect to W_l."""
+        g = np.zeros_like(Wl)
+        for m in range(self.M):
+            H = self.g.aggregate_block(m, Zprev)
+            T = H @ Wl
+            if l < self.L:
+                G = self.nu * (relu(T) - self.blk(Zl, m)) * relu_grad(T)
+            else:
+                r = self.blk(Zl, m) - T
+                G = -(self.blk(U, m) + self.rho * r)
+            g += H.T @ G
+        return g
+
+    # ------------------------------------------------------------------ W-update (Section 3.1)
+    def update_W(self, l, Wk, Zk, Uk):
+        """W_l^{k+1} = argmin P_l(W; tau): a gradient step of length 1/tau, tau found by backtracking
+        until  P_l(W^{k+1}; tau) >= phi(W^{k+1}, Z^k_{l-1}, Z^k_l (, U^k))."""
+        W = Wk[l]
+        phi0 = self.phi(l, W, Zk[l - 1], Zk[l], Uk)
+        grad = self.grad_phi_W(l, W, Zk[l - 1], Zk[l], Uk)
+        tau = self.tau[l]
+        trials = 0
+        if sqnorm(grad) <= (self.STEP_FLOOR * tau) ** 2 * sqnorm(W):
+            self.trials_W[l] = 0
+            return W.copy()
+        while True:
+            Wn = W - grad / tau
+            model = phi0 + inner(grad, Wn - W) + 0.5 * tau * sqnorm(Wn - W)
+            trials += 1
+            if self.phi(l, Wn, Zk[l - 1], Zk[l], Uk) <= model:
+                break
+            if trials > self.max_backtrack:
+                self.status |= self.STATUS_BACKTRACK_CAP
+                break
+            tau *= self.eta
+        self.tau[l] = tau
+        self.trials_W[l] = trials
+        return Wn
+
+    # ------------------------------------------------------------------ messages (Appendix A)
+    def first_order(self, l, Zl, Wnext):
+        """p_{l, r->m} = A~_{m,r} Z_{l,r} W_{l+1}  for every m and r in N_m or r = m.  Key (r, m)."""
+        p = {}
+        for r in range(self.M):
+            ZW = self.blk(Zl, r) @ Wnext
+            for m in self.g.nbr_and_self(r):          # r in N_m  <=>  m in N_r (undirected graph)
+                p[(r, m)] = self.g.block[(m, r)] @ ZW
+        return p
+
+    def second_order(self, l, p_l, Znext, U):
+        """s_{l, r->m} = [s1, s2] for r in N_m (Appendix A, second-order information).
+
+        l <= L-2:  s1 = Z_{l+1,r},                                   s2 = sum_{r' in N_r u {r} minus {m}} p_{l,r'->r}
+        l  = L-1:  s1 = Z_{L,r} - sum_{r' in N_r u {r} minus {m}} p_{L-1,r'->r},   s2 = U_r
+        """
+        s = {}
+        for m in range(self.M):
+            for r in self.g.nbrs(m):
+                acc = np.zeros_like(p_l[(r, r)])
+                for rp in self.g.nbr_and_self(r):
+                    if rp != m:
+                        acc = acc + p_l[(rp, r)]
+                if l <= self.L - 2:
+                    s[(r, m)] = (self.blk(Znext, r), acc)
+                else:
+                    s[(r, m)] = (self.blk(Znext, r) - acc, self.blk(U, r))
+        return s
+
+    # ------------------------------------------------------------------ psi  (Appendix A, Eqs. 3, 4)
+    def psi(self, l, m, Zlm, Wnext, Znext, U, p_prev, p_cur, s_cur):
+        """Objective of the Z_{l,m} subproblem, l = 1..L-1, in the message form."""
+        g = self.g
+        own_pre = sum(p_prev[(r, m)] for r in g.nbr_and_self(m))
+        val = 0.5 * self.nu * sqnorm(Zlm - relu(own_pre))
+        a = g.block[(m, m)] @ Zlm @ Wnext
+        for r in g.nbrs(m):
+            a = a + p_cur[(r, m)]
+        if l <= self.L - 2:
+            val += 0.5 * self.nu * sqnorm(self.blk(Znext, m) - relu(a))
+            for r in g.nbrs(m):
+                s1, s2 = s_cur[(r, m)]
+                val += 0.5 * self.nu * sqnorm(s1 - relu(g.block[(r, m)] @ Zlm @ Wnext + s2))
+        else:
+            res = self.blk(Znext, m) - a
+            val += inner(self.blk(U, m), res) + 0.5 * self.rho * sqnorm(res)
+            for r in g.nbrs(m):
+                s1, s2 = s_cur[(r, m)]
+                d = s1 - g.block[(r, m)] @ Zlm @ Wnext
+                val += inner(s2, d) + 0.5 * self.rho * sqnorm(d)
+        return val
+
+    def grad_psi(self, l, m, Zlm, Wnext, Znext, U, p_prev, p_cur, s_cur):
+        """Gradient of psi with respect to Z_{l,m}."""
+        g = self.g
+        own_pre = sum(p_prev[(r, m)] for r in g.nbr_and_self(m))
+        grad = self.nu * (Zlm - relu(own_pre))
+        a = g.block[(m, m)] @ Zlm @ Wnext
+        for r in g.nbrs(m):
+            a = a + p_cur[(r, m)]
+        if l <= self.L - 2:
+            Gm = self.nu * (relu(a) - self.blk(Znext, m)) * relu_grad(a)
+            grad = grad + g.block[(m, m)].T @ Gm @ Wnext.T
+            for r in g.nbrs(m):
+                s1, s2 = s_cur[(r, m)]
+                b = g.block[(r, m)] @ Zlm @ Wnext + s2
+                Gr = self.nu * (relu(b) - s1) * relu_grad(b)
+                grad = grad + g.block[(r, m)].T @ Gr @ Wnext.T
+        else:
+            res = self.blk(Znext, m) - a
+            Gm = -(self.blk(U, m) + self.rho * res)
+            grad = grad + g.block[(m, m)].T @ Gm @ Wnext.T
+            for r in g.nbrs(m):
+                s1, s2 = s_cur[(r, m)]
+                d = s1 - g.block[(r, m)] @ Zlm @ Wnext
+                Gr = -(s2 + self.rho * d)
+                grad = grad + g.block[(r, m)].T @ Gr @ Wnext.T
+        return grad
+
+    def update_Z_hidden(self, l, m, Zk, Wn, Uk, p_prev, p_cur, s_cur):
+        """Z_{l,m}^{k+1} = argmin Q_{l,m}(Z; theta): a gradient step of length 1/theta with backtracking
+        until  Q_{l,m}(Z^{k+1}; theta) >= psi(Z^{k+1}, ...)   (Appendix A, Eqs. 6-8)."""
+        Z = self.blk(Zk[l], m)
+        args = (Wn[l + 1], Zk[l + 1], Uk, p_prev, p_cur, s_cur)
+        psi0 = self.psi(l, m, Z, *args)
+        grad = self.grad_psi(l, m, Z, *args)
+        theta = self.theta[l][m]
+        trials = 0
+        if sqnorm(grad) <= (self.STEP_FLOOR * theta) ** 2 * sqnorm(Z):
+            self.trials_Z[l][m] = 0
+            return Z.copy()
+        while True:
+            Zn = Z - grad / theta
+            model = psi0 + inner(grad, Zn - Z) + 0.5 * theta * sqnorm(Zn - Z)
+            trials += 1
+            if self.psi(l, m, Zn, *args) <= model:
+                break
+            if trials > self.max_backtrack:
+                self.status |= self.STATUS_BACKTRACK_CAP
+                break
+            theta *= self.eta
+        self.theta[l][m] = theta
+        self.trials_Z[l][m] = trials
+        return Zn
+
+    # ------------------------------------------------------------------ last layer (Appendix A, Eq. 5)
+    def psi_last(self, m, ZLm, Uk, p_last):
+        c = sum(p_last[(r, m)] for r in self.g.nbr_and_self(m))
+        rows = self.g.rows(m)
+        return (self.risk_value(ZLm, self.Y[rows], self.labelled[rows])
+                + inner(self.blk(Uk, m), ZLm - c) + 0.5 * self.rho * sqnorm(ZLm - c))
+
+    def update_Z_last(self, m, Zk, Uk, p_last, J=None):
+        """Z_{L,m}^{k+1}: FISTA on Eq. 5, whose smooth part is the whole objective (no non-smooth term),
+        so the proximal map is the identity: x_j = y_j - grad(y_j)/Lip, with the usual momentum."""
+        J = self.J if J is None else J
+        rows = self.g.rows(m)
+        c = sum(p_last[(r, m)] for r in self.g.nbr_and_self(m))
+        Um = self.blk(Uk, m)
+        Ym = self.Y[rows]
+        lab = self.labelled[rows]
+        Lip = self.rho + (0.5 if self.risk == 0 else 1.0)
+
+        def grad(z):
+            g = Um + self.rho * (z - c)
+            g[lab] += self.risk_grad(z[lab], Ym[lab])
+            return g
+
+        x_prev = self.blk(Zk[self.L], m).copy()
+        y = x_prev.copy()
+        t = 1.0
+        x = x_prev
+        for _ in range(J):
+            x = y - grad(y) / Lip
+            t_next = 0.5 * (1.0 + np.sqrt(1.0 + 4.0 * t * t))
+            y = x + ((t - 1.0) / t_next) * (x - x_prev)
+            x_prev, t = x, t_next
+        x = x.copy()
+        x[~lab] = (c - Um / self.rho)[~lab]           # exact minimiser of the pure quadratic
+        return x
+
+    # ------------------------------------------------------------------ one iteration of Algorithm 1
+    def iterate(self, k=1):
+        for _ in range(k):
+            self._sweep()
+
+    def _sweep(self):
+        L, M = self.L, self.M
+        Wk, Zk, Uk = self.W, self.Z, self.U
+        # Line 3: W_l^{k+1} for every l from (Z^k, U^k)
+        Wn = [None] + [self.update_W(l, Wk, Zk, Uk) for l in range(1, L + 1)]
+        # messages with Z^k and W^{k+1}
+        p = [self.first_order(l, Zk[l], Wn[l + 1]) for l in range(0, L)]
+        s = [None] + [self.second_order(l, p[l], Zk[l + 1], Uk) for l in range(1, L)]
+        # Line 4: Z_{l,m}^{k+1} for every l, m from (W^{k+1}, Z^k, U^k)
+        Zn = [Zk[0]] + [np.empty_like(Zk[l]) for l in range(1, L + 1)]
+        for l in range(1, L):
+            for m in range(M):
+                Zn[l][self.g.rows(m)] = self.update_Z_hidden(l, m, Zk, Wn, Uk, p[l - 1], p[l], s[l])
+        for m in range(M):
+            Zn[L][self.g.rows(m)] = self.update_Z_last(m, Zk, Uk, p[L - 1])
+        # Line 5: U_m^{k+1} = U_m^k + rho (Z_{L,m}^k - sum_r p_{L-1,r->m}^k)       (Eq. 2)
+        Un = np.empty_like(Uk)
+        for m in range(M):
+            c = sum(p[L - 1][(r, m)] for r in self.g.nbr_and_self(m))
+            Un[self.g.rows(m)] = self.blk(Uk, m) + self.rho * (self.blk(Zk[L], m) - c)
+        # keep A~ Z_{L-1}^k W_L^k for the dual residual of the next readout
+        self.TL_prev = np.vstack([self.g.aggregate_block(m, Zk[L - 1]) @ Wk[L] for m in range(M)])
+        self.W, self.Z, self.U = Wn, Zn, Un
+        self.k += 1
+        if not all(np.all(np.isfinite(a)) for a in self.W[1:] + self.Z[1:] + [self.U]):
+            self.status |= self.STATUS_NONFINITE
+
+    # ------------------------------------------------------------------ readout
+    def stats(self):
+        """Objective of Problem 3, augmented Lagrangian (Eq. 1), residuals, at the current iterate."""
+        L, M = self.L, self.M
+        risk = sum(self.risk_value(self.blk(self.Z[L], m), self.Y[self.g.rows(m)],
+                                   self.labelled[self.g.rows(m)]) for m in range(M))
+        pen = [self.phi(l, self.W[l], self.Z[l - 1], self.Z[l]) for l in range(1, L)]
+        phiL = self.phi(L, self.W[L], self.Z[L - 1], self.Z[L], self.U)
+        TL = np.vstack([self.g.aggregate_block(m, self.Z[L - 1]) @ self.W[L] for m in range(M)])
+        primal = float(np.sqrt(sqnorm(self.Z[L] - TL)))
+        dual = 0.0 if self.TL_prev is None else self.rho * float(np.sqrt(sqnorm(TL - self.TL_prev)))
+        F = risk + sum(pen)
+        return dict(objective=F, lagrangian=F + phiL, risk=risk, primal_res=primal, dual_res=dual,
+                    layer_penalty=pen, iter=self.k, status=self.status)
+
+    # ------------------------------------------------------------------ accessors (caller's node order)
+    def get_W(self, l):
+        return self.W[l].copy()
+
+    def get_Z(self, l):
+        return self.g.to_old(self.Z[l])
+
+    def get_U(self):
+        return self.g.to_old(self.U)
+
+    def get_steps(self):
+        tau = np.array(self.tau[1:], dtype=np.float64)
+        theta = np.array([self.theta[l][m] for l in range(1, self.L) for m in range(self.M)], dtype=np.float64)
+        trials = np.array(self.trials_W[1:] + [self.trials_Z[l][m] for l in range(1, self.L)
+                                                for m in range(self.M)], dtype=np.int32)
+        return tau, theta, trials
+
+
+def make_oracle(w, iters=None):
+    """Build graph + oracle for a synth.Workload-like object (attributes only, no import of the generator)."""
+    g = OracleGraph(w.N, w.src, w.dst, w.M, w.comm)
+    h = w.hyper
+    o = AdmmOracle(g, w.dims, nu=h["nu"], rho=h["rho"], tau0=h["tau0"], theta0=h["theta0"], eta=h["eta"],
+                   max_backtrack=h["max_backtrack"], fista_iters=h["fista_iters"], risk=h["risk"],
+                   dual_form=h["dual_form"])
+    o.set_data(w.X, w.labels)
+    o.init(w.W0)
+    return o

@@ -1,0 +1,404 @@
+"""Pins for the oracle's ADMM part (paper, Section 3 and Appendix A).
+
+Each check ties a piece of the oracle to something other than itself: the augmented
+Lagrangian (Eq. 1) written out with dense matrices, finite differences, closed forms,
+the inequalities the step parameters must satisfy, and special cases.
+"""
+import copy
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle.admm import AdmmOracle, relu
+from oracle.graph import OracleGraph
+
+HYPER = dict(nu=0.7, rho=0.3, tau0=1e-3, theta0=1e-3, eta=2.0, max_backtrack=60, fista_iters=10)
+
+
+def tiny_problem(seed, N=30, M=3, dims=(6, 5, 4, 3), p=0.15, labelled=0.8, hyper=None, risk=0, forward_init=False):
+    rng = np.random.default_rng(seed)
+    edges = [(u, v) for u, v in itertools.combinations(range(N), 2) if rng.random() < p]
+    comm = rng.integers(0, M, size=N).astype(np.int32)
+    g = OracleGraph(N, [a for a, _ in edges], [b for _, b in edges], M, comm)
+    h = dict(HYPER)
+    h.update(hyper or {})
+    o = AdmmOracle(g, dims, risk=risk, **h)
+    X = rng.standard_normal((N, dims[0]))
+    labels = np.where(rng.random(N) < labelled, rng.integers(0, dims[-1], size=N), -1)
+    o.set_data(X, labels)
+    W0 = [rng.standard_normal((dims[l - 1], dims[l])) * 0.5 for l in range(1, len(dims))]
+    o.init(W0)
+    if not forward_init:          # a generic point: nothing is stationary, no ReLU argument is near 0
+        for l in range(1, o.L + 1):
+            o.Z[l] = rng.standard_normal(o.Z[l].shape)
+        o.U = rng.standard_normal(o.U.shape)
+    return o, rng
+
+
+def dense_lagrangian(o, W, Z, U):
+    """Eq. 1 in its full-graph form, with a dense A~ and explicit loops over layers."""
+    A = o.g.A.toarray()
+    L = o.L
+    zl = Z[L][o.labelled]
+    yl = o.Y[o.labelled]
+    if o.risk == 0:
+        val = float(np.sum(np.log(np.sum(np.exp(zl), axis=1)) - np.sum(yl * zl, axis=1)))
+    else:
+        val = 0.5 * float(np.sum((zl - yl) ** 2))
+    for l in range(1, L):
+        val += 0.5 * o.nu * float(np.sum((Z[l] - np.maximum(A @ Z[l - 1] @ W[l], 0.0)) ** 2))
+    r = Z[L] - A @ Z[L - 1] @ W[L]
+    val += float(np.sum(U * r)) + 0.5 * o.rho * float(np.sum(r * r))
+    return val
+
+
+def messages(o, W):
+    p = [o.first_order(l, o.Z[l], W[l + 1]) for l in range(o.L)]
+    s = [None] + [o.second_order(l, p[l], o.Z[l + 1], o.U) for l in range(1, o.L)]
+    return p, s
+
+
+# ---------------------------------------------------------------- aggregation and phi
+def test_blocked_A_Z_W_equals_brute_force_triple_loop():
+    o, rng = tiny_problem(0, N=14, M=3, dims=(3, 4, 2))
+    A = o.g.A.toarray()
+    Z0, W1 = o.Z[0], o.W[1]
+    N, C0, C1 = 14, 3, 4
+    want = np.zeros((N, C1))
+    for i in range(N):
+        for c in range(C1):
+            acc = 0.0
+            for j in range(N):
+                for k in range(C0):
+                    acc += A[i, j] * Z0[j, k] * W1[k, c]
+            want[i, c] = acc
+    got = np.vstack([o.g.aggregate_block(m, Z0) @ W1 for m in range(o.M)])
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-13)
+
+
+def test_phi_blocked_equals_full_graph_form():
+    o, _ = tiny_problem(1)
+    A = o.g.A.toarray()
+    for l in range(1, o.L):
+        want = 0.5 * o.nu * np.sum((o.Z[l] - relu(A @ o.Z[l - 1] @ o.W[l])) ** 2)
+        assert o.phi(l, o.W[l], o.Z[l - 1], o.Z[l]) == pytest.approx(want, rel=1e-12)
+    L = o.L
+    r = o.Z[L] - A @ o.Z[L - 1] @ o.W[L]
+    want = np.sum(o.U * r) + 0.5 * o.rho * np.sum(r * r)
+    assert o.phi(L, o.W[L], o.Z[L - 1], o.Z[L], o.U) == pytest.approx(want, rel=1e-12)
+
+
+def test_first_order_messages_sum_to_the_full_aggregation():
+    o, _ = tiny_problem(2)
+    A = o.g.A.toarray()
+    for l in range(o.L):
+        p = o.first_order(l, o.Z[l], o.W[l + 1])
+        full = A @ o.Z[l] @ o.W[l + 1]
+        for m in range(o.M):
+            got = sum(p[(r, m)] for r in o.g.nbr_and_self(m))
+            np.testing.assert_allclose(got, full[o.g.rows(m)], rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("l", [1, 2, 3])
+def test_grad_phi_matches_central_differences(l):
+    o, rng = tiny_problem(3)
+    W = o.W[l]
+    g = o.grad_phi_W(l, W, o.Z[l - 1], o.Z[l], o.U)
+    for _ in range(5):
+        d = rng.standard_normal(W.shape)
+        h = 1e-6
+        fd = (o.phi(l, W + h * d, o.Z[l - 1], o.Z[l], o.U) - o.phi(l, W - h * d, o.Z[l - 1], o.Z[l], o.U)) / (2 * h)
+        assert fd == pytest.approx(float(np.sum(g * d)), rel=1e-6, abs=1e-9)
+
+
+# ---------------------------------------------------------------- psi: message form vs Eq. 1
+@pytest.mark.parametrize("seed", [4, 5])
+def test_psi_message_form_equals_lagrangian_up_to_a_constant(seed):
+    """psi_{l,m}(Z) - psi_{l,m}(Z') must equal L_rho(.., Z_{l,m}=Z, ..) - L_rho(.., Z_{l,m}=Z', ..):
+    the second-order messages carry exactly the terms of Eq. 1 that depend on Z_{l,m}."""
+    o, rng = tiny_problem(seed)
+    p, s = messages(o, o.W)
+    for l in range(1, o.L):
+        for m in range(o.M):
+            rows = o.g.rows(m)
+            if rows.stop == rows.start:
+                continue
+            Za = rng.standard_normal((rows.stop - rows.start, o.dims[l]))
+            Zb = rng.standard_normal(Za.shape)
+            args = (o.W[l + 1], o.Z[l + 1], o.U, p[l - 1], p[l], s[l])
+            d_psi = o.psi(l, m, Za, *args) - o.psi(l, m, Zb, *args)
+            vals = []
+            for Zx in (Za, Zb):
+                Z = [z.copy() for z in o.Z]
+                Z[l][rows] = Zx
+                vals.append(dense_lagrangian(o, o.W, Z, o.U))
+            assert d_psi == pytest.approx(vals[0] - vals[1], rel=1e-10, abs=1e-10)
+
+
+@pytest.mark.parametrize("seed", [6, 7])
+def test_grad_psi_matches_central_differences_and_full_graph_gradient(seed):
+    o, rng = tiny_problem(seed)
+    p, s = messages(o, o.W)
+    A = o.g.A.toarray()
+    for l in range(1, o.L):
+        # full-graph gradient of Eq. 1 with respect to Z_l at the current point
+        Tn = A @ o.Z[l] @ o.W[l + 1]
+        if l + 1 < o.L:
+            G = o.nu * (relu(Tn) - o.Z[l + 1]) * (Tn > 0)
+        else:
+            G = -(o.U + o.rho * (o.Z[l + 1] - Tn))
+        full = o.nu * (o.Z[l] - relu(A @ o.Z[l - 1] @ o.W[l])) + A.T @ G @ o.W[l + 1].T
+        for m in range(o.M):
+            rows = o.g.rows(m)
+            if rows.stop == rows.start:
+                continue
+            Z = o.Z[l][rows]
+            args = (o.W[l + 1], o.Z[l + 1], o.U, p[l - 1], p[l], s[l])
+            g = o.grad_psi(l, m, Z, *args)
+            np.testing.assert_allclose(g, full[rows], rtol=1e-10, atol=1e-12)
+            for _ in range(3):
+                d = rng.standard_normal(Z.shape)
+                h = 1e-6
+                fd = (o.psi(l, m, Z + h * d, *args) - o.psi(l, m, Z - h * d, *args)) / (2 * h)
+                assert fd == pytest.approx(float(np.sum(g * d)), rel=1e-6, abs=1e-9)
+
+
+# ---------------------------------------------------------------- quadratic models and backtracking
+def test_W_step_minimises_the_quadratic_model_and_meets_the_tau_condition():
+    o, _ = tiny_problem(8)
+    for l in range(1, o.L + 1):
+        W = o.W[l]
+        phi0 = o.phi(l, W, o.Z[l - 1], o.Z[l], o.U)
+        grad = o.grad_phi_W(l, W, o.Z[l - 1], o.Z[l], o.U)
+        Wn = o.update_W(l, o.W, o.Z, o.U)
+        tau = o.tau[l]
+        # gradient of P_l at the new point vanishes:  grad + tau (Wn - W) = 0
+        np.testing.assert_allclose(grad + tau * (Wn - W), 0.0, atol=1e-12 * max(1.0, np.abs(grad).max()))
+        phin = o.phi(l, Wn, o.Z[l - 1], o.Z[l], o.U)
+        model = phi0 + np.sum(grad * (Wn - W)) + 0.5 * tau * np.sum((Wn - W) ** 2)
+        assert phin <= model + 1e-12 * abs(model)            # the condition on tau
+        assert phin <= phi0                                   # so the subproblem value cannot rise
+        assert model == pytest.approx(phi0 - np.sum(grad ** 2) / (2 * tau), rel=1e-12)
+        # tau is the first value of the doubling sequence that passes: the one before fails
+        if o.trials_W[l] > 1:
+            tp = tau / o.eta
+            Wp = W - grad / tp
+            assert o.phi(l, Wp, o.Z[l - 1], o.Z[l], o.U) > phi0 - np.sum(grad ** 2) / (2 * tp)
+            assert tau == pytest.approx(np.float32(HYPER["tau0"]) * o.eta ** (o.trials_W[l] - 1), rel=1e-12)
+
+
+def test_Z_step_minimises_the_quadratic_model_and_meets_the_theta_condition():
+    o, _ = tiny_problem(9)
+    p, s = messages(o, o.W)
+    searched = 0
+    for l in range(1, o.L):
+        for m in range(o.M):
+            rows = o.g.rows(m)
+            if rows.stop == rows.start:
+                continue
+            Z = o.Z[l][rows]
+            args = (o.W[l + 1], o.Z[l + 1], o.U, p[l - 1], p[l], s[l])
+            psi0 = o.psi(l, m, Z, *args)
+            grad = o.grad_psi(l, m, Z, *args)
+            Zn = o.update_Z_hidden(l, m, o.Z, o.W, o.U, p[l - 1], p[l], s[l])
+            th = o.theta[l][m]
+            np.testing.assert_allclose(grad + th * (Zn - Z), 0.0, atol=1e-12 * max(1.0, np.abs(grad).max()))
+            psin = o.psi(l, m, Zn, *args)
+            assert psin <= psi0 - np.sum(grad ** 2) / (2 * th) + 1e-12 * abs(psi0)
+            if o.trials_Z[l][m] > 1:
+                searched += 1
+                tp = th / o.eta
+                assert o.psi(l, m, Z - grad / tp, *args) > psi0 - np.sum(grad ** 2) / (2 * tp)
+    assert searched > 0
+
+
+def test_backtracking_cap_raises_the_status_bit():
+    o, _ = tiny_problem(10, hyper=dict(max_backtrack=1))
+    o.iterate(1)
+    assert o.status & AdmmOracle.STATUS_BACKTRACK_CAP
+    assert max(o.get_steps()[2]) == 2
+
+
+# ---------------------------------------------------------------- last layer
+def test_last_layer_least_squares_has_its_closed_form():
+    o, _ = tiny_problem(11, risk=1)
+    p, _ = messages(o, o.W)
+    A = o.g.A.toarray()
+    T = A @ o.Z[o.L - 1] @ o.W[o.L]
+    for m in range(o.M):
+        rows = o.g.rows(m)
+        got = o.update_Z_last(m, o.Z, o.U, p[o.L - 1])
+        lab = o.labelled[rows]
+        want = (o.Y[rows] + o.rho * T[rows] - o.U[rows]) / (1.0 + o.rho)
+        np.testing.assert_allclose(got[lab], want[lab], rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(got[~lab], (T[rows] - o.U[rows] / o.rho)[~lab], rtol=1e-12, atol=1e-12)
+
+
+def test_last_layer_cross_entropy_fista_approaches_the_newton_solution():
+    o, _ = tiny_problem(12)
+    p, _ = messages(o, o.W)
+    A = o.g.A.toarray()
+    T = A @ o.Z[o.L - 1] @ o.W[o.L]
+    for m in range(o.M):
+        rows = o.g.rows(m)
+        lab = o.labelled[rows]
+        b = (T[rows] - o.U[rows] / o.rho)
+        # per-row Newton on  lse(z) - z_y + rho/2 ||z - b||^2
+        want = b.copy()
+        for i in np.flatnonzero(lab):
+            z = b[i].copy()
+            y = o.Y[rows][i]
+            for _ in range(100):
+                e = np.exp(z - z.max())
+                q = e / e.sum()
+                grad = q - y + o.rho * (z - b[i])
+                H = np.diag(q) - np.outer(q, q) + o.rho * np.eye(z.size)
+                z = z - np.linalg.solve(H, grad)
+            assert np.max(np.abs(grad)) < 1e-12
+            want[i] = z
+        errs = []
+        for J in (10, 100, 1000):
+            got = o.update_Z_last(m, o.Z, o.U, p[o.L - 1], J=J)
+            errs.append(np.max(np.abs(got - want)))
+            np.testing.assert_allclose(got[~lab], want[~lab], rtol=1e-12, atol=1e-12)   # unlabelled rows: b
+        assert errs[2] < 1e-6 and errs[2] < errs[0]
+        # J FISTA steps never do worse than the start on the subproblem's own objective
+        start = o.psi_last(m, o.Z[o.L][rows], o.U, p[o.L - 1])
+        assert o.psi_last(m, o.update_Z_last(m, o.Z, o.U, p[o.L - 1]), o.U, p[o.L - 1]) < start
+
+
+def test_psi_last_equals_lagrangian_up_to_a_constant():
+    o, rng = tiny_problem(13)
+    p, _ = messages(o, o.W)
+    for m in range(o.M):
+        rows = o.g.rows(m)
+        Za, Zb = (rng.standard_normal((rows.stop - rows.start, o.dims[-1])) for _ in range(2))
+        vals = []
+        for Zx in (Za, Zb):
+            Z = [z.copy() for z in o.Z]
+            Z[o.L][rows] = Zx
+            vals.append(dense_lagrangian(o, o.W, Z, o.U))
+        d = o.psi_last(m, Za, o.U, p[o.L - 1]) - o.psi_last(m, Zb, o.U, p[o.L - 1])
+        assert d == pytest.approx(vals[0] - vals[1], rel=1e-10, abs=1e-10)
+
+
+# ---------------------------------------------------------------- whole sweep
+def test_forward_pass_start_has_zero_penalties_and_zero_residual():
+    o, _ = tiny_problem(14, forward_init=True)
+    st = o.stats()
+    assert st["primal_res"] == 0.0 and all(v == 0.0 for v in st["layer_penalty"])
+    assert st["objective"] == st["risk"] == st["lagrangian"]
+    for l in range(1, o.L + 1):
+        assert np.all(o.grad_phi_W(l, o.W[l], o.Z[l - 1], o.Z[l], o.U) == 0.0)
+
+
+def test_sweep_is_jacobi_dual_step_and_readout_are_consistent():
+    o, _ = tiny_problem(15)
+    A = o.g.A.toarray()
+    W0, Z0, U0 = copy.deepcopy(o.W), copy.deepcopy(o.Z), o.U.copy()
+    o.iterate(1)
+    # W^{k+1} depends on (W^k, Z^k, U^k) only: recompute each layer alone from the saved iterate
+    o2, _ = tiny_problem(15)
+    for l in range(1, o.L + 1):
+        np.testing.assert_array_equal(o2.update_W(l, W0, Z0, U0), o.W[l])
+    # dual step as printed (Eq. 2): U^{k+1} - U^k = rho (Z_L^k - A~ Z_{L-1}^k W_L^{k+1})
+    r = Z0[o.L] - A @ Z0[o.L - 1] @ o.W[o.L]
+    np.testing.assert_allclose(o.U - U0, o.rho * r, rtol=1e-10, atol=1e-12)
+    assert np.linalg.norm(o.U - U0) == pytest.approx(o.rho * np.linalg.norm(r), rel=1e-10)
+    # readout against Eq. 1 written densely
+    st = o.stats()
+    assert st["lagrangian"] == pytest.approx(dense_lagrangian(o, o.W, o.Z, o.U), rel=1e-11)
+    assert st["primal_res"] == pytest.approx(np.linalg.norm(o.Z[o.L] - A @ o.Z[o.L - 1] @ o.W[o.L]), rel=1e-11)
+    assert st["dual_res"] == pytest.approx(
+        o.rho * np.linalg.norm(A @ o.Z[o.L - 1] @ o.W[o.L] - A @ Z0[o.L - 1] @ W0[o.L]), rel=1e-10)
+    # every Z_{l,m}^{k+1} lowers L_rho(W^{k+1}, Z^k with that block replaced, U^k)
+    for l in range(1, o.L + 1):
+        for m in range(o.M):
+            rows = o.g.rows(m)
+            Z = [z.copy() for z in Z0]
+            Z[l][rows] = o.Z[l][rows]
+            assert dense_lagrangian(o, o.W, Z, U0) <= dense_lagrangian(o, o.W, Z0, U0) + 1e-10
+
+
+def test_disconnected_communities_decouple_in_the_Z_update():
+    """Without inter-community edges N_m is empty, no s-terms exist, and Z_{l,m}^{k+1} equals what a
+    one-community problem on the subgraph of V_m alone produces from the same W^{k+1}."""
+    rng = np.random.default_rng(16)
+    N, M, dims = 24, 3, (4, 5, 3)
+    comm = np.repeat(np.arange(M), N // M).astype(np.int32)
+    edges = [(u, v) for u, v in itertools.combinations(range(N), 2) if comm[u] == comm[v] and rng.random() < 0.3]
+    g = OracleGraph(N, [a for a, _ in edges], [b for _, b in edges], M, comm)
+    assert not g.neighbour.any()
+    X = rng.standard_normal((N, dims[0]))
+    labels = rng.integers(0, dims[-1], size=N)
+    W0 = [rng.standard_normal((dims[l - 1], dims[l])) for l in range(1, 3)]
+    big = AdmmOracle(g, dims, **HYPER)
+    big.set_data(X, labels)
+    big.init(W0)
+    Zr = [None] + [rng.standard_normal(big.Z[l].shape) for l in (1, 2)]
+    Ur = rng.standard_normal(big.U.shape)
+    big.Z[1:] = [z.copy() for z in Zr[1:]]
+    big.U = Ur.copy()
+    p = [big.first_order(l, big.Z[l], big.W[l + 1]) for l in range(2)]
+    s = [None, big.second_order(1, p[1], big.Z[2], big.U)]
+    for m in range(M):
+        idx = np.flatnonzero(comm == m)
+        loc = {int(o_): i for i, o_ in enumerate(idx)}
+        sub_edges = [(loc[u], loc[v]) for u, v in edges if comm[u] == m]
+        gs = OracleGraph(len(idx), [a for a, _ in sub_edges], [b for _, b in sub_edges], 1, None)
+        # degrees inside an isolated community are the same as in the union graph
+        small = AdmmOracle(gs, dims, **HYPER)
+        small.set_data(X[idx], labels[idx])
+        small.init(W0)
+        small.Z[1], small.Z[2], small.U = Zr[1][idx], Zr[2][idx], Ur[idx]
+        ps = [small.first_order(l, small.Z[l], small.W[l + 1]) for l in range(2)]
+        ss = [None, small.second_order(1, ps[1], small.Z[2], small.U)]
+        want = small.update_Z_hidden(1, 0, small.Z, small.W, small.U, ps[0], ps[1], ss[1])
+        got = big.update_Z_hidden(1, m, big.Z, big.W, big.U, p[0], p[1], s[1])
+        np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
+
+
+def test_relabelling_nodes_and_communities_leaves_the_iterates_unchanged():
+    rng = np.random.default_rng(17)
+    N, M, dims = 40, 4, (5, 6, 4, 3)
+    edges = [(u, v) for u, v in itertools.combinations(range(N), 2) if rng.random() < 0.1]
+    comm = rng.integers(0, M, size=N).astype(np.int32)
+    X = rng.standard_normal((N, dims[0]))
+    labels = rng.integers(0, dims[-1], size=N)
+    W0 = [rng.standard_normal((dims[l - 1], dims[l])) * 0.5 for l in range(1, len(dims))]
+    hyper = dict(HYPER, nu=1e-2, rho=1e-2)
+
+    def run(node_map, comm_map):
+        comm2 = np.empty(N, dtype=np.int32)
+        comm2[node_map] = comm_map[comm]
+        X2 = np.empty_like(X)
+        X2[node_map] = X
+        lab2 = np.empty_like(labels)
+        lab2[node_map] = labels
+        g = OracleGraph(N, [node_map[a] for a, _ in edges], [node_map[b] for _, b in edges], M, comm2)
+        o = AdmmOracle(g, dims, **hyper)
+        o.set_data(X2, lab2)
+        o.init(W0)
+        o.iterate(4)
+        return o, [o.get_Z(l)[node_map] for l in range(1, o.L + 1)]
+
+    oa, Za = run(np.arange(N), np.arange(M))
+    ob, Zb = run(rng.permutation(N), rng.permutation(M))
+    for l in range(1, oa.L + 1):
+        np.testing.assert_allclose(ob.W[l], oa.W[l], rtol=1e-9, atol=1e-11)
+        np.testing.assert_allclose(Zb[l - 1], Za[l - 1], rtol=1e-9, atol=1e-11)
+    assert ob.stats()["objective"] == pytest.approx(oa.stats()["objective"], rel=1e-10)
+
+
+def test_empty_graph_reduces_to_a_plain_multilayer_perceptron_penalty():
+    rng = np.random.default_rng(18)
+    N, dims = 12, (3, 4, 2)
+    g = OracleGraph(N, [], [], 2, None)
+    o = AdmmOracle(g, dims, **HYPER)
+    X = rng.standard_normal((N, 3))
+    o.set_data(X, rng.integers(0, 2, size=N))
+    o.init([rng.standard_normal((3, 4)), rng.standard_normal((4, 2))])
+    o.Z[1] = rng.standard_normal((N, 4))
+    assert o.phi(1, o.W[1], o.Z[0], o.Z[1]) == pytest.approx(
+        0.5 * o.nu * np.sum((o.Z[1] - relu(o.Z[0] @ o.W[1])) ** 2), rel=1e-13)
