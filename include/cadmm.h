@@ -1,0 +1,172 @@
+/*
+ * cadmm.h - C ABI of the community-blocked ADMM sweep for GCN training on one MI355X (gfx950).
+ *
+ * The calls follow the inputs and outputs of the paper's Algorithm 1 (REQUIRE Y, Z_0, nu, rho;
+ * ENSURE W_l, Z_{l,m}) and its Problems 1-3 (Section 2): build the graph and its communities,
+ * set model and data, initialise W/Z/U, run k ADMM iterations, read the objective and residuals.
+ *
+ * General conventions
+ *   - Every call returns CADMM_OK (0) or a negative CADMM_E* code; nothing throws, aborts or
+ *     prints.  cadmm_last_error() gives a text for the last failure on that context.
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device memory on the
+ *     context's GPU.  The caller owns every buffer it passes.  Inputs are copied; outputs are
+ *     written into caller memory.
+ *   - All device memory the library uses comes from ONE caller-provided workspace
+ *     (cadmm_workspace_bytes / cadmm_set_workspace).  The library never calls hipMalloc for
+ *     device memory; it allocates only small pinned host buffers for readouts.
+ *   - Node order at the boundary is the caller's.  Internally nodes are renumbered so that
+ *     every community is a contiguous row range (stable sort on (community, id)); that
+ *     numbering is visible through cadmm_get_graph and is the row order of the cadmm_op_*
+ *     kernel-level calls.
+ *   - Matrices are dense row-major fp32.  Layer widths C_0..C_L as in the paper's notation
+ *     table (C_l = number of neurons of layer l, C_0 = input features, C_L = classes).
+ *   - All work is enqueued on the HIP stream given at creation.  cadmm_run does not
+ *     synchronise; the cadmm_get_*, cadmm_eval calls do.
+ *   - Call order: create -> build_graph -> set_model -> workspace_bytes -> set_workspace ->
+ *     set_data -> init -> { run | eval | get_* | set_state }*.  A call out of order returns
+ *     CADMM_EORDER.
+ */
+#ifndef CADMM_H
+#define CADMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CADMM_OK          0
+#define CADMM_EINVAL     -1   /* bad argument (null pointer, id out of range, size mismatch)   */
+#define CADMM_EORDER     -2   /* call out of order                                              */
+#define CADMM_ENOMEM     -3   /* workspace too small / host allocation failed                   */
+#define CADMM_EHIP       -4   /* a HIP runtime call failed                                      */
+#define CADMM_EUNSUPPORTED -5 /* valid request this build does not implement                    */
+
+#define CADMM_STATUS_BACKTRACK_CAP 1  /* a step-size search used all max_backtrack multiplications */
+#define CADMM_STATUS_NONFINITE     2  /* a non-finite value was seen in a reduction                 */
+
+typedef struct cadmm_ctx cadmm_ctx;   /* opaque */
+
+/* Create a context on GPU `device`.  hip_stream: a hipStream_t (NULL = the default stream).
+ * device = -1 gives a host-only context: graph construction, its getters, set_model and
+ * workspace_bytes work; every call that needs the GPU returns CADMM_EUNSUPPORTED / CADMM_EORDER. */
+int  cadmm_create(cadmm_ctx** out, int device, void* hip_stream);
+void cadmm_destroy(cadmm_ctx* ctx);
+const char* cadmm_last_error(cadmm_ctx* ctx);
+
+/*
+ * Graph and communities (paper, Section 2: undirected unweighted graph G(V,E), normalised
+ * adjacency A~ = (D+I)^(-1/2)(A+I)(D+I)^(-1/2), partition into M communities V_m, neighbour
+ * sets N_m, blocks A~_{m,r}).
+ *   src,dst  host int32[n_edges], endpoints in [0,N); any order, both orientations, repeats and
+ *            self pairs are tolerated and normalised away.
+ *   comm     host int32[N], values in [0,M); NULL = contiguous chunks of ceil(N/M) nodes.
+ * Builds a CSR of A~ in the internal numbering (sorted columns, so each row's entries are
+ * grouped by community), the per-row community segments, and uploads it to the workspace once
+ * that is set.  Values: (float)(1.0 / sqrt((double)d_i * (double)d_j)), d_i = 1 + degree.
+ */
+int  cadmm_build_graph(cadmm_ctx* ctx, int64_t N, int64_t n_edges, const int32_t* src,
+                       const int32_t* dst, int32_t M, const int32_t* comm);
+/* nnz = 2E + N stored entries; n_segments = number of (row, community) pairs that occur;
+ * n_halo_rows = rows with at least one neighbour in another community. */
+int  cadmm_graph_sizes(cadmm_ctx* ctx, int64_t* nnz, int64_t* n_segments, int64_t* n_halo_rows);
+/*
+ * Copy the graph out (host pointers, any may be NULL to skip):
+ *   perm[N]            internal row -> caller's node id
+ *   row_ptr[N+1], col[nnz], val[nnz]        CSR of A~, internal numbering
+ *   seg_ptr[n_segments+1], seg_row[n_segments], seg_comm[n_segments]
+ *                      segments in (row, community) order; seg_ptr indexes col/val
+ *   comm_row_ptr[M+1]  first internal row of every community
+ *   neighbour[M*M]     neighbour[m*M+r] = 1 iff r is in N_m
+ */
+int  cadmm_get_graph(cadmm_ctx* ctx, int32_t* perm, int64_t* row_ptr, int32_t* col, float* val,
+                     int64_t* seg_ptr, int32_t* seg_row, int32_t* seg_comm, int64_t* comm_row_ptr,
+                     uint8_t* neighbour);
+/* Order in which cadmm_op_aggregate_segments writes its rows: segments sorted by
+ * (community, row).  order[j] = index of that segment in the (row, community) order above. */
+int  cadmm_get_segment_order(cadmm_ctx* ctx, int64_t* order /* host [n_segments] */);
+
+/*
+ * Model and hyper-parameters (Problem 2: nu; Eq. 1: rho; Section 3.1 / Appendix A: the step
+ * parameters tau_l, theta_{l,m} and their conditions).
+ *   L >= 2 layers, C[0..L] widths.  risk: 0 = softmax cross-entropy summed over labelled
+ *   rows, 1 = 1/2 ||Z_L - Y||^2 over labelled rows.
+ *   tau0/theta0: first candidates at k = 0; eta > 1: growth factor of the search;
+ *   max_backtrack: multiplications allowed per search (<= 64); fista_iters: J steps of the
+ *   last-layer solver (Appendix A, Eq. 5); dual_form: 0 = dual step with the superscripts as
+ *   printed in Eq. 2 (only form built).
+ */
+typedef struct {
+    int32_t L;
+    const int32_t* C;
+    int32_t risk;
+    float nu, rho, tau0, theta0, eta;
+    int32_t max_backtrack, fista_iters, dual_form;
+} cadmm_model;
+int  cadmm_set_model(cadmm_ctx* ctx, const cadmm_model* model);
+
+/* Device bytes needed for graph + state + scratch (valid after build_graph and set_model). */
+int  cadmm_workspace_bytes(cadmm_ctx* ctx, size_t* bytes);
+/* Hand over the workspace: device pointer, 256-byte aligned, at least workspace_bytes long.
+ * It must stay valid until cadmm_destroy.  Uploads the graph. */
+int  cadmm_set_workspace(cadmm_ctx* ctx, void* dev_ptr, size_t bytes);
+
+/* Z_0 = X (N x C_0, row-major, caller's node order; host pointer, or device pointer if
+ * x_on_device != 0) and the label matrix Y as class ids: labels host int32[N], -1 = unlabelled. */
+int  cadmm_set_data(cadmm_ctx* ctx, const float* X, const int32_t* labels, int x_on_device);
+
+/* W0: L host pointers, W0[l-1] is C_{l-1} x C_l.  Sets Z_l to the forward pass of Problem 1's
+ * constraints (Z_l = relu(A~ Z_{l-1} W_l), Z_L = A~ Z_{L-1} W_L), U = 0, tau = tau0,
+ * theta = theta0, iteration counter 0. */
+int  cadmm_init(cadmm_ctx* ctx, const float* const* W0);
+
+/* k iterations of Algorithm 1 (W-update, Z-update, U-update), enqueued on the stream. */
+int  cadmm_run(cadmm_ctx* ctx, int32_t k);
+
+/*
+ * Readout at the current iterate (synchronises).  objective = R(Z_L,Y) + sum_{l<L} nu/2
+ * ||Z_l - relu(A~ Z_{l-1} W_l)||^2 (Problem 2); lagrangian = Eq. 1; primal_res =
+ * ||Z_L - A~ Z_{L-1} W_L||_F; dual_res = rho ||A~ Z_{L-1}^k W_L^k - A~ Z_{L-1}^{k-1} W_L^{k-1}||_F
+ * (0 before the first iteration).  layer_penalty: host double[L-1] or NULL.
+ */
+typedef struct {
+    double objective, lagrangian, risk, primal_res, dual_res;
+    int32_t iter, status;
+} cadmm_stats;
+int  cadmm_eval(cadmm_ctx* ctx, cadmm_stats* out, double* layer_penalty);
+
+/* State readout, host pointers, caller's node order.  l in 1..L for W, 0..L for Z. */
+int  cadmm_get_W(cadmm_ctx* ctx, int32_t l, float* dst);
+int  cadmm_get_Z(cadmm_ctx* ctx, int32_t l, float* dst);
+int  cadmm_get_U(cadmm_ctx* ctx, float* dst);
+/* tau[L], theta[(L-1)*M] (layer-major), n_trials[L + (L-1)*M] and sq_grad[L + (L-1)*M]
+ * (squared gradient norms) of the last iteration.  Any pointer may be NULL. */
+int  cadmm_get_steps(cadmm_ctx* ctx, double* tau, double* theta, int32_t* n_trials, double* sq_grad);
+/* Overwrite state (resume / tests).  Any pointer may be NULL (= keep).  W: L host pointers;
+ * Z: L host pointers for layers 1..L (caller's node order); U: N x C_L. */
+int  cadmm_set_state(cadmm_ctx* ctx, const float* const* W, const float* const* Z, const float* U,
+                     const double* tau, const double* theta);
+
+/*
+ * Kernel-level calls on device buffers in the INTERNAL row order (for tests and profiling).
+ * They run the same kernels the sweep uses.
+ *   aggregate:           Y = A~ X                         X,Y device N x width    (Problem 3's
+ *                        blocked sum A~_{m,m} X_m + sum_{r in N_m} A~_{m,r} X_r for every m)
+ *   aggregate_segments:  P[(i,c)] = sum_{j in V_c} A~_ij V_j   one row per segment, written in
+ *                        the order of cadmm_get_segment_order (Appendix A: A~_{r,m} applied to
+ *                        a change of Z_{l,m}, for every r in N_m or r = m)
+ *   transform:           out = A B        A device n x K, B device K x C, out n x C
+ *   wgrad:               out = A^T G      A device n x K, G device n x C, out K x C
+ */
+int  cadmm_op_aggregate(cadmm_ctx* ctx, const float* X, int32_t width, float* Y);
+int  cadmm_op_aggregate_segments(cadmm_ctx* ctx, const float* V, int32_t width, float* P);
+int  cadmm_op_transform(cadmm_ctx* ctx, const float* A, int64_t n, int32_t K, const float* B,
+                        int32_t C, float* out);
+int  cadmm_op_wgrad(cadmm_ctx* ctx, const float* A, const float* G, int64_t n, int32_t K,
+                    int32_t C, float* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CADMM_H */

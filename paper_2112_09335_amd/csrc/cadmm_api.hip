@@ -1,0 +1,613 @@
+// C ABI of the community-blocked ADMM sweep: context, workspace layout, and the schedule of one
+// iteration of the paper's Algorithm 1 (W-update, Z-update, U-update) as a fixed sequence of kernel
+// launches on one HIP stream.  Nothing is read back from the device inside cadmm_run.
+#include "../../include/cadmm.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "host_graph.h"
+#include "kernels.h"
+
+using namespace cadmm;
+
+struct cadmm_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    std::string err;
+    HostGraph hg;
+    bool has_graph = false, has_model = false, has_ws = false, has_data = false, has_init = false;
+    // model
+    int L = 0;
+    std::vector<int> C;
+    int risk = 0, max_bt = 60, J = 10;
+    float nu = 0, rho = 0, tau0 = 0, theta0 = 0, eta = 2;
+    // workspace
+    char* ws = nullptr;
+    size_t ws_bytes = 0;
+    // graph on the device
+    int64_t* d_row_ptr = nullptr;
+    int32_t* d_col = nullptr;
+    float* d_val = nullptr;
+    int32_t* d_row_comm = nullptr;
+    int32_t* d_perm = nullptr;
+    int64_t* d_segc_lo = nullptr;
+    int64_t* d_segc_hi = nullptr;
+    int32_t* d_segc_row = nullptr;
+    int32_t* d_chunk_unit = nullptr;
+    int32_t* d_chunk_kind = nullptr;
+    int32_t* d_chunk_begin = nullptr;
+    int32_t* d_chunk_end = nullptr;
+    int32_t* d_unit_chunk_ptr = nullptr;
+    int32_t* d_labels = nullptr;
+    // state and per-layer buffers, index l = 0..L (unused slots stay null)
+    std::vector<float*> Z, W, H, T, G;
+    float* U = nullptr;
+    float* TLprev = nullptr;
+    float* tmpA = nullptr;      // N x max width: staging, G W^T
+    float* tmpB = nullptr;      // N x max hidden width: gradient of the Z subproblem
+    float* tmpV = nullptr;      // N x max next width
+    float* P = nullptr;         // n_seg x max next width
+    float* gradW = nullptr;
+    float* Wt = nullptr;
+    float* tn_partial = nullptr;
+    size_t tn_partial_floats = 0;
+    double* partials = nullptr;
+    Unit* unitsW = nullptr;     // [L]
+    Unit* unitsZ = nullptr;     // [(L-1) * M]
+    LayerScalars* scalars = nullptr;   // [L+1]
+    int32_t* status = nullptr;
+    bool base_valid = false, have_prev = false, dual_valid = false;
+    int iter = 0;
+};
+
+namespace {
+
+int fail(cadmm_ctx* c, int code, const std::string& msg) {
+    if (c) c->err = msg;
+    return code;
+}
+
+int hip_fail(cadmm_ctx* c, hipError_t e, const char* what) {
+    return fail(c, CADMM_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define HIP_TRY(ctx, call)                                        \
+    do {                                                          \
+        hipError_t e_ = (call);                                   \
+        if (e_ != hipSuccess) return hip_fail(ctx, e_, #call);    \
+    } while (0)
+
+struct Bump {
+    char* base;
+    size_t off = 0;
+    template <class T>
+    T* take(size_t count) {
+        off = (off + 255) & ~(size_t)255;
+        T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+        off += count * sizeof(T);
+        return p;
+    }
+};
+
+int max_of(const std::vector<int>& v, int lo, int hi) {
+    int m = 0;
+    for (int i = lo; i <= hi; ++i) m = v[i] > m ? v[i] : m;
+    return m;
+}
+
+// Assign every device buffer inside the workspace; with base == nullptr only the size is computed.
+size_t layout(cadmm_ctx* c, char* base) {
+    const HostGraph& g = c->hg;
+    const int L = c->L;
+    const int64_t N = g.N;
+    Bump b{base};
+    c->d_row_ptr = b.take<int64_t>(N + 1);
+    c->d_col = b.take<int32_t>(g.nnz);
+    c->d_val = b.take<float>(g.nnz);
+    c->d_row_comm = b.take<int32_t>(N);
+    c->d_perm = b.take<int32_t>(N);
+    c->d_segc_lo = b.take<int64_t>(g.n_seg);
+    c->d_segc_hi = b.take<int64_t>(g.n_seg);
+    c->d_segc_row = b.take<int32_t>(g.n_seg);
+    const size_t nch = g.chunks.size();
+    c->d_chunk_unit = b.take<int32_t>(nch);
+    c->d_chunk_kind = b.take<int32_t>(nch);
+    c->d_chunk_begin = b.take<int32_t>(nch);
+    c->d_chunk_end = b.take<int32_t>(nch);
+    c->d_unit_chunk_ptr = b.take<int32_t>(g.M + 1);
+    c->d_labels = b.take<int32_t>(N);
+    c->Z.assign(L + 1, nullptr);
+    c->W.assign(L + 1, nullptr);
+    c->H.assign(L + 1, nullptr);
+    c->T.assign(L + 1, nullptr);
+    c->G.assign(L + 1, nullptr);
+    for (int l = 0; l <= L; ++l) c->Z[l] = b.take<float>(N * c->C[l]);
+    for (int l = 1; l <= L; ++l) {
+        c->W[l] = b.take<float>((size_t)c->C[l - 1] * c->C[l]);
+        c->H[l] = b.take<float>(N * c->C[l - 1]);
+        c->T[l] = b.take<float>(N * c->C[l]);
+        c->G[l] = b.take<float>(N * c->C[l]);
+    }
+    c->U = b.take<float>(N * c->C[L]);
+    c->TLprev = b.take<float>(N * c->C[L]);
+    c->tmpA = b.take<float>(N * max_of(c->C, 0, L));
+    c->tmpB = b.take<float>(N * max_of(c->C, 1, L - 1));
+    c->tmpV = b.take<float>(N * max_of(c->C, 2, L));
+    c->P = b.take<float>(g.n_seg * max_of(c->C, 2, L));
+    size_t wmax = 0, tnmax = 0;
+    for (int l = 1; l <= L; ++l) {
+        size_t w = (size_t)c->C[l - 1] * c->C[l];
+        wmax = w > wmax ? w : wmax;
+        size_t t = gemm_tn_scratch_floats(N, c->C[l - 1], c->C[l]);
+        tnmax = t > tnmax ? t : tnmax;
+    }
+    c->gradW = b.take<float>(wmax);
+    c->Wt = b.take<float>(wmax);
+    c->tn_partial = b.take<float>(tnmax);
+    c->tn_partial_floats = tnmax;
+    size_t np = (size_t)kReduceBlocks * kMaxCand;
+    size_t np2 = nch * (kMaxCand + 2);
+    c->partials = b.take<double>(np > np2 ? np : np2);
+    c->unitsW = b.take<Unit>(L);
+    c->unitsZ = b.take<Unit>((size_t)(L - 1) * g.M);
+    c->scalars = b.take<LayerScalars>(L + 1);
+    c->status = b.take<int32_t>(4);
+    return (b.off + 255) & ~(size_t)255;
+}
+
+template <class T>
+hipError_t upload(hipStream_t s, T* dst, const std::vector<T>& src) {
+    if (src.empty()) return hipSuccess;
+    return hipMemcpyAsync(dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice, s);
+}
+
+SearchParams search_params(const cadmm_ctx* c) {
+    SearchParams sp;
+    sp.nu = c->nu;
+    sp.rho = c->rho;
+    sp.eta = c->eta;
+    sp.max_backtrack = c->max_bt;
+    return sp;
+}
+
+void aggregate(cadmm_ctx* c, const float* X, float* Y, int width, const SpmmEpilogue& epi) {
+    launch_spmm(c->stream, c->d_row_ptr, c->d_row_ptr + 1, c->d_col, c->d_val, X, Y, c->hg.N, width, epi);
+}
+
+// H_l, T_l = H_l W_l, phi_l and G_l for every layer at the current iterate.  This is both the start
+// of a sweep and the readout of the previous one, so it is computed once per iterate.
+void base_eval(cadmm_ctx* c) {
+    if (c->base_valid) return;
+    const int L = c->L;
+    const int64_t N = c->hg.N;
+    for (int l = 1; l <= L; ++l) {
+        if (l >= 2) aggregate(c, c->Z[l - 1], c->H[l], c->C[l - 1], SpmmEpilogue());
+        launch_gemm_nn(c->stream, c->H[l], c->W[l], c->T[l], N, c->C[l - 1], c->C[l]);
+        launch_phi_G(c->stream, c->T[l], c->Z[l], c->U, c->G[l], l == L ? c->TLprev : nullptr, c->have_prev ? 1 : 0,
+                     N * c->C[l], l == L, c->nu, c->rho, c->partials, c->scalars + l);
+    }
+    c->dual_valid = c->have_prev;
+    c->have_prev = true;
+    c->base_valid = true;
+}
+
+void sweep(cadmm_ctx* c) {
+    const int L = c->L;
+    const int64_t N = c->hg.N;
+    const int M = c->hg.M;
+    hipStream_t s = c->stream;
+    const SearchParams sp = search_params(c);
+    const int more_passes = (c->max_bt + kMaxCand - 1) / kMaxCand;
+    base_eval(c);
+
+    // ---- W-update, every layer from (W^k, Z^k, U^k)   (Section 3.1)
+    for (int l = 1; l <= L; ++l) {
+        const int K = c->C[l - 1], Cl = c->C[l];
+        const int64_t count = N * Cl;
+        const int last = (l == L);
+        Unit* unit = c->unitsW + (l - 1);
+        launch_gemm_tn(s, c->H[l], c->G[l], c->gradW, N, K, Cl, c->tn_partial);      // grad phi = H^T G
+        launch_w_norms(s, c->gradW, c->W[l], K * Cl, unit);
+        float* Q = c->G[l];                                                          // G_l is no longer needed
+        launch_gemm_nn(s, c->H[l], c->gradW, Q, N, K, Cl);                           // T(W - g/tau) = T - Q/tau
+        launch_w_trial(s, c->T[l], Q, c->Z[l], c->U, count, last, 1, sp, unit, c->partials, c->status);
+        for (int p = 0; p < more_passes; ++p)
+            launch_w_trial(s, c->T[l], Q, c->Z[l], c->U, count, last, kMaxCand, sp, unit, c->partials, c->status);
+        launch_w_step(s, c->W[l], c->gradW, K * Cl, c->T[l], Q, count, unit);        // W^{k+1}; T_l = A~ Z^k W^{k+1}
+    }
+
+    // ---- Z-update, hidden layers, every community from (W^{k+1}, Z^k, U^k)   (Appendix A, Eqs. 3, 4, 6-8)
+    // Ascending l keeps the update Jacobi although Z_l is overwritten in place: layer l reads Z_{l+1}^k
+    // (not yet touched) and T_l, T_{l+1}, which were formed from Z^k before any Z changed.
+    for (int l = 1; l <= L - 1; ++l) {
+        const int Cl = c->C[l], Cn = c->C[l + 1];
+        const int next_last = (l + 1 == L);
+        Unit* units = c->unitsZ + (size_t)(l - 1) * M;
+        launch_G_only(s, c->T[l + 1], c->Z[l + 1], c->U, c->G[l + 1], N * Cn, next_last, c->nu, c->rho);
+        launch_transpose(s, c->W[l + 1], c->Wt, Cl, Cn);
+        launch_gemm_nn(s, c->G[l + 1], c->Wt, c->tmpA, N, Cn, Cl);                   // G_{l+1} W_{l+1}^T
+        SpmmEpilogue epi;
+        epi.kind = 1; epi.Zl = c->Z[l]; epi.Tl = c->T[l]; epi.nu = c->nu;
+        aggregate(c, c->tmpA, c->tmpB, Cl, epi);                                     // grad psi, all communities
+        launch_gemm_nn(s, c->tmpB, c->W[l + 1], c->tmpV, N, Cl, Cn);                 // grad W_{l+1}
+        launch_spmm(s, c->d_segc_lo, c->d_segc_hi, c->d_col, c->d_val, c->tmpV, c->P, c->hg.n_seg, Cn,
+                    SpmmEpilogue());                                                 // A~_{r,m} (grad W) per segment
+        launch_reset_units(s, units, M);
+        ZTrialArgs a;
+        a.chunk_unit = c->d_chunk_unit; a.chunk_kind = c->d_chunk_kind;
+        a.chunk_begin = c->d_chunk_begin; a.chunk_end = c->d_chunk_end;
+        a.n_chunks = (int32_t)c->hg.chunks.size();
+        a.unit_chunk_ptr = c->d_unit_chunk_ptr; a.M = M;
+        a.segc_row = c->d_segc_row;
+        a.Zl = c->Z[l]; a.gradZ = c->tmpB; a.Tl = c->T[l]; a.Cl = Cl;
+        a.Tn = c->T[l + 1]; a.Zn = c->Z[l + 1]; a.U = c->U; a.P = c->P; a.Cn = Cn;
+        a.next_is_last = next_last;
+        a.sp = sp; a.units = units; a.partials = c->partials; a.status = c->status;
+        a.first_pass = 1; a.ncand = 1;
+        launch_z_trial(s, a);
+        a.first_pass = 0; a.ncand = kMaxCand;
+        for (int p = 0; p < more_passes; ++p) launch_z_trial(s, a);
+        launch_z_step(s, c->Z[l], c->tmpB, c->d_row_comm, N, Cl, units);
+    }
+
+    // ---- last layer Z_L (Eq. 5) and the dual step (Eq. 2), both from Z_L^k, U^k and T_L = A~ Z_{L-1}^k W_L^{k+1}
+    launch_last_layer(s, c->Z[L], c->U, c->T[L], c->d_labels, N, c->C[L], c->risk, c->rho, c->J);
+    c->iter++;
+    c->base_valid = false;
+}
+
+int check_launch(cadmm_ctx* c, const char* where) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(c, e, where);
+    return CADMM_OK;
+}
+
+// copy an N x C matrix out in the caller's node order
+int download_rows(cadmm_ctx* c, const float* src_internal, int C, float* dst_host) {
+    const int64_t N = c->hg.N;
+    launch_permute_rows(c->stream, src_internal, c->tmpA, c->d_perm, N, C, 1);   // tmpA[perm[r]] = src[r]
+    HIP_TRY(c, hipMemcpyAsync(dst_host, c->tmpA, (size_t)N * C * sizeof(float), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return check_launch(c, "download_rows");
+}
+
+int upload_rows(cadmm_ctx* c, const float* src, int on_device, int C, float* dst_internal) {
+    const int64_t N = c->hg.N;
+    HIP_TRY(c, hipMemcpyAsync(c->tmpA, src, (size_t)N * C * sizeof(float),
+                              on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, c->stream));
+    launch_permute_rows(c->stream, c->tmpA, dst_internal, c->d_perm, N, C, 0);   // dst[r] = tmpA[perm[r]]
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return check_launch(c, "upload_rows");
+}
+
+}  // namespace
+
+extern "C" {
+
+int cadmm_create(cadmm_ctx** out, int device, void* hip_stream) {
+    if (!out) return CADMM_EINVAL;
+    *out = nullptr;
+    if (device >= 0) {
+        int ndev = 0;
+        if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) return CADMM_EHIP;
+        if (hipSetDevice(device) != hipSuccess) return CADMM_EHIP;
+    }
+    cadmm_ctx* c = new (std::nothrow) cadmm_ctx();
+    if (!c) return CADMM_ENOMEM;
+    c->device = device;
+    c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+    *out = c;
+    return CADMM_OK;
+}
+
+void cadmm_destroy(cadmm_ctx* ctx) {
+    if (!ctx) return;
+    if (ctx->device >= 0) (void)hipStreamSynchronize(ctx->stream);
+    delete ctx;
+}
+
+const char* cadmm_last_error(cadmm_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int cadmm_build_graph(cadmm_ctx* c, int64_t N, int64_t n_edges, const int32_t* src, const int32_t* dst, int32_t M,
+                      const int32_t* comm) {
+    if (!c) return CADMM_EINVAL;
+    if (c->has_ws) return fail(c, CADMM_EORDER, "graph cannot change after the workspace is set");
+    std::string e = build_host_graph(c->hg, N, n_edges, src, dst, M, comm, kChunkRows);
+    if (!e.empty()) { c->has_graph = false; return fail(c, CADMM_EINVAL, e); }
+    c->has_graph = true;
+    return CADMM_OK;
+}
+
+int cadmm_graph_sizes(cadmm_ctx* c, int64_t* nnz, int64_t* n_segments, int64_t* n_halo_rows) {
+    if (!c) return CADMM_EINVAL;
+    if (!c->has_graph) return fail(c, CADMM_EORDER, "build_graph first");
+    if (nnz) *nnz = c->hg.nnz;
+    if (n_segments) *n_segments = c->hg.n_seg;
+    if (n_halo_rows) *n_halo_rows = c->hg.n_halo_rows;
+    return CADMM_OK;
+}
+
+int cadmm_get_graph(cadmm_ctx* c, int32_t* perm, int64_t* row_ptr, int32_t* col, float* val, int64_t* seg_ptr,
+                    int32_t* seg_row, int32_t* seg_comm, int64_t* comm_row_ptr, uint8_t* neighbour) {
+    if (!c) return CADMM_EINVAL;
+    if (!c->has_graph) return fail(c, CADMM_EORDER, "build_graph first");
+    const HostGraph& g = c->hg;
+    auto cp = [](auto* dst, const auto& v) { if (dst && !v.empty()) std::memcpy(dst, v.data(), v.size() * sizeof(v[0])); };
+    cp(perm, g.perm); cp(row_ptr, g.row_ptr); cp(col, g.col); cp(val, g.val);
+    cp(seg_ptr, g.seg_ptr); cp(seg_row, g.seg_row); cp(seg_comm, g.seg_comm);
+    cp(comm_row_ptr, g.comm_row_ptr); cp(neighbour, g.neighbour);
+    return CADMM_OK;
+}
+
+int cadmm_get_segment_order(cadmm_ctx* c, int64_t* order) {
+    if (!c || !order) return CADMM_EINVAL;
+    if (!c->has_graph) return fail(c, CADMM_EORDER, "build_graph first");
+    if (!c->hg.segc_order.empty()) std::memcpy(order, c->hg.segc_order.data(), c->hg.segc_order.size() * sizeof(int64_t));
+    return CADMM_OK;
+}
+
+int cadmm_set_model(cadmm_ctx* c, const cadmm_model* m) {
+    if (!c || !m || !m->C) return CADMM_EINVAL;
+    if (c->has_ws) return fail(c, CADMM_EORDER, "model cannot change after the workspace is set");
+    if (m->L < 2 || m->L > 64) return fail(c, CADMM_EINVAL, "L must be in [2, 64]");
+    for (int l = 0; l <= m->L; ++l)
+        if (m->C[l] < 1 || m->C[l] > 4096) return fail(c, CADMM_EINVAL, "layer width must be in [1, 4096]");
+    if (m->C[m->L] > 64) return fail(c, CADMM_EUNSUPPORTED, "at most 64 classes");
+    if (m->risk != 0 && m->risk != 1) return fail(c, CADMM_EINVAL, "risk must be 0 or 1");
+    if (!(m->nu > 0) || !(m->rho > 0) || !(m->tau0 > 0) || !(m->theta0 > 0) || !(m->eta > 1))
+        return fail(c, CADMM_EINVAL, "nu, rho, tau0, theta0 must be positive and eta > 1");
+    if (m->max_backtrack < 0 || m->max_backtrack > 64) return fail(c, CADMM_EINVAL, "max_backtrack must be in [0, 64]");
+    if (m->fista_iters < 0) return fail(c, CADMM_EINVAL, "fista_iters must be non-negative");
+    if (m->dual_form != 0) return fail(c, CADMM_EUNSUPPORTED, "only dual_form 0 is built");
+    c->L = m->L;
+    c->C.assign(m->C, m->C + m->L + 1);
+    c->risk = m->risk;
+    c->nu = m->nu; c->rho = m->rho; c->tau0 = m->tau0; c->theta0 = m->theta0; c->eta = m->eta;
+    c->max_bt = m->max_backtrack;
+    c->J = m->fista_iters;
+    c->has_model = true;
+    return CADMM_OK;
+}
+
+int cadmm_workspace_bytes(cadmm_ctx* c, size_t* bytes) {
+    if (!c || !bytes) return CADMM_EINVAL;
+    if (!c->has_graph || !c->has_model) return fail(c, CADMM_EORDER, "build_graph and set_model first");
+    if (c->has_ws) { *bytes = c->ws_bytes; return CADMM_OK; }
+    *bytes = layout(c, nullptr);
+    return CADMM_OK;
+}
+
+int cadmm_set_workspace(cadmm_ctx* c, void* dev_ptr, size_t bytes) {
+    if (!c || !dev_ptr) return CADMM_EINVAL;
+    if (!c->has_graph || !c->has_model) return fail(c, CADMM_EORDER, "build_graph and set_model first");
+    if (c->has_ws) return fail(c, CADMM_EORDER, "workspace already set");
+    if (c->device < 0) return fail(c, CADMM_EUNSUPPORTED, "host-only context (device -1) has no device path");
+    if ((reinterpret_cast<uintptr_t>(dev_ptr) & 255) != 0) return fail(c, CADMM_EINVAL, "workspace must be 256-byte aligned");
+    const size_t need = layout(c, nullptr);
+    if (bytes < need) return fail(c, CADMM_ENOMEM, "workspace too small");
+    HIP_TRY(c, hipSetDevice(c->device));
+    layout(c, static_cast<char*>(dev_ptr));
+    c->ws = static_cast<char*>(dev_ptr);
+    c->ws_bytes = need;
+    const HostGraph& g = c->hg;
+    hipStream_t s = c->stream;
+    HIP_TRY(c, upload(s, c->d_row_ptr, g.row_ptr));
+    HIP_TRY(c, upload(s, c->d_col, g.col));
+    HIP_TRY(c, upload(s, c->d_val, g.val));
+    HIP_TRY(c, upload(s, c->d_row_comm, g.row_comm));
+    HIP_TRY(c, upload(s, c->d_perm, g.perm));
+    HIP_TRY(c, upload(s, c->d_segc_lo, g.segc_lo));
+    HIP_TRY(c, upload(s, c->d_segc_hi, g.segc_hi));
+    HIP_TRY(c, upload(s, c->d_segc_row, g.segc_row));
+    std::vector<int32_t> cu, ck, cb, ce;
+    for (const Chunk& ch : g.chunks) { cu.push_back(ch.unit); ck.push_back(ch.kind); cb.push_back(ch.begin); ce.push_back(ch.end); }
+    HIP_TRY(c, upload(s, c->d_chunk_unit, cu));
+    HIP_TRY(c, upload(s, c->d_chunk_kind, ck));
+    HIP_TRY(c, upload(s, c->d_chunk_begin, cb));
+    HIP_TRY(c, upload(s, c->d_chunk_end, ce));
+    HIP_TRY(c, upload(s, c->d_unit_chunk_ptr, g.unit_chunk_ptr));
+    HIP_TRY(c, hipMemsetAsync(c->status, 0, 4 * sizeof(int32_t), s));
+    HIP_TRY(c, hipStreamSynchronize(s));     // the host vectors above must outlive the copies
+    c->has_ws = true;
+    return CADMM_OK;
+}
+
+int cadmm_set_data(cadmm_ctx* c, const float* X, const int32_t* labels, int x_on_device) {
+    if (!c || !X || !labels) return CADMM_EINVAL;
+    if (!c->has_ws) return fail(c, CADMM_EORDER, "set_workspace first");
+    const int64_t N = c->hg.N;
+    std::vector<int32_t> lab(N);
+    for (int64_t r = 0; r < N; ++r) {
+        int32_t y = labels[c->hg.perm[r]];
+        if (y < -1 || y >= c->C[c->L]) return fail(c, CADMM_EINVAL, "label out of range");
+        lab[r] = y;
+    }
+    HIP_TRY(c, hipMemcpyAsync(c->d_labels, lab.data(), N * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+    int rc = upload_rows(c, X, x_on_device, c->C[0], c->Z[0]);     // synchronises
+    if (rc != CADMM_OK) return rc;
+    c->has_data = true;
+    c->has_init = false;
+    return CADMM_OK;
+}
+
+int cadmm_init(cadmm_ctx* c, const float* const* W0) {
+    if (!c || !W0) return CADMM_EINVAL;
+    if (!c->has_data) return fail(c, CADMM_EORDER, "set_data first");
+    const int L = c->L;
+    const int64_t N = c->hg.N;
+    hipStream_t s = c->stream;
+    for (int l = 1; l <= L; ++l) {
+        if (!W0[l - 1]) return fail(c, CADMM_EINVAL, "null weight pointer");
+        HIP_TRY(c, hipMemcpyAsync(c->W[l], W0[l - 1], (size_t)c->C[l - 1] * c->C[l] * sizeof(float),
+                                  hipMemcpyHostToDevice, s));
+    }
+    aggregate(c, c->Z[0], c->H[1], c->C[0], SpmmEpilogue());      // A~ Z_0 never changes
+    for (int l = 1; l <= L; ++l) {
+        if (l >= 2) aggregate(c, c->Z[l - 1], c->H[l], c->C[l - 1], SpmmEpilogue());
+        launch_gemm_nn(s, c->H[l], c->W[l], c->T[l], N, c->C[l - 1], c->C[l]);
+        launch_relu(s, c->T[l], c->Z[l], N * c->C[l], l < L);
+    }
+    HIP_TRY(c, hipMemsetAsync(c->U, 0, (size_t)N * c->C[L] * sizeof(float), s));
+    HIP_TRY(c, hipMemsetAsync(c->status, 0, 4 * sizeof(int32_t), s));
+    launch_fill_units(s, c->unitsW, L, (double)c->tau0);
+    launch_fill_units(s, c->unitsZ, (L - 1) * c->hg.M, (double)c->theta0);
+    HIP_TRY(c, hipStreamSynchronize(s));                           // W0 host buffers may be freed by the caller
+    c->iter = 0;
+    c->base_valid = false;
+    c->have_prev = false;
+    c->dual_valid = false;
+    c->has_init = true;
+    return check_launch(c, "init");
+}
+
+int cadmm_run(cadmm_ctx* c, int32_t k) {
+    if (!c || k < 0) return CADMM_EINVAL;
+    if (!c->has_init) return fail(c, CADMM_EORDER, "init first");
+    for (int i = 0; i < k; ++i) sweep(c);
+    return check_launch(c, "run");
+}
+
+int cadmm_eval(cadmm_ctx* c, cadmm_stats* out, double* layer_penalty) {
+    if (!c || !out) return CADMM_EINVAL;
+    if (!c->has_init) return fail(c, CADMM_EORDER, "init first");
+    const int L = c->L;
+    base_eval(c);
+    launch_risk(c->stream, c->Z[L], c->d_labels, c->hg.N, c->C[L], c->risk, c->partials, c->scalars + L);
+    std::vector<LayerScalars> sc(L + 1);
+    int32_t st[4] = {0, 0, 0, 0};
+    HIP_TRY(c, hipMemcpyAsync(sc.data(), c->scalars, (L + 1) * sizeof(LayerScalars), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(st, c->status, sizeof(st), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    double pen = 0.0;
+    for (int l = 1; l < L; ++l) {
+        pen += sc[l].phi;
+        if (layer_penalty) layer_penalty[l - 1] = sc[l].phi;
+    }
+    out->risk = sc[L].risk;
+    out->objective = sc[L].risk + pen;
+    out->lagrangian = out->objective + sc[L].phi;
+    out->primal_res = std::sqrt(sc[L].res2);
+    out->dual_res = c->dual_valid ? (double)c->rho * std::sqrt(sc[L].dT2) : 0.0;
+    out->iter = c->iter;
+    out->status = st[0];
+    if (!std::isfinite(out->lagrangian)) out->status |= CADMM_STATUS_NONFINITE;
+    return check_launch(c, "eval");
+}
+
+int cadmm_get_W(cadmm_ctx* c, int32_t l, float* dst) {
+    if (!c || !dst) return CADMM_EINVAL;
+    if (!c->has_init) return fail(c, CADMM_EORDER, "init first");
+    if (l < 1 || l > c->L) return fail(c, CADMM_EINVAL, "layer out of range");
+    HIP_TRY(c, hipMemcpyAsync(dst, c->W[l], (size_t)c->C[l - 1] * c->C[l] * sizeof(float), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return CADMM_OK;
+}
+
+int cadmm_get_Z(cadmm_ctx* c, int32_t l, float* dst) {
+    if (!c || !dst) return CADMM_EINVAL;
+    if (!c->has_data) return fail(c, CADMM_EORDER, "set_data first");
+    if (l < 0 || l > c->L) return fail(c, CADMM_EINVAL, "layer out of range");
+    if (l > 0 && !c->has_init) return fail(c, CADMM_EORDER, "init first");
+    return download_rows(c, c->Z[l], c->C[l], dst);
+}
+
+int cadmm_get_U(cadmm_ctx* c, float* dst) {
+    if (!c || !dst) return CADMM_EINVAL;
+    if (!c->has_init) return fail(c, CADMM_EORDER, "init first");
+    return download_rows(c, c->U, c->C[c->L], dst);
+}
+
+int cadmm_get_steps(cadmm_ctx* c, double* tau, double* theta, int32_t* n_trials, double* sq_grad) {
+    if (!c) return CADMM_EINVAL;
+    if (!c->has_init) return fail(c, CADMM_EORDER, "init first");
+    const int L = c->L, M = c->hg.M;
+    const int nz = (L - 1) * M;
+    std::vector<Unit> uw(L), uz(nz);
+    HIP_TRY(c, hipMemcpyAsync(uw.data(), c->unitsW, L * sizeof(Unit), hipMemcpyDeviceToHost, c->stream));
+    if (nz) HIP_TRY(c, hipMemcpyAsync(uz.data(), c->unitsZ, nz * sizeof(Unit), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    for (int l = 0; l < L; ++l) {
+        if (tau) tau[l] = uw[l].step;
+        if (n_trials) n_trials[l] = uw[l].ntrials;
+        if (sq_grad) sq_grad[l] = uw[l].g;
+    }
+    for (int i = 0; i < nz; ++i) {
+        if (theta) theta[i] = uz[i].step;
+        if (n_trials) n_trials[L + i] = uz[i].ntrials;
+        if (sq_grad) sq_grad[L + i] = uz[i].g;
+    }
+    return CADMM_OK;
+}
+
+int cadmm_set_state(cadmm_ctx* c, const float* const* W, const float* const* Z, const float* U, const double* tau,
+                    const double* theta) {
+    if (!c) return CADMM_EINVAL;
+    if (!c->has_init) return fail(c, CADMM_EORDER, "init first");
+    const int L = c->L, M = c->hg.M;
+    hipStream_t s = c->stream;
+    if (W)
+        for (int l = 1; l <= L; ++l)
+            if (W[l - 1])
+                HIP_TRY(c, hipMemcpyAsync(c->W[l], W[l - 1], (size_t)c->C[l - 1] * c->C[l] * sizeof(float), hipMemcpyHostToDevice, s));
+    if (Z)
+        for (int l = 1; l <= L; ++l)
+            if (Z[l - 1]) {
+                int rc = upload_rows(c, Z[l - 1], 0, c->C[l], c->Z[l]);
+                if (rc != CADMM_OK) return rc;
+            }
+    if (U) {
+        int rc = upload_rows(c, U, 0, c->C[L], c->U);
+        if (rc != CADMM_OK) return rc;
+    }
+    if (tau || theta) {
+        const int nz = (L - 1) * M;
+        std::vector<Unit> uw(L), uz(nz);
+        HIP_TRY(c, hipMemcpyAsync(uw.data(), c->unitsW, L * sizeof(Unit), hipMemcpyDeviceToHost, s));
+        if (nz) HIP_TRY(c, hipMemcpyAsync(uz.data(), c->unitsZ, nz * sizeof(Unit), hipMemcpyDeviceToHost, s));
+        HIP_TRY(c, hipStreamSynchronize(s));
+        if (tau) for (int l = 0; l < L; ++l) { if (!(tau[l] > 0)) return fail(c, CADMM_EINVAL, "tau must be positive"); uw[l].step = tau[l]; }
+        if (theta) for (int i = 0; i < nz; ++i) { if (!(theta[i] > 0)) return fail(c, CADMM_EINVAL, "theta must be positive"); uz[i].step = theta[i]; }
+        HIP_TRY(c, hipMemcpyAsync(c->unitsW, uw.data(), L * sizeof(Unit), hipMemcpyHostToDevice, s));
+        if (nz) HIP_TRY(c, hipMemcpyAsync(c->unitsZ, uz.data(), nz * sizeof(Unit), hipMemcpyHostToDevice, s));
+    }
+    HIP_TRY(c, hipStreamSynchronize(s));
+    c->base_valid = false;
+    c->have_prev = false;
+    c->dual_valid = false;
+    return CADMM_OK;
+}
+
+int cadmm_op_aggregate(cadmm_ctx* c, const float* X, int32_t width, float* Y) {
+    if (!c || !X || !Y || width < 1) return CADMM_EINVAL;
+    if (!c->has_ws) return fail(c, CADMM_EORDER, "set_workspace first");
+    aggregate(c, X, Y, width, SpmmEpilogue());
+    return check_launch(c, "op_aggregate");
+}
+
+int cadmm_op_aggregate_segments(cadmm_ctx* c, const float* V, int32_t width, float* P) {
+    if (!c || !V || !P || width < 1) return CADMM_EINVAL;
+    if (!c->has_ws) return fail(c, CADMM_EORDER, "set_workspace first");
+    launch_spmm(c->stream, c->d_segc_lo, c->d_segc_hi, c->d_col, c->d_val, V, P, c->hg.n_seg, width, SpmmEpilogue());
+    return check_launch(c, "op_aggregate_segments");
+}
+
+int cadmm_op_transform(cadmm_ctx* c, const float* A, int64_t n, int32_t K, const float* B, int32_t C, float* out) {
+    if (!c || !A || !B || !out || n < 1 || K < 1 || C < 1) return CADMM_EINVAL;
+    launch_gemm_nn(c->stream, A, B, out, n, K, C);
+    return check_launch(c, "op_transform");
+}
+
+int cadmm_op_wgrad(cadmm_ctx* c, const float* A, const float* G, int64_t n, int32_t K, int32_t C, float* out) {
+    if (!c || !A || !G || !out || n < 1 || K < 1 || C < 1) return CADMM_EINVAL;
+    if (!c->has_ws) return fail(c, CADMM_EORDER, "set_workspace first");
+    if (gemm_tn_scratch_floats(n, K, C) > c->tn_partial_floats) return fail(c, CADMM_ENOMEM, "shape needs more scratch than the model reserved");
+    launch_gemm_tn(c->stream, A, G, out, n, K, C, c->tn_partial);
+    return check_launch(c, "op_wgrad");
+}
+
+}  // extern "C"

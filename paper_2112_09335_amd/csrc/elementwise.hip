@@ -1,0 +1,590 @@
+// Fused elementwise kernels and reductions of the ADMM sweep (gfx950): subproblem values phi / psi and
+// their pre-activation gradients, the step-size searches for tau_l (Section 3.1) and theta_{l,m}
+// (Appendix A) run entirely on the device, the last-layer solver fused with the dual step (Eq. 5, Eq. 2).
+//
+// All of these are bound by HBM traffic.  State is fp32; every sum and every quantity that decides a
+// step-size test is formed in fp64 from the fp32 inputs (the fp64 vector rate of the chip is far above
+// what these memory-bound passes need).  Reductions are two-stage and order-fixed: each block writes its
+// partial sums, a finishing kernel adds them in index order, so results are reproducible run to run.
+//
+// A step-size search is a sequence of passes enqueued by the host without reading anything back: a pass
+// evaluates up to kMaxCand candidates step*eta^j in one sweep over memory, the finishing kernel picks the
+// first that passes the test  value(step) - value(0) <= -||grad||^2 / (2 step)  and marks the search
+// done; later passes see the flag and return at once.
+#include "kernels.h"
+
+namespace cadmm {
+
+namespace {
+
+constexpr double kStepFloor = 1e-12;   // a step that moves the block by less than this fraction is not taken
+
+__device__ __forceinline__ double block_sum(double v, double* sm) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double t = 0.0;
+    const int nw = blockDim.x >> 6;
+    for (int w = 0; w < nw; ++w) t += sm[w];
+    return t;
+}
+
+__device__ __forceinline__ void decide(Unit* u, const double* D, int ncand, SearchParams sp, int32_t* status) {
+    double step = u->step;
+    const double g = u->g;
+    int nt = u->ntrials;
+    for (int j = 0; j < ncand; ++j) {
+        ++nt;
+        const double d = D[j];
+        if (!(d == d) || fabs(d) > 1.7e308) atomicOr(status, 2);
+        if (d <= -g / (2.0 * step)) { u->step = step; u->ntrials = nt; u->done = 1; return; }
+        if (nt > sp.max_backtrack) {
+            u->step = step; u->ntrials = nt; u->done = 1;
+            atomicOr(status, 1);
+            return;
+        }
+        step *= (double)sp.eta;
+    }
+    u->step = step;
+    u->ntrials = nt;
+}
+
+__device__ __forceinline__ void floor_or_start(Unit* u, double g, double bnorm) {
+    u->g = g;
+    u->bnorm = bnorm;
+    u->ntrials = 0;
+    const double lim = kStepFloor * u->step;
+    if (g <= lim * lim * bnorm) { u->done = 1; u->skip = 1; }
+    else { u->done = 0; u->skip = 0; }
+}
+
+// ------------------------------------------------------------------------------------------ phi and G
+// hidden layer:  e = relu(t) - z,  phi += e^2 (scaled nu/2 at the end),  G = nu e 1[t>0]
+// last layer:    r = z - t,        phi += u r + rho/2 r^2,               G = -(u + rho r)
+template <int LAST>
+__global__ __launch_bounds__(256) void phi_G_kernel(const float* __restrict__ T, const float* __restrict__ Z,
+                                                    const float* __restrict__ U, float* __restrict__ G,
+                                                    float* __restrict__ Tprev, int have_prev, int64_t count,
+                                                    float nu, float rho, double* __restrict__ partials) {
+    __shared__ double sm[4];
+    double s_phi = 0.0, s_res = 0.0, s_dt = 0.0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+        const float t = T[i], z = Z[i];
+        if (LAST) {
+            const float u = U[i];
+            const double r = (double)z - (double)t;
+            s_phi += (double)u * r + 0.5 * (double)rho * r * r;
+            s_res += r * r;
+            if (G) G[i] = -(u + rho * (z - t));
+            if (Tprev) {
+                if (have_prev) { const double d = (double)t - (double)Tprev[i]; s_dt += d * d; }
+                Tprev[i] = t;
+            }
+        } else {
+            const double e = (double)fmaxf(t, 0.f) - (double)z;
+            s_phi += e * e;
+            if (G) G[i] = (t > 0.f) ? nu * (float)e : 0.f;
+        }
+    }
+    s_phi = block_sum(s_phi, sm);
+    if (LAST) { s_res = block_sum(s_res, sm); s_dt = block_sum(s_dt, sm); }
+    if (threadIdx.x == 0) {
+        partials[blockIdx.x * 3 + 0] = s_phi;
+        partials[blockIdx.x * 3 + 1] = s_res;
+        partials[blockIdx.x * 3 + 2] = s_dt;
+    }
+}
+
+__global__ __launch_bounds__(256) void phi_G_finish_kernel(const double* __restrict__ partials, int nblocks, int last,
+                                                           float nu, LayerScalars* out) {
+    __shared__ double sm[4];
+    double a = 0.0, b = 0.0, c = 0.0;
+    for (int i = threadIdx.x; i < nblocks; i += blockDim.x) {
+        a += partials[i * 3 + 0];
+        b += partials[i * 3 + 1];
+        c += partials[i * 3 + 2];
+    }
+    a = block_sum(a, sm);
+    b = block_sum(b, sm);
+    c = block_sum(c, sm);
+    if (threadIdx.x == 0) {
+        out->phi = last ? a : 0.5 * (double)nu * a;
+        out->res2 = b;
+        out->dT2 = c;
+    }
+}
+
+template <int LAST>
+__global__ __launch_bounds__(256) void G_only_kernel(const float* __restrict__ T, const float* __restrict__ Z,
+                                                     const float* __restrict__ U, float* __restrict__ G,
+                                                     int64_t count, float nu, float rho) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+        const float t = T[i], z = Z[i];
+        if (LAST) G[i] = -(U[i] + rho * (z - t));
+        else G[i] = (t > 0.f) ? nu * (float)((double)t - (double)z) : 0.f;
+    }
+}
+
+// ------------------------------------------------------------------------------------------ risk
+__global__ __launch_bounds__(256) void risk_kernel(const float* __restrict__ ZL, const int32_t* __restrict__ labels,
+                                                   int64_t N, int CL, int risk, double* __restrict__ partials) {
+    __shared__ double sm[4];
+    double s = 0.0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N; i += stride) {
+        const int y = labels[i];
+        if (y < 0) continue;
+        const float* z = ZL + i * CL;
+        if (risk == 0) {
+            double mx = (double)z[0];
+            for (int c = 1; c < CL; ++c) mx = fmax(mx, (double)z[c]);
+            double se = 0.0;
+            for (int c = 0; c < CL; ++c) se += exp((double)z[c] - mx);
+            s += mx + log(se) - (double)z[y];
+        } else {
+            for (int c = 0; c < CL; ++c) {
+                const double d = (double)z[c] - (c == y ? 1.0 : 0.0);
+                s += 0.5 * d * d;
+            }
+        }
+    }
+    s = block_sum(s, sm);
+    if (threadIdx.x == 0) partials[blockIdx.x] = s;
+}
+
+__global__ __launch_bounds__(256) void risk_finish_kernel(const double* __restrict__ partials, int nblocks,
+                                                          LayerScalars* out) {
+    __shared__ double sm[4];
+    double a = 0.0;
+    for (int i = threadIdx.x; i < nblocks; i += blockDim.x) a += partials[i];
+    a = block_sum(a, sm);
+    if (threadIdx.x == 0) out->risk = a;
+}
+
+// ------------------------------------------------------------------------------------------ W search
+__global__ __launch_bounds__(256) void w_norms_kernel(const float* __restrict__ gradW, const float* __restrict__ W,
+                                                      int count, Unit* unit) {
+    __shared__ double sm[4];
+    double g = 0.0, b = 0.0;
+    for (int i = threadIdx.x; i < count; i += blockDim.x) {
+        const double x = (double)gradW[i], w = (double)W[i];
+        g += x * x;
+        b += w * w;
+    }
+    g = block_sum(g, sm);
+    b = block_sum(b, sm);
+    if (threadIdx.x == 0) floor_or_start(unit, g, b);
+}
+
+template <int LAST, int NC>
+__global__ __launch_bounds__(256) void w_trial_kernel(const float* __restrict__ T0, const float* __restrict__ Q,
+                                                      const float* __restrict__ Z, const float* __restrict__ U,
+                                                      int64_t count, SearchParams sp, const Unit* unit,
+                                                      double* __restrict__ partials) {
+    __shared__ double sm[4];
+    if (unit->done) return;
+    double inv[NC];
+    {
+        double step = unit->step;
+#pragma unroll
+        for (int j = 0; j < NC; ++j) { inv[j] = 1.0 / step; step *= (double)sp.eta; }
+    }
+    double D[NC];
+#pragma unroll
+    for (int j = 0; j < NC; ++j) D[j] = 0.0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+        const double t0 = (double)T0[i], q = (double)Q[i], z = (double)Z[i];
+        if (LAST) {
+            const double u = (double)U[i];
+            const double r0 = z - t0;
+#pragma unroll
+            for (int j = 0; j < NC; ++j) {
+                const double dq = q * inv[j];          // r_new - r_old
+                D[j] += dq * (u + 0.5 * (double)sp.rho * (2.0 * r0 + dq));
+            }
+        } else {
+            const double e0 = fmax(t0, 0.0) - z;
+#pragma unroll
+            for (int j = 0; j < NC; ++j) {
+                const double e1 = fmax(t0 - q * inv[j], 0.0) - z;
+                D[j] += (e1 - e0) * (e1 + e0);
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < NC; ++j) {
+        const double s = block_sum(D[j], sm);
+        if (threadIdx.x == 0) partials[blockIdx.x * kMaxCand + j] = LAST ? s : 0.5 * (double)sp.nu * s;
+    }
+}
+
+__global__ __launch_bounds__(256) void w_trial_finish_kernel(const double* __restrict__ partials, int nblocks,
+                                                             int ncand, SearchParams sp, Unit* unit, int32_t* status) {
+    __shared__ double sm[4];
+    __shared__ double D[kMaxCand];
+    if (unit->done) return;
+    for (int j = 0; j < ncand; ++j) {
+        double a = 0.0;
+        for (int i = threadIdx.x; i < nblocks; i += blockDim.x) a += partials[i * kMaxCand + j];
+        a = block_sum(a, sm);
+        if (threadIdx.x == 0) D[j] = a;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) decide(unit, D, ncand, sp, status);
+}
+
+__global__ __launch_bounds__(256) void w_step_kernel(float* __restrict__ W, const float* __restrict__ gradW,
+                                                     int count_w, float* __restrict__ T, const float* __restrict__ Q,
+                                                     int64_t count_t, const Unit* unit) {
+    if (unit->skip) return;
+    const double inv = 1.0 / unit->step;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t i0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (int64_t i = i0; i < count_t; i += stride) T[i] = (float)((double)T[i] - (double)Q[i] * inv);
+    for (int64_t i = i0; i < count_w; i += stride) W[i] = (float)((double)W[i] - (double)gradW[i] * inv);
+}
+
+// ------------------------------------------------------------------------------------------ Z search
+// One block per chunk.  kind 0: rows [begin,end) of community `unit`, own term
+//     nu/2 ||Z - relu(T_l)||^2  under  Z -> Z - gradZ/theta;
+// kind 1: segments [begin,end) (community,row order) of the next layer's term, whose pre-activation
+//     row T_{l+1,i} moves by -P_s/theta as seen from this community.
+template <int NC>
+__global__ __launch_bounds__(256) void z_trial_kernel(ZTrialArgs a) {
+    __shared__ double sm[4];
+    const int ch = blockIdx.x;
+    const int unit = a.chunk_unit[ch];
+    const Unit* u = a.units + unit;
+    if (u->done) return;
+    const int kind = a.chunk_kind[ch];
+    const int begin = a.chunk_begin[ch], end = a.chunk_end[ch];
+    double inv[NC];
+    {
+        double step = u->step;
+#pragma unroll
+        for (int j = 0; j < NC; ++j) { inv[j] = 1.0 / step; step *= (double)a.sp.eta; }
+    }
+    double D[NC];
+#pragma unroll
+    for (int j = 0; j < NC; ++j) D[j] = 0.0;
+    double sg = 0.0, sb = 0.0;
+    const int width = kind == 0 ? a.Cl : a.Cn;
+    int cshift = 0;
+    while ((1 << cshift) < width && cshift < 8) ++cshift;
+    const int cp = 1 << cshift;
+    const int c_first = threadIdx.x & (cp - 1);
+    const int r_first = threadIdx.x >> cshift;
+    const int r_step = 256 >> cshift;
+    if (kind == 0) {
+        for (int r = begin + r_first; r < end; r += r_step) {
+            const int64_t base = (int64_t)r * width;
+            for (int c = c_first; c < width; c += cp) {
+                const double z = (double)a.Zl[base + c], gz = (double)a.gradZ[base + c], t = (double)a.Tl[base + c];
+                const double e0 = z - fmax(t, 0.0);
+                if (a.first_pass) { sg += gz * gz; sb += z * z; }
+#pragma unroll
+                for (int j = 0; j < NC; ++j) {
+                    const double dz = -gz * inv[j];
+                    D[j] += 0.5 * (double)a.sp.nu * dz * (2.0 * e0 + dz);
+                }
+            }
+        }
+    } else {
+        for (int s = begin + r_first; s < end; s += r_step) {
+            const int64_t row = a.segc_row[s];
+            const int64_t base = row * width, pbase = (int64_t)s * width;
+            for (int c = c_first; c < width; c += cp) {
+                const double t0 = (double)a.Tn[base + c], z = (double)a.Zn[base + c], p = (double)a.P[pbase + c];
+                if (a.next_is_last) {
+                    const double uu = (double)a.U[base + c];
+                    const double r0 = z - t0;
+#pragma unroll
+                    for (int j = 0; j < NC; ++j) {
+                        const double dq = p * inv[j];
+                        D[j] += dq * (uu + 0.5 * (double)a.sp.rho * (2.0 * r0 + dq));
+                    }
+                } else {
+                    const double e0 = fmax(t0, 0.0) - z;
+#pragma unroll
+                    for (int j = 0; j < NC; ++j) {
+                        const double e1 = fmax(t0 - p * inv[j], 0.0) - z;
+                        D[j] += 0.5 * (double)a.sp.nu * (e1 - e0) * (e1 + e0);
+                    }
+                }
+            }
+        }
+    }
+    double* out = a.partials + (int64_t)ch * (kMaxCand + 2);
+#pragma unroll
+    for (int j = 0; j < NC; ++j) {
+        const double s = block_sum(D[j], sm);
+        if (threadIdx.x == 0) out[j] = s;
+    }
+    if (a.first_pass) {
+        sg = block_sum(sg, sm);
+        sb = block_sum(sb, sm);
+        if (threadIdx.x == 0) { out[kMaxCand] = sg; out[kMaxCand + 1] = sb; }
+    }
+}
+
+__global__ __launch_bounds__(256) void z_trial_finish_kernel(ZTrialArgs a) {
+    __shared__ double sm[4];
+    __shared__ double D[kMaxCand + 2];
+    const int unit = blockIdx.x;
+    Unit* u = a.units + unit;
+    if (u->done) return;
+    const int c0 = a.unit_chunk_ptr[unit], c1 = a.unit_chunk_ptr[unit + 1];
+    const int nq = a.first_pass ? kMaxCand + 2 : a.ncand;
+    for (int q = 0; q < nq; ++q) {
+        if (q >= a.ncand && q < kMaxCand) continue;
+        double s = 0.0;
+        for (int i = c0 + threadIdx.x; i < c1; i += blockDim.x) s += a.partials[(int64_t)i * (kMaxCand + 2) + q];
+        s = block_sum(s, sm);
+        if (threadIdx.x == 0) D[q] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if (a.first_pass) {
+            floor_or_start(u, D[kMaxCand], D[kMaxCand + 1]);
+            if (u->done) return;
+        }
+        decide(u, D, a.ncand, a.sp, a.status);
+    }
+}
+
+__global__ __launch_bounds__(256) void z_step_kernel(float* __restrict__ Zl, const float* __restrict__ gradZ,
+                                                     const int32_t* __restrict__ row_comm, int64_t N, int Cl,
+                                                     const Unit* __restrict__ units) {
+    int cshift = 0;
+    while ((1 << cshift) < Cl && cshift < 8) ++cshift;
+    const int cp = 1 << cshift;
+    const int c_first = threadIdx.x & (cp - 1);
+    const int64_t r_step = (int64_t)gridDim.x * (256 >> cshift);
+    for (int64_t r = (int64_t)blockIdx.x * (256 >> cshift) + (threadIdx.x >> cshift); r < N; r += r_step) {
+        const Unit* u = units + row_comm[r];
+        if (u->skip) continue;
+        const double inv = 1.0 / u->step;
+        const int64_t base = r * Cl;
+        for (int c = c_first; c < Cl; c += cp)
+            Zl[base + c] = (float)((double)Zl[base + c] - (double)gradZ[base + c] * inv);
+    }
+}
+
+// ------------------------------------------------------------------------------------------ last layer + dual
+// One thread per node row, the row lives in registers.  FISTA on
+//   R(z, y_i) + <u, z - c> + rho/2 ||z - c||^2,   c = row of A~ Z_{L-1}^k W_L^{k+1},
+// whose smooth part is the whole objective: x_j = y_j - grad(y_j)/Lip, Lip = rho + (1/2 | 1).
+template <int MAXC>
+__global__ __launch_bounds__(256) void last_layer_kernel(float* __restrict__ ZL, float* __restrict__ U,
+                                                         const float* __restrict__ TL,
+                                                         const int32_t* __restrict__ labels, int64_t N, int CL,
+                                                         int risk, float rho, int J) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= N) return;
+    float c[MAXC], u[MAXC], xp[MAXC], y[MAXC], x[MAXC];
+    const int64_t base = i * CL;
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+        if (j < CL) {
+            c[j] = TL[base + j];
+            u[j] = U[base + j];
+            xp[j] = ZL[base + j];
+        } else { c[j] = 0.f; u[j] = 0.f; xp[j] = 0.f; }
+        y[j] = xp[j];
+        x[j] = xp[j];
+    }
+    // dual step with the iterates as printed in Eq. 2: Z_L^k and the aggregation with W_L^{k+1}
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j)
+        if (j < CL) U[base + j] = u[j] + rho * (xp[j] - c[j]);
+    const int lab = labels[i];
+    if (lab < 0) {
+#pragma unroll
+        for (int j = 0; j < MAXC; ++j)
+            if (j < CL) ZL[base + j] = c[j] - u[j] / rho;
+        return;
+    }
+    const float lip = rho + (risk == 0 ? 0.5f : 1.0f);
+    const float inv_lip = 1.0f / lip;
+    float t = 1.0f;
+    for (int it = 0; it < J; ++it) {
+        float g[MAXC];
+        if (risk == 0) {
+            float mx = -3.4e38f;
+#pragma unroll
+            for (int j = 0; j < MAXC; ++j)
+                if (j < CL) mx = fmaxf(mx, y[j]);
+            float se = 0.f;
+#pragma unroll
+            for (int j = 0; j < MAXC; ++j) {
+                g[j] = (j < CL) ? expf(y[j] - mx) : 0.f;
+                se += g[j];
+            }
+            const float inv_se = 1.0f / se;
+#pragma unroll
+            for (int j = 0; j < MAXC; ++j) g[j] = g[j] * inv_se - (j == lab ? 1.f : 0.f);
+        } else {
+#pragma unroll
+            for (int j = 0; j < MAXC; ++j) g[j] = y[j] - (j == lab ? 1.f : 0.f);
+        }
+        const float tn = 0.5f * (1.0f + sqrtf(1.0f + 4.0f * t * t));
+        const float mom = (t - 1.0f) / tn;
+#pragma unroll
+        for (int j = 0; j < MAXC; ++j) {
+            const float grad = g[j] + u[j] + rho * (y[j] - c[j]);
+            x[j] = y[j] - grad * inv_lip;
+            y[j] = x[j] + mom * (x[j] - xp[j]);
+            xp[j] = x[j];
+        }
+        t = tn;
+    }
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j)
+        if (j < CL) ZL[base + j] = x[j];
+}
+
+__global__ __launch_bounds__(256) void relu_kernel(const float* __restrict__ T, float* __restrict__ Z, int64_t count,
+                                                   int apply_relu) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride)
+        Z[i] = apply_relu ? fmaxf(T[i], 0.f) : T[i];
+}
+
+__global__ void fill_units_kernel(Unit* units, int n, double step) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    Unit u;
+    u.step = step; u.g = 0.0; u.bnorm = 0.0; u.done = 0; u.skip = 0; u.ntrials = 0; u.pad = 0;
+    units[i] = u;
+}
+
+__global__ void reset_units_kernel(Unit* units, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    units[i].done = 0;
+    units[i].skip = 0;
+    units[i].ntrials = 0;
+}
+
+__global__ __launch_bounds__(256) void permute_rows_kernel(const float* __restrict__ src, float* __restrict__ dst,
+                                                           const int32_t* __restrict__ idx, int64_t N, int C,
+                                                           int scatter) {
+    const int64_t total = N * (int64_t)C;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += stride) {
+        const int64_t r = e / C;
+        const int c = (int)(e - r * C);
+        const int64_t o = (int64_t)idx[r] * C + c;
+        if (scatter) dst[o] = src[e];
+        else dst[e] = src[o];
+    }
+}
+
+inline int flat_grid(int64_t count) {
+    int64_t nb = (count + 1023) / 1024;     // about four elements per thread at least
+    if (nb < 1) nb = 1;
+    if (nb > kReduceBlocks) nb = kReduceBlocks;
+    return (int)nb;
+}
+
+}  // namespace
+
+void launch_phi_G(hipStream_t s, const float* T, const float* Z, const float* U, float* G, float* Tprev,
+                  int have_prev, int64_t count, int last, float nu, float rho, double* partials,
+                  LayerScalars* out) {
+    const int nb = flat_grid(count);
+    if (last)
+        hipLaunchKernelGGL((phi_G_kernel<1>), dim3(nb), dim3(256), 0, s, T, Z, U, G, Tprev, have_prev, count, nu, rho,
+                           partials);
+    else
+        hipLaunchKernelGGL((phi_G_kernel<0>), dim3(nb), dim3(256), 0, s, T, Z, U, G, Tprev, have_prev, count, nu, rho,
+                           partials);
+    hipLaunchKernelGGL(phi_G_finish_kernel, dim3(1), dim3(256), 0, s, partials, nb, last, nu, out);
+}
+
+void launch_G_only(hipStream_t s, const float* T, const float* Z, const float* U, float* G, int64_t count,
+                   int last, float nu, float rho) {
+    const int nb = flat_grid(count);
+    if (last) hipLaunchKernelGGL((G_only_kernel<1>), dim3(nb), dim3(256), 0, s, T, Z, U, G, count, nu, rho);
+    else hipLaunchKernelGGL((G_only_kernel<0>), dim3(nb), dim3(256), 0, s, T, Z, U, G, count, nu, rho);
+}
+
+void launch_risk(hipStream_t s, const float* ZL, const int32_t* labels, int64_t N, int CL, int risk,
+                 double* partials, LayerScalars* out) {
+    const int nb = flat_grid(N * 4);
+    hipLaunchKernelGGL(risk_kernel, dim3(nb), dim3(256), 0, s, ZL, labels, N, CL, risk, partials);
+    hipLaunchKernelGGL(risk_finish_kernel, dim3(1), dim3(256), 0, s, partials, nb, out);
+}
+
+void launch_w_norms(hipStream_t s, const float* gradW, const float* W, int count, Unit* unit) {
+    hipLaunchKernelGGL(w_norms_kernel, dim3(1), dim3(256), 0, s, gradW, W, count, unit);
+}
+
+void launch_w_trial(hipStream_t s, const float* T0, const float* Q, const float* Z, const float* U,
+                    int64_t count, int last, int ncand, SearchParams sp, Unit* unit, double* partials,
+                    int32_t* status) {
+    const int nb = flat_grid(count);
+    if (ncand == 1) {
+        if (last) hipLaunchKernelGGL((w_trial_kernel<1, 1>), dim3(nb), dim3(256), 0, s, T0, Q, Z, U, count, sp, unit, partials);
+        else hipLaunchKernelGGL((w_trial_kernel<0, 1>), dim3(nb), dim3(256), 0, s, T0, Q, Z, U, count, sp, unit, partials);
+    } else {
+        ncand = kMaxCand;
+        if (last) hipLaunchKernelGGL((w_trial_kernel<1, kMaxCand>), dim3(nb), dim3(256), 0, s, T0, Q, Z, U, count, sp, unit, partials);
+        else hipLaunchKernelGGL((w_trial_kernel<0, kMaxCand>), dim3(nb), dim3(256), 0, s, T0, Q, Z, U, count, sp, unit, partials);
+    }
+    hipLaunchKernelGGL(w_trial_finish_kernel, dim3(1), dim3(256), 0, s, partials, nb, ncand, sp, unit, status);
+}
+
+void launch_w_step(hipStream_t s, float* W, const float* gradW, int count_w, float* T, const float* Q,
+                   int64_t count_t, const Unit* unit) {
+    const int nb = flat_grid(count_t > count_w ? count_t : count_w);
+    hipLaunchKernelGGL(w_step_kernel, dim3(nb), dim3(256), 0, s, W, gradW, count_w, T, Q, count_t, unit);
+}
+
+void launch_z_trial(hipStream_t s, const ZTrialArgs& a0) {
+    ZTrialArgs a = a0;
+    if (a.n_chunks > 0) {
+        if (a.ncand == 1) hipLaunchKernelGGL((z_trial_kernel<1>), dim3(a.n_chunks), dim3(256), 0, s, a);
+        else { a.ncand = kMaxCand; hipLaunchKernelGGL((z_trial_kernel<kMaxCand>), dim3(a.n_chunks), dim3(256), 0, s, a); }
+    }
+    hipLaunchKernelGGL(z_trial_finish_kernel, dim3(a.M), dim3(256), 0, s, a);
+}
+
+void launch_z_step(hipStream_t s, float* Zl, const float* gradZ, const int32_t* row_comm, int64_t N, int Cl,
+                   const Unit* units) {
+    const int nb = flat_grid(N * (int64_t)Cl);
+    hipLaunchKernelGGL(z_step_kernel, dim3(nb), dim3(256), 0, s, Zl, gradZ, row_comm, N, Cl, units);
+}
+
+void launch_last_layer(hipStream_t s, float* ZL, float* U, const float* TL, const int32_t* labels, int64_t N,
+                       int CL, int risk, float rho, int J) {
+    const unsigned nb = (unsigned)((N + 255) / 256);
+    if (CL <= 8) hipLaunchKernelGGL((last_layer_kernel<8>), dim3(nb), dim3(256), 0, s, ZL, U, TL, labels, N, CL, risk, rho, J);
+    else if (CL <= 16) hipLaunchKernelGGL((last_layer_kernel<16>), dim3(nb), dim3(256), 0, s, ZL, U, TL, labels, N, CL, risk, rho, J);
+    else if (CL <= 32) hipLaunchKernelGGL((last_layer_kernel<32>), dim3(nb), dim3(256), 0, s, ZL, U, TL, labels, N, CL, risk, rho, J);
+    else hipLaunchKernelGGL((last_layer_kernel<64>), dim3(nb), dim3(256), 0, s, ZL, U, TL, labels, N, CL, risk, rho, J);
+}
+
+void launch_relu(hipStream_t s, const float* T, float* Z, int64_t count, int apply_relu) {
+    hipLaunchKernelGGL(relu_kernel, dim3(flat_grid(count)), dim3(256), 0, s, T, Z, count, apply_relu);
+}
+
+void launch_fill_units(hipStream_t s, Unit* units, int n, double step) {
+    hipLaunchKernelGGL(fill_units_kernel, dim3((n + 255) / 256), dim3(256), 0, s, units, n, step);
+}
+
+void launch_reset_units(hipStream_t s, Unit* units, int n) {
+    hipLaunchKernelGGL(reset_units_kernel, dim3((n + 255) / 256), dim3(256), 0, s, units, n);
+}
+
+void launch_permute_rows(hipStream_t s, const float* src, float* dst, const int32_t* idx, int64_t N, int C,
+                         int scatter) {
+    hipLaunchKernelGGL(permute_rows_kernel, dim3(flat_grid(N * (int64_t)C)), dim3(256), 0, s, src, dst, idx, N, C, scatter);
+}
+
+}  // namespace cadmm

@@ -1,0 +1,340 @@
+// Dense fp32 contractions of the sweep on the gfx950 matrix cores (v_mfma_f32_32x32x2_f32):
+//   gemm_nn : out[n x C] = A[n x K] B[K x C]     (T_l = H_l W_l, Q = H_l gradW, G W^T, gradZ W;
+//                                                 paper Section 3.1 and Appendix A)
+//   gemm_tn : out[K x C] = A[n x K]^T G[n x C]   (gradient of phi with respect to W_l: a sum over all
+//                                                 nodes of all communities, Section 3.1)
+// n is the number of nodes (huge), K and C are layer widths (3..512).
+//
+// Tiling: 256 threads = 4 wavefronts; block tile 128 x BN (BN = 128: 2x2 waves of 64x64; BN = 32: 4x1
+// waves of 32x32), K-step 16, operands staged through LDS, next tile prefetched into registers while
+// the current one feeds the MFMAs.  MFMA operand layout for 32x32x2 (64 lanes): lane holds
+// A[i = lane%32][k = lane/32] and B[k = lane/32][j = lane%32]; accumulator register r of a lane is
+// C[8*(r/4) + 4*(lane/32) + r%4][lane%32].
+// gemm_tn splits n into chunks, each block reduces one chunk for one 128 x BN output tile into a
+// partial matrix; a second kernel adds the partials in chunk order in fp64 (deterministic).
+#include "kernels.h"
+
+namespace cadmm {
+
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128;
+constexpr int BK = 16;
+
+__device__ __forceinline__ float4 ld4_guard(const float* base, int64_t off, bool ok, bool aligned, int valid) {
+    // valid: number of in-range elements (0..4) starting at off
+    if (!ok || valid <= 0) return make_float4(0.f, 0.f, 0.f, 0.f);
+    if (aligned && valid >= 4) return *reinterpret_cast<const float4*>(base + off);
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    v.x = base[off];
+    if (valid > 1) v.y = base[off + 1];
+    if (valid > 2) v.z = base[off + 2];
+    if (valid > 3) v.w = base[off + 3];
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------------ NN
+template <int BN>
+__global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ A, const float* __restrict__ B,
+                                                      float* __restrict__ out, int64_t n, int K, int C) {
+    constexpr int WN = (BN == 128) ? 2 : 1;       // waves along columns
+    constexpr int WM = 4 / WN;                    // waves along rows
+    constexpr int TM = BM / (WM * 32);            // 32x32 tiles per wave along rows
+    constexpr int TN = BN / (WN * 32);
+    constexpr int LDA = BK + 1;
+    constexpr int LDB = BN + 4;
+    constexpr int B_F4 = BK * BN / 4;             // float4 loads for the B tile
+    constexpr int B_PER_T = (B_F4 + 255) / 256;
+
+    __shared__ __align__(16) float As[BM * LDA];
+    __shared__ __align__(16) float Bs[BK * LDB];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int ctiles = (C + BN - 1) / BN;
+    const int64_t m0 = (int64_t)(blockIdx.x / ctiles) * BM;
+    const int c0 = (blockIdx.x % ctiles) * BN;
+    const bool a_al = (K % 4) == 0;
+    const bool b_al = (C % 4) == 0;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    float4 ra[2], rb[B_PER_T];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int f = tid + 256 * i;
+            const int row = f >> 2, kq = f & 3;
+            const int64_t gr = m0 + row;
+            const int k = k0 + 4 * kq;
+            ra[i] = ld4_guard(A, gr * K + k, gr < n, a_al, K - k);
+        }
+#pragma unroll
+        for (int i = 0; i < B_PER_T; ++i) {
+            const int f = tid + 256 * i;
+            if (f < B_F4) {
+                const int kr = f / (BN / 4), cq = f % (BN / 4);
+                const int k = k0 + kr, c = c0 + 4 * cq;
+                rb[i] = ld4_guard(B, (int64_t)k * C + c, k < K, b_al, C - c);
+            }
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int f = tid + 256 * i;
+            const int row = f >> 2, kq = f & 3;
+            float* d = As + row * LDA + 4 * kq;
+            d[0] = ra[i].x; d[1] = ra[i].y; d[2] = ra[i].z; d[3] = ra[i].w;
+        }
+#pragma unroll
+        for (int i = 0; i < B_PER_T; ++i) {
+            const int f = tid + 256 * i;
+            if (f < B_F4) {
+                const int kr = f / (BN / 4), cq = f % (BN / 4);
+                *reinterpret_cast<float4*>(Bs + kr * LDB + 4 * cq) = rb[i];
+            }
+        }
+    };
+
+    const int nk = (K + BK - 1) / BK;
+    fetch(0);
+    for (int kt = 0; kt < nk; ++kt) {
+        __syncthreads();            // previous tile fully consumed
+        stash();
+        __syncthreads();
+        if (kt + 1 < nk) fetch((kt + 1) * BK);
+        const int li = lane & 31, lk = lane >> 5;
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            float a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = As[(wm * TM * 32 + i * 32 + li) * LDA + kk + lk];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = Bs[(kk + lk) * LDB + wn * TN * 32 + j * 32 + li];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    }
+    const int li = lane & 31, lk = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int c = c0 + wn * TN * 32 + j * 32 + li;
+            if (c >= C) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = m0 + wm * TM * 32 + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+                if (row < n) out[row * C + c] = acc[i][j][r];
+            }
+        }
+}
+
+// ------------------------------------------------------------------------------------------------ TN
+// Block (chunk, ktile, ctile): partial[chunk][k][c] = sum_{rows of chunk} A[row][k] G[row][c].
+template <int BN>
+__global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ A, const float* __restrict__ G,
+                                                      float* __restrict__ partial, int64_t n, int K, int C,
+                                                      int64_t rows_per_chunk) {
+    constexpr int WN = (BN == 128) ? 2 : 1;
+    constexpr int WM = 4 / WN;
+    constexpr int TM = BM / (WM * 32);
+    constexpr int TN = BN / (WN * 32);
+    constexpr int LDA = BM + 4;
+    constexpr int LDG = BN + 4;
+    constexpr int G_F4 = BK * BN / 4;
+    constexpr int G_PER_T = (G_F4 + 255) / 256;
+
+    __shared__ __align__(16) float As[BK * LDA];
+    __shared__ __align__(16) float Gs[BK * LDG];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int ktiles = (K + BM - 1) / BM;
+    const int ctiles = (C + BN - 1) / BN;
+    const int tile = blockIdx.x % (ktiles * ctiles);
+    const int64_t chunk = blockIdx.x / (ktiles * ctiles);
+    const int k0 = (tile / ctiles) * BM;
+    const int c0 = (tile % ctiles) * BN;
+    const int64_t r_begin = chunk * rows_per_chunk;
+    const int64_t r_end = (r_begin + rows_per_chunk < n) ? (r_begin + rows_per_chunk) : n;
+    const bool a_al = (K % 4) == 0;
+    const bool g_al = (C % 4) == 0;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    float4 ra[2], rg[G_PER_T];
+    auto fetch = [&](int64_t r0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {              // A tile: 16 rows x 128 k = 512 float4
+            const int f = tid + 256 * i;
+            const int rr = f >> 5, kq = f & 31;
+            const int64_t gr = r0 + rr;
+            const int k = k0 + 4 * kq;
+            ra[i] = ld4_guard(A, gr * K + k, gr < r_end, a_al, K - k);
+        }
+#pragma unroll
+        for (int i = 0; i < G_PER_T; ++i) {
+            const int f = tid + 256 * i;
+            if (f < G_F4) {
+                const int rr = f / (BN / 4), cq = f % (BN / 4);
+                const int64_t gr = r0 + rr;
+                const int c = c0 + 4 * cq;
+                rg[i] = ld4_guard(G, gr * C + c, gr < r_end, g_al, C - c);
+            }
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int f = tid + 256 * i;
+            const int rr = f >> 5, kq = f & 31;
+            *reinterpret_cast<float4*>(As + rr * LDA + 4 * kq) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < G_PER_T; ++i) {
+            const int f = tid + 256 * i;
+            if (f < G_F4) {
+                const int rr = f / (BN / 4), cq = f % (BN / 4);
+                *reinterpret_cast<float4*>(Gs + rr * LDG + 4 * cq) = rg[i];
+            }
+        }
+    };
+
+    const int li = lane & 31, lk = lane >> 5;
+    if (r_begin < r_end) fetch(r_begin);
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += BK) {
+        __syncthreads();
+        stash();
+        __syncthreads();
+        if (r0 + BK < r_end) fetch(r0 + BK);
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            float a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = As[(kk + lk) * LDA + wm * TM * 32 + i * 32 + li];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = Gs[(kk + lk) * LDG + wn * TN * 32 + j * 32 + li];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    }
+    float* dst = partial + chunk * (int64_t)K * C;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int c = c0 + wn * TN * 32 + j * 32 + li;
+            if (c >= C) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int k = k0 + wm * TM * 32 + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+                if (k < K) dst[(int64_t)k * C + c] = acc[i][j][r];
+            }
+        }
+}
+
+__global__ __launch_bounds__(256) void gemm_tn_reduce_kernel(const float* __restrict__ partial,
+                                                             float* __restrict__ out, int64_t count, int nchunks) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    double acc = 0.0;
+    for (int c = 0; c < nchunks; ++c) acc += (double)partial[(int64_t)c * count + i];
+    out[i] = (float)acc;
+}
+
+__global__ __launch_bounds__(256) void transpose_kernel(const float* __restrict__ in, float* __restrict__ out,
+                                                        int K, int C) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= K * C) return;
+    const int k = i / C, c = i % C;
+    out[c * K + k] = in[i];
+}
+
+struct TnPlan {
+    int nchunks;
+    int64_t rows_per_chunk;
+    int bn;
+    int tiles;
+};
+
+TnPlan tn_plan(int64_t n, int K, int C) {
+    TnPlan p;
+    p.bn = (C > 32) ? 128 : 32;
+    const int ktiles = (K + BM - 1) / BM;
+    const int ctiles = (C + p.bn - 1) / p.bn;
+    p.tiles = ktiles * ctiles;
+    int64_t want = (2048 + p.tiles - 1) / p.tiles;          // about 2048 blocks in flight
+    int64_t max_chunks = (n + 255) / 256;                   // at least 256 rows per chunk
+    int64_t nch = want < max_chunks ? want : max_chunks;
+    if (nch < 1) nch = 1;
+    int64_t rpc = (n + nch - 1) / nch;
+    rpc = (rpc + BK - 1) / BK * BK;
+    p.rows_per_chunk = rpc;
+    p.nchunks = (int)((n + rpc - 1) / rpc);
+    if (p.nchunks < 1) p.nchunks = 1;
+    return p;
+}
+
+}  // namespace
+
+void launch_gemm_nn(hipStream_t s, const float* A, const float* B, float* out, int64_t n, int K, int C) {
+    if (n <= 0 || C <= 0) return;
+    const int64_t mt = (n + BM - 1) / BM;
+    if (C > 32) {
+        const int ct = (C + 127) / 128;
+        hipLaunchKernelGGL((gemm_nn_kernel<128>), dim3((unsigned)(mt * ct)), dim3(256), 0, s, A, B, out, n, K, C);
+    } else {
+        hipLaunchKernelGGL((gemm_nn_kernel<32>), dim3((unsigned)mt), dim3(256), 0, s, A, B, out, n, K, C);
+    }
+}
+
+size_t gemm_tn_scratch_floats(int64_t n, int K, int C) {
+    TnPlan p = tn_plan(n, K, C);
+    return (size_t)p.nchunks * K * C;
+}
+
+void launch_gemm_tn(hipStream_t s, const float* A, const float* G, float* out, int64_t n, int K, int C,
+                    float* partial) {
+    if (K <= 0 || C <= 0) return;
+    TnPlan p = tn_plan(n, K, C);
+    const unsigned nb = (unsigned)((int64_t)p.nchunks * p.tiles);
+    if (p.bn == 128)
+        hipLaunchKernelGGL((gemm_tn_kernel<128>), dim3(nb), dim3(256), 0, s, A, G, partial, n, K, C, p.rows_per_chunk);
+    else
+        hipLaunchKernelGGL((gemm_tn_kernel<32>), dim3(nb), dim3(256), 0, s, A, G, partial, n, K, C, p.rows_per_chunk);
+    const int64_t count = (int64_t)K * C;
+    hipLaunchKernelGGL(gemm_tn_reduce_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, partial, out,
+                       count, p.nchunks);
+}
+
+void launch_transpose(hipStream_t s, const float* in, float* out, int K, int C) {
+    hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)((K * C + 255) / 256)), dim3(256), 0, s, in, out, K, C);
+}
+
+}  // namespace cadmm

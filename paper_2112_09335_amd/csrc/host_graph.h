@@ -1,0 +1,48 @@
+// Host-side graph structures of the community-blocked ADMM library (integer work, done once).
+#pragma once
+#include <cstdint>
+#include <string>
+#include <vector>
+
+namespace cadmm {
+
+// Work unit of the per-community reductions of the Z step-size search: a run of rows of one
+// community (kind 0) or a run of that community's segments in (community,row) order (kind 1).
+struct Chunk {
+    int32_t unit;    // community
+    int32_t kind;    // 0 = own rows, 1 = segments
+    int32_t begin;   // first row / first segment (index into the (community,row)-sorted list)
+    int32_t end;     // one past the last
+};
+
+struct HostGraph {
+    int64_t N = 0, E = 0, nnz = 0, n_seg = 0, n_halo_rows = 0;
+    int32_t M = 0;
+    std::vector<int32_t> perm;          // [N] internal row -> caller id
+    std::vector<int32_t> inv_perm;      // [N] caller id -> internal row
+    std::vector<int64_t> comm_row_ptr;  // [M+1]
+    std::vector<int32_t> row_comm;      // [N] community of an internal row
+    std::vector<int64_t> row_ptr;       // [N+1]
+    std::vector<int32_t> col;           // [nnz]
+    std::vector<float>   val;           // [nnz]
+    // segments, (row, community) order
+    std::vector<int64_t> seg_ptr;       // [n_seg+1]
+    std::vector<int32_t> seg_row;       // [n_seg]
+    std::vector<int32_t> seg_comm;      // [n_seg]
+    std::vector<uint8_t> neighbour;     // [M*M]
+    // segments, (community, row) order
+    std::vector<int64_t> segc_order;    // [n_seg] index into the (row, community) order
+    std::vector<int64_t> segc_lo;       // [n_seg] first entry in col/val
+    std::vector<int64_t> segc_hi;       // [n_seg] one past the last entry
+    std::vector<int32_t> segc_row;      // [n_seg]
+    std::vector<int64_t> segc_comm_ptr; // [M+1]
+    // reduction chunks for the Z search, grouped by community
+    std::vector<Chunk>   chunks;
+    std::vector<int32_t> unit_chunk_ptr; // [M+1]
+};
+
+// Returns an empty string on success, an error text otherwise.
+std::string build_host_graph(HostGraph& g, int64_t N, int64_t n_edges, const int32_t* src,
+                             const int32_t* dst, int32_t M, const int32_t* comm, int chunk_rows);
+
+}  // namespace cadmm

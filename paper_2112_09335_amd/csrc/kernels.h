@@ -1,0 +1,113 @@
+// Launch wrappers of the HIP kernels (gfx950).  All pointers are device pointers; all work is
+// enqueued on `s`.  Row-major fp32 matrices whose leading dimension equals their width.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace cadmm {
+
+// ---------------------------------------------------------------- sparse aggregation (spmm.hip)
+// Y[r,:] = sum_{p in [lo[r], hi[r])} val[p] * X[col[p],:]   for r < nrows.
+// epilogue 0: store;  1: Y = nu * (Zl - relu(Tl)) + sum  (gradient of the Z subproblem).
+struct SpmmEpilogue {
+    int kind = 0;
+    const float* Zl = nullptr;
+    const float* Tl = nullptr;
+    float nu = 0.f;
+};
+void launch_spmm(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32_t* col, const float* val,
+                 const float* X, float* Y, int64_t nrows, int width, const SpmmEpilogue& epi);
+
+// ---------------------------------------------------------------- dense contractions (gemm.hip)
+// out[n x C] = A[n x K] * B[K x C]
+void launch_gemm_nn(hipStream_t s, const float* A, const float* B, float* out, int64_t n, int K, int C);
+// out[K x C] = A[n x K]^T * G[n x C]; partial: scratch of gemm_tn_scratch_floats(n,K,C) floats.
+size_t gemm_tn_scratch_floats(int64_t n, int K, int C);
+void launch_gemm_tn(hipStream_t s, const float* A, const float* G, float* out, int64_t n, int K, int C,
+                    float* partial);
+// out[C x K] = in[K x C]^T (small)
+void launch_transpose(hipStream_t s, const float* in, float* out, int K, int C);
+
+// ---------------------------------------------------------------- fused elementwise + reductions (elementwise.hip)
+constexpr int kReduceBlocks = 2048;      // grid of the flat reducing kernels
+constexpr int kMaxCand = 8;              // step-size candidates evaluated per pass
+constexpr int kChunkRows = 128;          // rows / segments per reduction chunk of the Z search
+
+// One step-size search ("unit"): a layer's tau, or a (layer, community)'s theta.
+struct Unit {
+    double step;       // current first candidate / accepted value
+    double g;          // squared gradient norm
+    double bnorm;      // squared norm of the block that moves
+    int32_t done;      // search finished
+    int32_t skip;      // step below resolution: block stays
+    int32_t ntrials;   // candidates tested this iteration
+    int32_t pad;
+};
+
+// Readout scalars of one layer's base evaluation.
+struct LayerScalars {
+    double phi;        // phi_l at the base point
+    double res2;       // ||Z_L - T_L||^2           (last layer only)
+    double dT2;        // ||T_L - T_L(previous)||^2 (last layer only)
+    double risk;       // R(Z_L, Y)                 (last layer only)
+};
+
+struct SearchParams {
+    float nu, rho, eta;
+    int32_t max_backtrack;
+};
+
+// phi_l and G_l at T (hidden: G = nu (relu(T)-Z) 1[T>0]; last: G = -(U + rho (Z - T))).
+// last != 0 additionally accumulates ||Z-T||^2, ||T-Tprev||^2 (if have_prev) and writes Tprev = T.
+void launch_phi_G(hipStream_t s, const float* T, const float* Z, const float* U, float* G, float* Tprev,
+                  int have_prev, int64_t count, int last, float nu, float rho, double* partials,
+                  LayerScalars* out);
+// G only (no reduction), same formulas.
+void launch_G_only(hipStream_t s, const float* T, const float* Z, const float* U, float* G, int64_t count,
+                   int last, float nu, float rho);
+// R(Z_L, Y) summed over labelled rows -> out->risk
+void launch_risk(hipStream_t s, const float* ZL, const int32_t* labels, int64_t N, int CL, int risk,
+                 double* partials, LayerScalars* out);
+// unit.g = ||gradW||^2, unit.bnorm = ||W||^2, applies the step floor, resets the search state.
+void launch_w_norms(hipStream_t s, const float* gradW, const float* W, int count, Unit* unit);
+// One pass of the W search: candidates step*eta^j, j < ncand, on phi_l(T0 - Q/step).
+void launch_w_trial(hipStream_t s, const float* T0, const float* Q, const float* Z, const float* U,
+                    int64_t count, int last, int ncand, SearchParams sp, Unit* unit, double* partials,
+                    int32_t* status);
+// W -= gradW/step (count_w entries), T = T0 - Q/step (count_t entries); no-op if unit.skip.
+void launch_w_step(hipStream_t s, float* W, const float* gradW, int count_w, float* T, const float* Q,
+                   int64_t count_t, const Unit* unit);
+
+// Z search, layer l (widths Cl, Cn = C_{l+1}).  Device arrays of the graph:
+struct ZTrialArgs {
+    const int32_t* chunk_unit; const int32_t* chunk_kind; const int32_t* chunk_begin; const int32_t* chunk_end;
+    int32_t n_chunks;
+    const int32_t* unit_chunk_ptr; int32_t M;
+    const int32_t* segc_row;
+    const float* Zl; const float* gradZ; const float* Tl; int Cl;       // own term, rows of the community
+    const float* Tn; const float* Zn; const float* U; const float* P; int Cn;   // next layer, per segment
+    int next_is_last;
+    int first_pass;        // also accumulate ||gradZ_m||^2 and ||Z_m||^2, apply the step floor
+    int ncand;
+    SearchParams sp;
+    Unit* units;           // [M]
+    double* partials;      // [n_chunks * (kMaxCand + 2)]
+    int32_t* status;
+};
+void launch_z_trial(hipStream_t s, const ZTrialArgs& a);
+// Z_l[i,:] -= gradZ[i,:] / theta[comm(i)]
+void launch_z_step(hipStream_t s, float* Zl, const float* gradZ, const int32_t* row_comm, int64_t N, int Cl,
+                   const Unit* units);
+// Last layer (Appendix A, Eq. 5) by J FISTA steps per row, fused with the dual step (Eq. 2):
+//   U_new = U + rho (Z_L - T_L),  Z_L_new = FISTA(start Z_L; c = T_L, U, rho)
+void launch_last_layer(hipStream_t s, float* ZL, float* U, const float* TL, const int32_t* labels, int64_t N,
+                       int CL, int risk, float rho, int J);
+void launch_relu(hipStream_t s, const float* T, float* Z, int64_t count, int apply_relu);
+void launch_fill_units(hipStream_t s, Unit* units, int n, double step);
+void launch_reset_units(hipStream_t s, Unit* units, int n);
+// gather / scatter rows between caller order and internal order: dst[r,:] = src[idx[r],:] or dst[idx[r],:] = src[r,:]
+void launch_permute_rows(hipStream_t s, const float* src, float* dst, const int32_t* idx, int64_t N, int C,
+                         int scatter);
+
+}  // namespace cadmm

@@ -1,0 +1,97 @@
+"""GPU parity of the whole ADMM sweep against the CPU oracle, iteration by iteration, on the same seeded
+inputs (tolerance 1e-4 relative on W, Z, U and the objective; step-size trajectories identical)."""
+import copy
+
+import numpy as np
+import pytest
+
+from oracle.admm import make_oracle
+from paper_2112_09335_amd import synth
+from parity import compare_iterate, say
+
+pytestmark = pytest.mark.gpu
+
+
+def run_case(w, iters, tag):
+    from paper_2112_09335_amd import binding
+    say(f"[{tag}] N={w.N} M={w.M} dims={w.dims} E={w.E} iters={iters}")
+    solver = binding.Solver.from_workload(w, 0)
+    orc = make_oracle(w)
+    worst = compare_iterate(solver, orc, f"{tag} it0")
+    for k in range(1, iters + 1):
+        solver.run(1)
+        orc.iterate(1)
+        worst = max(worst, compare_iterate(solver, orc, f"{tag} it{k}"))
+        say(f"[{tag}] it{k} ok, worst rel err so far {worst:.2e}")
+    solver.close()
+    return worst
+
+
+def test_config1_tiny_sbm_all_iterations():
+    w = synth.config(1)
+    run_case(w, w.iters, "config1")
+
+
+def test_config2_mid_sbm_scaled():
+    w = synth.config(2, 0.1)             # N = 2000, 500 -> 128 -> 3
+    run_case(w, 12, "config2/10")
+
+
+def test_config3_three_layers_scaled():
+    w = synth.config(3, 0.01)            # N = 2000, 32 communities, 128 -> 256 -> 256 -> 10
+    run_case(w, 8, "config3/100")
+
+
+def test_config4_powerlaw_scaled():
+    w = synth.config(4, 0.002)           # N = 4000, 64 communities, hubs, 128 -> 256 -> 16
+    run_case(w, 8, "config4/500")
+
+
+def test_config5_deep_scaled():
+    w = synth.config(5, 0.002, M=4)      # N = 1000, 8 layers of 512
+    run_case(w, 4, "config5/500")
+
+
+def test_unlabelled_nodes_least_squares_risk_one_community_and_ragged_sizes():
+    w = synth.make_workload("ragged", 11, 1237, 5, [37, 50, 9, 6], 6, 6, graph="sbm", features="gaussian",
+                            avg_degree=6, frac_intra=0.7, labelled_fraction=0.4)
+    w.comm = np.where(w.comm == 3, 4, w.comm).astype(np.int32)      # community 3 is empty
+    run_case(w, 6, "ragged-ce")
+    w2 = copy.deepcopy(w)
+    w2.hyper["risk"] = 1
+    run_case(w2, 4, "ragged-lsq")
+    w3 = synth.make_workload("single", 12, 600, 1, [20, 33, 4], 4, 5, graph="sbm", features="gaussian",
+                             avg_degree=8, frac_intra=1.0)
+    run_case(w3, 5, "one-community")
+    w4 = synth.make_workload("noedges", 13, 300, 3, [10, 12, 3], 3, 3, graph="empty", features="gaussian")
+    run_case(w4, 3, "empty-graph")
+
+
+def test_backtracking_cap_status_and_resume_are_consistent():
+    from paper_2112_09335_amd import binding
+    w = synth.config(1, 0.5)
+    w.hyper["max_backtrack"] = 2
+    run_case(w, 3, "cap")                # both sides must raise the same status bit
+    # resume: 4 iterations == 2 iterations, state out and in again, 2 more (bit for bit on the GPU side)
+    w = synth.config(1, 0.5)
+    a = binding.Solver.from_workload(w, 0)
+    a.run(4)
+    b = binding.Solver.from_workload(w, 0)
+    b.run(2)
+    tau, theta, _, _ = b.get_steps()
+    W = [b.get_W(l) for l in range(1, w.L + 1)]
+    Z = [b.get_Z(l) for l in range(1, w.L + 1)]
+    U = b.get_U()
+    c = binding.Solver.from_workload(w, 0)
+    c.set_state(W=W, Z=Z, U=U, tau=tau, theta=theta)
+    c.run(2)
+    for l in range(1, w.L + 1):
+        assert np.array_equal(a.get_W(l), c.get_W(l))
+        assert np.array_equal(a.get_Z(l), c.get_Z(l))
+    assert np.array_equal(a.get_U(), c.get_U())
+    # and the run itself is reproducible bit for bit
+    d = binding.Solver.from_workload(w, 0)
+    d.run(4)
+    assert np.array_equal(a.get_Z(1), d.get_Z(1)) and a.eval()["objective"] == d.eval()["objective"]
+    for s in (a, b, c, d):
+        s.close()

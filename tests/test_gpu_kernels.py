@@ -1,0 +1,100 @@
+"""GPU parity of the individual kernels (through the C ABI) against fp64 numpy / scipy on the oracle's graph."""
+import numpy as np
+import pytest
+import scipy.sparse as sp
+
+from oracle.graph import OracleGraph
+from paper_2112_09335_amd import synth
+from parity import say
+
+pytestmark = pytest.mark.gpu
+
+HYPER = dict(nu=1e-3, rho=1e-3, tau0=1e-3, theta0=1e-3, eta=2.0, max_backtrack=60, fista_iters=10)
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import torch
+    from paper_2112_09335_amd import binding
+    w = synth.config(3, 0.03)        # N = 6000, 32 communities, degree 15: several tiles, ragged tails
+    s = binding.Solver(0)
+    s.build_graph(w.N, w.src, w.dst, w.M, w.comm)
+    s.set_model([512, 512, 512, 16], **HYPER)        # reserves scratch for the widest shapes below
+    s.set_workspace()
+    g = OracleGraph(w.N, w.src, w.dst, w.M, w.comm)
+    yield s, g, torch
+    s.close()
+
+
+def rel_err(got, ref):
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-300))
+
+
+@pytest.mark.parametrize("width", [1, 3, 7, 16, 64, 100, 128, 256, 500, 512, 1030])
+def test_aggregate_matches_sparse_product(ctx, width):
+    s, g, torch = ctx
+    say("aggregate width", width)
+    rng = np.random.default_rng(width)
+    X = rng.standard_normal((g.N, width)).astype(np.float32)
+    Y = s.op_aggregate(torch.from_numpy(X).cuda())
+    torch.cuda.synchronize()
+    ref = g.A @ X.astype(np.float64)
+    assert rel_err(Y.cpu().numpy().astype(np.float64), ref) < 2e-6
+
+
+def test_aggregate_is_exact_on_integers_scaled_by_the_values(ctx):
+    """With X = e_j (unit columns) the result reproduces the stored values of A~ bit for bit."""
+    s, g, torch = ctx
+    say("aggregate unit columns")
+    cols = [0, 17, g.N - 1]
+    X = np.zeros((g.N, 4), np.float32)
+    for k, j in enumerate(cols):
+        X[j, k] = 1.0
+    Y = s.op_aggregate(torch.from_numpy(X).cuda()).cpu().numpy()
+    A32 = g.A.astype(np.float32).toarray() if g.N <= 8000 else None
+    for k, j in enumerate(cols):
+        assert np.array_equal(Y[:, k], A32[:, j])
+
+
+@pytest.mark.parametrize("width", [3, 10, 16, 256])
+def test_aggregate_segments_matches_per_community_products(ctx, width):
+    s, g, torch = ctx
+    say("aggregate_segments width", width)
+    rng = np.random.default_rng(100 + width)
+    V = rng.standard_normal((g.N, width)).astype(np.float32)
+    P = s.op_aggregate_segments(torch.from_numpy(V).cuda()).cpu().numpy().astype(np.float64)
+    # the segments of a row partition its entries, so seg_ptr is the row pointer of an n_seg x N matrix
+    S = sp.csr_matrix((g.val, g.col, g.seg_ptr), shape=(g.n_segments, g.N))
+    ref = (S @ V.astype(np.float64))[s.get_segment_order()]
+    assert P.shape == ref.shape
+    assert rel_err(P, ref) < 2e-6
+    # summing a row's segments gives the full aggregation
+    full = np.zeros((g.N, width))
+    np.add.at(full, g.seg_row[s.get_segment_order()], P)
+    assert rel_err(full, g.A @ V.astype(np.float64)) < 2e-6
+
+
+@pytest.mark.parametrize("n,K,C", [(1000, 256, 256), (777, 500, 128), (300, 128, 3), (1000, 7, 64), (129, 16, 256),
+                                   (4100, 512, 512), (513, 10, 256), (2000, 256, 16), (64, 64, 64), (1, 5, 2)])
+def test_transform_matches_fp64_product(ctx, n, K, C):
+    s, g, torch = ctx
+    say("transform", n, K, C)
+    rng = np.random.default_rng(n + K + C)
+    A = rng.standard_normal((n, K)).astype(np.float32)
+    B = rng.standard_normal((K, C)).astype(np.float32)
+    out = s.op_transform(torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()).cpu().numpy().astype(np.float64)
+    ref = A.astype(np.float64) @ B.astype(np.float64)
+    assert rel_err(out, ref) < 1e-5
+
+
+@pytest.mark.parametrize("n,K,C", [(6000, 256, 256), (5000, 500, 128), (3000, 128, 3), (6000, 512, 512), (4097, 256, 16),
+                                   (100, 7, 5), (17, 300, 40)])
+def test_wgrad_matches_fp64_product(ctx, n, K, C):
+    s, g, torch = ctx
+    say("wgrad", n, K, C)
+    rng = np.random.default_rng(n + K + C + 1)
+    A = rng.standard_normal((n, K)).astype(np.float32)
+    G = rng.standard_normal((n, C)).astype(np.float32)
+    out = s.op_wgrad(torch.from_numpy(A).cuda(), torch.from_numpy(G).cuda()).cpu().numpy().astype(np.float64)
+    ref = A.astype(np.float64).T @ G.astype(np.float64)
+    assert rel_err(out, ref) < 1e-5
