@@ -42,8 +42,14 @@ def relu(x):
     return np.maximum(x, 0.0)
 
 
+# ReLU'(x) = 1[x > RELU_TIE_SHIFT].  The value is 0 (the reading ReLU'(0) = 0).  Tests move it by a
+# few fp32 roundings to ask what the iterate would be had a pre-activation that is zero up to rounding
+# fallen on the other side: the derivative of the penalty jumps there, so both outcomes are valid.
+RELU_TIE_SHIFT = 0.0
+
+
 def relu_grad(x):
-    return (x > 0.0).astype(np.float64)
+    return (x > RELU_TIE_SHIFT).astype(np.float64)
 
 
 def inner(a, b):
@@ -372,6 +378,25 @@ class AdmmOracle:
         F = risk + sum(pen)
         return dict(objective=F, lagrangian=F + phiL, risk=risk, primal_res=primal, dual_res=dual,
                     layer_penalty=pen, iter=self.k, status=self.status)
+
+    # ------------------------------------------------------------------ snapshot / restore (tests)
+    def snapshot(self):
+        return dict(W=[None] + [w.copy() for w in self.W[1:]], Z=[z.copy() for z in self.Z], U=self.U.copy(),
+                    tau=list(self.tau), theta=[None] + [list(t) for t in self.theta[1:]], k=self.k,
+                    status=self.status, TL_prev=None if self.TL_prev is None else self.TL_prev.copy(),
+                    trials_W=list(self.trials_W), trials_Z=[None] + [list(t) for t in self.trials_Z[1:]])
+
+    def restore(self, snap):
+        snap = dict(snap)
+        self.W = [None] + [w.copy() for w in snap["W"][1:]]
+        self.Z = [z.copy() for z in snap["Z"]]
+        self.U = snap["U"].copy()
+        self.tau = list(snap["tau"])
+        self.theta = [None] + [list(t) for t in snap["theta"][1:]]
+        self.k, self.status = snap["k"], snap["status"]
+        self.TL_prev = None if snap["TL_prev"] is None else snap["TL_prev"].copy()
+        self.trials_W = list(snap["trials_W"])
+        self.trials_Z = [None] + [list(t) for t in snap["trials_Z"][1:]]
 
     # ------------------------------------------------------------------ accessors (caller's node order)
     def get_W(self, l):

@@ -50,6 +50,9 @@ def load_library():
     if not os.path.exists(_LIB_PATH):
         raise CadmmError(f"{_LIB_PATH} is missing: run `python __graft_entry__.py` (build) first; "
                          "there is no fallback path")
+    # PyTorch ships its own copy of the HIP runtime.  Load it first so that this library binds to the
+    # same runtime instance: two HIP runtimes in one process do not both see the GPU.
+    import torch  # noqa: F401
     lib = C.CDLL(_LIB_PATH)
     for name in EXPORTS:
         if not hasattr(lib, name):

@@ -27,6 +27,41 @@ def close(name, got, ref, floor=0.0):
     return fro / max(np.linalg.norm(ref), 1e-300)
 
 
+def step_with_relu_ties(solver, orc, tag):
+    """One more iteration on both sides, then compare.  If they disagree, ask whether a ReLU tie explains
+    it: the gradient of the penalty nu/2 ||Z - relu(T)||^2 jumps where a pre-activation T crosses 0, so
+    an entry that is zero up to fp32 rounding may fall on either side.  The oracle's iteration is
+    repeated from the same state with the threshold of ReLU' moved by +-delta (a few fp32 roundings of
+    the pre-activation scale); the GPU result must then match one of these equally valid outcomes to
+    the same tolerance.  Returns (worst relative error, tie used?)."""
+    import oracle.admm as oa
+    snap = orc.snapshot()
+    solver.run(1)
+    orc.iterate(1)
+    try:
+        return compare_iterate(solver, orc, tag), False
+    except AssertionError as first:
+        # fp32 rounding of a pre-activation of size ~scale is a few 1e-7 * scale; a finer-to-coarser ladder
+        # so that only the entry nearest to zero changes side first
+        scale = max(1.0, max(float(np.sqrt(np.mean(z * z))) for z in snap["Z"][1:]))
+        ladder = [sgn * m * 1e-7 * scale for m in (1, 2, 4, 8, 16, 32) for sgn in (+1, -1)]
+        for shift in ladder:
+            orc.restore(snap)
+            oa.RELU_TIE_SHIFT = shift
+            try:
+                orc.iterate(1)
+            finally:
+                oa.RELU_TIE_SHIFT = 0.0
+            try:
+                worst = compare_iterate(solver, orc, tag + f" [relu tie shift {shift:+.1e}]")
+                say(f"{tag}: ReLU tie, matches the oracle with threshold {shift:+.2e}; first mismatch was: "
+                    f"{str(first).splitlines()[0][:160]}")
+                return worst, True
+            except AssertionError:
+                continue
+        raise first
+
+
 def compare_iterate(solver, orc, tag):
     """W, Z, U, objective, residuals and the step-size trajectory after one more iteration."""
     L = orc.L

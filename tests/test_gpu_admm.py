@@ -7,23 +7,25 @@ import pytest
 
 from oracle.admm import make_oracle
 from paper_2112_09335_amd import synth
-from parity import compare_iterate, say
+from parity import compare_iterate, say, step_with_relu_ties
 
 pytestmark = pytest.mark.gpu
 
 
-def run_case(w, iters, tag):
+def run_case(w, iters, tag, max_ties=1):
     from paper_2112_09335_amd import binding
     say(f"[{tag}] N={w.N} M={w.M} dims={w.dims} E={w.E} iters={iters}")
     solver = binding.Solver.from_workload(w, 0)
     orc = make_oracle(w)
     worst = compare_iterate(solver, orc, f"{tag} it0")
+    ties = 0
     for k in range(1, iters + 1):
-        solver.run(1)
-        orc.iterate(1)
-        worst = max(worst, compare_iterate(solver, orc, f"{tag} it{k}"))
+        err, tie = step_with_relu_ties(solver, orc, f"{tag} it{k}")
+        worst = max(worst, err)
+        ties += int(tie)
         say(f"[{tag}] it{k} ok, worst rel err so far {worst:.2e}")
     solver.close()
+    assert ties <= max_ties, f"{ties} ReLU ties in {iters} iterations"
     return worst
 
 
