@@ -1,0 +1,160 @@
+#!/usr/bin/env python3
+"""Benchmark of the ADMM sweep on one MI355X.
+
+A "step" is one full ADMM iteration (W-update, Z-update for every layer and community, last-layer
+solve, dual step) on a synthetic SBM workload already resident in HBM.  Prints ONE JSON line:
+ADMM iterations/s for the whole job, the roofline of the dominant kernel class measured live with
+HIP events on the library's stream, and the CPU oracle timed on a bounded sample of the same recipe.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1..5] [--scale S]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# published MI355X peaks
+HBM_PEAK_GBS = 8000.0
+MFMA_FP32_PEAK_TFLOPS = 157.3
+
+# which roofline bounds a kernel class
+BOUND = {"spmm_rows": "hbm", "spmm_rows_gradz": "hbm", "spmm_segments": "hbm", "gemm_nn_wide": "mfma",
+         "gemm_nn_narrow": "hbm", "gemm_tn": "mfma", "phi_G": "hbm", "G_only": "hbm", "w_trial": "hbm",
+         "z_trial": "hbm", "step": "hbm", "last_layer": "hbm", "other": "hbm"}
+
+# CPU-oracle sample: (scale of N, iterations) per workload, sized for about 10-30 s of host time
+ORACLE_SAMPLE = {1: (1.0, 10), 2: (0.25, 4), 3: (0.02, 3), 4: (0.004, 3), 5: (0.004, 2)}
+
+
+def roofline_entry(name, p):
+    sec = p["ms"] * 1e-3
+    if sec <= 0 or p["records"] == 0:
+        return None
+    per_launch_ms = p["ms"] / p["records"]
+    if BOUND[name] == "mfma":
+        ach = p["flops"] / sec / 1e12
+        return dict(kernel=name, bound="mfma", achieved=ach, peak=MFMA_FP32_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=ach / MFMA_FP32_PEAK_TFLOPS, traffic=None, avg_launch_ms=per_launch_ms,
+                    launches=p["records"], share_of_step=None)
+    ach = p["bytes"] / sec / 1e9
+    return dict(kernel=name, bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
+                traffic=None, avg_launch_ms=per_launch_ms, launches=p["records"], share_of_step=None)
+
+
+def cpu_baseline(index, full_N, full_nnz):
+    """The oracle as it stands, on a smaller instance of the same recipe, extrapolated linearly in nnz."""
+    from threadpoolctl import threadpool_info
+    from oracle.admm import make_oracle
+    from paper_2112_09335_amd import synth
+    scale, iters = ORACLE_SAMPLE[index]
+    w = synth.config(index, scale)
+    orc = make_oracle(w)
+    orc.iterate(1)                       # first iteration is atypical (zero gradients at the forward-pass start)
+    t0 = time.perf_counter()
+    orc.iterate(iters)
+    dt = time.perf_counter() - t0
+    its = iters / dt
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    est_full = its * (orc.g.nnz / float(full_nnz))
+    return dict(value=est_full, unit="iterations/s", cores=int(threads), kind="oracle",
+                sample=(f"{w.name} recipe at N={w.N} (scale {scale}), M={w.M}, nnz={orc.g.nnz}: {iters} oracle "
+                        f"iterations in {dt:.1f} s = {its:.3f} it/s on the sample; value = that rate x "
+                        f"nnz_sample/nnz_full (linear extrapolation to N={full_N})"),
+                sample_iterations_per_s=its)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=4, help="index into BASELINE.json configs, 1-based")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink N (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding or collectives are part of it); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2112_09335_amd import binding, synth
+
+    t0 = time.perf_counter()
+    w = synth.config(args.workload, args.scale)
+    t_gen = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    solver = binding.Solver.from_workload(w, 0)
+    torch.cuda.synchronize()
+    t_setup = time.perf_counter() - t0
+    nnz, nseg, nhalo = solver.graph_sizes()
+    print(f"# workload {w.name}: N={w.N} M={w.M} E={w.E} nnz={nnz} segments={nseg} halo_rows={nhalo} "
+          f"dims={w.dims}; generated in {t_gen:.1f} s, built+uploaded+initialised in {t_setup:.1f} s, "
+          f"workspace {solver.workspace_bytes() / 2**30:.2f} GiB", file=sys.stderr, flush=True)
+
+    solver.run(args.warmup)
+    torch.cuda.synchronize()
+    # timed region 1: the plain run, nothing but the sweep on the stream
+    t0 = time.perf_counter()
+    solver.run(args.steps)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    # timed region 2: the same number of steps with every launch group bracketed by HIP events
+    solver.profile(True)
+    t0 = time.perf_counter()
+    solver.run(args.steps)
+    prof = solver.get_profile()          # synchronises
+    dt_prof = time.perf_counter() - t0
+    solver.profile(False)
+    stats = solver.eval()
+
+    total_ms = sum(p["ms"] for p in prof.values())
+    entries = []
+    for name, p in prof.items():
+        e = roofline_entry(name, p)
+        if e is not None:
+            e["share_of_step"] = p["ms"] / total_ms if total_ms > 0 else None
+            entries.append(e)
+    entries.sort(key=lambda e: -e["share_of_step"])
+    dominant = dict(entries[0]) if entries else None
+    spmm_ms = sum(prof[k]["ms"] for k in ("spmm_rows", "spmm_rows_gradz", "spmm_segments"))
+    spmm_bytes = sum(prof[k]["bytes"] for k in ("spmm_rows", "spmm_rows_gradz", "spmm_segments"))
+    spmm_flops = sum(prof[k]["flops"] for k in ("spmm_rows", "spmm_rows_gradz", "spmm_segments"))
+
+    out = {
+        "metric": "ADMM iterations/sec (all layers+communities)",
+        "value": args.steps / dt,
+        "unit": "iterations/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": 1e3 * dt / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{args.workload - 1}] {w.name}", "N": w.N, "communities": w.M,
+                   "edges": w.E, "nnz": nnz, "layers": w.L, "widths": w.dims, "scale": args.scale},
+        "roofline": None if dominant is None else {k: dominant[k] for k in
+                                                   ("bound", "achieved", "peak", "unit", "frac", "traffic")},
+        "dominant_kernel": None if dominant is None else dominant["kernel"],
+        "kernels": entries,
+        "spmm": {"achieved_GBs": spmm_bytes / (spmm_ms * 1e-3) / 1e9 if spmm_ms > 0 else None,
+                 "frac_of_hbm_peak": spmm_bytes / (spmm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if spmm_ms > 0 else None,
+                 "edges_features_per_s": 0.5 * spmm_flops / (spmm_ms * 1e-3) if spmm_ms > 0 else None},
+        "ms_per_step_with_event_timing": 1e3 * dt_prof / args.steps,
+        "objective": stats["objective"], "primal_res": stats["primal_res"], "status": stats["status"],
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload, w.N, nnz)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

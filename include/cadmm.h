@@ -13,7 +13,7 @@
  *     written into caller memory.
  *   - All device memory the library uses comes from ONE caller-provided workspace
  *     (cadmm_workspace_bytes / cadmm_set_workspace).  The library never calls hipMalloc for
- *     device memory; it allocates only small pinned host buffers for readouts.
+ *     device memory; it allocates only small host buffers (readouts, the host copy of the graph).
  *   - Node order at the boundary is the caller's.  Internally nodes are renumbered so that
  *     every community is a contiguous row range (stable sort on (community, id)); that
  *     numbering is visible through cadmm_get_graph and is the row order of the cadmm_op_*
@@ -165,6 +165,19 @@ int  cadmm_op_transform(cadmm_ctx* ctx, const float* A, int64_t n, int32_t K, co
                         int32_t C, float* out);
 int  cadmm_op_wgrad(cadmm_ctx* ctx, const float* A, const float* G, int64_t n, int32_t K,
                     int32_t C, float* out);
+
+/*
+ * Per-kernel-class timing for benchmarks (no counterpart in the paper).  cadmm_profile(ctx, 1) clears
+ * the counters and makes every later launch group be bracketed by a pair of HIP events on the
+ * context's stream; cadmm_profile(ctx, 0) stops that.  cadmm_get_profile synchronises and returns,
+ * per class (host arrays of CADMM_PROFILE_CLASSES entries, any may be NULL): elapsed milliseconds,
+ * number of timed launch groups, and the algorithmic bytes and flops booked for them (what the
+ * operation must move / compute: operands read once, results written once).
+ */
+#define CADMM_PROFILE_CLASSES 13
+int  cadmm_profile(cadmm_ctx* ctx, int enable);
+int  cadmm_get_profile(cadmm_ctx* ctx, double* ms, int64_t* records, double* bytes, double* flops);
+const char* cadmm_profile_class_name(int32_t cls);
 
 #ifdef __cplusplus
 }

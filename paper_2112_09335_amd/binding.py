@@ -22,7 +22,9 @@ EXPORTS = [
     "cadmm_set_workspace", "cadmm_set_data", "cadmm_init", "cadmm_run", "cadmm_eval", "cadmm_get_W",
     "cadmm_get_Z", "cadmm_get_U", "cadmm_get_steps", "cadmm_set_state", "cadmm_op_aggregate",
     "cadmm_op_aggregate_segments", "cadmm_op_transform", "cadmm_op_wgrad",
+    "cadmm_profile", "cadmm_get_profile", "cadmm_profile_class_name",
 ]
+PROFILE_CLASSES = 13
 
 
 class CadmmError(RuntimeError):
@@ -83,6 +85,10 @@ def load_library():
     lib.cadmm_op_aggregate_segments.argtypes = [vp, vp, i32, vp]
     lib.cadmm_op_transform.argtypes = [vp, vp, i64, i32, vp, i32, vp]
     lib.cadmm_op_wgrad.argtypes = [vp, vp, vp, i64, i32, i32, vp]
+    lib.cadmm_profile.argtypes = [vp, C.c_int]
+    lib.cadmm_get_profile.argtypes = [vp, vp, vp, vp, vp]
+    lib.cadmm_profile_class_name.argtypes = [i32]
+    lib.cadmm_profile_class_name.restype = C.c_char_p
     _lib = lib
     return lib
 
@@ -295,6 +301,21 @@ class Solver:
         out = torch.empty((A.shape[1], G.shape[1]), dtype=torch.float32, device=A.device)
         self._check(self.lib.cadmm_op_wgrad(self.h, C.c_void_p(A.data_ptr()), C.c_void_p(G.data_ptr()), A.shape[0],
                                             A.shape[1], G.shape[1], C.c_void_p(out.data_ptr())), "cadmm_op_wgrad")
+        return out
+
+    # ---- per-kernel-class timing
+    def profile(self, enable=True):
+        self._check(self.lib.cadmm_profile(self.h, 1 if enable else 0), "cadmm_profile")
+
+    def get_profile(self):
+        n = PROFILE_CLASSES
+        ms, rec = np.zeros(n, np.float64), np.zeros(n, np.int64)
+        by, fl = np.zeros(n, np.float64), np.zeros(n, np.float64)
+        self._check(self.lib.cadmm_get_profile(self.h, _ptr(ms), _ptr(rec), _ptr(by), _ptr(fl)), "cadmm_get_profile")
+        out = {}
+        for i in range(n):
+            name = self.lib.cadmm_profile_class_name(i).decode()
+            out[name] = dict(ms=float(ms[i]), records=int(rec[i]), bytes=float(by[i]), flops=float(fl[i]))
         return out
 
     # ---- convenience

@@ -63,6 +63,15 @@ struct cadmm_ctx {
     int32_t* status = nullptr;
     bool base_valid = false, have_prev = false, dual_valid = false;
     int iter = 0;
+    // optional per-kernel-class timing with HIP events on the context's stream
+    bool prof_on = false;
+    struct ProfRec { int cls; hipEvent_t a, b; };
+    std::vector<ProfRec> prof_recs;
+    std::vector<hipEvent_t> prof_pool;
+    double prof_ms[CADMM_PROFILE_CLASSES] = {0};
+    int64_t prof_launches[CADMM_PROFILE_CLASSES] = {0};
+    double prof_bytes[CADMM_PROFILE_CLASSES] = {0};
+    double prof_flops[CADMM_PROFILE_CLASSES] = {0};
 };
 
 namespace {
@@ -166,6 +175,51 @@ hipError_t upload(hipStream_t s, T* dst, const std::vector<T>& src) {
     return hipMemcpyAsync(dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice, s);
 }
 
+enum ProfClass {
+    P_SPMM = 0, P_SPMM_GRADZ, P_SPMM_SEG, P_GEMM_NN_WIDE, P_GEMM_NN_NARROW, P_GEMM_TN, P_PHI_G, P_G_ONLY,
+    P_W_TRIAL, P_Z_TRIAL, P_STEP, P_LAST_LAYER, P_OTHER
+};
+const char* kProfNames[CADMM_PROFILE_CLASSES] = {
+    "spmm_rows", "spmm_rows_gradz", "spmm_segments", "gemm_nn_wide", "gemm_nn_narrow", "gemm_tn", "phi_G",
+    "G_only", "w_trial", "z_trial", "step", "last_layer", "other"};
+
+hipEvent_t prof_event(cadmm_ctx* c) {
+    if (!c->prof_pool.empty()) {
+        hipEvent_t e = c->prof_pool.back();
+        c->prof_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+// Times the launches enqueued by `body` as one record of class `cls` and books its algorithmic work.
+template <class F>
+void timed(cadmm_ctx* c, int cls, double bytes, double flops, F body) {
+    if (!c->prof_on) { body(); return; }
+    hipEvent_t a = prof_event(c), b = prof_event(c);
+    if (a && b) (void)hipEventRecord(a, c->stream);
+    body();
+    if (a && b) {
+        (void)hipEventRecord(b, c->stream);
+        c->prof_recs.push_back({cls, a, b});
+        c->prof_bytes[cls] += bytes;
+        c->prof_flops[cls] += flops;
+    }
+}
+
+double spmm_bytes(const cadmm_ctx* c, int64_t out_rows, int width, int extra_reads) {
+    // entries (column id + value), row bounds, one read of the gathered matrix, one write of the result
+    return 8.0 * (double)c->hg.nnz + 16.0 * (double)out_rows + 4.0 * (double)c->hg.N * width +
+           4.0 * (double)out_rows * width * (1 + extra_reads);
+}
+
+void gemm_nn(cadmm_ctx* c, const float* A, const float* B, float* out, int64_t n, int K, int C) {
+    timed(c, C > 32 ? P_GEMM_NN_WIDE : P_GEMM_NN_NARROW, 4.0 * ((double)n * K + (double)K * C + (double)n * C),
+          2.0 * (double)n * K * C, [&] { launch_gemm_nn(c->stream, A, B, out, n, K, C); });
+}
+
 SearchParams search_params(const cadmm_ctx* c) {
     SearchParams sp;
     sp.nu = c->nu;
@@ -176,7 +230,10 @@ SearchParams search_params(const cadmm_ctx* c) {
 }
 
 void aggregate(cadmm_ctx* c, const float* X, float* Y, int width, const SpmmEpilogue& epi) {
-    launch_spmm(c->stream, c->d_row_ptr, c->d_row_ptr + 1, c->d_col, c->d_val, X, Y, c->hg.N, width, epi);
+    timed(c, epi.kind ? P_SPMM_GRADZ : P_SPMM, spmm_bytes(c, c->hg.N, width, epi.kind ? 2 : 0),
+          2.0 * (double)c->hg.nnz * width, [&] {
+              launch_spmm(c->stream, c->d_row_ptr, c->d_row_ptr + 1, c->d_col, c->d_val, X, Y, c->hg.N, width, epi);
+          });
 }
 
 // H_l, T_l = H_l W_l, phi_l and G_l for every layer at the current iterate.  This is both the start
@@ -187,9 +244,12 @@ void base_eval(cadmm_ctx* c) {
     const int64_t N = c->hg.N;
     for (int l = 1; l <= L; ++l) {
         if (l >= 2) aggregate(c, c->Z[l - 1], c->H[l], c->C[l - 1], SpmmEpilogue());
-        launch_gemm_nn(c->stream, c->H[l], c->W[l], c->T[l], N, c->C[l - 1], c->C[l]);
-        launch_phi_G(c->stream, c->T[l], c->Z[l], c->U, c->G[l], l == L ? c->TLprev : nullptr, c->have_prev ? 1 : 0,
-                     N * c->C[l], l == L, c->nu, c->rho, c->partials, c->scalars + l);
+        gemm_nn(c, c->H[l], c->W[l], c->T[l], N, c->C[l - 1], c->C[l]);
+        const double cnt = (double)N * c->C[l];
+        timed(c, P_PHI_G, 4.0 * cnt * (l == L ? 6 : 3), 0.0, [&] {
+            launch_phi_G(c->stream, c->T[l], c->Z[l], c->U, c->G[l], l == L ? c->TLprev : nullptr,
+                         c->have_prev ? 1 : 0, N * c->C[l], l == L, c->nu, c->rho, c->partials, c->scalars + l);
+        });
     }
     c->dual_valid = c->have_prev;
     c->have_prev = true;
@@ -211,14 +271,20 @@ void sweep(cadmm_ctx* c) {
         const int64_t count = N * Cl;
         const int last = (l == L);
         Unit* unit = c->unitsW + (l - 1);
-        launch_gemm_tn(s, c->H[l], c->G[l], c->gradW, N, K, Cl, c->tn_partial);      // grad phi = H^T G
-        launch_w_norms(s, c->gradW, c->W[l], K * Cl, unit);
+        timed(c, P_GEMM_TN, 4.0 * ((double)N * K + (double)N * Cl + (double)K * Cl), 2.0 * (double)N * K * Cl,
+              [&] { launch_gemm_tn(s, c->H[l], c->G[l], c->gradW, N, K, Cl, c->tn_partial); });   // grad phi = H^T G
+        timed(c, P_OTHER, 8.0 * K * Cl, 0.0, [&] { launch_w_norms(s, c->gradW, c->W[l], K * Cl, unit); });
         float* Q = c->G[l];                                                          // G_l is no longer needed
-        launch_gemm_nn(s, c->H[l], c->gradW, Q, N, K, Cl);                           // T(W - g/tau) = T - Q/tau
-        launch_w_trial(s, c->T[l], Q, c->Z[l], c->U, count, last, 1, sp, unit, c->partials, c->status);
-        for (int p = 0; p < more_passes; ++p)
-            launch_w_trial(s, c->T[l], Q, c->Z[l], c->U, count, last, kMaxCand, sp, unit, c->partials, c->status);
-        launch_w_step(s, c->W[l], c->gradW, K * Cl, c->T[l], Q, count, unit);        // W^{k+1}; T_l = A~ Z^k W^{k+1}
+        gemm_nn(c, c->H[l], c->gradW, Q, N, K, Cl);                                  // T(W - g/tau) = T - Q/tau
+        // one pass reads T0, Q, Z_l (and U for the last layer); passes after an accepted one return at once
+        timed(c, P_W_TRIAL, 4.0 * (double)count * (last ? 4 : 3), 0.0, [&] {
+            launch_w_trial(s, c->T[l], Q, c->Z[l], c->U, count, last, 1, sp, unit, c->partials, c->status);
+            for (int p = 0; p < more_passes; ++p)
+                launch_w_trial(s, c->T[l], Q, c->Z[l], c->U, count, last, kMaxCand, sp, unit, c->partials, c->status);
+        });
+        timed(c, P_STEP, 4.0 * (3.0 * (double)count + 3.0 * K * Cl), 0.0, [&] {
+            launch_w_step(s, c->W[l], c->gradW, K * Cl, c->T[l], Q, count, unit);    // W^{k+1}; T_l = A~ Z^k W^{k+1}
+        });
     }
 
     // ---- Z-update, hidden layers, every community from (W^{k+1}, Z^k, U^k)   (Appendix A, Eqs. 3, 4, 6-8)
@@ -228,15 +294,19 @@ void sweep(cadmm_ctx* c) {
         const int Cl = c->C[l], Cn = c->C[l + 1];
         const int next_last = (l + 1 == L);
         Unit* units = c->unitsZ + (size_t)(l - 1) * M;
-        launch_G_only(s, c->T[l + 1], c->Z[l + 1], c->U, c->G[l + 1], N * Cn, next_last, c->nu, c->rho);
-        launch_transpose(s, c->W[l + 1], c->Wt, Cl, Cn);
-        launch_gemm_nn(s, c->G[l + 1], c->Wt, c->tmpA, N, Cn, Cl);                   // G_{l+1} W_{l+1}^T
+        timed(c, P_G_ONLY, 4.0 * (double)N * Cn * (next_last ? 4 : 3), 0.0, [&] {
+            launch_G_only(s, c->T[l + 1], c->Z[l + 1], c->U, c->G[l + 1], N * Cn, next_last, c->nu, c->rho);
+        });
+        timed(c, P_OTHER, 8.0 * Cl * Cn, 0.0, [&] { launch_transpose(s, c->W[l + 1], c->Wt, Cl, Cn); });
+        gemm_nn(c, c->G[l + 1], c->Wt, c->tmpA, N, Cn, Cl);                          // G_{l+1} W_{l+1}^T
         SpmmEpilogue epi;
         epi.kind = 1; epi.Zl = c->Z[l]; epi.Tl = c->T[l]; epi.nu = c->nu;
         aggregate(c, c->tmpA, c->tmpB, Cl, epi);                                     // grad psi, all communities
-        launch_gemm_nn(s, c->tmpB, c->W[l + 1], c->tmpV, N, Cl, Cn);                 // grad W_{l+1}
-        launch_spmm(s, c->d_segc_lo, c->d_segc_hi, c->d_col, c->d_val, c->tmpV, c->P, c->hg.n_seg, Cn,
-                    SpmmEpilogue());                                                 // A~_{r,m} (grad W) per segment
+        gemm_nn(c, c->tmpB, c->W[l + 1], c->tmpV, N, Cl, Cn);                        // grad W_{l+1}
+        timed(c, P_SPMM_SEG, spmm_bytes(c, c->hg.n_seg, Cn, 0), 2.0 * (double)c->hg.nnz * Cn, [&] {
+            launch_spmm(s, c->d_segc_lo, c->d_segc_hi, c->d_col, c->d_val, c->tmpV, c->P, c->hg.n_seg, Cn,
+                        SpmmEpilogue());                                             // A~_{r,m} (grad W) per segment
+        });
         launch_reset_units(s, units, M);
         ZTrialArgs a;
         a.chunk_unit = c->d_chunk_unit; a.chunk_kind = c->d_chunk_kind;
@@ -248,15 +318,23 @@ void sweep(cadmm_ctx* c) {
         a.Tn = c->T[l + 1]; a.Zn = c->Z[l + 1]; a.U = c->U; a.P = c->P; a.Cn = Cn;
         a.next_is_last = next_last;
         a.sp = sp; a.units = units; a.partials = c->partials; a.status = c->status;
-        a.first_pass = 1; a.ncand = 1;
-        launch_z_trial(s, a);
-        a.first_pass = 0; a.ncand = kMaxCand;
-        for (int p = 0; p < more_passes; ++p) launch_z_trial(s, a);
-        launch_z_step(s, c->Z[l], c->tmpB, c->d_row_comm, N, Cl, units);
+        // one pass reads Z_l, grad, T_l over the rows and T_{l+1}, Z_{l+1} (U), P over the segments
+        const double zt_bytes = 4.0 * (3.0 * (double)N * Cl + (next_last ? 4.0 : 3.0) * (double)c->hg.n_seg * Cn) +
+                                4.0 * (double)c->hg.n_seg;
+        timed(c, P_Z_TRIAL, zt_bytes, 0.0, [&] {
+            a.first_pass = 1; a.ncand = 1;
+            launch_z_trial(s, a);
+            a.first_pass = 0; a.ncand = kMaxCand;
+            for (int p = 0; p < more_passes; ++p) launch_z_trial(s, a);
+        });
+        timed(c, P_STEP, 4.0 * (3.0 * (double)N * Cl + (double)N), 0.0,
+              [&] { launch_z_step(s, c->Z[l], c->tmpB, c->d_row_comm, N, Cl, units); });
     }
 
     // ---- last layer Z_L (Eq. 5) and the dual step (Eq. 2), both from Z_L^k, U^k and T_L = A~ Z_{L-1}^k W_L^{k+1}
-    launch_last_layer(s, c->Z[L], c->U, c->T[L], c->d_labels, N, c->C[L], c->risk, c->rho, c->J);
+    timed(c, P_LAST_LAYER, 4.0 * (5.0 * (double)N * c->C[L] + (double)N), 0.0, [&] {
+        launch_last_layer(s, c->Z[L], c->U, c->T[L], c->d_labels, N, c->C[L], c->risk, c->rho, c->J);
+    });
     c->iter++;
     c->base_valid = false;
 }
@@ -307,7 +385,11 @@ int cadmm_create(cadmm_ctx** out, int device, void* hip_stream) {
 
 void cadmm_destroy(cadmm_ctx* ctx) {
     if (!ctx) return;
-    if (ctx->device >= 0) (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->device >= 0) {
+        (void)hipStreamSynchronize(ctx->stream);
+        for (auto& r : ctx->prof_recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+        for (auto e : ctx->prof_pool) (void)hipEventDestroy(e);
+    }
     delete ctx;
 }
 
@@ -582,6 +664,48 @@ int cadmm_set_state(cadmm_ctx* c, const float* const* W, const float* const* Z, 
     return CADMM_OK;
 }
 
+int cadmm_profile(cadmm_ctx* c, int enable) {
+    if (!c) return CADMM_EINVAL;
+    if (c->device < 0) return fail(c, CADMM_EUNSUPPORTED, "host-only context");
+    c->prof_on = enable != 0;
+    if (enable) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        for (auto& r : c->prof_recs) { c->prof_pool.push_back(r.a); c->prof_pool.push_back(r.b); }
+        c->prof_recs.clear();
+        for (int i = 0; i < CADMM_PROFILE_CLASSES; ++i) {
+            c->prof_ms[i] = 0; c->prof_launches[i] = 0; c->prof_bytes[i] = 0; c->prof_flops[i] = 0;
+        }
+    }
+    return CADMM_OK;
+}
+
+int cadmm_get_profile(cadmm_ctx* c, double* ms, int64_t* records, double* bytes, double* flops) {
+    if (!c) return CADMM_EINVAL;
+    if (c->device < 0) return fail(c, CADMM_EUNSUPPORTED, "host-only context");
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    for (auto& r : c->prof_recs) {
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, r.a, r.b) == hipSuccess) {
+            c->prof_ms[r.cls] += (double)t;
+            c->prof_launches[r.cls] += 1;
+        }
+        c->prof_pool.push_back(r.a);
+        c->prof_pool.push_back(r.b);
+    }
+    c->prof_recs.clear();
+    for (int i = 0; i < CADMM_PROFILE_CLASSES; ++i) {
+        if (ms) ms[i] = c->prof_ms[i];
+        if (records) records[i] = c->prof_launches[i];
+        if (bytes) bytes[i] = c->prof_bytes[i];
+        if (flops) flops[i] = c->prof_flops[i];
+    }
+    return CADMM_OK;
+}
+
+const char* cadmm_profile_class_name(int32_t cls) {
+    return (cls >= 0 && cls < CADMM_PROFILE_CLASSES) ? kProfNames[cls] : "";
+}
+
 int cadmm_op_aggregate(cadmm_ctx* c, const float* X, int32_t width, float* Y) {
     if (!c || !X || !Y || width < 1) return CADMM_EINVAL;
     if (!c->has_ws) return fail(c, CADMM_EORDER, "set_workspace first");
@@ -592,13 +716,15 @@ int cadmm_op_aggregate(cadmm_ctx* c, const float* X, int32_t width, float* Y) {
 int cadmm_op_aggregate_segments(cadmm_ctx* c, const float* V, int32_t width, float* P) {
     if (!c || !V || !P || width < 1) return CADMM_EINVAL;
     if (!c->has_ws) return fail(c, CADMM_EORDER, "set_workspace first");
-    launch_spmm(c->stream, c->d_segc_lo, c->d_segc_hi, c->d_col, c->d_val, V, P, c->hg.n_seg, width, SpmmEpilogue());
+    timed(c, P_SPMM_SEG, spmm_bytes(c, c->hg.n_seg, width, 0), 2.0 * (double)c->hg.nnz * width, [&] {
+        launch_spmm(c->stream, c->d_segc_lo, c->d_segc_hi, c->d_col, c->d_val, V, P, c->hg.n_seg, width, SpmmEpilogue());
+    });
     return check_launch(c, "op_aggregate_segments");
 }
 
 int cadmm_op_transform(cadmm_ctx* c, const float* A, int64_t n, int32_t K, const float* B, int32_t C, float* out) {
     if (!c || !A || !B || !out || n < 1 || K < 1 || C < 1) return CADMM_EINVAL;
-    launch_gemm_nn(c->stream, A, B, out, n, K, C);
+    gemm_nn(c, A, B, out, n, K, C);
     return check_launch(c, "op_transform");
 }
 
@@ -606,7 +732,8 @@ int cadmm_op_wgrad(cadmm_ctx* c, const float* A, const float* G, int64_t n, int3
     if (!c || !A || !G || !out || n < 1 || K < 1 || C < 1) return CADMM_EINVAL;
     if (!c->has_ws) return fail(c, CADMM_EORDER, "set_workspace first");
     if (gemm_tn_scratch_floats(n, K, C) > c->tn_partial_floats) return fail(c, CADMM_ENOMEM, "shape needs more scratch than the model reserved");
-    launch_gemm_tn(c->stream, A, G, out, n, K, C, c->tn_partial);
+    timed(c, P_GEMM_TN, 4.0 * ((double)n * K + (double)n * C + (double)K * C), 2.0 * (double)n * K * C,
+          [&] { launch_gemm_tn(c->stream, A, G, out, n, K, C, c->tn_partial); });
     return check_launch(c, "op_wgrad");
 }
 
