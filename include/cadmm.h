@@ -179,6 +179,11 @@ int  cadmm_profile(cadmm_ctx* ctx, int enable);
 int  cadmm_get_profile(cadmm_ctx* ctx, double* ms, int64_t* records, double* bytes, double* flops);
 const char* cadmm_profile_class_name(int32_t cls);
 
+/* Process-wide tuning knobs for experiments.  "spmm_tile_cols": feature columns handled per
+ * aggregation launch (0 = all at once); "spmm_xcd_remap": 1 = each XCD walks one contiguous eighth of
+ * the rows (default), 0 = blocks in plain order. */
+int  cadmm_tune(cadmm_ctx* ctx, const char* key, int32_t value);
+
 #ifdef __cplusplus
 }
 #endif

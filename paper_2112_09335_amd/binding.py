@@ -22,7 +22,7 @@ EXPORTS = [
     "cadmm_set_workspace", "cadmm_set_data", "cadmm_init", "cadmm_run", "cadmm_eval", "cadmm_get_W",
     "cadmm_get_Z", "cadmm_get_U", "cadmm_get_steps", "cadmm_set_state", "cadmm_op_aggregate",
     "cadmm_op_aggregate_segments", "cadmm_op_transform", "cadmm_op_wgrad",
-    "cadmm_profile", "cadmm_get_profile", "cadmm_profile_class_name",
+    "cadmm_profile", "cadmm_get_profile", "cadmm_profile_class_name", "cadmm_tune",
 ]
 PROFILE_CLASSES = 13
 
@@ -85,6 +85,7 @@ def load_library():
     lib.cadmm_op_aggregate_segments.argtypes = [vp, vp, i32, vp]
     lib.cadmm_op_transform.argtypes = [vp, vp, i64, i32, vp, i32, vp]
     lib.cadmm_op_wgrad.argtypes = [vp, vp, vp, i64, i32, i32, vp]
+    lib.cadmm_tune.argtypes = [vp, C.c_char_p, i32]
     lib.cadmm_profile.argtypes = [vp, C.c_int]
     lib.cadmm_get_profile.argtypes = [vp, vp, vp, vp, vp]
     lib.cadmm_profile_class_name.argtypes = [i32]
@@ -302,6 +303,9 @@ class Solver:
         self._check(self.lib.cadmm_op_wgrad(self.h, C.c_void_p(A.data_ptr()), C.c_void_p(G.data_ptr()), A.shape[0],
                                             A.shape[1], G.shape[1], C.c_void_p(out.data_ptr())), "cadmm_op_wgrad")
         return out
+
+    def tune(self, key, value):
+        self._check(self.lib.cadmm_tune(self.h, key.encode(), int(value)), "cadmm_tune")
 
     # ---- per-kernel-class timing
     def profile(self, enable=True):

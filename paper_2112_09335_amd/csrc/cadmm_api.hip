@@ -24,6 +24,10 @@ struct cadmm_ctx {
     // model
     int L = 0;
     std::vector<int> C;
+    // agg_first[l]: layer l forms T_l as A~ (Z_{l-1} W_l), aggregating on the narrow side C_l, instead of
+    // (A~ Z_{l-1}) W_l.  Its W-update then needs three aggregations of width C_l, so it pays if
+    // 3 C_l < C_{l-1}.  In those layers the slot H[l] holds A~ G_l (N x C_l).
+    std::vector<char> agg_first;
     int risk = 0, max_bt = 60, J = 10;
     float nu = 0, rho = 0, tau0 = 0, theta0 = 0, eta = 2;
     // workspace
@@ -44,6 +48,12 @@ struct cadmm_ctx {
     int32_t* d_chunk_end = nullptr;
     int32_t* d_unit_chunk_ptr = nullptr;
     int32_t* d_labels = nullptr;
+    // split rows of the CSR row list and of the segment list; side buffer for their parts
+    int64_t* d_lr_part_lo = nullptr; int64_t* d_lr_part_hi = nullptr;
+    int32_t* d_lr_row = nullptr; int32_t* d_lr_ptr = nullptr;
+    int64_t* d_ls_part_lo = nullptr; int64_t* d_ls_part_hi = nullptr;
+    int32_t* d_ls_row = nullptr; int32_t* d_ls_ptr = nullptr;
+    float* side = nullptr;
     // state and per-layer buffers, index l = 0..L (unused slots stay null)
     std::vector<float*> Z, W, H, T, G;
     float* U = nullptr;
@@ -130,6 +140,18 @@ size_t layout(cadmm_ctx* c, char* base) {
     c->d_chunk_end = b.take<int32_t>(nch);
     c->d_unit_chunk_ptr = b.take<int32_t>(g.M + 1);
     c->d_labels = b.take<int32_t>(N);
+    c->d_lr_part_lo = b.take<int64_t>(g.long_rows.n_parts());
+    c->d_lr_part_hi = b.take<int64_t>(g.long_rows.n_parts());
+    c->d_lr_row = b.take<int32_t>(g.long_rows.n_long());
+    c->d_lr_ptr = b.take<int32_t>(g.long_rows.n_long() + 1);
+    c->d_ls_part_lo = b.take<int64_t>(g.long_segs.n_parts());
+    c->d_ls_part_hi = b.take<int64_t>(g.long_segs.n_parts());
+    c->d_ls_row = b.take<int32_t>(g.long_segs.n_long());
+    c->d_ls_ptr = b.take<int32_t>(g.long_segs.n_long() + 1);
+    {
+        const int64_t np_ = g.long_rows.n_parts() > g.long_segs.n_parts() ? g.long_rows.n_parts() : g.long_segs.n_parts();
+        c->side = b.take<float>((size_t)np_ * max_of(c->C, 0, L));
+    }
     c->Z.assign(L + 1, nullptr);
     c->W.assign(L + 1, nullptr);
     c->H.assign(L + 1, nullptr);
@@ -138,7 +160,7 @@ size_t layout(cadmm_ctx* c, char* base) {
     for (int l = 0; l <= L; ++l) c->Z[l] = b.take<float>(N * c->C[l]);
     for (int l = 1; l <= L; ++l) {
         c->W[l] = b.take<float>((size_t)c->C[l - 1] * c->C[l]);
-        c->H[l] = b.take<float>(N * c->C[l - 1]);
+        c->H[l] = b.take<float>(N * (c->agg_first[l] ? c->C[l] : c->C[l - 1]));
         c->T[l] = b.take<float>(N * c->C[l]);
         c->G[l] = b.take<float>(N * c->C[l]);
     }
@@ -209,15 +231,37 @@ void timed(cadmm_ctx* c, int cls, double bytes, double flops, F body) {
     }
 }
 
+SpmmLong long_rows_of(const cadmm_ctx* c) {
+    SpmmLong lg;
+    lg.max_len = kSplitThreshold;
+    lg.n_parts = c->hg.long_rows.n_parts(); lg.part_lo = c->d_lr_part_lo; lg.part_hi = c->d_lr_part_hi;
+    lg.n_long = c->hg.long_rows.n_long(); lg.long_row = c->d_lr_row; lg.long_part_ptr = c->d_lr_ptr;
+    lg.side = c->side;
+    return lg;
+}
+
+SpmmLong long_segs_of(const cadmm_ctx* c) {
+    SpmmLong lg;
+    lg.max_len = kSplitThreshold;
+    lg.n_parts = c->hg.long_segs.n_parts(); lg.part_lo = c->d_ls_part_lo; lg.part_hi = c->d_ls_part_hi;
+    lg.n_long = c->hg.long_segs.n_long(); lg.long_row = c->d_ls_row; lg.long_part_ptr = c->d_ls_ptr;
+    lg.side = c->side;
+    return lg;
+}
+
 double spmm_bytes(const cadmm_ctx* c, int64_t out_rows, int width, int extra_reads) {
     // entries (column id + value), row bounds, one read of the gathered matrix, one write of the result
     return 8.0 * (double)c->hg.nnz + 16.0 * (double)out_rows + 4.0 * (double)c->hg.N * width +
            4.0 * (double)out_rows * width * (1 + extra_reads);
 }
 
-void gemm_nn(cadmm_ctx* c, const float* A, const float* B, float* out, int64_t n, int K, int C) {
-    timed(c, C > 32 ? P_GEMM_NN_WIDE : P_GEMM_NN_NARROW, 4.0 * ((double)n * K + (double)K * C + (double)n * C),
-          2.0 * (double)n * K * C, [&] { launch_gemm_nn(c->stream, A, B, out, n, K, C); });
+void gemm_nn(cadmm_ctx* c, const float* A, const float* B, float* out, int64_t n, int K, int C,
+             const GemmEpilogue& epi = GemmEpilogue()) {
+    // MFMA-bound when both widths fill a tile, otherwise bound by streaming the tall operand / result
+    const bool wide = C > 32 && K > 32;
+    timed(c, wide ? P_GEMM_NN_WIDE : P_GEMM_NN_NARROW,
+          4.0 * ((double)n * K + (double)K * C + (double)n * C * (epi.kind ? 3 : 1)), 2.0 * (double)n * K * C,
+          [&] { launch_gemm_nn(c->stream, A, B, out, n, K, C, epi); });
 }
 
 SearchParams search_params(const cadmm_ctx* c) {
@@ -232,8 +276,22 @@ SearchParams search_params(const cadmm_ctx* c) {
 void aggregate(cadmm_ctx* c, const float* X, float* Y, int width, const SpmmEpilogue& epi) {
     timed(c, epi.kind ? P_SPMM_GRADZ : P_SPMM, spmm_bytes(c, c->hg.N, width, epi.kind ? 2 : 0),
           2.0 * (double)c->hg.nnz * width, [&] {
-              launch_spmm(c->stream, c->d_row_ptr, c->d_row_ptr + 1, c->d_col, c->d_val, X, Y, c->hg.N, width, epi);
+              launch_spmm(c->stream, c->d_row_ptr, c->d_row_ptr + 1, c->d_col, c->d_val, X, Y, c->hg.N, width, epi,
+                          long_rows_of(c));
           });
+}
+
+// T_l = A~ Z_{l-1} W_l in the association chosen for the layer.  Used by the initial forward pass and
+// by every base evaluation, so that re-evaluating an unchanged point reproduces T_l bit for bit.
+void compute_T(cadmm_ctx* c, int l) {
+    const int64_t N = c->hg.N;
+    if (c->agg_first[l]) {
+        gemm_nn(c, c->Z[l - 1], c->W[l], c->tmpV, N, c->C[l - 1], c->C[l]);
+        aggregate(c, c->tmpV, c->T[l], c->C[l], SpmmEpilogue());
+    } else {
+        if (l >= 2) aggregate(c, c->Z[l - 1], c->H[l], c->C[l - 1], SpmmEpilogue());
+        gemm_nn(c, c->H[l], c->W[l], c->T[l], N, c->C[l - 1], c->C[l]);
+    }
 }
 
 // H_l, T_l = H_l W_l, phi_l and G_l for every layer at the current iterate.  This is both the start
@@ -243,8 +301,7 @@ void base_eval(cadmm_ctx* c) {
     const int L = c->L;
     const int64_t N = c->hg.N;
     for (int l = 1; l <= L; ++l) {
-        if (l >= 2) aggregate(c, c->Z[l - 1], c->H[l], c->C[l - 1], SpmmEpilogue());
-        gemm_nn(c, c->H[l], c->W[l], c->T[l], N, c->C[l - 1], c->C[l]);
+        compute_T(c, l);
         const double cnt = (double)N * c->C[l];
         timed(c, P_PHI_G, 4.0 * cnt * (l == L ? 6 : 3), 0.0, [&] {
             launch_phi_G(c->stream, c->T[l], c->Z[l], c->U, c->G[l], l == L ? c->TLprev : nullptr,
@@ -271,11 +328,25 @@ void sweep(cadmm_ctx* c) {
         const int64_t count = N * Cl;
         const int last = (l == L);
         Unit* unit = c->unitsW + (l - 1);
+        // grad phi = (A~ Z_{l-1})^T G_l = Z_{l-1}^T (A~ G_l)   (A~ is symmetric)
+        const float* left = c->H[l];
+        const float* right = c->G[l];
+        if (c->agg_first[l]) {
+            aggregate(c, c->G[l], c->H[l], Cl, SpmmEpilogue());
+            left = c->Z[l - 1];
+            right = c->H[l];
+        }
         timed(c, P_GEMM_TN, 4.0 * ((double)N * K + (double)N * Cl + (double)K * Cl), 2.0 * (double)N * K * Cl,
-              [&] { launch_gemm_tn(s, c->H[l], c->G[l], c->gradW, N, K, Cl, c->tn_partial); });   // grad phi = H^T G
+              [&] { launch_gemm_tn(s, left, right, c->gradW, N, K, Cl, c->tn_partial); });
         timed(c, P_OTHER, 8.0 * K * Cl, 0.0, [&] { launch_w_norms(s, c->gradW, c->W[l], K * Cl, unit); });
         float* Q = c->G[l];                                                          // G_l is no longer needed
-        gemm_nn(c, c->H[l], c->gradW, Q, N, K, Cl);                                  // T(W - g/tau) = T - Q/tau
+        // T(W - g/tau) = T - Q/tau with Q = A~ Z_{l-1} gradW
+        if (c->agg_first[l]) {
+            gemm_nn(c, c->Z[l - 1], c->gradW, c->tmpV, N, K, Cl);
+            aggregate(c, c->tmpV, Q, Cl, SpmmEpilogue());
+        } else {
+            gemm_nn(c, c->H[l], c->gradW, Q, N, K, Cl);
+        }
         // one pass reads T0, Q, Z_l (and U for the last layer); passes after an accepted one return at once
         timed(c, P_W_TRIAL, 4.0 * (double)count * (last ? 4 : 3), 0.0, [&] {
             launch_w_trial(s, c->T[l], Q, c->Z[l], c->U, count, last, 1, sp, unit, c->partials, c->status);
@@ -298,14 +369,23 @@ void sweep(cadmm_ctx* c) {
             launch_G_only(s, c->T[l + 1], c->Z[l + 1], c->U, c->G[l + 1], N * Cn, next_last, c->nu, c->rho);
         });
         timed(c, P_OTHER, 8.0 * Cl * Cn, 0.0, [&] { launch_transpose(s, c->W[l + 1], c->Wt, Cl, Cn); });
-        gemm_nn(c, c->G[l + 1], c->Wt, c->tmpA, N, Cn, Cl);                          // G_{l+1} W_{l+1}^T
-        SpmmEpilogue epi;
-        epi.kind = 1; epi.Zl = c->Z[l]; epi.Tl = c->T[l]; epi.nu = c->nu;
-        aggregate(c, c->tmpA, c->tmpB, Cl, epi);                                     // grad psi, all communities
+        // grad psi (all communities at once) = nu (Z_l - relu(T_l)) + A~ G_{l+1} W_{l+1}^T; aggregate on the
+        // narrower of the two widths, the penalty term rides in the epilogue of whichever kernel comes last
+        if (Cn < Cl) {
+            aggregate(c, c->G[l + 1], c->tmpA, Cn, SpmmEpilogue());                  // A~ G_{l+1}
+            GemmEpilogue ge;
+            ge.kind = 1; ge.Zl = c->Z[l]; ge.Tl = c->T[l]; ge.nu = c->nu;
+            gemm_nn(c, c->tmpA, c->Wt, c->tmpB, N, Cn, Cl, ge);
+        } else {
+            gemm_nn(c, c->G[l + 1], c->Wt, c->tmpA, N, Cn, Cl);                      // G_{l+1} W_{l+1}^T
+            SpmmEpilogue epi;
+            epi.kind = 1; epi.Zl = c->Z[l]; epi.Tl = c->T[l]; epi.nu = c->nu;
+            aggregate(c, c->tmpA, c->tmpB, Cl, epi);
+        }
         gemm_nn(c, c->tmpB, c->W[l + 1], c->tmpV, N, Cl, Cn);                        // grad W_{l+1}
         timed(c, P_SPMM_SEG, spmm_bytes(c, c->hg.n_seg, Cn, 0), 2.0 * (double)c->hg.nnz * Cn, [&] {
             launch_spmm(s, c->d_segc_lo, c->d_segc_hi, c->d_col, c->d_val, c->tmpV, c->P, c->hg.n_seg, Cn,
-                        SpmmEpilogue());                                             // A~_{r,m} (grad W) per segment
+                        SpmmEpilogue(), long_segs_of(c));                            // A~_{r,m} (grad W) per segment
         });
         launch_reset_units(s, units, M);
         ZTrialArgs a;
@@ -452,6 +532,8 @@ int cadmm_set_model(cadmm_ctx* c, const cadmm_model* m) {
     c->nu = m->nu; c->rho = m->rho; c->tau0 = m->tau0; c->theta0 = m->theta0; c->eta = m->eta;
     c->max_bt = m->max_backtrack;
     c->J = m->fista_iters;
+    c->agg_first.assign(c->L + 1, 0);
+    for (int l = 2; l <= c->L; ++l) c->agg_first[l] = (3 * c->C[l] < c->C[l - 1]) ? 1 : 0;
     c->has_model = true;
     return CADMM_OK;
 }
@@ -493,6 +575,14 @@ int cadmm_set_workspace(cadmm_ctx* c, void* dev_ptr, size_t bytes) {
     HIP_TRY(c, upload(s, c->d_chunk_begin, cb));
     HIP_TRY(c, upload(s, c->d_chunk_end, ce));
     HIP_TRY(c, upload(s, c->d_unit_chunk_ptr, g.unit_chunk_ptr));
+    HIP_TRY(c, upload(s, c->d_lr_part_lo, g.long_rows.part_lo));
+    HIP_TRY(c, upload(s, c->d_lr_part_hi, g.long_rows.part_hi));
+    HIP_TRY(c, upload(s, c->d_lr_row, g.long_rows.long_row));
+    HIP_TRY(c, upload(s, c->d_lr_ptr, g.long_rows.long_part_ptr));
+    HIP_TRY(c, upload(s, c->d_ls_part_lo, g.long_segs.part_lo));
+    HIP_TRY(c, upload(s, c->d_ls_part_hi, g.long_segs.part_hi));
+    HIP_TRY(c, upload(s, c->d_ls_row, g.long_segs.long_row));
+    HIP_TRY(c, upload(s, c->d_ls_ptr, g.long_segs.long_part_ptr));
     HIP_TRY(c, hipMemsetAsync(c->status, 0, 4 * sizeof(int32_t), s));
     HIP_TRY(c, hipStreamSynchronize(s));     // the host vectors above must outlive the copies
     c->has_ws = true;
@@ -530,8 +620,7 @@ int cadmm_init(cadmm_ctx* c, const float* const* W0) {
     }
     aggregate(c, c->Z[0], c->H[1], c->C[0], SpmmEpilogue());      // A~ Z_0 never changes
     for (int l = 1; l <= L; ++l) {
-        if (l >= 2) aggregate(c, c->Z[l - 1], c->H[l], c->C[l - 1], SpmmEpilogue());
-        launch_gemm_nn(s, c->H[l], c->W[l], c->T[l], N, c->C[l - 1], c->C[l]);
+        compute_T(c, l);
         launch_relu(s, c->T[l], c->Z[l], N * c->C[l], l < L);
     }
     HIP_TRY(c, hipMemsetAsync(c->U, 0, (size_t)N * c->C[L] * sizeof(float), s));
@@ -706,9 +795,17 @@ const char* cadmm_profile_class_name(int32_t cls) {
     return (cls >= 0 && cls < CADMM_PROFILE_CLASSES) ? kProfNames[cls] : "";
 }
 
+int cadmm_tune(cadmm_ctx* c, const char* key, int32_t value) {
+    if (!c || !key) return CADMM_EINVAL;
+    if (std::strcmp(key, "spmm_tile_cols") == 0) { set_spmm_tile_cols(value); return CADMM_OK; }
+    if (std::strcmp(key, "spmm_xcd_remap") == 0) { set_spmm_xcd_remap(value); return CADMM_OK; }
+    return fail(c, CADMM_EINVAL, "unknown tuning key");
+}
+
 int cadmm_op_aggregate(cadmm_ctx* c, const float* X, int32_t width, float* Y) {
     if (!c || !X || !Y || width < 1) return CADMM_EINVAL;
     if (!c->has_ws) return fail(c, CADMM_EORDER, "set_workspace first");
+    if (width > max_of(c->C, 0, c->L)) return fail(c, CADMM_ENOMEM, "width exceeds the widest layer the workspace was sized for");
     aggregate(c, X, Y, width, SpmmEpilogue());
     return check_launch(c, "op_aggregate");
 }
@@ -716,8 +813,10 @@ int cadmm_op_aggregate(cadmm_ctx* c, const float* X, int32_t width, float* Y) {
 int cadmm_op_aggregate_segments(cadmm_ctx* c, const float* V, int32_t width, float* P) {
     if (!c || !V || !P || width < 1) return CADMM_EINVAL;
     if (!c->has_ws) return fail(c, CADMM_EORDER, "set_workspace first");
+    if (width > max_of(c->C, 0, c->L)) return fail(c, CADMM_ENOMEM, "width exceeds the widest layer the workspace was sized for");
     timed(c, P_SPMM_SEG, spmm_bytes(c, c->hg.n_seg, width, 0), 2.0 * (double)c->hg.nnz * width, [&] {
-        launch_spmm(c->stream, c->d_segc_lo, c->d_segc_hi, c->d_col, c->d_val, V, P, c->hg.n_seg, width, SpmmEpilogue());
+        launch_spmm(c->stream, c->d_segc_lo, c->d_segc_hi, c->d_col, c->d_val, V, P, c->hg.n_seg, width, SpmmEpilogue(),
+                    long_segs_of(c));
     });
     return check_launch(c, "op_aggregate_segments");
 }

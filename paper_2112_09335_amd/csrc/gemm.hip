@@ -36,9 +36,12 @@ __device__ __forceinline__ float4 ld4_guard(const float* base, int64_t off, bool
 }
 
 // ------------------------------------------------------------------------------------------------ NN
-template <int BN>
+// EPI 1: out = nu * (Zl - relu(Tl)) + A B   (gradient of the Z subproblem, Appendix A)
+template <int BN, int EPI>
 __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ A, const float* __restrict__ B,
-                                                      float* __restrict__ out, int64_t n, int K, int C) {
+                                                      float* __restrict__ out, int64_t n, int K, int C,
+                                                      const float* __restrict__ Zl, const float* __restrict__ Tl,
+                                                      float nu) {
     constexpr int WN = (BN == 128) ? 2 : 1;       // waves along columns
     constexpr int WM = 4 / WN;                    // waves along rows
     constexpr int TM = BM / (WM * 32);            // 32x32 tiles per wave along rows
@@ -139,7 +142,11 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int64_t row = m0 + wm * TM * 32 + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
-                if (row < n) out[row * C + c] = acc[i][j][r];
+                if (row < n) {
+                    float v = acc[i][j][r];
+                    if constexpr (EPI == 1) v = nu * (Zl[row * C + c] - fmaxf(Tl[row * C + c], 0.f)) + v;
+                    out[row * C + c] = v;
+                }
             }
         }
 }
@@ -303,14 +310,23 @@ TnPlan tn_plan(int64_t n, int K, int C) {
 
 }  // namespace
 
-void launch_gemm_nn(hipStream_t s, const float* A, const float* B, float* out, int64_t n, int K, int C) {
+void launch_gemm_nn(hipStream_t s, const float* A, const float* B, float* out, int64_t n, int K, int C,
+                    const GemmEpilogue& epi) {
     if (n <= 0 || C <= 0) return;
     const int64_t mt = (n + BM - 1) / BM;
     if (C > 32) {
         const int ct = (C + 127) / 128;
-        hipLaunchKernelGGL((gemm_nn_kernel<128>), dim3((unsigned)(mt * ct)), dim3(256), 0, s, A, B, out, n, K, C);
+        dim3 grid((unsigned)(mt * ct));
+        if (epi.kind == 1)
+            hipLaunchKernelGGL((gemm_nn_kernel<128, 1>), grid, dim3(256), 0, s, A, B, out, n, K, C, epi.Zl, epi.Tl, epi.nu);
+        else
+            hipLaunchKernelGGL((gemm_nn_kernel<128, 0>), grid, dim3(256), 0, s, A, B, out, n, K, C, nullptr, nullptr, 0.f);
     } else {
-        hipLaunchKernelGGL((gemm_nn_kernel<32>), dim3((unsigned)mt), dim3(256), 0, s, A, B, out, n, K, C);
+        dim3 grid((unsigned)mt);
+        if (epi.kind == 1)
+            hipLaunchKernelGGL((gemm_nn_kernel<32, 1>), grid, dim3(256), 0, s, A, B, out, n, K, C, epi.Zl, epi.Tl, epi.nu);
+        else
+            hipLaunchKernelGGL((gemm_nn_kernel<32, 0>), grid, dim3(256), 0, s, A, B, out, n, K, C, nullptr, nullptr, 0.f);
     }
 }
 

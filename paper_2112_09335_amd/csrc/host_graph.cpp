@@ -25,6 +25,21 @@ void parallel_rows(int64_t n, F f) {
     for (auto& x : th) x.join();
 }
 
+void split_long(LongRows& lr, const int64_t* lo, const int64_t* hi, int64_t nrows) {
+    lr = LongRows();
+    lr.long_part_ptr.push_back(0);
+    for (int64_t r = 0; r < nrows; ++r) {
+        const int64_t len = hi[r] - lo[r];
+        if (len <= kSplitThreshold) continue;
+        for (int64_t p = lo[r]; p < hi[r]; p += kSplitPart) {
+            lr.part_lo.push_back(p);
+            lr.part_hi.push_back(p + kSplitPart < hi[r] ? p + kSplitPart : hi[r]);
+        }
+        lr.long_row.push_back((int32_t)r);
+        lr.long_part_ptr.push_back((int32_t)lr.part_lo.size());
+    }
+}
+
 }  // namespace
 
 std::string build_host_graph(HostGraph& g, int64_t N, int64_t n_edges, const int32_t* src,
@@ -180,6 +195,9 @@ std::string build_host_graph(HostGraph& g, int64_t N, int64_t n_edges, const int
             g.segc_row[(size_t)j] = g.seg_row[(size_t)s];
         }
     }
+
+    split_long(g.long_rows, g.row_ptr.data(), g.row_ptr.data() + 1, N);
+    split_long(g.long_segs, g.segc_lo.data(), g.segc_hi.data(), g.n_seg);
 
     // reduction chunks: for every community its own rows, then its segments
     g.unit_chunk_ptr.assign(M + 1, 0);

@@ -15,6 +15,20 @@ struct Chunk {
     int32_t end;     // one past the last
 };
 
+// Rows of a row list (CSR rows, or segments) that are too long for one lane group are cut into parts;
+// each part is aggregated like an ordinary row into a side buffer and the parts of a row are then
+// added in order (deterministic, no atomics).
+struct LongRows {
+    std::vector<int64_t> part_lo, part_hi;   // [n_parts] entry range of a part
+    std::vector<int32_t> long_row;           // [n_long] index of the split row in its row list
+    std::vector<int32_t> long_part_ptr;      // [n_long+1] parts of a split row
+    int64_t n_parts() const { return (int64_t)part_lo.size(); }
+    int64_t n_long() const { return (int64_t)long_row.size(); }
+};
+
+constexpr int kSplitThreshold = 384;   // rows with more entries are split ...
+constexpr int kSplitPart = 256;        // ... into parts of at most this many entries
+
 struct HostGraph {
     int64_t N = 0, E = 0, nnz = 0, n_seg = 0, n_halo_rows = 0;
     int32_t M = 0;
@@ -36,6 +50,8 @@ struct HostGraph {
     std::vector<int64_t> segc_hi;       // [n_seg] one past the last entry
     std::vector<int32_t> segc_row;      // [n_seg]
     std::vector<int64_t> segc_comm_ptr; // [M+1]
+    LongRows long_rows;                 // of the CSR rows
+    LongRows long_segs;                 // of the segments in (community, row) order
     // reduction chunks for the Z search, grouped by community
     std::vector<Chunk>   chunks;
     std::vector<int32_t> unit_chunk_ptr; // [M+1]

@@ -16,12 +16,37 @@ struct SpmmEpilogue {
     const float* Tl = nullptr;
     float nu = 0.f;
 };
+// Long rows (more than max_len entries) are skipped by the row kernel; their parts are aggregated into
+// `side` (n_parts x width) and added in order by a combine kernel, which also applies the epilogue.
+struct SpmmLong {
+    int max_len = 0;                 // 0 = no splitting
+    int64_t n_parts = 0;
+    const int64_t* part_lo = nullptr;
+    const int64_t* part_hi = nullptr;
+    int64_t n_long = 0;
+    const int32_t* long_row = nullptr;
+    const int32_t* long_part_ptr = nullptr;
+    float* side = nullptr;
+};
 void launch_spmm(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32_t* col, const float* val,
-                 const float* X, float* Y, int64_t nrows, int width, const SpmmEpilogue& epi);
+                 const float* X, float* Y, int64_t nrows, int width, const SpmmEpilogue& epi,
+                 const SpmmLong& lg);
+// columns of the feature matrix handled per launch (0 = all); smaller tiles keep a community's share of
+// the gathered matrix inside one XCD's L2 at the price of re-reading the entries once per tile
+void set_spmm_tile_cols(int cols);
+// 1: every XCD walks one contiguous eighth of the rows (default); 0: blocks in plain order
+void set_spmm_xcd_remap(int on);
 
 // ---------------------------------------------------------------- dense contractions (gemm.hip)
-// out[n x C] = A[n x K] * B[K x C]
-void launch_gemm_nn(hipStream_t s, const float* A, const float* B, float* out, int64_t n, int K, int C);
+// out[n x C] = A[n x K] * B[K x C];  epilogue 1: out = nu * (Zl - relu(Tl)) + A B
+struct GemmEpilogue {
+    int kind = 0;
+    const float* Zl = nullptr;
+    const float* Tl = nullptr;
+    float nu = 0.f;
+};
+void launch_gemm_nn(hipStream_t s, const float* A, const float* B, float* out, int64_t n, int K, int C,
+                    const GemmEpilogue& epi = GemmEpilogue());
 // out[K x C] = A[n x K]^T * G[n x C]; partial: scratch of gemm_tn_scratch_floats(n,K,C) floats.
 size_t gemm_tn_scratch_floats(int64_t n, int K, int C);
 void launch_gemm_tn(hipStream_t s, const float* A, const float* G, float* out, int64_t n, int K, int C,

@@ -19,11 +19,55 @@ def ctx():
     w = synth.config(3, 0.03)        # N = 6000, 32 communities, degree 15: several tiles, ragged tails
     s = binding.Solver(0)
     s.build_graph(w.N, w.src, w.dst, w.M, w.comm)
-    s.set_model([512, 512, 512, 16], **HYPER)        # reserves scratch for the widest shapes below
+    s.set_model([1030, 512, 512, 16], **HYPER)       # reserves scratch for the widest shapes below
     s.set_workspace()
     g = OracleGraph(w.N, w.src, w.dst, w.M, w.comm)
     yield s, g, torch
     s.close()
+
+
+@pytest.fixture(scope="module")
+def hub_ctx():
+    """A graph with hub rows far beyond the split threshold (a few nodes adjacent to thousands of others),
+    so that the split-row path of the aggregation (parts + ordered combine) is exercised, ragged sizes."""
+    import torch
+    from paper_2112_09335_amd import binding
+    rng = np.random.default_rng(77)
+    N, M = 5003, 5
+    comm = rng.integers(0, M, size=N).astype(np.int32)
+    src = [rng.integers(0, N, size=12000)]
+    dst = [rng.integers(0, N, size=12000)]
+    for hub, deg in ((0, 4000), (17, 1500), (N - 1, 385), (99, 384), (100, 383)):
+        nb = rng.choice(N, size=deg, replace=False)
+        src.append(np.full(deg, hub))
+        dst.append(nb)
+    src = np.concatenate(src).astype(np.int32)
+    dst = np.concatenate(dst).astype(np.int32)
+    s = binding.Solver(0)
+    s.build_graph(N, src, dst, M, comm)
+    s.set_model([300, 64, 16], **HYPER)
+    s.set_workspace()
+    g = OracleGraph(N, src, dst, M, comm)
+    assert np.diff(g.row_ptr).max() > 3000
+    yield s, g, torch
+    s.close()
+
+
+@pytest.mark.parametrize("width,tile", [(3, 0), (16, 0), (64, 0), (256, 0), (300, 0), (256, 32), (256, 64), (300, 128), (7, 4)])
+def test_aggregate_with_hub_rows_and_column_tiles(hub_ctx, width, tile):
+    s, g, torch = hub_ctx
+    say("hub aggregate width", width, "tile", tile)
+    rng = np.random.default_rng(width + tile)
+    X = rng.standard_normal((g.N, width)).astype(np.float32)
+    s.tune("spmm_tile_cols", tile)
+    try:
+        Y = s.op_aggregate(torch.from_numpy(X).cuda()).cpu().numpy().astype(np.float64)
+        P = s.op_aggregate_segments(torch.from_numpy(X).cuda()).cpu().numpy().astype(np.float64)
+    finally:
+        s.tune("spmm_tile_cols", 0)
+    assert rel_err(Y, g.A @ X.astype(np.float64)) < 3e-6
+    S = sp.csr_matrix((g.val, g.col, g.seg_ptr), shape=(g.n_segments, g.N))
+    assert rel_err(P, (S @ X.astype(np.float64))[s.get_segment_order()]) < 3e-6
 
 
 def rel_err(got, ref):
