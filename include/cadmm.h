@@ -181,7 +181,8 @@ const char* cadmm_profile_class_name(int32_t cls);
 
 /* Process-wide tuning knobs for experiments.  "spmm_tile_cols": feature columns handled per
  * aggregation launch (0 = all at once); "spmm_xcd_remap": 1 = each XCD walks one contiguous eighth of
- * the rows (default), 0 = blocks in plain order. */
+ * the rows, 0 = blocks in plain order (default); "spmm_groups_log2": lane groups that share one output
+ * row, as a power of two (-1 = chosen from the mean row length). */
 int  cadmm_tune(cadmm_ctx* ctx, const char* key, int32_t value);
 
 #ifdef __cplusplus

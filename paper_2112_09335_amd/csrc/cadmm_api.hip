@@ -237,6 +237,7 @@ SpmmLong long_rows_of(const cadmm_ctx* c) {
     lg.n_parts = c->hg.long_rows.n_parts(); lg.part_lo = c->d_lr_part_lo; lg.part_hi = c->d_lr_part_hi;
     lg.n_long = c->hg.long_rows.n_long(); lg.long_row = c->d_lr_row; lg.long_part_ptr = c->d_lr_ptr;
     lg.side = c->side;
+    lg.mean_len = (int)(c->hg.nnz / (c->hg.N > 0 ? c->hg.N : 1));
     return lg;
 }
 
@@ -246,6 +247,7 @@ SpmmLong long_segs_of(const cadmm_ctx* c) {
     lg.n_parts = c->hg.long_segs.n_parts(); lg.part_lo = c->d_ls_part_lo; lg.part_hi = c->d_ls_part_hi;
     lg.n_long = c->hg.long_segs.n_long(); lg.long_row = c->d_ls_row; lg.long_part_ptr = c->d_ls_ptr;
     lg.side = c->side;
+    lg.mean_len = (int)(c->hg.nnz / (c->hg.n_seg > 0 ? c->hg.n_seg : 1));
     return lg;
 }
 
@@ -799,6 +801,7 @@ int cadmm_tune(cadmm_ctx* c, const char* key, int32_t value) {
     if (!c || !key) return CADMM_EINVAL;
     if (std::strcmp(key, "spmm_tile_cols") == 0) { set_spmm_tile_cols(value); return CADMM_OK; }
     if (std::strcmp(key, "spmm_xcd_remap") == 0) { set_spmm_xcd_remap(value); return CADMM_OK; }
+    if (std::strcmp(key, "spmm_groups_log2") == 0) { set_spmm_groups_log2(value); return CADMM_OK; }
     return fail(c, CADMM_EINVAL, "unknown tuning key");
 }
 

@@ -20,6 +20,7 @@ struct SpmmEpilogue {
 // `side` (n_parts x width) and added in order by a combine kernel, which also applies the epilogue.
 struct SpmmLong {
     int max_len = 0;                 // 0 = no splitting
+    int mean_len = 0;                // mean entries per row of the row list (chooses the lane groups per row)
     int64_t n_parts = 0;
     const int64_t* part_lo = nullptr;
     const int64_t* part_hi = nullptr;
@@ -36,6 +37,8 @@ void launch_spmm(hipStream_t s, const int64_t* lo, const int64_t* hi, const int3
 void set_spmm_tile_cols(int cols);
 // 1: every XCD walks one contiguous eighth of the rows (default); 0: blocks in plain order
 void set_spmm_xcd_remap(int on);
+// lane groups per output row as a power of two (-1 = from the mean row length)
+void set_spmm_groups_log2(int v);
 
 // ---------------------------------------------------------------- dense contractions (gemm.hip)
 // out[n x C] = A[n x K] * B[K x C];  epilogue 1: out = nu * (Zl - relu(Tl)) + A B

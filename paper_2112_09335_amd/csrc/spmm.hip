@@ -6,13 +6,15 @@
 // grouped by community and a (row, community) segment is a contiguous entry range [lo, hi).
 // Features are row-major fp32.
 //
-// Mapping: a group of LPR lanes (a power of two, up to the 64-lane wavefront) owns one output row;
-// every lane keeps VEC*R accumulators, so a gathered neighbour row is read by the group with one
-// fully coalesced VEC*4-byte load per lane and no cross-lane reduction is needed.  The entry loop is
-// unrolled by four so that four independent row gathers are in flight per group.  The bound is HBM
-// / L2 traffic of the gathers.  Blocks are renumbered so that each XCD (blockIdx mod 8) walks one
-// contiguous eighth of the rows: neighbours are mostly in the same community, i.e. in the same
-// row range, and stay in that XCD's L2.
+// Mapping: a group of LPR lanes (a power of two, up to the 64-lane wavefront) reads one gathered
+// neighbour row with one fully coalesced VEC*4-byte load per lane and keeps VEC*R accumulators per lane.
+// GPR such groups share one output row and take its entries round-robin, four entries in flight per
+// group; their partial sums are added by a wavefront-level xor-shuffle reduction.  GPR follows the mean
+// row length, so short rows (segments) pack several rows into a wavefront and long rows spread over it.
+// Rows beyond a length threshold (power-law hubs) are cut into parts that run as extra rows of the same
+// launch into a side buffer; a small kernel adds a row's parts in order.  Everything is order-fixed:
+// no atomics, results are reproducible.  The bound is the L2 / HBM traffic of the gathers.
+// Blocks can be renumbered so that each XCD (blockIdx mod 8) walks one contiguous eighth of the rows.
 #include "kernels.h"
 
 namespace cadmm {
@@ -44,22 +46,39 @@ __device__ __forceinline__ void store_vec(float* p, const float (&src)[VEC]) {
 
 template <int VEC, int R, int EPI>
 __global__ __launch_bounds__(256) void spmm_rows_kernel(
-    const int64_t* __restrict__ lo, const int64_t* __restrict__ hi, const int32_t* __restrict__ col,
-    const float* __restrict__ val, const float* __restrict__ X, float* __restrict__ Y, int64_t nrows,
-    int width, int lpr_log2, int col0, int col1, int max_len, int xcd_remap, const float* __restrict__ Zl,
-    const float* __restrict__ Tl, float nu) {
-    // XCD-aware renumbering: gridDim.x is a multiple of 8
+    const int64_t* __restrict__ lo, const int64_t* __restrict__ hi, const int64_t* __restrict__ part_lo,
+    const int64_t* __restrict__ part_hi, int64_t nrows, int64_t nparts, const int32_t* __restrict__ col,
+    const float* __restrict__ val, const float* __restrict__ X, float* __restrict__ Y, float* __restrict__ side,
+    int width, int lpr_log2, int gpr_log2, int col0, int col1, int max_len, int xcd_remap,
+    const float* __restrict__ Zl, const float* __restrict__ Tl, float nu) {
+    // optional XCD-aware renumbering: gridDim.x is a multiple of 8
     const int per_xcd = gridDim.x >> 3;
     const int64_t lb = xcd_remap ? (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3) : (int64_t)blockIdx.x;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int rows_per_wave = 64 >> lpr_log2;
-    const int64_t row = (lb * 4 + wave) * rows_per_wave + (lane >> lpr_log2);
-    if (row >= nrows) return;
+    const int span_log2 = lpr_log2 + gpr_log2;          // lanes that share one output row
+    const int64_t vrow = ((lb * 4 + wave) << (6 - span_log2)) + (lane >> span_log2);
+    if (vrow >= nrows + nparts) return;                 // uniform over the row's lane span
     const int lpr = 1 << lpr_log2;
+    const int gpr = 1 << gpr_log2;
+    const int grp = (lane >> lpr_log2) & (gpr - 1);
     const int sub = lane & (lpr - 1);
-    const int cbase = col0 + sub * VEC;       // first column of repeat 0
-    const int cstride = lpr * VEC;            // columns between repeats
+    const int cbase = col0 + sub * VEC;                 // first column of repeat 0
+    const int cstride = lpr * VEC;                      // columns between repeats
+
+    int64_t p, e;
+    float* dst;
+    bool is_part = vrow >= nrows;
+    if (!is_part) {
+        p = lo[vrow];
+        e = hi[vrow];
+        if (max_len > 0 && e - p > max_len) return;     // split row: its parts follow in the same launch
+        dst = Y + vrow * (int64_t)width;
+    } else {
+        p = part_lo[vrow - nrows];
+        e = part_hi[vrow - nrows];
+        dst = side + (vrow - nrows) * (int64_t)width;
+    }
 
     float acc[R][VEC];
 #pragma unroll
@@ -67,22 +86,24 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[r][v] = 0.f;
 
-    int64_t p = lo[row];
-    const int64_t e = hi[row];
-    if (max_len > 0 && e - p > max_len) return;     // split row: its parts are handled separately
-    for (; p + 4 <= e; p += 4) {
+    // the groups of a row take entries p+grp, p+grp+gpr, ...; four of them in flight per group
+    for (int64_t q = p + grp; q < e; q += 4 * gpr) {
         int32_t c[4];
         float a[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) { c[u] = col[p + u]; a[u] = val[p + u]; }
+        for (int u = 0; u < 4; ++u) {
+            const int64_t qu = q + u * gpr;
+            const bool ok = qu < e;
+            c[u] = ok ? col[qu] : -1;
+            a[u] = ok ? val[qu] : 0.f;
+        }
         float x[4][R][VEC];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const float* xr = X + (int64_t)c[u] * width;
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int cc = cbase + r * cstride;
-                if (cc < col1) load_vec<VEC>(x[u][r], xr + cc);
+                if (c[u] >= 0 && cc < col1) load_vec<VEC>(x[u][r], X + (int64_t)c[u] * width + cc);
                 else {
 #pragma unroll
                     for (int v = 0; v < VEC; ++v) x[u][r][v] = 0.f;
@@ -96,40 +117,36 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) acc[r][v] = fmaf(a[u], x[u][r][v], acc[r][v]);
     }
-    for (; p < e; ++p) {
-        const int32_t c = col[p];
-        const float a = val[p];
-        const float* xr = X + (int64_t)c * width;
+    // wavefront-level reduction across the groups of the row
+    for (int off = lpr; off < (lpr << gpr_log2); off <<= 1) {
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int cc = cbase + r * cstride;
-            if (cc < col1) {
-                float x[VEC];
-                load_vec<VEC>(x, xr + cc);
+        for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) acc[r][v] = fmaf(a, x[v], acc[r][v]);
-            }
-        }
+            for (int v = 0; v < VEC; ++v) acc[r][v] += __shfl_xor(acc[r][v], off, 64);
     }
+    if (grp != 0) return;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int cc = cbase + r * cstride;
         if (cc < col1) {
-            const int64_t o = row * (int64_t)width + cc;
             if constexpr (EPI == 1) {
-                float z[VEC], t[VEC];
-                load_vec<VEC>(z, Zl + o);
-                load_vec<VEC>(t, Tl + o);
+                if (!is_part) {
+                    const int64_t o = vrow * (int64_t)width + cc;
+                    float z[VEC], t[VEC];
+                    load_vec<VEC>(z, Zl + o);
+                    load_vec<VEC>(t, Tl + o);
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) acc[r][v] = nu * (z[v] - fmaxf(t[v], 0.f)) + acc[r][v];
+                    for (int v = 0; v < VEC; ++v) acc[r][v] = nu * (z[v] - fmaxf(t[v], 0.f)) + acc[r][v];
+                }
             }
-            store_vec<VEC>(Y + o, acc[r]);
+            store_vec<VEC>(dst + cc, acc[r]);
         }
     }
 }
 
 int g_tile_cols = 0;
-int g_xcd_remap = 1;
+int g_xcd_remap = 0;
+int g_gpr_log2 = -1;      // -1: chosen from the mean row length
 
 // Adds the parts of every split row in part order and applies the epilogue.  One lane group per row.
 template <int VEC, int EPI>
@@ -167,32 +184,22 @@ __global__ __launch_bounds__(256) void spmm_combine_kernel(const float* __restri
 
 template <int VEC, int R>
 void launch_cfg(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32_t* col, const float* val,
-                const float* X, float* Y, int64_t nrows, int width, int lpr_log2, int col0, int col1, int max_len,
-                const SpmmEpilogue& epi) {
-    const int rows_per_block = 4 * (64 >> lpr_log2);
-    int64_t nb = (nrows + rows_per_block - 1) / rows_per_block;
+                const float* X, float* Y, int64_t nrows, int width, int lpr_log2, int gpr_log2, int col0, int col1,
+                const SpmmEpilogue& epi, const SpmmLong& lg, bool split) {
+    const int64_t nparts = split ? lg.n_parts : 0;
+    const int rows_per_block = 4 * (64 >> (lpr_log2 + gpr_log2));
+    int64_t nb = (nrows + nparts + rows_per_block - 1) / rows_per_block;
     nb = (nb + 7) / 8 * 8;
     dim3 grid((unsigned)nb), block(256);
+    const int max_len = split ? lg.max_len : 0;
     if (epi.kind == 1)
-        hipLaunchKernelGGL((spmm_rows_kernel<VEC, R, 1>), grid, block, 0, s, lo, hi, col, val, X, Y, nrows, width,
-                           lpr_log2, col0, col1, max_len, g_xcd_remap, epi.Zl, epi.Tl, epi.nu);
+        hipLaunchKernelGGL((spmm_rows_kernel<VEC, R, 1>), grid, block, 0, s, lo, hi, lg.part_lo, lg.part_hi, nrows,
+                           nparts, col, val, X, Y, lg.side, width, lpr_log2, gpr_log2, col0, col1, max_len,
+                           g_xcd_remap, epi.Zl, epi.Tl, epi.nu);
     else
-        hipLaunchKernelGGL((spmm_rows_kernel<VEC, R, 0>), grid, block, 0, s, lo, hi, col, val, X, Y, nrows, width,
-                           lpr_log2, col0, col1, max_len, g_xcd_remap, nullptr, nullptr, 0.f);
-}
-
-
-template <int VEC>
-void launch_tile(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32_t* col, const float* val,
-                 const float* X, float* Y, int64_t nrows, int width, int col0, int col1, int max_len,
-                 const SpmmEpilogue& epi) {
-    const int lanes_needed = (col1 - col0 + VEC - 1) / VEC;
-    int lpr_log2 = 0;
-    while ((1 << lpr_log2) < lanes_needed && lpr_log2 < 6) ++lpr_log2;
-    const int reps = (lanes_needed + (1 << lpr_log2) - 1) >> lpr_log2;
-    if (reps <= 1) launch_cfg<VEC, 1>(s, lo, hi, col, val, X, Y, nrows, width, lpr_log2, col0, col1, max_len, epi);
-    else if (reps <= 2) launch_cfg<VEC, 2>(s, lo, hi, col, val, X, Y, nrows, width, lpr_log2, col0, col1, max_len, epi);
-    else launch_cfg<VEC, 4>(s, lo, hi, col, val, X, Y, nrows, width, lpr_log2, col0, col1, max_len, epi);
+        hipLaunchKernelGGL((spmm_rows_kernel<VEC, R, 0>), grid, block, 0, s, lo, hi, lg.part_lo, lg.part_hi, nrows,
+                           nparts, col, val, X, Y, lg.side, width, lpr_log2, gpr_log2, col0, col1, max_len,
+                           g_xcd_remap, nullptr, nullptr, 0.f);
 }
 
 template <int VEC>
@@ -204,10 +211,19 @@ void launch_vec(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32
     const bool split = lg.max_len > 0 && lg.n_long > 0;
     for (int col0 = 0; col0 < width; col0 += tile) {
         const int col1 = (width - col0 < tile) ? width : col0 + tile;
-        launch_tile<VEC>(s, lo, hi, col, val, X, Y, nrows, width, col0, col1, split ? lg.max_len : 0, epi);
+        const int lanes_needed = (col1 - col0 + VEC - 1) / VEC;
+        int lpr_log2 = 0;
+        while ((1 << lpr_log2) < lanes_needed && lpr_log2 < 6) ++lpr_log2;
+        const int reps = (lanes_needed + (1 << lpr_log2) - 1) >> lpr_log2;
+        // lane groups per row: as many as the wavefront allows, but not more than about half the mean row length
+        int gpr_log2 = 0;
+        const int mean_len = lg.mean_len > 0 ? lg.mean_len : 1;
+        while (lpr_log2 + gpr_log2 < 6 && (2 << gpr_log2) < mean_len / 2) ++gpr_log2;
+        if (g_gpr_log2 >= 0) gpr_log2 = (lpr_log2 + g_gpr_log2 <= 6) ? g_gpr_log2 : 6 - lpr_log2;
+        if (reps <= 1) launch_cfg<VEC, 1>(s, lo, hi, col, val, X, Y, nrows, width, lpr_log2, gpr_log2, col0, col1, epi, lg, split);
+        else if (reps <= 2) launch_cfg<VEC, 2>(s, lo, hi, col, val, X, Y, nrows, width, lpr_log2, gpr_log2, col0, col1, epi, lg, split);
+        else launch_cfg<VEC, 4>(s, lo, hi, col, val, X, Y, nrows, width, lpr_log2, gpr_log2, col0, col1, epi, lg, split);
         if (split) {
-            launch_tile<VEC>(s, lg.part_lo, lg.part_hi, col, val, X, lg.side, lg.n_parts, width, col0, col1, 0,
-                             SpmmEpilogue());
             dim3 grid((unsigned)lg.n_long), block(64);
             if (epi.kind == 1)
                 hipLaunchKernelGGL((spmm_combine_kernel<VEC, 1>), grid, block, 0, s, lg.side, lg.long_row,
@@ -223,6 +239,7 @@ void launch_vec(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32
 
 void set_spmm_tile_cols(int cols) { g_tile_cols = cols > 0 ? cols : 0; }
 void set_spmm_xcd_remap(int on) { g_xcd_remap = on ? 1 : 0; }
+void set_spmm_groups_log2(int v) { g_gpr_log2 = v; }
 
 void launch_spmm(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32_t* col, const float* val,
                  const float* X, float* Y, int64_t nrows, int width, const SpmmEpilogue& epi, const SpmmLong& lg) {
