@@ -22,10 +22,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 MFMA_FP32_PEAK_TFLOPS = 157.3
 
-# which roofline bounds a kernel class
-BOUND = {"spmm_rows": "hbm", "spmm_rows_gradz": "hbm", "spmm_segments": "hbm", "gemm_nn_wide": "mfma",
-         "gemm_nn_narrow": "hbm", "gemm_tn": "mfma", "phi_G": "hbm", "G_only": "hbm", "w_trial": "hbm",
-         "z_trial": "hbm", "step": "hbm", "last_layer": "hbm", "other": "hbm"}
+# A kernel class is priced against the MFMA roofline if its arithmetic intensity (algorithmic flops per
+# algorithmic byte over the timed region) is above the machine balance, else against HBM bandwidth.
+MACHINE_BALANCE = MFMA_FP32_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)      # flop per byte
 
 # CPU-oracle sample: (scale of N, iterations) per workload, sized for about 10-30 s of host time
 ORACLE_SAMPLE = {1: (1.0, 10), 2: (0.25, 4), 3: (0.02, 3), 4: (0.004, 3), 5: (0.004, 2)}
@@ -36,7 +35,7 @@ def roofline_entry(name, p):
     if sec <= 0 or p["records"] == 0:
         return None
     per_launch_ms = p["ms"] / p["records"]
-    if BOUND[name] == "mfma":
+    if name.startswith("gemm") and p["bytes"] > 0 and p["flops"] / p["bytes"] > MACHINE_BALANCE:
         ach = p["flops"] / sec / 1e12
         return dict(kernel=name, bound="mfma", achieved=ach, peak=MFMA_FP32_PEAK_TFLOPS, unit="TFLOP/s",
                     frac=ach / MFMA_FP32_PEAK_TFLOPS, traffic=None, avg_launch_ms=per_launch_ms,
@@ -122,9 +121,10 @@ def main():
             entries.append(e)
     entries.sort(key=lambda e: -e["share_of_step"])
     dominant = dict(entries[0]) if entries else None
-    spmm_ms = sum(prof[k]["ms"] for k in ("spmm_rows", "spmm_rows_gradz", "spmm_segments"))
-    spmm_bytes = sum(prof[k]["bytes"] for k in ("spmm_rows", "spmm_rows_gradz", "spmm_segments"))
-    spmm_flops = sum(prof[k]["flops"] for k in ("spmm_rows", "spmm_rows_gradz", "spmm_segments"))
+    spmm_keys = [k for k in prof if k.startswith("spmm")]
+    spmm_ms = sum(prof[k]["ms"] for k in spmm_keys)
+    spmm_bytes = sum(prof[k]["bytes"] for k in spmm_keys)
+    spmm_flops = sum(prof[k]["flops"] for k in spmm_keys)
 
     out = {
         "metric": "ADMM iterations/sec (all layers+communities)",

@@ -24,7 +24,7 @@ EXPORTS = [
     "cadmm_op_aggregate_segments", "cadmm_op_transform", "cadmm_op_wgrad",
     "cadmm_profile", "cadmm_get_profile", "cadmm_profile_class_name", "cadmm_tune",
 ]
-PROFILE_CLASSES = 13
+PROFILE_CLASSES = 15
 
 
 class CadmmError(RuntimeError):

@@ -197,13 +197,16 @@ hipError_t upload(hipStream_t s, T* dst, const std::vector<T>& src) {
     return hipMemcpyAsync(dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice, s);
 }
 
+// One class per kernel symbol (and role, where one symbol serves two), so that the live timings can be
+// set beside a profiler's per-kernel averages.
 enum ProfClass {
-    P_SPMM = 0, P_SPMM_GRADZ, P_SPMM_SEG, P_GEMM_NN_WIDE, P_GEMM_NN_NARROW, P_GEMM_TN, P_PHI_G, P_G_ONLY,
-    P_W_TRIAL, P_Z_TRIAL, P_STEP, P_LAST_LAYER, P_OTHER
+    P_SPMM = 0, P_SPMM_GRADZ, P_SPMM_SEG, P_GEMM_NN_128, P_GEMM_NN_128_GRADZ, P_GEMM_NN_32, P_GEMM_TN, P_PHI_G,
+    P_G_ONLY, P_W_TRIAL, P_Z_TRIAL, P_W_STEP, P_Z_STEP, P_LAST_LAYER, P_OTHER
 };
 const char* kProfNames[CADMM_PROFILE_CLASSES] = {
-    "spmm_rows", "spmm_rows_gradz", "spmm_segments", "gemm_nn_wide", "gemm_nn_narrow", "gemm_tn", "phi_G",
-    "G_only", "w_trial", "z_trial", "step", "last_layer", "other"};
+    "spmm_rows_kernel[rows]", "spmm_rows_kernel[rows,gradz]", "spmm_rows_kernel[segments]", "gemm_nn_kernel<128,0>",
+    "gemm_nn_kernel<128,1>", "gemm_nn_kernel<32>", "gemm_tn_kernel+reduce", "phi_G_kernel", "G_only_kernel",
+    "w_trial_kernel", "z_trial_kernel", "w_step_kernel", "z_step_kernel", "last_layer_kernel", "other"};
 
 hipEvent_t prof_event(cadmm_ctx* c) {
     if (!c->prof_pool.empty()) {
@@ -259,9 +262,7 @@ double spmm_bytes(const cadmm_ctx* c, int64_t out_rows, int width, int extra_rea
 
 void gemm_nn(cadmm_ctx* c, const float* A, const float* B, float* out, int64_t n, int K, int C,
              const GemmEpilogue& epi = GemmEpilogue()) {
-    // MFMA-bound when both widths fill a tile, otherwise bound by streaming the tall operand / result
-    const bool wide = C > 32 && K > 32;
-    timed(c, wide ? P_GEMM_NN_WIDE : P_GEMM_NN_NARROW,
+    timed(c, C > 32 ? (epi.kind ? P_GEMM_NN_128_GRADZ : P_GEMM_NN_128) : P_GEMM_NN_32,
           4.0 * ((double)n * K + (double)K * C + (double)n * C * (epi.kind ? 3 : 1)), 2.0 * (double)n * K * C,
           [&] { launch_gemm_nn(c->stream, A, B, out, n, K, C, epi); });
 }
@@ -355,7 +356,7 @@ void sweep(cadmm_ctx* c) {
             for (int p = 0; p < more_passes; ++p)
                 launch_w_trial(s, c->T[l], Q, c->Z[l], c->U, count, last, kMaxCand, sp, unit, c->partials, c->status);
         });
-        timed(c, P_STEP, 4.0 * (3.0 * (double)count + 3.0 * K * Cl), 0.0, [&] {
+        timed(c, P_W_STEP, 4.0 * (3.0 * (double)count + 3.0 * K * Cl), 0.0, [&] {
             launch_w_step(s, c->W[l], c->gradW, K * Cl, c->T[l], Q, count, unit);    // W^{k+1}; T_l = A~ Z^k W^{k+1}
         });
     }
@@ -409,7 +410,7 @@ void sweep(cadmm_ctx* c) {
             a.first_pass = 0; a.ncand = kMaxCand;
             for (int p = 0; p < more_passes; ++p) launch_z_trial(s, a);
         });
-        timed(c, P_STEP, 4.0 * (3.0 * (double)N * Cl + (double)N), 0.0,
+        timed(c, P_Z_STEP, 4.0 * (3.0 * (double)N * Cl + (double)N), 0.0,
               [&] { launch_z_step(s, c->Z[l], c->tmpB, c->d_row_comm, N, Cl, units); });
     }
 

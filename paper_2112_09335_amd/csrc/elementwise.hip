@@ -19,6 +19,22 @@ namespace {
 
 constexpr double kStepFloor = 1e-12;   // a step that moves the block by less than this fraction is not taken
 
+// VEC consecutive floats per lane: 16-byte accesses when the element count allows (VEC = 4), else scalar
+template <int VEC>
+__device__ __forceinline__ void ldv(float (&d)[VEC], const float* p) {
+    if constexpr (VEC == 4) {
+        const float4 v = *reinterpret_cast<const float4*>(p);
+        d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+    } else {
+        d[0] = *p;
+    }
+}
+template <int VEC>
+__device__ __forceinline__ void stv(float* p, const float (&d)[VEC]) {
+    if constexpr (VEC == 4) *reinterpret_cast<float4*>(p) = make_float4(d[0], d[1], d[2], d[3]);
+    else *p = d[0];
+}
+
 __device__ __forceinline__ double block_sum(double v, double* sm) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
@@ -63,31 +79,40 @@ __device__ __forceinline__ void floor_or_start(Unit* u, double g, double bnorm) 
 // ------------------------------------------------------------------------------------------ phi and G
 // hidden layer:  e = relu(t) - z,  phi += e^2 (scaled nu/2 at the end),  G = nu e 1[t>0]
 // last layer:    r = z - t,        phi += u r + rho/2 r^2,               G = -(u + rho r)
-template <int LAST>
+template <int LAST, int VEC>
 __global__ __launch_bounds__(256) void phi_G_kernel(const float* __restrict__ T, const float* __restrict__ Z,
                                                     const float* __restrict__ U, float* __restrict__ G,
                                                     float* __restrict__ Tprev, int have_prev, int64_t count,
                                                     float nu, float rho, double* __restrict__ partials) {
     __shared__ double sm[4];
     double s_phi = 0.0, s_res = 0.0, s_dt = 0.0;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
-        const float t = T[i], z = Z[i];
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x * VEC;
+    for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * VEC; i < count; i += stride) {
+        float t[VEC], z[VEC], g[VEC];
+        ldv<VEC>(t, T + i);
+        ldv<VEC>(z, Z + i);
         if (LAST) {
-            const float u = U[i];
-            const double r = (double)z - (double)t;
-            s_phi += (double)u * r + 0.5 * (double)rho * r * r;
-            s_res += r * r;
-            if (G) G[i] = -(u + rho * (z - t));
-            if (Tprev) {
-                if (have_prev) { const double d = (double)t - (double)Tprev[i]; s_dt += d * d; }
-                Tprev[i] = t;
+            float u[VEC], tp[VEC];
+            ldv<VEC>(u, U + i);
+            if (Tprev && have_prev) ldv<VEC>(tp, Tprev + i);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                const double r = (double)z[v] - (double)t[v];
+                s_phi += (double)u[v] * r + 0.5 * (double)rho * r * r;
+                s_res += r * r;
+                g[v] = -(u[v] + rho * (z[v] - t[v]));
+                if (Tprev && have_prev) { const double d = (double)t[v] - (double)tp[v]; s_dt += d * d; }
             }
+            if (Tprev) stv<VEC>(Tprev + i, t);
         } else {
-            const double e = (double)fmaxf(t, 0.f) - (double)z;
-            s_phi += e * e;
-            if (G) G[i] = (t > 0.f) ? nu * (float)e : 0.f;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                const double e = (double)fmaxf(t[v], 0.f) - (double)z[v];
+                s_phi += e * e;
+                g[v] = (t[v] > 0.f) ? nu * (float)e : 0.f;
+            }
         }
+        if (G) stv<VEC>(G + i, g);
     }
     s_phi = block_sum(s_phi, sm);
     if (LAST) { s_res = block_sum(s_res, sm); s_dt = block_sum(s_dt, sm); }
@@ -117,15 +142,25 @@ __global__ __launch_bounds__(256) void phi_G_finish_kernel(const double* __restr
     }
 }
 
-template <int LAST>
+template <int LAST, int VEC>
 __global__ __launch_bounds__(256) void G_only_kernel(const float* __restrict__ T, const float* __restrict__ Z,
                                                      const float* __restrict__ U, float* __restrict__ G,
                                                      int64_t count, float nu, float rho) {
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
-        const float t = T[i], z = Z[i];
-        if (LAST) G[i] = -(U[i] + rho * (z - t));
-        else G[i] = (t > 0.f) ? nu * (float)((double)t - (double)z) : 0.f;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x * VEC;
+    for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * VEC; i < count; i += stride) {
+        float t[VEC], z[VEC], g[VEC];
+        ldv<VEC>(t, T + i);
+        ldv<VEC>(z, Z + i);
+        if (LAST) {
+            float u[VEC];
+            ldv<VEC>(u, U + i);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) g[v] = -(u[v] + rho * (z[v] - t[v]));
+        } else {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) g[v] = (t[v] > 0.f) ? nu * (float)((double)t[v] - (double)z[v]) : 0.f;
+        }
+        stv<VEC>(G + i, g);
     }
 }
 
@@ -180,7 +215,7 @@ __global__ __launch_bounds__(256) void w_norms_kernel(const float* __restrict__ 
     if (threadIdx.x == 0) floor_or_start(unit, g, b);
 }
 
-template <int LAST, int NC>
+template <int LAST, int NC, int VEC>
 __global__ __launch_bounds__(256) void w_trial_kernel(const float* __restrict__ T0, const float* __restrict__ Q,
                                                       const float* __restrict__ Z, const float* __restrict__ U,
                                                       int64_t count, SearchParams sp, const Unit* unit,
@@ -196,23 +231,31 @@ __global__ __launch_bounds__(256) void w_trial_kernel(const float* __restrict__ 
     double D[NC];
 #pragma unroll
     for (int j = 0; j < NC; ++j) D[j] = 0.0;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
-        const double t0 = (double)T0[i], q = (double)Q[i], z = (double)Z[i];
-        if (LAST) {
-            const double u = (double)U[i];
-            const double r0 = z - t0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x * VEC;
+    for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * VEC; i < count; i += stride) {
+        float t0v[VEC], qv[VEC], zv[VEC], uv[VEC];
+        ldv<VEC>(t0v, T0 + i);
+        ldv<VEC>(qv, Q + i);
+        ldv<VEC>(zv, Z + i);
+        if (LAST) ldv<VEC>(uv, U + i);
 #pragma unroll
-            for (int j = 0; j < NC; ++j) {
-                const double dq = q * inv[j];          // r_new - r_old
-                D[j] += dq * (u + 0.5 * (double)sp.rho * (2.0 * r0 + dq));
-            }
-        } else {
-            const double e0 = fmax(t0, 0.0) - z;
+        for (int v = 0; v < VEC; ++v) {
+            const double t0 = (double)t0v[v], q = (double)qv[v], z = (double)zv[v];
+            if (LAST) {
+                const double u = (double)uv[v];
+                const double r0 = z - t0;
 #pragma unroll
-            for (int j = 0; j < NC; ++j) {
-                const double e1 = fmax(t0 - q * inv[j], 0.0) - z;
-                D[j] += (e1 - e0) * (e1 + e0);
+                for (int j = 0; j < NC; ++j) {
+                    const double dq = q * inv[j];          // r_new - r_old
+                    D[j] += dq * (u + 0.5 * (double)sp.rho * (2.0 * r0 + dq));
+                }
+            } else {
+                const double e0 = fmax(t0, 0.0) - z;
+#pragma unroll
+                for (int j = 0; j < NC; ++j) {
+                    const double e1 = fmax(t0 - q * inv[j], 0.0) - z;
+                    D[j] += (e1 - e0) * (e1 + e0);
+                }
             }
         }
     }
@@ -238,15 +281,23 @@ __global__ __launch_bounds__(256) void w_trial_finish_kernel(const double* __res
     if (threadIdx.x == 0) decide(unit, D, ncand, sp, status);
 }
 
+template <int VEC>
 __global__ __launch_bounds__(256) void w_step_kernel(float* __restrict__ W, const float* __restrict__ gradW,
                                                      int count_w, float* __restrict__ T, const float* __restrict__ Q,
                                                      int64_t count_t, const Unit* unit) {
     if (unit->skip) return;
     const double inv = 1.0 / unit->step;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    const int64_t i0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (int64_t i = i0; i < count_t; i += stride) T[i] = (float)((double)T[i] - (double)Q[i] * inv);
-    for (int64_t i = i0; i < count_w; i += stride) W[i] = (float)((double)W[i] - (double)gradW[i] * inv);
+    const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t nthreads = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = gtid * VEC; i < count_t; i += nthreads * VEC) {
+        float t[VEC], q[VEC];
+        ldv<VEC>(t, T + i);
+        ldv<VEC>(q, Q + i);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) t[v] = (float)((double)t[v] - (double)q[v] * inv);
+        stv<VEC>(T + i, t);
+    }
+    for (int64_t i = gtid; i < count_w; i += nthreads) W[i] = (float)((double)W[i] - (double)gradW[i] * inv);
 }
 
 // ------------------------------------------------------------------------------------------ Z search
@@ -254,7 +305,7 @@ __global__ __launch_bounds__(256) void w_step_kernel(float* __restrict__ W, cons
 //     nu/2 ||Z - relu(T_l)||^2  under  Z -> Z - gradZ/theta;
 // kind 1: segments [begin,end) (community,row order) of the next layer's term, whose pre-activation
 //     row T_{l+1,i} moves by -P_s/theta as seen from this community.
-template <int NC>
+template <int NC, int VEC>
 __global__ __launch_bounds__(256) void z_trial_kernel(ZTrialArgs a) {
     __shared__ double sm[4];
     const int ch = blockIdx.x;
@@ -274,23 +325,32 @@ __global__ __launch_bounds__(256) void z_trial_kernel(ZTrialArgs a) {
     for (int j = 0; j < NC; ++j) D[j] = 0.0;
     double sg = 0.0, sb = 0.0;
     const int width = kind == 0 ? a.Cl : a.Cn;
+    const int wv = (width + VEC - 1) / VEC;       // lane slots per row
     int cshift = 0;
-    while ((1 << cshift) < width && cshift < 8) ++cshift;
+    while ((1 << cshift) < wv && cshift < 8) ++cshift;
     const int cp = 1 << cshift;
     const int c_first = threadIdx.x & (cp - 1);
     const int r_first = threadIdx.x >> cshift;
     const int r_step = 256 >> cshift;
+    const double hnu = 0.5 * (double)a.sp.nu, hrho = 0.5 * (double)a.sp.rho;
     if (kind == 0) {
         for (int r = begin + r_first; r < end; r += r_step) {
             const int64_t base = (int64_t)r * width;
-            for (int c = c_first; c < width; c += cp) {
-                const double z = (double)a.Zl[base + c], gz = (double)a.gradZ[base + c], t = (double)a.Tl[base + c];
-                const double e0 = z - fmax(t, 0.0);
-                if (a.first_pass) { sg += gz * gz; sb += z * z; }
+            for (int cv = c_first; cv < wv; cv += cp) {
+                float zv[VEC], gv[VEC], tv[VEC];
+                ldv<VEC>(zv, a.Zl + base + cv * VEC);
+                ldv<VEC>(gv, a.gradZ + base + cv * VEC);
+                ldv<VEC>(tv, a.Tl + base + cv * VEC);
 #pragma unroll
-                for (int j = 0; j < NC; ++j) {
-                    const double dz = -gz * inv[j];
-                    D[j] += 0.5 * (double)a.sp.nu * dz * (2.0 * e0 + dz);
+                for (int v = 0; v < VEC; ++v) {
+                    const double z = (double)zv[v], gz = (double)gv[v], t = (double)tv[v];
+                    const double e0 = z - fmax(t, 0.0);
+                    if (a.first_pass) { sg += gz * gz; sb += z * z; }
+#pragma unroll
+                    for (int j = 0; j < NC; ++j) {
+                        const double dz = -gz * inv[j];
+                        D[j] += hnu * dz * (2.0 * e0 + dz);
+                    }
                 }
             }
         }
@@ -298,22 +358,30 @@ __global__ __launch_bounds__(256) void z_trial_kernel(ZTrialArgs a) {
         for (int s = begin + r_first; s < end; s += r_step) {
             const int64_t row = a.segc_row[s];
             const int64_t base = row * width, pbase = (int64_t)s * width;
-            for (int c = c_first; c < width; c += cp) {
-                const double t0 = (double)a.Tn[base + c], z = (double)a.Zn[base + c], p = (double)a.P[pbase + c];
-                if (a.next_is_last) {
-                    const double uu = (double)a.U[base + c];
-                    const double r0 = z - t0;
+            for (int cv = c_first; cv < wv; cv += cp) {
+                float tv[VEC], zv[VEC], pv[VEC], uv[VEC];
+                ldv<VEC>(tv, a.Tn + base + cv * VEC);
+                ldv<VEC>(zv, a.Zn + base + cv * VEC);
+                ldv<VEC>(pv, a.P + pbase + cv * VEC);
+                if (a.next_is_last) ldv<VEC>(uv, a.U + base + cv * VEC);
 #pragma unroll
-                    for (int j = 0; j < NC; ++j) {
-                        const double dq = p * inv[j];
-                        D[j] += dq * (uu + 0.5 * (double)a.sp.rho * (2.0 * r0 + dq));
-                    }
-                } else {
-                    const double e0 = fmax(t0, 0.0) - z;
+                for (int v = 0; v < VEC; ++v) {
+                    const double t0 = (double)tv[v], z = (double)zv[v], p = (double)pv[v];
+                    if (a.next_is_last) {
+                        const double uu = (double)uv[v];
+                        const double r0 = z - t0;
 #pragma unroll
-                    for (int j = 0; j < NC; ++j) {
-                        const double e1 = fmax(t0 - p * inv[j], 0.0) - z;
-                        D[j] += 0.5 * (double)a.sp.nu * (e1 - e0) * (e1 + e0);
+                        for (int j = 0; j < NC; ++j) {
+                            const double dq = p * inv[j];
+                            D[j] += dq * (uu + hrho * (2.0 * r0 + dq));
+                        }
+                    } else {
+                        const double e0 = fmax(t0, 0.0) - z;
+#pragma unroll
+                        for (int j = 0; j < NC; ++j) {
+                            const double e1 = fmax(t0 - p * inv[j], 0.0) - z;
+                            D[j] += hnu * (e1 - e0) * (e1 + e0);
+                        }
                     }
                 }
             }
@@ -357,11 +425,13 @@ __global__ __launch_bounds__(256) void z_trial_finish_kernel(ZTrialArgs a) {
     }
 }
 
+template <int VEC>
 __global__ __launch_bounds__(256) void z_step_kernel(float* __restrict__ Zl, const float* __restrict__ gradZ,
                                                      const int32_t* __restrict__ row_comm, int64_t N, int Cl,
                                                      const Unit* __restrict__ units) {
+    const int wv = (Cl + VEC - 1) / VEC;
     int cshift = 0;
-    while ((1 << cshift) < Cl && cshift < 8) ++cshift;
+    while ((1 << cshift) < wv && cshift < 8) ++cshift;
     const int cp = 1 << cshift;
     const int c_first = threadIdx.x & (cp - 1);
     const int64_t r_step = (int64_t)gridDim.x * (256 >> cshift);
@@ -370,8 +440,14 @@ __global__ __launch_bounds__(256) void z_step_kernel(float* __restrict__ Zl, con
         if (u->skip) continue;
         const double inv = 1.0 / u->step;
         const int64_t base = r * Cl;
-        for (int c = c_first; c < Cl; c += cp)
-            Zl[base + c] = (float)((double)Zl[base + c] - (double)gradZ[base + c] * inv);
+        for (int cv = c_first; cv < wv; cv += cp) {
+            float z[VEC], g[VEC];
+            ldv<VEC>(z, Zl + base + cv * VEC);
+            ldv<VEC>(g, gradZ + base + cv * VEC);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) z[v] = (float)((double)z[v] - (double)g[v] * inv);
+            stv<VEC>(Zl + base + cv * VEC, z);
+        }
     }
 }
 
@@ -498,20 +574,22 @@ void launch_phi_G(hipStream_t s, const float* T, const float* Z, const float* U,
                   int have_prev, int64_t count, int last, float nu, float rho, double* partials,
                   LayerScalars* out) {
     const int nb = flat_grid(count);
-    if (last)
-        hipLaunchKernelGGL((phi_G_kernel<1>), dim3(nb), dim3(256), 0, s, T, Z, U, G, Tprev, have_prev, count, nu, rho,
-                           partials);
-    else
-        hipLaunchKernelGGL((phi_G_kernel<0>), dim3(nb), dim3(256), 0, s, T, Z, U, G, Tprev, have_prev, count, nu, rho,
-                           partials);
+    const bool v4 = (count % 4) == 0;
+#define CADMM_PHI_G(L_, V_) hipLaunchKernelGGL((phi_G_kernel<L_, V_>), dim3(nb), dim3(256), 0, s, T, Z, U, G, Tprev, have_prev, count, nu, rho, partials)
+    if (last) { if (v4) CADMM_PHI_G(1, 4); else CADMM_PHI_G(1, 1); }
+    else { if (v4) CADMM_PHI_G(0, 4); else CADMM_PHI_G(0, 1); }
+#undef CADMM_PHI_G
     hipLaunchKernelGGL(phi_G_finish_kernel, dim3(1), dim3(256), 0, s, partials, nb, last, nu, out);
 }
 
 void launch_G_only(hipStream_t s, const float* T, const float* Z, const float* U, float* G, int64_t count,
                    int last, float nu, float rho) {
     const int nb = flat_grid(count);
-    if (last) hipLaunchKernelGGL((G_only_kernel<1>), dim3(nb), dim3(256), 0, s, T, Z, U, G, count, nu, rho);
-    else hipLaunchKernelGGL((G_only_kernel<0>), dim3(nb), dim3(256), 0, s, T, Z, U, G, count, nu, rho);
+    const bool v4 = (count % 4) == 0;
+#define CADMM_G_ONLY(L_, V_) hipLaunchKernelGGL((G_only_kernel<L_, V_>), dim3(nb), dim3(256), 0, s, T, Z, U, G, count, nu, rho)
+    if (last) { if (v4) CADMM_G_ONLY(1, 4); else CADMM_G_ONLY(1, 1); }
+    else { if (v4) CADMM_G_ONLY(0, 4); else CADMM_G_ONLY(0, 1); }
+#undef CADMM_G_ONLY
 }
 
 void launch_risk(hipStream_t s, const float* ZL, const int32_t* labels, int64_t N, int CL, int risk,
@@ -529,28 +607,39 @@ void launch_w_trial(hipStream_t s, const float* T0, const float* Q, const float*
                     int64_t count, int last, int ncand, SearchParams sp, Unit* unit, double* partials,
                     int32_t* status) {
     const int nb = flat_grid(count);
+    const bool v4 = (count % 4) == 0;
+#define CADMM_W_TRIAL(L_, N_, V_) hipLaunchKernelGGL((w_trial_kernel<L_, N_, V_>), dim3(nb), dim3(256), 0, s, T0, Q, Z, U, count, sp, unit, partials)
     if (ncand == 1) {
-        if (last) hipLaunchKernelGGL((w_trial_kernel<1, 1>), dim3(nb), dim3(256), 0, s, T0, Q, Z, U, count, sp, unit, partials);
-        else hipLaunchKernelGGL((w_trial_kernel<0, 1>), dim3(nb), dim3(256), 0, s, T0, Q, Z, U, count, sp, unit, partials);
+        if (last) { if (v4) CADMM_W_TRIAL(1, 1, 4); else CADMM_W_TRIAL(1, 1, 1); }
+        else { if (v4) CADMM_W_TRIAL(0, 1, 4); else CADMM_W_TRIAL(0, 1, 1); }
     } else {
         ncand = kMaxCand;
-        if (last) hipLaunchKernelGGL((w_trial_kernel<1, kMaxCand>), dim3(nb), dim3(256), 0, s, T0, Q, Z, U, count, sp, unit, partials);
-        else hipLaunchKernelGGL((w_trial_kernel<0, kMaxCand>), dim3(nb), dim3(256), 0, s, T0, Q, Z, U, count, sp, unit, partials);
+        if (last) { if (v4) CADMM_W_TRIAL(1, kMaxCand, 4); else CADMM_W_TRIAL(1, kMaxCand, 1); }
+        else { if (v4) CADMM_W_TRIAL(0, kMaxCand, 4); else CADMM_W_TRIAL(0, kMaxCand, 1); }
     }
+#undef CADMM_W_TRIAL
     hipLaunchKernelGGL(w_trial_finish_kernel, dim3(1), dim3(256), 0, s, partials, nb, ncand, sp, unit, status);
 }
 
 void launch_w_step(hipStream_t s, float* W, const float* gradW, int count_w, float* T, const float* Q,
                    int64_t count_t, const Unit* unit) {
     const int nb = flat_grid(count_t > count_w ? count_t : count_w);
-    hipLaunchKernelGGL(w_step_kernel, dim3(nb), dim3(256), 0, s, W, gradW, count_w, T, Q, count_t, unit);
+    if (count_t % 4 == 0) hipLaunchKernelGGL((w_step_kernel<4>), dim3(nb), dim3(256), 0, s, W, gradW, count_w, T, Q, count_t, unit);
+    else hipLaunchKernelGGL((w_step_kernel<1>), dim3(nb), dim3(256), 0, s, W, gradW, count_w, T, Q, count_t, unit);
 }
 
 void launch_z_trial(hipStream_t s, const ZTrialArgs& a0) {
     ZTrialArgs a = a0;
     if (a.n_chunks > 0) {
-        if (a.ncand == 1) hipLaunchKernelGGL((z_trial_kernel<1>), dim3(a.n_chunks), dim3(256), 0, s, a);
-        else { a.ncand = kMaxCand; hipLaunchKernelGGL((z_trial_kernel<kMaxCand>), dim3(a.n_chunks), dim3(256), 0, s, a); }
+        const bool v4 = (a.Cl % 4) == 0 && (a.Cn % 4) == 0;
+        if (a.ncand == 1) {
+            if (v4) hipLaunchKernelGGL((z_trial_kernel<1, 4>), dim3(a.n_chunks), dim3(256), 0, s, a);
+            else hipLaunchKernelGGL((z_trial_kernel<1, 1>), dim3(a.n_chunks), dim3(256), 0, s, a);
+        } else {
+            a.ncand = kMaxCand;
+            if (v4) hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 4>), dim3(a.n_chunks), dim3(256), 0, s, a);
+            else hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 1>), dim3(a.n_chunks), dim3(256), 0, s, a);
+        }
     }
     hipLaunchKernelGGL(z_trial_finish_kernel, dim3(a.M), dim3(256), 0, s, a);
 }
@@ -558,7 +647,8 @@ void launch_z_trial(hipStream_t s, const ZTrialArgs& a0) {
 void launch_z_step(hipStream_t s, float* Zl, const float* gradZ, const int32_t* row_comm, int64_t N, int Cl,
                    const Unit* units) {
     const int nb = flat_grid(N * (int64_t)Cl);
-    hipLaunchKernelGGL(z_step_kernel, dim3(nb), dim3(256), 0, s, Zl, gradZ, row_comm, N, Cl, units);
+    if (Cl % 4 == 0) hipLaunchKernelGGL((z_step_kernel<4>), dim3(nb), dim3(256), 0, s, Zl, gradZ, row_comm, N, Cl, units);
+    else hipLaunchKernelGGL((z_step_kernel<1>), dim3(nb), dim3(256), 0, s, Zl, gradZ, row_comm, N, Cl, units);
 }
 
 void launch_last_layer(hipStream_t s, float* ZL, float* U, const float* TL, const int32_t* labels, int64_t N,
