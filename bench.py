@@ -72,7 +72,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", type=int, default=4, help="index into BASELINE.json configs, 1-based")
+    ap.add_argument("--workload", type=int, default=4, help="benchmark configuration 1..5 (synth.config)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink N (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()

@@ -1,0 +1,97 @@
+#!/usr/bin/env python3
+"""Time single kernels of the library on a synthetic workload (for profiling under rocprofv3).
+
+    python paper_2112_09335_amd/kernel_bench.py --workload 4 --ops copy aggregate:256 segments:16 \
+           transform:256:256 wgrad:128:256 --reps 5
+
+ops:  copy            a plain device copy of 1 GiB (torch), the calibration point for memory counters
+      aggregate:W     Y = A~ X, X of width W                    (cadmm_op_aggregate)
+      segments:W      per-(row, community) aggregation          (cadmm_op_aggregate_segments)
+      transform:K:C   out[N x C] = A[N x K] B[K x C]            (cadmm_op_transform)
+      wgrad:K:C       out[K x C] = A[N x K]^T G[N x C]          (cadmm_op_wgrad)
+Prints one line per op: mean milliseconds, algorithmic bytes and flops, and the resulting rates.
+"""
+import argparse
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", type=int, default=4)
+    ap.add_argument("--scale", type=float, default=1.0)
+    ap.add_argument("--ops", nargs="+", default=["copy", "aggregate:256"])
+    ap.add_argument("--reps", type=int, default=5)
+    ap.add_argument("--tune", nargs="*", default=[], help="key=value tuning knobs")
+    args = ap.parse_args()
+
+    import torch
+    from paper_2112_09335_amd import binding, synth
+
+    w = synth.config(args.workload, args.scale)
+    s = binding.Solver.from_workload(w, 0)
+    for kv in args.tune:
+        k, v = kv.split("=")
+        s.tune(k, int(v))
+    nnz, nseg, _ = s.graph_sizes()
+    N = w.N
+    print(f"# {w.name}: N={N} nnz={nnz} segments={nseg}", flush=True)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(args.reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / args.reps
+
+    for op in args.ops:
+        parts = op.split(":")
+        kind = parts[0]
+        if kind == "copy":
+            n = 1 << 28                                           # 1 GiB of fp32
+            src = torch.randn(n, device="cuda")
+            dst = torch.empty_like(src)
+            ms = timed(lambda: dst.copy_(src))
+            byt, flop = 8.0 * n, 0.0
+        elif kind == "aggregate":
+            W = int(parts[1])
+            X = torch.randn(N, W, device="cuda")
+            ms = timed(lambda: s.op_aggregate(X))
+            byt = 8.0 * nnz + 16.0 * N + 8.0 * N * W
+            flop = 2.0 * nnz * W
+        elif kind == "segments":
+            W = int(parts[1])
+            X = torch.randn(N, W, device="cuda")
+            ms = timed(lambda: s.op_aggregate_segments(X))
+            byt = 8.0 * nnz + 16.0 * nseg + 4.0 * N * W + 4.0 * nseg * W
+            flop = 2.0 * nnz * W
+        elif kind == "transform":
+            K, C = int(parts[1]), int(parts[2])
+            A = torch.randn(N, K, device="cuda")
+            B = torch.randn(K, C, device="cuda")
+            ms = timed(lambda: s.op_transform(A, B))
+            byt = 4.0 * (N * K + K * C + N * C)
+            flop = 2.0 * N * K * C
+        elif kind == "wgrad":
+            K, C = int(parts[1]), int(parts[2])
+            A = torch.randn(N, K, device="cuda")
+            G = torch.randn(N, C, device="cuda")
+            ms = timed(lambda: s.op_wgrad(A, G))
+            byt = 4.0 * (N * K + N * C + K * C)
+            flop = 2.0 * N * K * C
+        else:
+            raise SystemExit(f"unknown op {op}")
+        print(f"{op:20s} {ms:9.3f} ms   algorithmic {byt / 1e9:8.3f} GB -> {byt / ms / 1e6:8.1f} GB/s   "
+              f"{flop / 1e9:9.2f} GFLOP -> {flop / ms / 1e9:7.2f} TFLOP/s", flush=True)
+
+
+if __name__ == "__main__":
+    main()
