@@ -60,6 +60,36 @@ def sqnorm(a):
     return float(np.sum(a * a))
 
 
+def fista_rows(z0, c, u, y, lab, rho, J, risk):
+    """J FISTA steps per row on  R(z, y) + <u, z - c> + rho/2 ||z - c||^2  from z0 (Appendix A, Eq. 5).
+    The smooth part is the whole objective, so x_j = y_j - grad(y_j)/Lip with the usual momentum; rows
+    without label take the exact minimiser c - u/rho of their quadratic."""
+    Lip = rho + (0.5 if risk == 0 else 1.0)
+
+    def grad(z):
+        g = u + rho * (z - c)
+        zl = z[lab]
+        if risk == 0:
+            e = np.exp(zl - zl.max(axis=1, keepdims=True))
+            g[lab] += e / e.sum(axis=1, keepdims=True) - y[lab]
+        else:
+            g[lab] += zl - y[lab]
+        return g
+
+    x_prev = z0.copy()
+    yk = x_prev.copy()
+    t = 1.0
+    x = x_prev
+    for _ in range(J):
+        x = yk - grad(yk) / Lip
+        t_next = 0.5 * (1.0 + np.sqrt(1.0 + 4.0 * t * t))
+        yk = x + ((t - 1.0) / t_next) * (x - x_prev)
+        x_prev, t = x, t_next
+    x = x.copy()
+    x[~lab] = (c - u / rho)[~lab]
+    return x
+
+
 class AdmmOracle:
     STATUS_BACKTRACK_CAP = 1
     STATUS_NONFINITE = 2
@@ -94,6 +124,7 @@ class AdmmOracle:
     # ------------------------------------------------------------------ data / init
     def set_data(self, X_old, labels_old):
         self.Z = [None] * (self.L + 1)
+        self._AZ0 = None
         self.Z[0] = self.g.to_new(np.asarray(X_old, dtype=np.float64))
         self.labels = self.g.to_new(np.asarray(labels_old, dtype=np.int64))
         CL = self.dims[-1]
@@ -309,28 +340,8 @@ class AdmmOracle:
         J = self.J if J is None else J
         rows = self.g.rows(m)
         c = sum(p_last[(r, m)] for r in self.g.nbr_and_self(m))
-        Um = self.blk(Uk, m)
-        Ym = self.Y[rows]
-        lab = self.labelled[rows]
-        Lip = self.rho + (0.5 if self.risk == 0 else 1.0)
-
-        def grad(z):
-            g = Um + self.rho * (z - c)
-            g[lab] += self.risk_grad(z[lab], Ym[lab])
-            return g
-
-        x_prev = self.blk(Zk[self.L], m).copy()
-        y = x_prev.copy()
-        t = 1.0
-        x = x_prev
-        for _ in range(J):
-            x = y - grad(y) / Lip
-            t_next = 0.5 * (1.0 + np.sqrt(1.0 + 4.0 * t * t))
-            y = x + ((t - 1.0) / t_next) * (x - x_prev)
-            x_prev, t = x, t_next
-        x = x.copy()
-        x[~lab] = (c - Um / self.rho)[~lab]           # exact minimiser of the pure quadratic
-        return x
+        return fista_rows(self.blk(Zk[self.L], m), c, self.blk(Uk, m), self.Y[rows], self.labelled[rows],
+                          self.rho, J, self.risk)
 
     # ------------------------------------------------------------------ one iteration of Algorithm 1
     def iterate(self, k=1):
@@ -378,6 +389,39 @@ class AdmmOracle:
         F = risk + sum(pen)
         return dict(objective=F, lagrangian=F + phiL, risk=risk, primal_res=primal, dual_res=dual,
                     layer_penalty=pen, iter=self.k, status=self.status)
+
+    def phi_full_graph(self, l, Wl, Zprev, Zl, U=None):
+        """phi in its full-graph form (the right-hand sides of its two definitions in Section 3)."""
+        A = self.g.A
+        if Wl.shape[0] > Wl.shape[1]:
+            T = A @ (Zprev @ Wl)
+        elif Zprev is self.Z[0]:                      # A~ Z_0 never changes: keep it between calls
+            if getattr(self, "_AZ0", None) is None:
+                self._AZ0 = A @ Zprev
+            T = self._AZ0 @ Wl
+        else:
+            T = (A @ Zprev) @ Wl
+        if l < self.L:
+            return 0.5 * self.nu * sqnorm(Zl - relu(T))
+        r = Zl - T
+        return inner(U, r) + 0.5 * self.rho * sqnorm(r)
+
+    def stats_full_graph(self, W=None, Z=None, U=None):
+        """The same readout from the full-graph forms (right-hand sides of the definitions of phi and of
+        Problem 2 / Eq. 1), with the sparse A~ applied to narrow products.  Needs no block split, so it
+        runs on graphs with millions of nodes."""
+        W = self.W if W is None else W
+        Z = self.Z if Z is None else Z
+        U = self.U if U is None else U
+        L, A = self.L, self.g.A
+        risk = self.risk_value(Z[L], self.Y, self.labelled)
+        pen = [self.phi_full_graph(l, W[l], Z[l - 1], Z[l]) for l in range(1, L)]
+        TL = A @ (Z[L - 1] @ W[L])
+        r = Z[L] - TL
+        phiL = inner(U, r) + 0.5 * self.rho * sqnorm(r)
+        F = risk + sum(pen)
+        return dict(objective=F, lagrangian=F + phiL, risk=risk, primal_res=float(np.sqrt(sqnorm(r))),
+                    layer_penalty=pen, TL=TL)
 
     # ------------------------------------------------------------------ snapshot / restore (tests)
     def snapshot(self):

@@ -24,7 +24,7 @@ import scipy.sparse as sp
 
 
 class OracleGraph:
-    def __init__(self, N, src, dst, M, comm=None):
+    def __init__(self, N, src, dst, M, comm=None, split=True):
         N = int(N)
         M = int(M)
         src = np.asarray(src, dtype=np.int64).ravel()
@@ -101,8 +101,8 @@ class OracleGraph:
         halo[rows[cr != cc]] = True
         self.n_halo_rows = int(halo.sum())
 
-        # blocks A~_{m,r}, r in N_m or r == m
-        self.block = self.split_blocks(self.A)
+        # blocks A~_{m,r}, r in N_m or r == m (skipped for very large graphs that only use the full-graph forms)
+        self.block = self.split_blocks(self.A) if split else None
 
     def split_blocks(self, matrix):
         """Cut an N x N sparse matrix into the blocks (m, r), r in N_m or r == m."""

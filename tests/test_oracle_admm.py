@@ -321,6 +321,17 @@ def test_sweep_is_jacobi_dual_step_and_readout_are_consistent():
             assert dense_lagrangian(o, o.W, Z, U0) <= dense_lagrangian(o, o.W, Z0, U0) + 1e-10
 
 
+def test_full_graph_readout_equals_blocked_readout():
+    o, _ = tiny_problem(19)
+    o.iterate(2)
+    a, b = o.stats(), o.stats_full_graph()
+    for key in ("objective", "lagrangian", "risk", "primal_res"):
+        assert b[key] == pytest.approx(a[key], rel=1e-12)
+    for l in range(1, o.L + 1):
+        assert o.phi_full_graph(l, o.W[l], o.Z[l - 1], o.Z[l], o.U) == pytest.approx(
+            o.phi(l, o.W[l], o.Z[l - 1], o.Z[l], o.U), rel=1e-12)
+
+
 def test_disconnected_communities_decouple_in_the_Z_update():
     """Without inter-community edges N_m is empty, no s-terms exist, and Z_{l,m}^{k+1} equals what a
     one-community problem on the subgraph of V_m alone produces from the same W^{k+1}."""
