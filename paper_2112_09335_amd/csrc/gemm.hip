@@ -266,13 +266,20 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ 
         }
 }
 
+// Eight lanes share one output entry: lane j adds chunks j, j+8, ... in order, then the eight partial
+// sums are added in lane order by a shuffle tree (fixed order, so the result is reproducible).
 __global__ __launch_bounds__(256) void gemm_tn_reduce_kernel(const float* __restrict__ partial,
                                                              float* __restrict__ out, int64_t count, int nchunks) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= count) return;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = t >> 3;
+    const int j = (int)(t & 7);
     double acc = 0.0;
-    for (int c = 0; c < nchunks; ++c) acc += (double)partial[(int64_t)c * count + i];
-    out[i] = (float)acc;
+    if (i < count)
+        for (int c = j; c < nchunks; c += 8) acc += (double)partial[(int64_t)c * count + i];
+    acc += __shfl_xor(acc, 1, 64);
+    acc += __shfl_xor(acc, 2, 64);
+    acc += __shfl_xor(acc, 4, 64);
+    if (i < count && j == 0) out[i] = (float)acc;
 }
 
 __global__ __launch_bounds__(256) void transpose_kernel(const float* __restrict__ in, float* __restrict__ out,
@@ -296,7 +303,7 @@ TnPlan tn_plan(int64_t n, int K, int C) {
     const int ktiles = (K + BM - 1) / BM;
     const int ctiles = (C + p.bn - 1) / p.bn;
     p.tiles = ktiles * ctiles;
-    int64_t want = (2048 + p.tiles - 1) / p.tiles;          // about 2048 blocks in flight
+    int64_t want = (1024 + p.tiles - 1) / p.tiles;          // about 1024 blocks, four per compute unit
     int64_t max_chunks = (n + 255) / 256;                   // at least 256 rows per chunk
     int64_t nch = want < max_chunks ? want : max_chunks;
     if (nch < 1) nch = 1;
@@ -345,7 +352,7 @@ void launch_gemm_tn(hipStream_t s, const float* A, const float* G, float* out, i
     else
         hipLaunchKernelGGL((gemm_tn_kernel<32>), dim3(nb), dim3(256), 0, s, A, G, partial, n, K, C, p.rows_per_chunk);
     const int64_t count = (int64_t)K * C;
-    hipLaunchKernelGGL(gemm_tn_reduce_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, partial, out,
+    hipLaunchKernelGGL(gemm_tn_reduce_kernel, dim3((unsigned)((count * 8 + 255) / 256)), dim3(256), 0, s, partial, out,
                        count, p.nchunks);
 }
 

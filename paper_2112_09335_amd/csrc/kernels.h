@@ -59,7 +59,7 @@ void launch_transpose(hipStream_t s, const float* in, float* out, int K, int C);
 
 // ---------------------------------------------------------------- fused elementwise + reductions (elementwise.hip)
 constexpr int kReduceBlocks = 2048;      // grid of the flat reducing kernels
-constexpr int kMaxCand = 8;              // step-size candidates evaluated per pass
+constexpr int kMaxCand = 16;             // step-size candidates evaluated per pass
 constexpr int kChunkRows = 128;          // rows / segments per reduction chunk of the Z search
 
 // One step-size search ("unit"): a layer's tau, or a (layer, community)'s theta.
