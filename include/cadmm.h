@@ -121,7 +121,9 @@ int  cadmm_set_data(cadmm_ctx* ctx, const float* X, const int32_t* labels, int x
  * theta = theta0, iteration counter 0. */
 int  cadmm_init(cadmm_ctx* ctx, const float* const* W0);
 
-/* k iterations of Algorithm 1 (W-update, Z-update, U-update), enqueued on the stream. */
+/* k iterations of Algorithm 1 (W-update, Z-update, U-update), enqueued on the stream.  On a
+ * non-default stream an iteration is captured once as a HIP graph and replayed (same kernels, same
+ * results); the library records no memset nodes. */
 int  cadmm_run(cadmm_ctx* ctx, int32_t k);
 
 /*
@@ -179,7 +181,9 @@ int  cadmm_profile(cadmm_ctx* ctx, int enable);
 int  cadmm_get_profile(cadmm_ctx* ctx, double* ms, int64_t* records, double* bytes, double* flops);
 const char* cadmm_profile_class_name(int32_t cls);
 
-/* Process-wide tuning knobs for experiments.  "spmm_tile_cols": feature columns handled per
+/* Tuning knobs for experiments.  "use_graph" (per context): 1 = cadmm_run replays one iteration as a
+ * captured HIP graph when the context's stream is not the default stream (default), 0 = plain launches.
+ * Process-wide: "spmm_tile_cols": feature columns handled per
  * aggregation launch (0 = all at once); "spmm_xcd_remap": 1 = each XCD walks one contiguous eighth of
  * the rows, 0 = blocks in plain order (default); "spmm_groups_log2": lane groups that share one output
  * row, as a power of two (-1 = chosen from the mean row length). */

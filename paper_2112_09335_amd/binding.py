@@ -119,7 +119,8 @@ class Solver:
                 raise CadmmError("no GPU visible: the HIP path cannot run (there is no CPU fallback)")
             self._torch = torch
             torch.cuda.set_device(device)
-            self.stream = torch.cuda.current_stream(device)
+            # a stream of its own (default priority): the library can then replay an iteration as a HIP graph
+            self.stream = torch.cuda.Stream(device=device)
             stream_handle = self.stream.cuda_stream
         h = C.c_void_p()
         rc = self.lib.cadmm_create(C.byref(h), device, C.c_void_p(stream_handle))
@@ -270,12 +271,21 @@ class Solver:
         self._check(self.lib.cadmm_set_state(self.h, Wp, Zp, _ptr(U), _ptr(tau), _ptr(theta)), "cadmm_set_state")
 
     # ---- kernel-level calls on torch device tensors (internal row order)
+    def _enter(self):
+        """Tensors come from torch's current stream; the library runs on its own."""
+        self.stream.wait_stream(self._torch.cuda.current_stream(self.device))
+
+    def _leave(self):
+        self._torch.cuda.current_stream(self.device).wait_stream(self.stream)
+
     def op_aggregate(self, X):
         torch = self._torch
         assert X.is_cuda and X.dtype == torch.float32 and X.is_contiguous() and X.shape[0] == self.N
         Y = torch.empty_like(X)
+        self._enter()
         self._check(self.lib.cadmm_op_aggregate(self.h, C.c_void_p(X.data_ptr()), X.shape[1],
                                                 C.c_void_p(Y.data_ptr())), "cadmm_op_aggregate")
+        self._leave()
         return Y
 
     def op_aggregate_segments(self, V):
@@ -283,25 +293,31 @@ class Solver:
         assert V.is_cuda and V.dtype == torch.float32 and V.is_contiguous() and V.shape[0] == self.N
         nseg = self.graph_sizes()[1]
         P = torch.empty((nseg, V.shape[1]), dtype=torch.float32, device=V.device)
+        self._enter()
         self._check(self.lib.cadmm_op_aggregate_segments(self.h, C.c_void_p(V.data_ptr()), V.shape[1],
                                                          C.c_void_p(P.data_ptr())), "cadmm_op_aggregate_segments")
+        self._leave()
         return P
 
     def op_transform(self, A, B):
         torch = self._torch
         assert A.is_cuda and B.is_cuda and A.is_contiguous() and B.is_contiguous() and A.shape[1] == B.shape[0]
         out = torch.empty((A.shape[0], B.shape[1]), dtype=torch.float32, device=A.device)
+        self._enter()
         self._check(self.lib.cadmm_op_transform(self.h, C.c_void_p(A.data_ptr()), A.shape[0], A.shape[1],
                                                 C.c_void_p(B.data_ptr()), B.shape[1], C.c_void_p(out.data_ptr())),
                     "cadmm_op_transform")
+        self._leave()
         return out
 
     def op_wgrad(self, A, G):
         torch = self._torch
         assert A.is_cuda and G.is_cuda and A.is_contiguous() and G.is_contiguous() and A.shape[0] == G.shape[0]
         out = torch.empty((A.shape[1], G.shape[1]), dtype=torch.float32, device=A.device)
+        self._enter()
         self._check(self.lib.cadmm_op_wgrad(self.h, C.c_void_p(A.data_ptr()), C.c_void_p(G.data_ptr()), A.shape[0],
                                             A.shape[1], G.shape[1], C.c_void_p(out.data_ptr())), "cadmm_op_wgrad")
+        self._leave()
         return out
 
     def tune(self, key, value):

@@ -73,6 +73,12 @@ struct cadmm_ctx {
     int32_t* status = nullptr;
     bool base_valid = false, have_prev = false, dual_valid = false;
     int iter = 0;
+    // One iteration captured as a HIP graph, per variant of the launch sequence (base evaluation already
+    // done or not; previous T_L available or not).  Replayed by cadmm_run when the stream is not the
+    // default stream; launch-bound problem sizes gain most.
+    bool use_graph = true;
+    struct GraphSlot { hipGraphExec_t exec = nullptr; bool tried = false; };
+    GraphSlot graphs[2][2];
     // optional per-kernel-class timing with HIP events on the context's stream
     bool prof_on = false;
     struct ProfRec { int cls; hipEvent_t a, b; };
@@ -341,7 +347,7 @@ void sweep(cadmm_ctx* c) {
         }
         timed(c, P_GEMM_TN, 4.0 * ((double)N * K + (double)N * Cl + (double)K * Cl), 2.0 * (double)N * K * Cl,
               [&] { launch_gemm_tn(s, left, right, c->gradW, N, K, Cl, c->tn_partial); });
-        timed(c, P_OTHER, 8.0 * K * Cl, 0.0, [&] { launch_w_norms(s, c->gradW, c->W[l], K * Cl, unit); });
+        timed(c, P_OTHER, 8.0 * K * Cl, 0.0, [&] { launch_w_norms(s, c->gradW, c->W[l], K * Cl, unit, c->partials); });
         float* Q = c->G[l];                                                          // G_l is no longer needed
         // T(W - g/tau) = T - Q/tau with Q = A~ Z_{l-1} gradW
         if (c->agg_first[l]) {
@@ -472,6 +478,9 @@ void cadmm_destroy(cadmm_ctx* ctx) {
         (void)hipStreamSynchronize(ctx->stream);
         for (auto& r : ctx->prof_recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
         for (auto e : ctx->prof_pool) (void)hipEventDestroy(e);
+        for (auto& row : ctx->graphs)
+            for (auto& slot : row)
+                if (slot.exec) (void)hipGraphExecDestroy(slot.exec);
     }
     delete ctx;
 }
@@ -642,7 +651,35 @@ int cadmm_init(cadmm_ctx* c, const float* const* W0) {
 int cadmm_run(cadmm_ctx* c, int32_t k) {
     if (!c || k < 0) return CADMM_EINVAL;
     if (!c->has_init) return fail(c, CADMM_EORDER, "init first");
-    for (int i = 0; i < k; ++i) sweep(c);
+    for (int i = 0; i < k; ++i) {
+        const bool graphable = c->use_graph && c->stream != nullptr && !c->prof_on;
+        if (!graphable) { sweep(c); continue; }
+        cadmm_ctx::GraphSlot& slot = c->graphs[c->base_valid ? 1 : 0][c->have_prev ? 1 : 0];
+        if (!slot.tried) {
+            // capture this variant once; the capture enqueues nothing, sweep() only advances the host flags
+            slot.tried = true;
+            const bool bv = c->base_valid, hp = c->have_prev, dv = c->dual_valid;
+            const int it = c->iter;
+            if (hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed) == hipSuccess) {
+                sweep(c);
+                hipGraph_t graph = nullptr;
+                hipError_t e = hipStreamEndCapture(c->stream, &graph);
+                if (e == hipSuccess && graph) {
+                    if (hipGraphInstantiate(&slot.exec, graph, nullptr, nullptr, 0) != hipSuccess) slot.exec = nullptr;
+                    (void)hipGraphDestroy(graph);
+                }
+                c->base_valid = bv; c->have_prev = hp; c->dual_valid = dv; c->iter = it;
+            }
+            (void)hipGetLastError();
+        }
+        if (slot.exec && hipGraphLaunch(slot.exec, c->stream) == hipSuccess) {
+            if (!c->base_valid) { c->dual_valid = c->have_prev; c->have_prev = true; }
+            c->base_valid = false;
+            c->iter++;
+        } else {
+            sweep(c);
+        }
+    }
     return check_launch(c, "run");
 }
 
@@ -800,6 +837,7 @@ const char* cadmm_profile_class_name(int32_t cls) {
 
 int cadmm_tune(cadmm_ctx* c, const char* key, int32_t value) {
     if (!c || !key) return CADMM_EINVAL;
+    if (std::strcmp(key, "use_graph") == 0) { c->use_graph = value != 0; return CADMM_OK; }
     if (std::strcmp(key, "spmm_tile_cols") == 0) { set_spmm_tile_cols(value); return CADMM_OK; }
     if (std::strcmp(key, "spmm_xcd_remap") == 0) { set_spmm_xcd_remap(value); return CADMM_OK; }
     if (std::strcmp(key, "spmm_groups_log2") == 0) { set_spmm_groups_log2(value); return CADMM_OK; }

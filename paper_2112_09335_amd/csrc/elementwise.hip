@@ -201,18 +201,27 @@ __global__ __launch_bounds__(256) void risk_finish_kernel(const double* __restri
 }
 
 // ------------------------------------------------------------------------------------------ W search
+// ||gradW||^2 and ||W||^2: per-block partial sums, then one block adds them in order and starts the search.
 __global__ __launch_bounds__(256) void w_norms_kernel(const float* __restrict__ gradW, const float* __restrict__ W,
-                                                      int count, Unit* unit) {
+                                                      int count, double* __restrict__ partials) {
     __shared__ double sm[4];
     double g = 0.0, b = 0.0;
-    for (int i = threadIdx.x; i < count; i += blockDim.x) {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < count; i += gridDim.x * blockDim.x) {
         const double x = (double)gradW[i], w = (double)W[i];
         g += x * x;
         b += w * w;
     }
     g = block_sum(g, sm);
     b = block_sum(b, sm);
-    if (threadIdx.x == 0) floor_or_start(unit, g, b);
+    if (threadIdx.x == 0) { partials[2 * blockIdx.x] = g; partials[2 * blockIdx.x + 1] = b; }
+}
+
+__global__ __launch_bounds__(64) void w_norms_finish_kernel(const double* __restrict__ partials, int nblocks,
+                                                            Unit* unit) {
+    if (threadIdx.x != 0) return;
+    double g = 0.0, b = 0.0;
+    for (int i = 0; i < nblocks; ++i) { g += partials[2 * i]; b += partials[2 * i + 1]; }
+    floor_or_start(unit, g, b);
 }
 
 template <int LAST, int NC, int VEC>
@@ -599,8 +608,12 @@ void launch_risk(hipStream_t s, const float* ZL, const int32_t* labels, int64_t 
     hipLaunchKernelGGL(risk_finish_kernel, dim3(1), dim3(256), 0, s, partials, nb, out);
 }
 
-void launch_w_norms(hipStream_t s, const float* gradW, const float* W, int count, Unit* unit) {
-    hipLaunchKernelGGL(w_norms_kernel, dim3(1), dim3(256), 0, s, gradW, W, count, unit);
+void launch_w_norms(hipStream_t s, const float* gradW, const float* W, int count, Unit* unit, double* partials) {
+    int nb = (count + 2047) / 2048;
+    if (nb > 64) nb = 64;
+    if (nb < 1) nb = 1;
+    hipLaunchKernelGGL(w_norms_kernel, dim3(nb), dim3(256), 0, s, gradW, W, count, partials);
+    hipLaunchKernelGGL(w_norms_finish_kernel, dim3(1), dim3(64), 0, s, partials, nb, unit);
 }
 
 void launch_w_trial(hipStream_t s, const float* T0, const float* Q, const float* Z, const float* U,

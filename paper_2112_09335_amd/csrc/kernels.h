@@ -98,7 +98,7 @@ void launch_G_only(hipStream_t s, const float* T, const float* Z, const float* U
 void launch_risk(hipStream_t s, const float* ZL, const int32_t* labels, int64_t N, int CL, int risk,
                  double* partials, LayerScalars* out);
 // unit.g = ||gradW||^2, unit.bnorm = ||W||^2, applies the step floor, resets the search state.
-void launch_w_norms(hipStream_t s, const float* gradW, const float* W, int count, Unit* unit);
+void launch_w_norms(hipStream_t s, const float* gradW, const float* W, int count, Unit* unit, double* partials);
 // One pass of the W search: candidates step*eta^j, j < ncand, on phi_l(T0 - Q/step).
 void launch_w_trial(hipStream_t s, const float* T0, const float* Q, const float* Z, const float* U,
                     int64_t count, int last, int ncand, SearchParams sp, Unit* unit, double* partials,

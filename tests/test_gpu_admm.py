@@ -97,3 +97,26 @@ def test_backtracking_cap_status_and_resume_are_consistent():
     assert np.array_equal(a.get_Z(1), d.get_Z(1)) and a.eval()["objective"] == d.eval()["objective"]
     for s in (a, b, c, d):
         s.close()
+
+
+def test_graph_replay_equals_plain_launches_bit_for_bit():
+    """cadmm_run replays a captured HIP graph; with readouts (eager kernels, synchronisations) between the
+    replays every iterate must equal the one from plain launches exactly."""
+    from paper_2112_09335_amd import binding
+    w = synth.config(2, 0.1)
+    a = binding.Solver.from_workload(w, 0)
+    b = binding.Solver.from_workload(w, 0)
+    b.tune("use_graph", 0)
+    for k in range(6):
+        a.run(1 if k % 2 == 0 else 2)
+        b.run(1 if k % 2 == 0 else 2)
+        sa, sb = a.eval(), b.eval()
+        assert sa == sb, (k, sa, sb)
+        for l in range(1, w.L + 1):
+            assert np.array_equal(a.get_W(l), b.get_W(l)), (k, l)
+            assert np.array_equal(a.get_Z(l), b.get_Z(l)), (k, l)
+        assert np.array_equal(a.get_U(), b.get_U())
+        ta, tb = a.get_steps(), b.get_steps()
+        assert all(np.array_equal(x, y) for x, y in zip(ta, tb))
+    a.close()
+    b.close()
