@@ -461,76 +461,95 @@ __global__ __launch_bounds__(256) void z_step_kernel(float* __restrict__ Zl, con
 }
 
 // ------------------------------------------------------------------------------------------ last layer + dual
-// One thread per node row, the row lives in registers.  FISTA on
+// 2^LPLOG lanes share one node row, four classes per lane, so a wavefront reads whole 64-byte-aligned
+// pieces of consecutive rows with 16-byte accesses; the row maximum and the softmax denominator are
+// formed by xor-shuffles inside the lane group.  FISTA on
 //   R(z, y_i) + <u, z - c> + rho/2 ||z - c||^2,   c = row of A~ Z_{L-1}^k W_L^{k+1},
 // whose smooth part is the whole objective: x_j = y_j - grad(y_j)/Lip, Lip = rho + (1/2 | 1).
-template <int MAXC>
+template <int LPLOG>
 __global__ __launch_bounds__(256) void last_layer_kernel(float* __restrict__ ZL, float* __restrict__ U,
                                                          const float* __restrict__ TL,
                                                          const int32_t* __restrict__ labels, int64_t N, int CL,
                                                          int risk, float rho, int J) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= N) return;
-    float c[MAXC], u[MAXC], xp[MAXC], y[MAXC], x[MAXC];
-    const int64_t base = i * CL;
+    constexpr int LP = 1 << LPLOG;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t row = t >> LPLOG;
+    const int j0 = (int)(t & (LP - 1)) * 4;
+    const bool act = row < N;                       // uniform over the lane group of a row
+    const int64_t base = (act ? row : 0) * CL + j0;
+    const bool vec = (CL % 4) == 0;
+    bool ok[4];
+    float c[4], u[4], xp[4], y[4], x[4];
 #pragma unroll
-    for (int j = 0; j < MAXC; ++j) {
-        if (j < CL) {
-            c[j] = TL[base + j];
-            u[j] = U[base + j];
-            xp[j] = ZL[base + j];
-        } else { c[j] = 0.f; u[j] = 0.f; xp[j] = 0.f; }
-        y[j] = xp[j];
-        x[j] = xp[j];
+    for (int v = 0; v < 4; ++v) ok[v] = act && (j0 + v < CL);
+    if (vec && ok[0]) {
+        const float4 a = *reinterpret_cast<const float4*>(TL + base);
+        const float4 b = *reinterpret_cast<const float4*>(U + base);
+        const float4 d = *reinterpret_cast<const float4*>(ZL + base);
+        c[0] = a.x; c[1] = a.y; c[2] = a.z; c[3] = a.w;
+        u[0] = b.x; u[1] = b.y; u[2] = b.z; u[3] = b.w;
+        xp[0] = d.x; xp[1] = d.y; xp[2] = d.z; xp[3] = d.w;
+    } else {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            c[v] = ok[v] ? TL[base + v] : 0.f;
+            u[v] = ok[v] ? U[base + v] : 0.f;
+            xp[v] = ok[v] ? ZL[base + v] : 0.f;
+        }
     }
-    // dual step with the iterates as printed in Eq. 2: Z_L^k and the aggregation with W_L^{k+1}
 #pragma unroll
-    for (int j = 0; j < MAXC; ++j)
-        if (j < CL) U[base + j] = u[j] + rho * (xp[j] - c[j]);
-    const int lab = labels[i];
+    for (int v = 0; v < 4; ++v) { y[v] = xp[v]; x[v] = xp[v]; }
+    // dual step with the iterates as printed in Eq. 2: Z_L^k and the aggregation with W_L^{k+1}
+    float un[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) un[v] = u[v] + rho * (xp[v] - c[v]);
+    const int lab = act ? labels[row] : -1;
     if (lab < 0) {
 #pragma unroll
-        for (int j = 0; j < MAXC; ++j)
-            if (j < CL) ZL[base + j] = c[j] - u[j] / rho;
-        return;
-    }
-    const float lip = rho + (risk == 0 ? 0.5f : 1.0f);
-    const float inv_lip = 1.0f / lip;
-    float t = 1.0f;
-    for (int it = 0; it < J; ++it) {
-        float g[MAXC];
-        if (risk == 0) {
-            float mx = -3.4e38f;
+        for (int v = 0; v < 4; ++v) x[v] = c[v] - u[v] / rho;       // exact minimiser of the quadratic
+    } else {
+        const float inv_lip = 1.0f / (rho + (risk == 0 ? 0.5f : 1.0f));
+        float tk = 1.0f;
+        for (int it = 0; it < J; ++it) {
+            float g[4];
+            if (risk == 0) {
+                float mx = -3.0e38f;
 #pragma unroll
-            for (int j = 0; j < MAXC; ++j)
-                if (j < CL) mx = fmaxf(mx, y[j]);
-            float se = 0.f;
+                for (int v = 0; v < 4; ++v) mx = ok[v] ? fmaxf(mx, y[v]) : mx;
 #pragma unroll
-            for (int j = 0; j < MAXC; ++j) {
-                g[j] = (j < CL) ? expf(y[j] - mx) : 0.f;
-                se += g[j];
+                for (int o = 1; o < LP; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+                float se = 0.f;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) { g[v] = ok[v] ? __expf(y[v] - mx) : 0.f; se += g[v]; }
+#pragma unroll
+                for (int o = 1; o < LP; o <<= 1) se += __shfl_xor(se, o, 64);
+                const float inv_se = 1.0f / se;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) g[v] = g[v] * inv_se - ((j0 + v) == lab ? 1.f : 0.f);
+            } else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) g[v] = y[v] - ((j0 + v) == lab ? 1.f : 0.f);
             }
-            const float inv_se = 1.0f / se;
+            const float tn = 0.5f * (1.0f + sqrtf(1.0f + 4.0f * tk * tk));
+            const float mom = (tk - 1.0f) / tn;
 #pragma unroll
-            for (int j = 0; j < MAXC; ++j) g[j] = g[j] * inv_se - (j == lab ? 1.f : 0.f);
-        } else {
-#pragma unroll
-            for (int j = 0; j < MAXC; ++j) g[j] = y[j] - (j == lab ? 1.f : 0.f);
+            for (int v = 0; v < 4; ++v) {
+                const float grad = g[v] + u[v] + rho * (y[v] - c[v]);
+                x[v] = y[v] - grad * inv_lip;
+                y[v] = x[v] + mom * (x[v] - xp[v]);
+                xp[v] = x[v];
+            }
+            tk = tn;
         }
-        const float tn = 0.5f * (1.0f + sqrtf(1.0f + 4.0f * t * t));
-        const float mom = (t - 1.0f) / tn;
-#pragma unroll
-        for (int j = 0; j < MAXC; ++j) {
-            const float grad = g[j] + u[j] + rho * (y[j] - c[j]);
-            x[j] = y[j] - grad * inv_lip;
-            y[j] = x[j] + mom * (x[j] - xp[j]);
-            xp[j] = x[j];
-        }
-        t = tn;
     }
+    if (vec && ok[0]) {
+        *reinterpret_cast<float4*>(U + base) = make_float4(un[0], un[1], un[2], un[3]);
+        *reinterpret_cast<float4*>(ZL + base) = make_float4(x[0], x[1], x[2], x[3]);
+    } else {
 #pragma unroll
-    for (int j = 0; j < MAXC; ++j)
-        if (j < CL) ZL[base + j] = x[j];
+        for (int v = 0; v < 4; ++v)
+            if (ok[v]) { U[base + v] = un[v]; ZL[base + v] = x[v]; }
+    }
 }
 
 __global__ __launch_bounds__(256) void relu_kernel(const float* __restrict__ T, float* __restrict__ Z, int64_t count,
@@ -666,11 +685,13 @@ void launch_z_step(hipStream_t s, float* Zl, const float* gradZ, const int32_t* 
 
 void launch_last_layer(hipStream_t s, float* ZL, float* U, const float* TL, const int32_t* labels, int64_t N,
                        int CL, int risk, float rho, int J) {
-    const unsigned nb = (unsigned)((N + 255) / 256);
-    if (CL <= 8) hipLaunchKernelGGL((last_layer_kernel<8>), dim3(nb), dim3(256), 0, s, ZL, U, TL, labels, N, CL, risk, rho, J);
-    else if (CL <= 16) hipLaunchKernelGGL((last_layer_kernel<16>), dim3(nb), dim3(256), 0, s, ZL, U, TL, labels, N, CL, risk, rho, J);
-    else if (CL <= 32) hipLaunchKernelGGL((last_layer_kernel<32>), dim3(nb), dim3(256), 0, s, ZL, U, TL, labels, N, CL, risk, rho, J);
-    else hipLaunchKernelGGL((last_layer_kernel<64>), dim3(nb), dim3(256), 0, s, ZL, U, TL, labels, N, CL, risk, rho, J);
+#define CADMM_LAST(LG_) hipLaunchKernelGGL((last_layer_kernel<LG_>), dim3((unsigned)(((N << LG_) + 255) / 256)), dim3(256), 0, s, ZL, U, TL, labels, N, CL, risk, rho, J)
+    if (CL <= 4) CADMM_LAST(0);
+    else if (CL <= 8) CADMM_LAST(1);
+    else if (CL <= 16) CADMM_LAST(2);
+    else if (CL <= 32) CADMM_LAST(3);
+    else CADMM_LAST(4);
+#undef CADMM_LAST
 }
 
 void launch_relu(hipStream_t s, const float* T, float* Z, int64_t count, int apply_relu) {
