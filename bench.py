@@ -26,6 +26,16 @@ MFMA_FP32_PEAK_TFLOPS = 157.3
 # algorithmic byte over the timed region) is above the machine balance, else against HBM bandwidth.
 MACHINE_BALANCE = MFMA_FP32_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)      # flop per byte
 
+# Bytes per launch that crossed the L2 -> fabric boundary (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of
+# known size), measured once with rocprofv3 --pmc on the single kernels of the default workload at full size;
+# the summary with the commands is profiles/kernel_memory_traffic_powerlaw_dcsbm_2M.txt.
+MEASURED_TRAFFIC = {
+    (4, "gemm_nn_kernel<128,0>"): 2.238e9 + 2.048e9,          # out[N x 256] = A[N x 128] B
+    (4, "spmm_rows_kernel[rows]"): 3.333e9 + 0.129e9,         # width 16
+    (4, "spmm_rows_kernel[segments]"): 5.299e9 + 0.659e9,     # width 16
+    (4, "gemm_nn_kernel<32>"): 2.629e9 + 0.128e9,             # out[N x 16] = A[N x 256] B
+}
+
 # CPU-oracle sample: (scale of N, iterations) per workload, sized for about 10-30 s of host time
 ORACLE_SAMPLE = {1: (1.0, 10), 2: (0.25, 4), 3: (0.02, 3), 4: (0.004, 3), 5: (0.004, 2)}
 
@@ -119,6 +129,9 @@ def main():
         if e is not None:
             e["share_of_step"] = p["ms"] / total_ms if total_ms > 0 else None
             entries.append(e)
+    if args.scale == 1.0:
+        for e in entries:
+            e["traffic"] = MEASURED_TRAFFIC.get((args.workload, e["kernel"]))
     entries.sort(key=lambda e: -e["share_of_step"])
     dominant = dict(entries[0]) if entries else None
     spmm_keys = [k for k in prof if k.startswith("spmm")]
