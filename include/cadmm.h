@@ -138,6 +138,15 @@ typedef struct {
 } cadmm_stats;
 int  cadmm_eval(cadmm_ctx* ctx, cadmm_stats* out, double* layer_penalty);
 
+/*
+ * Inference with the current weights (paper, Section 4.2: training / test accuracy): the forward pass
+ * Z_l = relu(A~ Z_{l-1} W_l), logits = A~ Z_{L-1} W_L from Z_0, class = argmax of a row (lowest index on
+ * ties).  pred: host int32[N] or NULL; logits: host N x C_L or NULL (both in the caller's node order);
+ * accuracy: fraction of labelled nodes whose class equals their label.  Synchronises.  Does not change
+ * W, Z, U.
+ */
+int  cadmm_predict(cadmm_ctx* ctx, int32_t* pred, float* logits, double* accuracy);
+
 /* State readout, host pointers, caller's node order.  l in 1..L for W, 0..L for Z. */
 int  cadmm_get_W(cadmm_ctx* ctx, int32_t l, float* dst);
 int  cadmm_get_Z(cadmm_ctx* ctx, int32_t l, float* dst);

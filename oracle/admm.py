@@ -423,6 +423,19 @@ class AdmmOracle:
         return dict(objective=F, lagrangian=F + phiL, risk=risk, primal_res=float(np.sqrt(sqnorm(r))),
                     layer_penalty=pen, TL=TL)
 
+    def predict(self):
+        """Inference with the current weights (Section 4.2): forward pass of Problem 1's constraints from
+        Z_0, class = index of the largest logit.  Returns (classes, logits, accuracy over labelled nodes),
+        classes and logits in the caller's node order."""
+        Z = self.Z[0]
+        for l in range(1, self.L + 1):
+            T = np.vstack([self.g.aggregate_block(m, Z) @ self.W[l] for m in range(self.M)])
+            Z = relu(T) if l < self.L else T
+        pred = np.argmax(Z, axis=1)
+        lab = self.labelled
+        acc = float(np.mean(pred[lab] == self.labels[lab])) if lab.any() else 0.0
+        return self.g.to_old(pred), self.g.to_old(Z), acc
+
     # ------------------------------------------------------------------ snapshot / restore (tests)
     def snapshot(self):
         return dict(W=[None] + [w.copy() for w in self.W[1:]], Z=[z.copy() for z in self.Z], U=self.U.copy(),

@@ -22,7 +22,7 @@ EXPORTS = [
     "cadmm_set_workspace", "cadmm_set_data", "cadmm_init", "cadmm_run", "cadmm_eval", "cadmm_get_W",
     "cadmm_get_Z", "cadmm_get_U", "cadmm_get_steps", "cadmm_set_state", "cadmm_op_aggregate",
     "cadmm_op_aggregate_segments", "cadmm_op_transform", "cadmm_op_wgrad",
-    "cadmm_profile", "cadmm_get_profile", "cadmm_profile_class_name", "cadmm_tune",
+    "cadmm_profile", "cadmm_get_profile", "cadmm_profile_class_name", "cadmm_tune", "cadmm_predict",
 ]
 PROFILE_CLASSES = 15
 
@@ -86,6 +86,7 @@ def load_library():
     lib.cadmm_op_transform.argtypes = [vp, vp, i64, i32, vp, i32, vp]
     lib.cadmm_op_wgrad.argtypes = [vp, vp, vp, i64, i32, i32, vp]
     lib.cadmm_tune.argtypes = [vp, C.c_char_p, i32]
+    lib.cadmm_predict.argtypes = [vp, vp, vp, C.POINTER(C.c_double)]
     lib.cadmm_profile.argtypes = [vp, C.c_int]
     lib.cadmm_get_profile.argtypes = [vp, vp, vp, vp, vp]
     lib.cadmm_profile_class_name.argtypes = [i32]
@@ -229,6 +230,14 @@ class Solver:
         self._check(self.lib.cadmm_eval(self.h, C.byref(st), _ptr(pen)), "cadmm_eval")
         return dict(objective=st.objective, lagrangian=st.lagrangian, risk=st.risk, primal_res=st.primal_res,
                     dual_res=st.dual_res, iter=st.iter, status=st.status, layer_penalty=list(pen[:self.L - 1]))
+
+    def predict(self):
+        """(classes [N], logits [N, C_L], accuracy over labelled nodes) with the current weights."""
+        pred = np.empty(self.N, np.int32)
+        logits = np.empty((self.N, self.dims[-1]), np.float32)
+        acc = C.c_double()
+        self._check(self.lib.cadmm_predict(self.h, _ptr(pred), _ptr(logits), C.byref(acc)), "cadmm_predict")
+        return pred, logits, float(acc.value)
 
     def get_W(self, l):
         out = np.empty((self.dims[l - 1], self.dims[l]), np.float32)

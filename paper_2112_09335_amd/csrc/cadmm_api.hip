@@ -48,6 +48,8 @@ struct cadmm_ctx {
     int32_t* d_chunk_end = nullptr;
     int32_t* d_unit_chunk_ptr = nullptr;
     int32_t* d_labels = nullptr;
+    int32_t* d_pred = nullptr;
+    std::vector<int32_t> h_labels;     // internal row order
     // split rows of the CSR row list and of the segment list; side buffer for their parts
     int64_t* d_lr_part_lo = nullptr; int64_t* d_lr_part_hi = nullptr;
     int32_t* d_lr_row = nullptr; int32_t* d_lr_ptr = nullptr;
@@ -146,6 +148,7 @@ size_t layout(cadmm_ctx* c, char* base) {
     c->d_chunk_end = b.take<int32_t>(nch);
     c->d_unit_chunk_ptr = b.take<int32_t>(g.M + 1);
     c->d_labels = b.take<int32_t>(N);
+    c->d_pred = b.take<int32_t>(N);
     c->d_lr_part_lo = b.take<int64_t>(g.long_rows.n_parts());
     c->d_lr_part_hi = b.take<int64_t>(g.long_rows.n_parts());
     c->d_lr_row = b.take<int32_t>(g.long_rows.n_long());
@@ -614,6 +617,7 @@ int cadmm_set_data(cadmm_ctx* c, const float* X, const int32_t* labels, int x_on
     HIP_TRY(c, hipMemcpyAsync(c->d_labels, lab.data(), N * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
     int rc = upload_rows(c, X, x_on_device, c->C[0], c->Z[0]);     // synchronises
     if (rc != CADMM_OK) return rc;
+    c->h_labels.swap(lab);
     c->has_data = true;
     c->has_init = false;
     return CADMM_OK;
@@ -708,6 +712,46 @@ int cadmm_eval(cadmm_ctx* c, cadmm_stats* out, double* layer_penalty) {
     out->status = st[0];
     if (!std::isfinite(out->lagrangian)) out->status |= CADMM_STATUS_NONFINITE;
     return check_launch(c, "eval");
+}
+
+int cadmm_predict(cadmm_ctx* c, int32_t* pred, float* logits, double* accuracy) {
+    if (!c) return CADMM_EINVAL;
+    if (!c->has_init) return fail(c, CADMM_EORDER, "init first");
+    const int L = c->L;
+    const int64_t N = c->hg.N;
+    hipStream_t s = c->stream;
+    // forward pass of Problem 1's constraints with the current weights; the per-layer scratch of the
+    // sweep is reused, so the next sweep or readout recomputes its base evaluation
+    const float* in = c->Z[0];
+    for (int l = 1; l <= L; ++l) {
+        if (c->agg_first[l]) {
+            gemm_nn(c, in, c->W[l], c->tmpV, N, c->C[l - 1], c->C[l]);
+            aggregate(c, c->tmpV, c->T[l], c->C[l], SpmmEpilogue());
+        } else {
+            if (l >= 2) aggregate(c, in, c->H[l], c->C[l - 1], SpmmEpilogue());
+            gemm_nn(c, c->H[l], c->W[l], c->T[l], N, c->C[l - 1], c->C[l]);
+        }
+        if (l < L) {
+            launch_relu(s, c->T[l], c->G[l], N * c->C[l], 1);
+            in = c->G[l];
+        }
+    }
+    c->base_valid = false;
+    launch_argmax_rows(s, c->T[L], c->d_pred, N, c->C[L]);
+    std::vector<int32_t> p((size_t)N);
+    HIP_TRY(c, hipMemcpyAsync(p.data(), c->d_pred, N * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    HIP_TRY(c, hipStreamSynchronize(s));
+    int64_t labelled = 0, hit = 0;
+    for (int64_t r = 0; r < N; ++r) {
+        if (pred) pred[c->hg.perm[r]] = p[r];
+        if (c->h_labels[r] >= 0) { ++labelled; hit += (p[r] == c->h_labels[r]); }
+    }
+    if (accuracy) *accuracy = labelled ? (double)hit / (double)labelled : 0.0;
+    if (logits) {
+        int rc = download_rows(c, c->T[L], c->C[L], logits);
+        if (rc != CADMM_OK) return rc;
+    }
+    return check_launch(c, "predict");
 }
 
 int cadmm_get_W(cadmm_ctx* c, int32_t l, float* dst) {

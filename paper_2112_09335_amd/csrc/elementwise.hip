@@ -559,6 +559,19 @@ __global__ __launch_bounds__(256) void relu_kernel(const float* __restrict__ T, 
         Z[i] = apply_relu ? fmaxf(T[i], 0.f) : T[i];
 }
 
+// class of every node: index of the largest entry of its row (the first one on equal values)
+__global__ __launch_bounds__(256) void argmax_rows_kernel(const float* __restrict__ T, int32_t* __restrict__ pred,
+                                                          int64_t N, int C) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= N) return;
+    const float* t = T + i * C;
+    int best = 0;
+    float bv = t[0];
+    for (int c = 1; c < C; ++c)
+        if (t[c] > bv) { bv = t[c]; best = c; }
+    pred[i] = best;
+}
+
 __global__ void fill_units_kernel(Unit* units, int n, double step) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
@@ -696,6 +709,10 @@ void launch_last_layer(hipStream_t s, float* ZL, float* U, const float* TL, cons
 
 void launch_relu(hipStream_t s, const float* T, float* Z, int64_t count, int apply_relu) {
     hipLaunchKernelGGL(relu_kernel, dim3(flat_grid(count)), dim3(256), 0, s, T, Z, count, apply_relu);
+}
+
+void launch_argmax_rows(hipStream_t s, const float* T, int32_t* pred, int64_t N, int C) {
+    hipLaunchKernelGGL(argmax_rows_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, s, T, pred, N, C);
 }
 
 void launch_fill_units(hipStream_t s, Unit* units, int n, double step) {

@@ -132,6 +132,7 @@ void launch_z_step(hipStream_t s, float* Zl, const float* gradZ, const int32_t* 
 void launch_last_layer(hipStream_t s, float* ZL, float* U, const float* TL, const int32_t* labels, int64_t N,
                        int CL, int risk, float rho, int J);
 void launch_relu(hipStream_t s, const float* T, float* Z, int64_t count, int apply_relu);
+void launch_argmax_rows(hipStream_t s, const float* T, int32_t* pred, int64_t N, int C);
 void launch_fill_units(hipStream_t s, Unit* units, int n, double step);
 void launch_reset_units(hipStream_t s, Unit* units, int n);
 // gather / scatter rows between caller order and internal order: dst[r,:] = src[idx[r],:] or dst[idx[r],:] = src[r,:]

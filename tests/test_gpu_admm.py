@@ -120,3 +120,29 @@ def test_graph_replay_equals_plain_launches_bit_for_bit():
         assert all(np.array_equal(x, y) for x, y in zip(ta, tb))
     a.close()
     b.close()
+
+
+def test_inference_matches_the_oracle_between_iterations():
+    from paper_2112_09335_amd import binding
+    w = synth.config(3, 0.01)
+    solver = binding.Solver.from_workload(w, 0)
+    orc = make_oracle(w)
+    accs = []
+    for k in range(0, 7):
+        if k:
+            solver.run(1)
+            orc.iterate(1)
+        pg, lg, ag = solver.predict()
+        po, lo, ao = orc.predict()
+        scale = np.abs(lo).max()
+        assert np.abs(lg - lo).max() <= 1e-4 * scale
+        top2 = np.sort(lo, axis=1)[:, -2:]
+        clear = (top2[:, 1] - top2[:, 0]) > 1e-3 * scale          # rows whose class is not a near tie
+        assert clear.mean() > 0.9
+        assert np.array_equal(pg[clear], po[clear])
+        assert abs(ag - ao) <= (~clear).mean() + 1e-12
+        accs.append(ag)
+        # predict leaves the iterate alone
+        assert abs(solver.eval()["objective"] - orc.stats()["objective"]) <= 1e-4 * orc.stats()["objective"]
+    say("accuracy per iteration", accs)
+    solver.close()

@@ -332,6 +332,24 @@ def test_full_graph_readout_equals_blocked_readout():
             o.phi(l, o.W[l], o.Z[l - 1], o.Z[l], o.U), rel=1e-12)
 
 
+def test_predict_is_the_forward_pass_with_a_dense_adjacency():
+    o, _ = tiny_problem(20, forward_init=True)
+    o.iterate(3)
+    A = o.g.A.toarray()
+    Z = o.Z[0]
+    for l in range(1, o.L + 1):
+        T = A @ Z @ o.W[l]
+        Z = np.maximum(T, 0.0) if l < o.L else T
+    pred, logits, acc = o.predict()
+    np.testing.assert_allclose(o.g.to_new(logits), Z, rtol=1e-12, atol=1e-13)
+    assert np.array_equal(o.g.to_new(pred), np.argmax(Z, axis=1))
+    lab = o.labelled
+    assert acc == pytest.approx(np.mean(np.argmax(Z, axis=1)[lab] == o.labels[lab]))
+    # at the forward-pass start the last layer's state is exactly these logits
+    o2, _ = tiny_problem(20, forward_init=True)
+    np.testing.assert_allclose(o2.predict()[1], o2.get_Z(o2.L), rtol=1e-12, atol=1e-13)
+
+
 def test_disconnected_communities_decouple_in_the_Z_update():
     """Without inter-community edges N_m is empty, no s-terms exist, and Z_{l,m}^{k+1} equals what a
     one-community problem on the subgraph of V_m alone produces from the same W^{k+1}."""
