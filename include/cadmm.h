@@ -95,7 +95,8 @@ int  cadmm_get_segment_order(cadmm_ctx* ctx, int64_t* order /* host [n_segments]
  *   tau0/theta0: first candidates at k = 0; eta > 1: growth factor of the search;
  *   max_backtrack: multiplications allowed per search (<= 64); fista_iters: J steps of the
  *   last-layer solver (Appendix A, Eq. 5); dual_form: 0 = dual step with the superscripts as
- *   printed in Eq. 2 (only form built).
+ *   printed in Eq. 2 (Z_L^k, W_L^{k+1}); 1 = dual ascent on the new iterates,
+ *   U^{k+1} = U^k + rho (Z_L^{k+1} - A~ Z_{L-1}^{k+1} W_L^{k+1}).
  */
 typedef struct {
     int32_t L;

@@ -27,7 +27,8 @@ only oracle <-> GPU agreement and the invariants in the tests hold them):
   * last layer: J FISTA steps of size 1/(rho + c_R) from the current Z_L
     (c_R = 1/2 for cross-entropy, 1 for least squares bounds the Hessian of R);
     a row without label has the exact minimiser  b = c - U/rho  of its quadratic;
-  * dual step with the superscripts as printed (Eq. 2): Z_L^k and p^k (p uses W^{k+1});
+  * dual step with the superscripts as printed (Eq. 2): Z_L^k and p^k (p uses W^{k+1}); dual_form = 1
+    selects the usual ADMM dual ascent on the new iterates (Z_L^{k+1}, Z_{L-1}^{k+1}, W_L^{k+1}) instead;
   * updates are Jacobi: W^{k+1} from (W^k, Z^k, U^k); every Z^{k+1}_{l,m} from
     (W^{k+1}, Z^k, U^k).
 """
@@ -113,8 +114,8 @@ class AdmmOracle:
         self.J = int(fista_iters)
         self.risk = int(risk)
         self.dual_form = int(dual_form)
-        if self.dual_form != 0:
-            raise NotImplementedError("only the dual step as printed (Eq. 2) is built")
+        if self.dual_form not in (0, 1):
+            raise ValueError("dual_form must be 0 (Eq. 2 as printed) or 1 (new iterates)")
         self.k = 0
         self.status = 0
         self.trials_W = [0] * (self.L + 1)
@@ -363,11 +364,17 @@ class AdmmOracle:
                 Zn[l][self.g.rows(m)] = self.update_Z_hidden(l, m, Zk, Wn, Uk, p[l - 1], p[l], s[l])
         for m in range(M):
             Zn[L][self.g.rows(m)] = self.update_Z_last(m, Zk, Uk, p[L - 1])
-        # Line 5: U_m^{k+1} = U_m^k + rho (Z_{L,m}^k - sum_r p_{L-1,r->m}^k)       (Eq. 2)
+        # Line 5: U_m^{k+1} = U_m^k + rho (Z_{L,m}^k - sum_r p_{L-1,r->m}^k)       (Eq. 2 as printed)
+        # dual_form 1 is the usual ADMM dual ascent on the new iterates instead:
+        #         U_m^{k+1} = U_m^k + rho (Z_{L,m}^{k+1} - sum_r A~_{m,r} Z_{L-1,r}^{k+1} W_L^{k+1})
         Un = np.empty_like(Uk)
         for m in range(M):
-            c = sum(p[L - 1][(r, m)] for r in self.g.nbr_and_self(m))
-            Un[self.g.rows(m)] = self.blk(Uk, m) + self.rho * (self.blk(Zk[L], m) - c)
+            if self.dual_form == 0:
+                c = sum(p[L - 1][(r, m)] for r in self.g.nbr_and_self(m))
+                Un[self.g.rows(m)] = self.blk(Uk, m) + self.rho * (self.blk(Zk[L], m) - c)
+            else:
+                c = self.g.aggregate_block(m, Zn[L - 1]) @ Wn[L]
+                Un[self.g.rows(m)] = self.blk(Uk, m) + self.rho * (self.blk(Zn[L], m) - c)
         # keep A~ Z_{L-1}^k W_L^k for the dual residual of the next readout
         self.TL_prev = np.vstack([self.g.aggregate_block(m, Zk[L - 1]) @ Wk[L] for m in range(M)])
         self.W, self.Z, self.U = Wn, Zn, Un

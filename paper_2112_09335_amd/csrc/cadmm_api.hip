@@ -28,7 +28,8 @@ struct cadmm_ctx {
     // (A~ Z_{l-1}) W_l.  Its W-update then needs three aggregations of width C_l, so it pays if
     // 3 C_l < C_{l-1}.  In those layers the slot H[l] holds A~ G_l (N x C_l).
     std::vector<char> agg_first;
-    int risk = 0, max_bt = 60, J = 10;
+    int risk = 0, max_bt = 60, J = 10, dual_form = 0;
+    bool u_pending = false;      // dual_form 1: the dual step of the last sweep is still to be applied
     float nu = 0, rho = 0, tau0 = 0, theta0 = 0, eta = 2;
     // workspace
     char* ws = nullptr;
@@ -80,7 +81,7 @@ struct cadmm_ctx {
     // default stream; launch-bound problem sizes gain most.
     bool use_graph = true;
     struct GraphSlot { hipGraphExec_t exec = nullptr; bool tried = false; };
-    GraphSlot graphs[2][2];
+    GraphSlot graphs[2][2][2];
     // optional per-kernel-class timing with HIP events on the context's stream
     bool prof_on = false;
     struct ProfRec { int cls; hipEvent_t a, b; };
@@ -317,9 +318,11 @@ void base_eval(cadmm_ctx* c) {
         const double cnt = (double)N * c->C[l];
         timed(c, P_PHI_G, 4.0 * cnt * (l == L ? 6 : 3), 0.0, [&] {
             launch_phi_G(c->stream, c->T[l], c->Z[l], c->U, c->G[l], l == L ? c->TLprev : nullptr,
-                         c->have_prev ? 1 : 0, N * c->C[l], l == L, c->nu, c->rho, c->partials, c->scalars + l);
+                         c->have_prev ? 1 : 0, (l == L && c->u_pending) ? 1 : 0, N * c->C[l], l == L, c->nu, c->rho,
+                         c->partials, c->scalars + l);
         });
     }
+    c->u_pending = false;
     c->dual_valid = c->have_prev;
     c->have_prev = true;
     c->base_valid = true;
@@ -425,8 +428,10 @@ void sweep(cadmm_ctx* c) {
 
     // ---- last layer Z_L (Eq. 5) and the dual step (Eq. 2), both from Z_L^k, U^k and T_L = A~ Z_{L-1}^k W_L^{k+1}
     timed(c, P_LAST_LAYER, 4.0 * (5.0 * (double)N * c->C[L] + (double)N), 0.0, [&] {
-        launch_last_layer(s, c->Z[L], c->U, c->T[L], c->d_labels, N, c->C[L], c->risk, c->rho, c->J);
+        launch_last_layer(s, c->Z[L], c->U, c->T[L], c->d_labels, N, c->C[L], c->risk, c->rho, c->J,
+                          c->dual_form == 0 ? 1 : 0);
     });
+    if (c->dual_form == 1) c->u_pending = true;      // applied by the next base evaluation, on the new iterates
     c->iter++;
     c->base_valid = false;
 }
@@ -481,9 +486,10 @@ void cadmm_destroy(cadmm_ctx* ctx) {
         (void)hipStreamSynchronize(ctx->stream);
         for (auto& r : ctx->prof_recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
         for (auto e : ctx->prof_pool) (void)hipEventDestroy(e);
-        for (auto& row : ctx->graphs)
-            for (auto& slot : row)
-                if (slot.exec) (void)hipGraphExecDestroy(slot.exec);
+        for (auto& plane : ctx->graphs)
+            for (auto& row : plane)
+                for (auto& slot : row)
+                    if (slot.exec) (void)hipGraphExecDestroy(slot.exec);
     }
     delete ctx;
 }
@@ -540,13 +546,14 @@ int cadmm_set_model(cadmm_ctx* c, const cadmm_model* m) {
         return fail(c, CADMM_EINVAL, "nu, rho, tau0, theta0 must be positive and eta > 1");
     if (m->max_backtrack < 0 || m->max_backtrack > 64) return fail(c, CADMM_EINVAL, "max_backtrack must be in [0, 64]");
     if (m->fista_iters < 0) return fail(c, CADMM_EINVAL, "fista_iters must be non-negative");
-    if (m->dual_form != 0) return fail(c, CADMM_EUNSUPPORTED, "only dual_form 0 is built");
+    if (m->dual_form != 0 && m->dual_form != 1) return fail(c, CADMM_EINVAL, "dual_form must be 0 or 1");
     c->L = m->L;
     c->C.assign(m->C, m->C + m->L + 1);
     c->risk = m->risk;
     c->nu = m->nu; c->rho = m->rho; c->tau0 = m->tau0; c->theta0 = m->theta0; c->eta = m->eta;
     c->max_bt = m->max_backtrack;
     c->J = m->fista_iters;
+    c->dual_form = m->dual_form;
     c->agg_first.assign(c->L + 1, 0);
     for (int l = 2; l <= c->L; ++l) c->agg_first[l] = (3 * c->C[l] < c->C[l - 1]) ? 1 : 0;
     c->has_model = true;
@@ -648,6 +655,7 @@ int cadmm_init(cadmm_ctx* c, const float* const* W0) {
     c->base_valid = false;
     c->have_prev = false;
     c->dual_valid = false;
+    c->u_pending = false;
     c->has_init = true;
     return check_launch(c, "init");
 }
@@ -658,11 +666,11 @@ int cadmm_run(cadmm_ctx* c, int32_t k) {
     for (int i = 0; i < k; ++i) {
         const bool graphable = c->use_graph && c->stream != nullptr && !c->prof_on;
         if (!graphable) { sweep(c); continue; }
-        cadmm_ctx::GraphSlot& slot = c->graphs[c->base_valid ? 1 : 0][c->have_prev ? 1 : 0];
+        cadmm_ctx::GraphSlot& slot = c->graphs[c->base_valid ? 1 : 0][c->have_prev ? 1 : 0][c->u_pending ? 1 : 0];
         if (!slot.tried) {
             // capture this variant once; the capture enqueues nothing, sweep() only advances the host flags
             slot.tried = true;
-            const bool bv = c->base_valid, hp = c->have_prev, dv = c->dual_valid;
+            const bool bv = c->base_valid, hp = c->have_prev, dv = c->dual_valid, up = c->u_pending;
             const int it = c->iter;
             if (hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed) == hipSuccess) {
                 sweep(c);
@@ -672,13 +680,14 @@ int cadmm_run(cadmm_ctx* c, int32_t k) {
                     if (hipGraphInstantiate(&slot.exec, graph, nullptr, nullptr, 0) != hipSuccess) slot.exec = nullptr;
                     (void)hipGraphDestroy(graph);
                 }
-                c->base_valid = bv; c->have_prev = hp; c->dual_valid = dv; c->iter = it;
+                c->base_valid = bv; c->have_prev = hp; c->dual_valid = dv; c->u_pending = up; c->iter = it;
             }
             (void)hipGetLastError();
         }
         if (slot.exec && hipGraphLaunch(slot.exec, c->stream) == hipSuccess) {
             if (!c->base_valid) { c->dual_valid = c->have_prev; c->have_prev = true; }
             c->base_valid = false;
+            c->u_pending = c->dual_form == 1;
             c->iter++;
         } else {
             sweep(c);
@@ -774,6 +783,7 @@ int cadmm_get_Z(cadmm_ctx* c, int32_t l, float* dst) {
 int cadmm_get_U(cadmm_ctx* c, float* dst) {
     if (!c || !dst) return CADMM_EINVAL;
     if (!c->has_init) return fail(c, CADMM_EORDER, "init first");
+    if (c->u_pending) base_eval(c);      // dual_form 1: the step of the last sweep rides on the base evaluation
     return download_rows(c, c->U, c->C[c->L], dst);
 }
 
@@ -805,6 +815,7 @@ int cadmm_set_state(cadmm_ctx* c, const float* const* W, const float* const* Z, 
     if (!c->has_init) return fail(c, CADMM_EORDER, "init first");
     const int L = c->L, M = c->hg.M;
     hipStream_t s = c->stream;
+    if (c->u_pending) base_eval(c);      // finish the pending dual step before anything is overwritten
     if (W)
         for (int l = 1; l <= L; ++l)
             if (W[l - 1])

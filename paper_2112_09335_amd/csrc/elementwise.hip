@@ -79,11 +79,14 @@ __device__ __forceinline__ void floor_or_start(Unit* u, double g, double bnorm) 
 // ------------------------------------------------------------------------------------------ phi and G
 // hidden layer:  e = relu(t) - z,  phi += e^2 (scaled nu/2 at the end),  G = nu e 1[t>0]
 // last layer:    r = z - t,        phi += u r + rho/2 r^2,               G = -(u + rho r)
+// apply_dual (last layer only): first take the dual ascent step U += rho (Z_L - T) on the iterate just
+// reached, then evaluate phi and G with the new U.
 template <int LAST, int VEC>
 __global__ __launch_bounds__(256) void phi_G_kernel(const float* __restrict__ T, const float* __restrict__ Z,
-                                                    const float* __restrict__ U, float* __restrict__ G,
-                                                    float* __restrict__ Tprev, int have_prev, int64_t count,
-                                                    float nu, float rho, double* __restrict__ partials) {
+                                                    float* __restrict__ U, float* __restrict__ G,
+                                                    float* __restrict__ Tprev, int have_prev, int apply_dual,
+                                                    int64_t count, float nu, float rho,
+                                                    double* __restrict__ partials) {
     __shared__ double sm[4];
     double s_phi = 0.0, s_res = 0.0, s_dt = 0.0;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x * VEC;
@@ -95,6 +98,11 @@ __global__ __launch_bounds__(256) void phi_G_kernel(const float* __restrict__ T,
             float u[VEC], tp[VEC];
             ldv<VEC>(u, U + i);
             if (Tprev && have_prev) ldv<VEC>(tp, Tprev + i);
+            if (apply_dual) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) u[v] = u[v] + rho * (z[v] - t[v]);
+                stv<VEC>(U + i, u);
+            }
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
                 const double r = (double)z[v] - (double)t[v];
@@ -470,7 +478,7 @@ template <int LPLOG>
 __global__ __launch_bounds__(256) void last_layer_kernel(float* __restrict__ ZL, float* __restrict__ U,
                                                          const float* __restrict__ TL,
                                                          const int32_t* __restrict__ labels, int64_t N, int CL,
-                                                         int risk, float rho, int J) {
+                                                         int risk, float rho, int J, int update_u) {
     constexpr int LP = 1 << LPLOG;
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t row = t >> LPLOG;
@@ -543,12 +551,15 @@ __global__ __launch_bounds__(256) void last_layer_kernel(float* __restrict__ ZL,
         }
     }
     if (vec && ok[0]) {
-        *reinterpret_cast<float4*>(U + base) = make_float4(un[0], un[1], un[2], un[3]);
+        if (update_u) *reinterpret_cast<float4*>(U + base) = make_float4(un[0], un[1], un[2], un[3]);
         *reinterpret_cast<float4*>(ZL + base) = make_float4(x[0], x[1], x[2], x[3]);
     } else {
 #pragma unroll
         for (int v = 0; v < 4; ++v)
-            if (ok[v]) { U[base + v] = un[v]; ZL[base + v] = x[v]; }
+            if (ok[v]) {
+                if (update_u) U[base + v] = un[v];
+                ZL[base + v] = x[v];
+            }
     }
 }
 
@@ -611,12 +622,12 @@ inline int flat_grid(int64_t count) {
 
 }  // namespace
 
-void launch_phi_G(hipStream_t s, const float* T, const float* Z, const float* U, float* G, float* Tprev,
-                  int have_prev, int64_t count, int last, float nu, float rho, double* partials,
+void launch_phi_G(hipStream_t s, const float* T, const float* Z, float* U, float* G, float* Tprev,
+                  int have_prev, int apply_dual, int64_t count, int last, float nu, float rho, double* partials,
                   LayerScalars* out) {
     const int nb = flat_grid(count);
     const bool v4 = (count % 4) == 0;
-#define CADMM_PHI_G(L_, V_) hipLaunchKernelGGL((phi_G_kernel<L_, V_>), dim3(nb), dim3(256), 0, s, T, Z, U, G, Tprev, have_prev, count, nu, rho, partials)
+#define CADMM_PHI_G(L_, V_) hipLaunchKernelGGL((phi_G_kernel<L_, V_>), dim3(nb), dim3(256), 0, s, T, Z, U, G, Tprev, have_prev, apply_dual, count, nu, rho, partials)
     if (last) { if (v4) CADMM_PHI_G(1, 4); else CADMM_PHI_G(1, 1); }
     else { if (v4) CADMM_PHI_G(0, 4); else CADMM_PHI_G(0, 1); }
 #undef CADMM_PHI_G
@@ -697,8 +708,8 @@ void launch_z_step(hipStream_t s, float* Zl, const float* gradZ, const int32_t* 
 }
 
 void launch_last_layer(hipStream_t s, float* ZL, float* U, const float* TL, const int32_t* labels, int64_t N,
-                       int CL, int risk, float rho, int J) {
-#define CADMM_LAST(LG_) hipLaunchKernelGGL((last_layer_kernel<LG_>), dim3((unsigned)(((N << LG_) + 255) / 256)), dim3(256), 0, s, ZL, U, TL, labels, N, CL, risk, rho, J)
+                       int CL, int risk, float rho, int J, int update_u) {
+#define CADMM_LAST(LG_) hipLaunchKernelGGL((last_layer_kernel<LG_>), dim3((unsigned)(((N << LG_) + 255) / 256)), dim3(256), 0, s, ZL, U, TL, labels, N, CL, risk, rho, J, update_u)
     if (CL <= 4) CADMM_LAST(0);
     else if (CL <= 8) CADMM_LAST(1);
     else if (CL <= 16) CADMM_LAST(2);

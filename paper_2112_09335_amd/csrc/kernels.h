@@ -88,8 +88,9 @@ struct SearchParams {
 
 // phi_l and G_l at T (hidden: G = nu (relu(T)-Z) 1[T>0]; last: G = -(U + rho (Z - T))).
 // last != 0 additionally accumulates ||Z-T||^2, ||T-Tprev||^2 (if have_prev) and writes Tprev = T.
-void launch_phi_G(hipStream_t s, const float* T, const float* Z, const float* U, float* G, float* Tprev,
-                  int have_prev, int64_t count, int last, float nu, float rho, double* partials,
+// apply_dual (last layer): U += rho (Z - T) is applied first (dual ascent on the iterate just reached).
+void launch_phi_G(hipStream_t s, const float* T, const float* Z, float* U, float* G, float* Tprev,
+                  int have_prev, int apply_dual, int64_t count, int last, float nu, float rho, double* partials,
                   LayerScalars* out);
 // G only (no reduction), same formulas.
 void launch_G_only(hipStream_t s, const float* T, const float* Z, const float* U, float* G, int64_t count,
@@ -129,8 +130,9 @@ void launch_z_step(hipStream_t s, float* Zl, const float* gradZ, const int32_t* 
                    const Unit* units);
 // Last layer (Appendix A, Eq. 5) by J FISTA steps per row, fused with the dual step (Eq. 2):
 //   U_new = U + rho (Z_L - T_L),  Z_L_new = FISTA(start Z_L; c = T_L, U, rho)
+// update_u = 0 leaves U alone (the dual step is then taken on the new iterates by the next phi_G)
 void launch_last_layer(hipStream_t s, float* ZL, float* U, const float* TL, const int32_t* labels, int64_t N,
-                       int CL, int risk, float rho, int J);
+                       int CL, int risk, float rho, int J, int update_u);
 void launch_relu(hipStream_t s, const float* T, float* Z, int64_t count, int apply_relu);
 void launch_argmax_rows(hipStream_t s, const float* T, int32_t* pred, int64_t N, int C);
 void launch_fill_units(hipStream_t s, Unit* units, int n, double step);

@@ -96,7 +96,7 @@ def test_bad_arguments_are_rejected_with_error_codes():
     with pytest.raises(binding.CadmmError):
         s.set_model([3, 2, 2], **dict(hyper, eta=1.0))
     with pytest.raises(binding.CadmmError):
-        s.set_model([3, 2, 2], **dict(hyper, dual_form=1))
+        s.set_model([3, 2, 2], **dict(hyper, dual_form=2))
     s.set_model([3, 2, 2], **hyper)
     assert s.workspace_bytes() > 0
     with pytest.raises(binding.CadmmError):

@@ -146,3 +146,12 @@ def test_inference_matches_the_oracle_between_iterations():
         assert abs(solver.eval()["objective"] - orc.stats()["objective"]) <= 1e-4 * orc.stats()["objective"]
     say("accuracy per iteration", accs)
     solver.close()
+
+
+def test_dual_ascent_on_new_iterates_variant():
+    w = synth.config(1, 0.5)
+    w.hyper["dual_form"] = 1
+    run_case(w, 6, "dual-form-1")
+    w = synth.config(3, 0.005)
+    w.hyper["dual_form"] = 1
+    run_case(w, 5, "dual-form-1/3-layer")

@@ -350,6 +350,23 @@ def test_predict_is_the_forward_pass_with_a_dense_adjacency():
     np.testing.assert_allclose(o2.predict()[1], o2.get_Z(o2.L), rtol=1e-12, atol=1e-13)
 
 
+def test_dual_form_1_is_dual_ascent_on_the_new_iterates():
+    o, _ = tiny_problem(21, hyper=dict(dual_form=1))
+    o0, _ = tiny_problem(21)
+    A = o.g.A.toarray()
+    U0 = o.U.copy()
+    o.iterate(1)
+    o0.iterate(1)
+    r_new = o.Z[o.L] - A @ o.Z[o.L - 1] @ o.W[o.L]
+    np.testing.assert_allclose(o.U - U0, o.rho * r_new, rtol=1e-10, atol=1e-12)
+    assert o.stats()["primal_res"] == pytest.approx(np.linalg.norm(o.U - U0) / o.rho, rel=1e-10)
+    # W and Z of the first iteration do not depend on the form of the dual step; U does
+    for l in range(1, o.L + 1):
+        np.testing.assert_array_equal(o.W[l], o0.W[l])
+        np.testing.assert_array_equal(o.Z[l], o0.Z[l])
+    assert np.abs(o.U - o0.U).max() > 1e-3
+
+
 def test_disconnected_communities_decouple_in_the_Z_update():
     """Without inter-community edges N_m is empty, no s-terms exist, and Z_{l,m}^{k+1} equals what a
     one-community problem on the subgraph of V_m alone produces from the same W^{k+1}."""
