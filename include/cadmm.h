@@ -193,6 +193,9 @@ const char* cadmm_profile_class_name(int32_t cls);
 
 /* Tuning knobs for experiments.  "use_graph" (per context): 1 = cadmm_run replays one iteration as a
  * captured HIP graph when the context's stream is not the default stream (default), 0 = plain launches.
+ * "t1_refresh" (per context): the first layer's pre-activation A~ Z_0 W_1 is carried from one iteration
+ * to the next through the W step (it does not depend on Z) and formed anew as a product every this
+ * many iterations (default 16; 0 = always form the product).
  * Process-wide: "spmm_tile_cols": feature columns handled per
  * aggregation launch (0 = all at once); "spmm_xcd_remap": 1 = each XCD walks one contiguous eighth of
  * the rows, 0 = blocks in plain order (default); "spmm_groups_log2": lane groups that share one output
