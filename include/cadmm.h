@@ -186,16 +186,16 @@ int  cadmm_op_wgrad(cadmm_ctx* ctx, const float* A, const float* G, int64_t n, i
  * number of timed launch groups, and the algorithmic bytes and flops booked for them (what the
  * operation must move / compute: operands read once, results written once).
  */
-#define CADMM_PROFILE_CLASSES 15
+#define CADMM_PROFILE_CLASSES 16
 int  cadmm_profile(cadmm_ctx* ctx, int enable);
 int  cadmm_get_profile(cadmm_ctx* ctx, double* ms, int64_t* records, double* bytes, double* flops);
 const char* cadmm_profile_class_name(int32_t cls);
 
 /* Tuning knobs for experiments.  "use_graph" (per context): 1 = cadmm_run replays one iteration as a
  * captured HIP graph when the context's stream is not the default stream (default), 0 = plain launches.
- * "t1_refresh" (per context): the first layer's pre-activation A~ Z_0 W_1 is carried from one iteration
- * to the next through the W step (it does not depend on Z) and formed anew as a product every this
- * many iterations (default 16; 0 = always form the product).
+ * "t1_refresh" (per context): the pre-activations A~ Z_{l-1} W_l are carried from one iteration to the
+ * next (through the W step, and through the segment products of the Z step) and formed anew every
+ * this many iterations (default 16; 0 = always form them anew).
  * Process-wide: "spmm_tile_cols": feature columns handled per
  * aggregation launch (0 = all at once); "spmm_xcd_remap": 1 = each XCD walks one contiguous eighth of
  * the rows, 0 = blocks in plain order (default); "spmm_groups_log2": lane groups that share one output

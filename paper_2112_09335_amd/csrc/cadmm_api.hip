@@ -50,6 +50,9 @@ struct cadmm_ctx {
     int32_t* d_unit_chunk_ptr = nullptr;
     int32_t* d_labels = nullptr;
     int32_t* d_pred = nullptr;
+    int64_t* d_row_seg_ptr = nullptr;
+    int32_t* d_seg_comm = nullptr;
+    int32_t* d_seg_pos = nullptr;
     std::vector<int32_t> h_labels;     // internal row order
     // split rows of the CSR row list and of the segment list; side buffer for their parts
     int64_t* d_lr_part_lo = nullptr; int64_t* d_lr_part_hi = nullptr;
@@ -64,7 +67,8 @@ struct cadmm_ctx {
     float* tmpA = nullptr;      // N x max width: staging, G W^T
     float* tmpB = nullptr;      // N x max hidden width: gradient of the Z subproblem
     float* tmpV = nullptr;      // N x max next width
-    float* P = nullptr;         // n_seg x max next width
+    float* P = nullptr;         // n_seg x max next width, the buffer of the layer being searched
+    float* Pbuf[2] = {nullptr, nullptr};   // layers alternate: P of layer l stays until layer l+1 is done
     float* gradW = nullptr;
     float* Wt = nullptr;
     float* tn_partial = nullptr;
@@ -76,9 +80,11 @@ struct cadmm_ctx {
     int32_t* status = nullptr;
     bool base_valid = false, have_prev = false, dual_valid = false;
     int iter = 0;
-    // T_1 = A~ Z_0 W_1 does not depend on any Z, so the W step's T_1 - Q/tau IS the next iteration's T_1.
-    // t1_age counts such updates since the last exact product (-1: T[1] is not an image of W_1); after
-    // t1_refresh of them the product is formed again, which bounds the rounding drift.
+    // The pre-activations T_l = A~ Z_{l-1} W_l are carried from one iteration to the next instead of being
+    // formed anew: the W step leaves T_l - Q/tau = A~ Z_{l-1}^k W_l^{k+1}, and the Z step of layer l-1 changes
+    // it by - sum_c P_(i,c) / theta_c (T_1 does not depend on any Z at all).  t1_age counts such updates since
+    // the last exact evaluation (-1: the T buffers are not images of the state); after t1_refresh of them
+    // everything is formed again, which bounds the rounding drift.
     int t1_age = -1;
     int t1_refresh = 16;
     // One iteration captured as a HIP graph, per variant of the launch sequence (base evaluation already
@@ -155,6 +161,9 @@ size_t layout(cadmm_ctx* c, char* base) {
     c->d_unit_chunk_ptr = b.take<int32_t>(g.M + 1);
     c->d_labels = b.take<int32_t>(N);
     c->d_pred = b.take<int32_t>(N);
+    c->d_row_seg_ptr = b.take<int64_t>(N + 1);
+    c->d_seg_comm = b.take<int32_t>(g.n_seg);
+    c->d_seg_pos = b.take<int32_t>(g.n_seg);
     c->d_lr_part_lo = b.take<int64_t>(g.long_rows.n_parts());
     c->d_lr_part_hi = b.take<int64_t>(g.long_rows.n_parts());
     c->d_lr_row = b.take<int32_t>(g.long_rows.n_long());
@@ -184,7 +193,9 @@ size_t layout(cadmm_ctx* c, char* base) {
     c->tmpA = b.take<float>(N * max_of(c->C, 0, L));
     c->tmpB = b.take<float>(N * max_of(c->C, 1, L - 1));
     c->tmpV = b.take<float>(N * max_of(c->C, 2, L));
-    c->P = b.take<float>(g.n_seg * max_of(c->C, 2, L));
+    c->Pbuf[0] = b.take<float>(g.n_seg * max_of(c->C, 2, L));
+    c->Pbuf[1] = L > 2 ? b.take<float>(g.n_seg * max_of(c->C, 2, L)) : c->Pbuf[0];
+    c->P = c->Pbuf[0];
     size_t wmax = 0, tnmax = 0;
     for (int l = 1; l <= L; ++l) {
         size_t w = (size_t)c->C[l - 1] * c->C[l];
@@ -216,12 +227,13 @@ hipError_t upload(hipStream_t s, T* dst, const std::vector<T>& src) {
 // set beside a profiler's per-kernel averages.
 enum ProfClass {
     P_SPMM = 0, P_SPMM_GRADZ, P_SPMM_SEG, P_GEMM_NN_128, P_GEMM_NN_128_GRADZ, P_GEMM_NN_32, P_GEMM_TN, P_PHI_G,
-    P_G_ONLY, P_W_TRIAL, P_Z_TRIAL, P_W_STEP, P_Z_STEP, P_LAST_LAYER, P_OTHER
+    P_G_ONLY, P_W_TRIAL, P_Z_TRIAL, P_W_STEP, P_Z_STEP, P_LAST_LAYER, P_T_CARRY, P_OTHER
 };
 const char* kProfNames[CADMM_PROFILE_CLASSES] = {
     "spmm_rows_kernel[rows]", "spmm_rows_kernel[rows,gradz]", "spmm_rows_kernel[segments]", "gemm_nn_kernel<128,0>",
     "gemm_nn_kernel<128,1>", "gemm_nn_kernel<32>", "gemm_tn_kernel+reduce", "phi_G_kernel", "G_only_kernel",
-    "w_trial_kernel", "z_trial_kernel", "w_step_kernel", "z_step_kernel", "last_layer_kernel", "other"};
+    "w_trial_kernel", "z_trial_kernel", "w_step_kernel", "z_step_kernel", "last_layer_kernel", "t_carry_kernel",
+    "other"};
 
 hipEvent_t prof_event(cadmm_ctx* c) {
     if (!c->prof_pool.empty()) {
@@ -305,14 +317,15 @@ bool t1_reusable(const cadmm_ctx* c) { return c->t1_age >= 0 && c->t1_age < c->t
 // by every base evaluation, so that re-evaluating an unchanged point reproduces T_l bit for bit.
 void compute_T(cadmm_ctx* c, int l) {
     const int64_t N = c->hg.N;
+    const bool carried = t1_reusable(c);               // T[l] already holds A~ Z_{l-1} W_l for the current state
     if (c->agg_first[l]) {
+        if (carried) return;
         gemm_nn(c, c->Z[l - 1], c->W[l], c->tmpV, N, c->C[l - 1], c->C[l]);
         aggregate(c, c->tmpV, c->T[l], c->C[l], SpmmEpilogue());
     } else {
-        if (l >= 2) aggregate(c, c->Z[l - 1], c->H[l], c->C[l - 1], SpmmEpilogue());
-        if (l == 1 && t1_reusable(c)) return;          // T[1] already holds A~ Z_0 W_1 for the current W_1
+        if (l >= 2) aggregate(c, c->Z[l - 1], c->H[l], c->C[l - 1], SpmmEpilogue());   // the W step needs H_l itself
+        if (carried) return;
         gemm_nn(c, c->H[l], c->W[l], c->T[l], N, c->C[l - 1], c->C[l]);
-        if (l == 1) c->t1_age = 0;
     }
 }
 
@@ -331,10 +344,22 @@ void base_eval(cadmm_ctx* c) {
                          c->partials, c->scalars + l);
         });
     }
+    if (!t1_reusable(c)) c->t1_age = 0;                // every T_l was just formed exactly
     c->u_pending = false;
     c->dual_valid = c->have_prev;
     c->have_prev = true;
     c->base_valid = true;
+}
+
+// T_l <- A~ Z_{l-1}^{k+1} W_l^{k+1}, from the segment products P of layer l-1 and its accepted theta.
+void carry_T(cadmm_ctx* c, int l) {
+    if (c->t1_refresh <= 0) return;
+    const int64_t N = c->hg.N;
+    const int Cl = c->C[l];
+    timed(c, P_T_CARRY, 4.0 * ((double)c->hg.n_seg * Cl + 2.0 * (double)N * Cl) + 8.0 * (double)c->hg.n_seg, 0.0, [&] {
+        launch_t_carry(c->stream, c->T[l], c->Pbuf[(l - 1) & 1], c->d_row_seg_ptr, c->d_seg_comm, c->d_seg_pos, N, Cl,
+                       c->unitsZ + (size_t)(l - 2) * c->hg.M);
+    });
 }
 
 void sweep(cadmm_ctx* c) {
@@ -380,7 +405,7 @@ void sweep(cadmm_ctx* c) {
         timed(c, P_W_STEP, 4.0 * (3.0 * (double)count + 3.0 * K * Cl), 0.0, [&] {
             launch_w_step(s, c->W[l], c->gradW, K * Cl, c->T[l], Q, count, unit);    // W^{k+1}; T_l = A~ Z^k W^{k+1}
         });
-        if (l == 1 && c->t1_age >= 0) c->t1_age++;
+
     }
 
     // ---- Z-update, hidden layers, every community from (W^{k+1}, Z^k, U^k)   (Appendix A, Eqs. 3, 4, 6-8)
@@ -390,6 +415,7 @@ void sweep(cadmm_ctx* c) {
         const int Cl = c->C[l], Cn = c->C[l + 1];
         const int next_last = (l + 1 == L);
         Unit* units = c->unitsZ + (size_t)(l - 1) * M;
+        c->P = c->Pbuf[l & 1];
         timed(c, P_G_ONLY, 4.0 * (double)N * Cn * (next_last ? 4 : 3), 0.0, [&] {
             launch_G_only(s, c->T[l + 1], c->Z[l + 1], c->U, c->G[l + 1], N * Cn, next_last, c->nu, c->rho);
         });
@@ -434,6 +460,8 @@ void sweep(cadmm_ctx* c) {
         });
         timed(c, P_Z_STEP, 4.0 * (3.0 * (double)N * Cl + (double)N), 0.0,
               [&] { launch_z_step(s, c->Z[l], c->tmpB, c->d_row_comm, N, Cl, units); });
+        // T_l is not read again in this sweep: bring it to the new Z_{l-1} (P and theta of layer l-1)
+        if (l >= 2) carry_T(c, l);
     }
 
     // ---- last layer Z_L (Eq. 5) and the dual step (Eq. 2), both from Z_L^k, U^k and T_L = A~ Z_{L-1}^k W_L^{k+1}
@@ -441,6 +469,8 @@ void sweep(cadmm_ctx* c) {
         launch_last_layer(s, c->Z[L], c->U, c->T[L], c->d_labels, N, c->C[L], c->risk, c->rho, c->J,
                           c->dual_form == 0 ? 1 : 0);
     });
+    carry_T(c, L);
+    if (c->t1_age >= 0) c->t1_age++;
     if (c->dual_form == 1) c->u_pending = true;      // applied by the next base evaluation, on the new iterates
     c->iter++;
     c->base_valid = false;
@@ -608,6 +638,9 @@ int cadmm_set_workspace(cadmm_ctx* c, void* dev_ptr, size_t bytes) {
     HIP_TRY(c, upload(s, c->d_chunk_begin, cb));
     HIP_TRY(c, upload(s, c->d_chunk_end, ce));
     HIP_TRY(c, upload(s, c->d_unit_chunk_ptr, g.unit_chunk_ptr));
+    HIP_TRY(c, upload(s, c->d_row_seg_ptr, g.row_seg_ptr));
+    HIP_TRY(c, upload(s, c->d_seg_comm, g.seg_comm));
+    HIP_TRY(c, upload(s, c->d_seg_pos, g.seg_pos));
     HIP_TRY(c, upload(s, c->d_lr_part_lo, g.long_rows.part_lo));
     HIP_TRY(c, upload(s, c->d_lr_part_hi, g.long_rows.part_hi));
     HIP_TRY(c, upload(s, c->d_lr_row, g.long_rows.long_row));
@@ -704,7 +737,7 @@ int cadmm_run(cadmm_ctx* c, int32_t k) {
             if (!c->base_valid) {
                 c->dual_valid = c->have_prev;
                 c->have_prev = true;
-                if (!t1_skip && !c->agg_first[1]) c->t1_age = 0;
+                if (!t1_skip) c->t1_age = 0;
             }
             if (c->t1_age >= 0) c->t1_age++;
             c->base_valid = false;
@@ -760,7 +793,6 @@ int cadmm_predict(cadmm_ctx* c, int32_t* pred, float* logits, double* accuracy) 
         } else {
             if (l >= 2) aggregate(c, in, c->H[l], c->C[l - 1], SpmmEpilogue());
             gemm_nn(c, c->H[l], c->W[l], c->T[l], N, c->C[l - 1], c->C[l]);
-            if (l == 1) c->t1_age = 0;
         }
         if (l < L) {
             launch_relu(s, c->T[l], c->G[l], N * c->C[l], 1);
@@ -768,6 +800,7 @@ int cadmm_predict(cadmm_ctx* c, int32_t* pred, float* logits, double* accuracy) 
         }
     }
     c->base_valid = false;
+    c->t1_age = -1;                 // the T buffers now hold the forward pass, not images of the state
     launch_argmax_rows(s, c->T[L], c->d_pred, N, c->C[L]);
     std::vector<int32_t> p((size_t)N);
     HIP_TRY(c, hipMemcpyAsync(p.data(), c->d_pred, N * sizeof(int32_t), hipMemcpyDeviceToHost, s));

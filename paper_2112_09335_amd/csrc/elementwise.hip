@@ -468,6 +468,48 @@ __global__ __launch_bounds__(256) void z_step_kernel(float* __restrict__ Zl, con
     }
 }
 
+// After Z_{l,m} <- Z_{l,m} - grad/theta_{l,m} the next layer's pre-activation A~ Z_l W_{l+1} of row i changes by
+// - sum over the segments (i, c) of P_{(i,c)} / theta_{l,c}  (P = A~_{., c} grad W_{l+1}, already formed for the
+// search).  Applying that keeps T_{l+1} valid for the next iteration without a new aggregation and product.
+template <int VEC>
+__global__ __launch_bounds__(256) void t_carry_kernel(float* __restrict__ Tn, const float* __restrict__ P,
+                                                      const int64_t* __restrict__ row_seg_ptr,
+                                                      const int32_t* __restrict__ seg_comm,
+                                                      const int32_t* __restrict__ seg_pos, int64_t N, int Cn,
+                                                      const Unit* __restrict__ units) {
+    const int wv = (Cn + VEC - 1) / VEC;
+    int cshift = 0;
+    while ((1 << cshift) < wv && cshift < 8) ++cshift;
+    const int cp = 1 << cshift;
+    const int c_first = threadIdx.x & (cp - 1);
+    const int64_t r_step = (int64_t)gridDim.x * (256 >> cshift);
+    for (int64_t r = (int64_t)blockIdx.x * (256 >> cshift) + (threadIdx.x >> cshift); r < N; r += r_step) {
+        const int64_t s0 = row_seg_ptr[r], s1 = row_seg_ptr[r + 1];
+        for (int cv = c_first; cv < wv; cv += cp) {
+            double acc[VEC];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[v] = 0.0;
+            bool any = false;
+            for (int64_t sgm = s0; sgm < s1; ++sgm) {
+                const Unit* u = units + seg_comm[sgm];
+                if (u->skip) continue;
+                any = true;
+                const double inv = 1.0 / u->step;
+                float p[VEC];
+                ldv<VEC>(p, P + (int64_t)seg_pos[sgm] * Cn + cv * VEC);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) acc[v] += (double)p[v] * inv;
+            }
+            if (!any) continue;
+            float t[VEC];
+            ldv<VEC>(t, Tn + r * Cn + cv * VEC);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) t[v] = (float)((double)t[v] - acc[v]);
+            stv<VEC>(Tn + r * Cn + cv * VEC, t);
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------------ last layer + dual
 // 2^LPLOG lanes share one node row, four classes per lane, so a wavefront reads whole 64-byte-aligned
 // pieces of consecutive rows with 16-byte accesses; the row maximum and the softmax denominator are
@@ -705,6 +747,13 @@ void launch_z_step(hipStream_t s, float* Zl, const float* gradZ, const int32_t* 
     const int nb = flat_grid(N * (int64_t)Cl);
     if (Cl % 4 == 0) hipLaunchKernelGGL((z_step_kernel<4>), dim3(nb), dim3(256), 0, s, Zl, gradZ, row_comm, N, Cl, units);
     else hipLaunchKernelGGL((z_step_kernel<1>), dim3(nb), dim3(256), 0, s, Zl, gradZ, row_comm, N, Cl, units);
+}
+
+void launch_t_carry(hipStream_t s, float* Tn, const float* P, const int64_t* row_seg_ptr, const int32_t* seg_comm,
+                    const int32_t* seg_pos, int64_t N, int Cn, const Unit* units) {
+    const int nb = flat_grid(N * (int64_t)Cn * 4);
+    if (Cn % 4 == 0) hipLaunchKernelGGL((t_carry_kernel<4>), dim3(nb), dim3(256), 0, s, Tn, P, row_seg_ptr, seg_comm, seg_pos, N, Cn, units);
+    else hipLaunchKernelGGL((t_carry_kernel<1>), dim3(nb), dim3(256), 0, s, Tn, P, row_seg_ptr, seg_comm, seg_pos, N, Cn, units);
 }
 
 void launch_last_layer(hipStream_t s, float* ZL, float* U, const float* TL, const int32_t* labels, int64_t N,

@@ -196,6 +196,10 @@ std::string build_host_graph(HostGraph& g, int64_t N, int64_t n_edges, const int
         }
     }
 
+    g.row_seg_ptr.assign(seg_cnt.begin(), seg_cnt.end());
+    g.seg_pos.resize((size_t)g.n_seg);
+    for (int64_t j = 0; j < g.n_seg; ++j) g.seg_pos[(size_t)g.segc_order[(size_t)j]] = (int32_t)j;
+
     split_long(g.long_rows, g.row_ptr.data(), g.row_ptr.data() + 1, N);
     split_long(g.long_segs, g.segc_lo.data(), g.segc_hi.data(), g.n_seg);
 

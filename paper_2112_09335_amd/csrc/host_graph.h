@@ -50,6 +50,8 @@ struct HostGraph {
     std::vector<int64_t> segc_hi;       // [n_seg] one past the last entry
     std::vector<int32_t> segc_row;      // [n_seg]
     std::vector<int64_t> segc_comm_ptr; // [M+1]
+    std::vector<int64_t> row_seg_ptr;   // [N+1] segments of a row in the (row, community) order
+    std::vector<int32_t> seg_pos;       // [n_seg] position of that segment in the (community, row) order
     LongRows long_rows;                 // of the CSR rows
     LongRows long_segs;                 // of the segments in (community, row) order
     // reduction chunks for the Z search, grouped by community

@@ -128,6 +128,10 @@ void launch_z_trial(hipStream_t s, const ZTrialArgs& a);
 // Z_l[i,:] -= gradZ[i,:] / theta[comm(i)]
 void launch_z_step(hipStream_t s, float* Zl, const float* gradZ, const int32_t* row_comm, int64_t N, int Cl,
                    const Unit* units);
+// Tn[i,:] -= sum over the segments (i,c) of row i of P[(i,c),:] / theta_c  (communities whose step was skipped
+// contribute nothing): the pre-activation of the next layer after the Z step, without a new aggregation.
+void launch_t_carry(hipStream_t s, float* Tn, const float* P, const int64_t* row_seg_ptr, const int32_t* seg_comm,
+                    const int32_t* seg_pos, int64_t N, int Cn, const Unit* units);
 // Last layer (Appendix A, Eq. 5) by J FISTA steps per row, fused with the dual step (Eq. 2):
 //   U_new = U + rho (Z_L - T_L),  Z_L_new = FISTA(start Z_L; c = T_L, U, rho)
 // update_u = 0 leaves U alone (the dual step is then taken on the new iterates by the next phi_G)
