@@ -186,13 +186,15 @@ int  cadmm_op_wgrad(cadmm_ctx* ctx, const float* A, const float* G, int64_t n, i
  * number of timed launch groups, and the algorithmic bytes and flops booked for them (what the
  * operation must move / compute: operands read once, results written once).
  */
-#define CADMM_PROFILE_CLASSES 16
+#define CADMM_PROFILE_CLASSES 17
 int  cadmm_profile(cadmm_ctx* ctx, int enable);
 int  cadmm_get_profile(cadmm_ctx* ctx, double* ms, int64_t* records, double* bytes, double* flops);
 const char* cadmm_profile_class_name(int32_t cls);
 
 /* Tuning knobs for experiments.  "use_graph" (per context): 1 = cadmm_run replays one iteration as a
  * captured HIP graph when the context's stream is not the default stream (default), 0 = plain launches.
+ * "use_lowrank" (per context): 1 = with a next layer of at most 16 units the Z gradient is kept as
+ * nu (Z_l - relu(T_l)) + (A~ G_{l+1}) W_{l+1}^T and rebuilt per element by its consumers (default), 0 = stored.
  * "t1_refresh" (per context): the pre-activations A~ Z_{l-1} W_l are carried from one iteration to the
  * next (through the W step, and through the segment products of the Z step) and formed anew every
  * this many iterations (default 16; 0 = always form them anew).

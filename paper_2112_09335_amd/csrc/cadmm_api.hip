@@ -71,6 +71,7 @@ struct cadmm_ctx {
     float* Pbuf[2] = {nullptr, nullptr};   // layers alternate: P of layer l stays until layer l+1 is done
     float* gradW = nullptr;
     float* Wt = nullptr;
+    float* Bcat = nullptr;      // [W_{l+1}; W_{l+1}^T W_{l+1}] for the low-rank form of the Z gradient
     float* tn_partial = nullptr;
     size_t tn_partial_floats = 0;
     double* partials = nullptr;
@@ -91,6 +92,7 @@ struct cadmm_ctx {
     // done or not; previous T_L available or not).  Replayed by cadmm_run when the stream is not the
     // default stream; launch-bound problem sizes gain most.
     bool use_graph = true;
+    bool use_lowrank = true;
     struct GraphSlot { hipGraphExec_t exec = nullptr; bool tried = false; };
     GraphSlot graphs[2][2][2][2];
     // optional per-kernel-class timing with HIP events on the context's stream
@@ -205,6 +207,7 @@ size_t layout(cadmm_ctx* c, char* base) {
     }
     c->gradW = b.take<float>(wmax);
     c->Wt = b.take<float>(wmax);
+    c->Bcat = b.take<float>((size_t)(max_of(c->C, 0, L) + kLowRankMax) * kLowRankMax);
     c->tn_partial = b.take<float>(tnmax);
     c->tn_partial_floats = tnmax;
     size_t np = (size_t)kReduceBlocks * kMaxCand;
@@ -227,13 +230,13 @@ hipError_t upload(hipStream_t s, T* dst, const std::vector<T>& src) {
 // set beside a profiler's per-kernel averages.
 enum ProfClass {
     P_SPMM = 0, P_SPMM_GRADZ, P_SPMM_SEG, P_GEMM_NN_128, P_GEMM_NN_128_GRADZ, P_GEMM_NN_32, P_GEMM_TN, P_PHI_G,
-    P_G_ONLY, P_W_TRIAL, P_Z_TRIAL, P_W_STEP, P_Z_STEP, P_LAST_LAYER, P_T_CARRY, P_OTHER
+    P_G_ONLY, P_W_TRIAL, P_Z_TRIAL, P_W_STEP, P_Z_STEP, P_LAST_LAYER, P_T_CARRY, P_GEMM_GRADZ, P_OTHER
 };
 const char* kProfNames[CADMM_PROFILE_CLASSES] = {
     "spmm_rows_kernel[rows]", "spmm_rows_kernel[rows,gradz]", "spmm_rows_kernel[segments]", "gemm_nn_kernel<128,0>",
     "gemm_nn_kernel<128,1>", "gemm_nn_kernel<32>", "gemm_tn_kernel+reduce", "phi_G_kernel", "G_only_kernel",
     "w_trial_kernel", "z_trial_kernel", "w_step_kernel", "z_step_kernel", "last_layer_kernel", "t_carry_kernel",
-    "other"};
+    "gemm_nn_gradz_kernel", "other"};
 
 hipEvent_t prof_event(cadmm_ctx* c) {
     if (!c->prof_pool.empty()) {
@@ -422,7 +425,17 @@ void sweep(cadmm_ctx* c) {
         timed(c, P_OTHER, 8.0 * Cl * Cn, 0.0, [&] { launch_transpose(s, c->W[l + 1], c->Wt, Cl, Cn); });
         // grad psi (all communities at once) = nu (Z_l - relu(T_l)) + A~ G_{l+1} W_{l+1}^T; aggregate on the
         // narrower of the two widths, the penalty term rides in the epilogue of whichever kernel comes last
-        if (Cn < Cl) {
+        // With a very narrow next layer the gradient nu (Z_l - relu(T_l)) + (A~ G_{l+1}) W_{l+1}^T is never
+        // stored: its consumers (the product with W_{l+1}, the search, the step) rebuild it per element from
+        // Z_l, T_l and the N x C_{l+1} factor, which removes a full write and two full reads of an N x C_l matrix.
+        const bool lowrank = c->use_lowrank && Cn <= kLowRankMax && Cn < Cl && Cn % 4 == 0 && Cl % 4 == 0 && Cl <= 1024;
+        if (lowrank) {
+            aggregate(c, c->G[l + 1], c->tmpA, Cn, SpmmEpilogue());                  // A~ G_{l+1}
+            timed(c, P_OTHER, 8.0 * Cl * Cn, 0.0, [&] {
+                launch_relu(s, c->W[l + 1], c->Bcat, (int64_t)Cl * Cn, 0);             // rows 0..Cl: W_{l+1}
+                launch_gemm_nn(s, c->Wt, c->W[l + 1], c->Bcat + (size_t)Cl * Cn, Cn, Cl, Cn);   // then W^T W
+            });
+        } else if (Cn < Cl) {
             aggregate(c, c->G[l + 1], c->tmpA, Cn, SpmmEpilogue());                  // A~ G_{l+1}
             GemmEpilogue ge;
             ge.kind = 1; ge.Zl = c->Z[l]; ge.Tl = c->T[l]; ge.nu = c->nu;
@@ -433,7 +446,12 @@ void sweep(cadmm_ctx* c) {
             epi.kind = 1; epi.Zl = c->Z[l]; epi.Tl = c->T[l]; epi.nu = c->nu;
             aggregate(c, c->tmpA, c->tmpB, Cl, epi);
         }
-        gemm_nn(c, c->tmpB, c->W[l + 1], c->tmpV, N, Cl, Cn);                        // grad W_{l+1}
+        if (lowrank)
+            timed(c, P_GEMM_GRADZ, 4.0 * (2.0 * (double)N * Cl + 2.0 * (double)N * Cn), 2.0 * (double)N * (Cl + Cn) * Cn, [&] {
+                launch_gemm_nn_gradz(s, c->Z[l], c->T[l], c->tmpA, c->Bcat, c->tmpV, N, Cl, Cn, Cn, c->nu);
+            });
+        else
+            gemm_nn(c, c->tmpB, c->W[l + 1], c->tmpV, N, Cl, Cn);                    // grad W_{l+1}
         timed(c, P_SPMM_SEG, spmm_bytes(c, c->hg.n_seg, Cn, 0), 2.0 * (double)c->hg.nnz * Cn, [&] {
             launch_spmm(s, c->d_segc_lo, c->d_segc_hi, c->d_col, c->d_val, c->tmpV, c->P, c->hg.n_seg, Cn,
                         SpmmEpilogue(), long_segs_of(c));                            // A~_{r,m} (grad W) per segment
@@ -445,21 +463,26 @@ void sweep(cadmm_ctx* c) {
         a.n_chunks = (int32_t)c->hg.chunks.size();
         a.unit_chunk_ptr = c->d_unit_chunk_ptr; a.M = M;
         a.segc_row = c->d_segc_row;
-        a.Zl = c->Z[l]; a.gradZ = c->tmpB; a.Tl = c->T[l]; a.Cl = Cl;
+        a.Zl = c->Z[l]; a.gradZ = lowrank ? nullptr : c->tmpB; a.Tl = c->T[l]; a.Cl = Cl;
+        a.SG = c->tmpA; a.Wt = c->Wt;
         a.Tn = c->T[l + 1]; a.Zn = c->Z[l + 1]; a.U = c->U; a.P = c->P; a.Cn = Cn;
         a.next_is_last = next_last;
         a.sp = sp; a.units = units; a.partials = c->partials; a.status = c->status;
         // one pass reads Z_l, grad, T_l over the rows and T_{l+1}, Z_{l+1} (U), P over the segments
-        const double zt_bytes = 4.0 * (3.0 * (double)N * Cl + (next_last ? 4.0 : 3.0) * (double)c->hg.n_seg * Cn) +
-                                4.0 * (double)c->hg.n_seg;
+        const double zt_bytes = 4.0 * ((lowrank ? 2.0 : 3.0) * (double)N * Cl + (lowrank ? (double)N * Cn : 0.0) +
+                                       (next_last ? 4.0 : 3.0) * (double)c->hg.n_seg * Cn) + 4.0 * (double)c->hg.n_seg;
         timed(c, P_Z_TRIAL, zt_bytes, 0.0, [&] {
             a.first_pass = 1; a.ncand = 1;
             launch_z_trial(s, a);
             a.first_pass = 0; a.ncand = kMaxCand;
             for (int p = 0; p < more_passes; ++p) launch_z_trial(s, a);
         });
-        timed(c, P_Z_STEP, 4.0 * (3.0 * (double)N * Cl + (double)N), 0.0,
-              [&] { launch_z_step(s, c->Z[l], c->tmpB, c->d_row_comm, N, Cl, units); });
+        timed(c, P_Z_STEP, 4.0 * (3.0 * (double)N * Cl + (double)N + (lowrank ? (double)N * Cn : 0.0)), 0.0, [&] {
+            if (lowrank)
+                launch_z_step_lowrank(s, c->Z[l], c->T[l], c->tmpA, c->Wt, c->nu, c->d_row_comm, N, Cl, Cn, units);
+            else
+                launch_z_step(s, c->Z[l], c->tmpB, c->d_row_comm, N, Cl, units);
+        });
         // T_l is not read again in this sweep: bring it to the new Z_{l-1} (P and theta of layer l-1)
         if (l >= 2) carry_T(c, l);
     }
@@ -949,6 +972,18 @@ const char* cadmm_profile_class_name(int32_t cls) {
 int cadmm_tune(cadmm_ctx* c, const char* key, int32_t value) {
     if (!c || !key) return CADMM_EINVAL;
     if (std::strcmp(key, "use_graph") == 0) { c->use_graph = value != 0; return CADMM_OK; }
+    if (std::strcmp(key, "use_lowrank") == 0) {
+        c->use_lowrank = value != 0;
+        for (auto& cube : c->graphs)
+            for (auto& plane : cube)
+                for (auto& row : plane)
+                    for (auto& slot : row) {
+                        if (slot.exec) (void)hipGraphExecDestroy(slot.exec);
+                        slot.exec = nullptr;
+                        slot.tried = false;
+                    }
+        return CADMM_OK;
+    }
     if (std::strcmp(key, "t1_refresh") == 0) { c->t1_refresh = value; c->t1_age = -1; return CADMM_OK; }
     if (std::strcmp(key, "spmm_tile_cols") == 0) { set_spmm_tile_cols(value); return CADMM_OK; }
     if (std::strcmp(key, "spmm_xcd_remap") == 0) { set_spmm_xcd_remap(value); return CADMM_OK; }

@@ -322,7 +322,23 @@ __global__ __launch_bounds__(256) void w_step_kernel(float* __restrict__ W, cons
 //     nu/2 ||Z - relu(T_l)||^2  under  Z -> Z - gradZ/theta;
 // kind 1: segments [begin,end) (community,row order) of the next layer's term, whose pre-activation
 //     row T_{l+1,i} moves by -P_s/theta as seen from this community.
-template <int NC, int VEC>
+// grad[v] = nu (z[v] - relu(t[v])) + sum_k sg[k] wt[k][v], always in this order (the step kernel must
+// reproduce the very same values the search saw)
+__device__ __forceinline__ void lowrank_grad(float (&g)[4], const float (&z)[4], const float (&t)[4],
+                                             const float (&sg)[kLowRankMax], const float (&wt)[kLowRankMax][4], int Cn,
+                                             float nu) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) g[v] = nu * (z[v] - fmaxf(t[v], 0.f));
+#pragma unroll
+    for (int k = 0; k < kLowRankMax; ++k) {
+        if (k < Cn) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) g[v] = fmaf(sg[k], wt[k][v], g[v]);
+        }
+    }
+}
+
+template <int NC, int VEC, int LR>
 __global__ __launch_bounds__(256) void z_trial_kernel(ZTrialArgs a) {
     __shared__ double sm[4];
     const int ch = blockIdx.x;
@@ -351,13 +367,32 @@ __global__ __launch_bounds__(256) void z_trial_kernel(ZTrialArgs a) {
     const int r_step = 256 >> cshift;
     const double hnu = 0.5 * (double)a.sp.nu, hrho = 0.5 * (double)a.sp.rho;
     if (kind == 0) {
+        // low-rank gradient: this thread's four columns of Wt stay in registers (one column slot per thread)
+        float wt[LR ? kLowRankMax : 1][4];
+        if constexpr (LR == 1) {
+#pragma unroll
+            for (int k = 0; k < kLowRankMax; ++k) {
+                if (k < a.Cn && c_first < wv) ldv<4>(wt[k], a.Wt + (int64_t)k * width + c_first * 4);
+                else { wt[k][0] = 0.f; wt[k][1] = 0.f; wt[k][2] = 0.f; wt[k][3] = 0.f; }
+            }
+        }
         for (int r = begin + r_first; r < end; r += r_step) {
             const int64_t base = (int64_t)r * width;
+            float srow[LR ? kLowRankMax : 1];      // this row of the N x Cn factor
+            if constexpr (LR == 1) {
+#pragma unroll
+                for (int k4 = 0; k4 < kLowRankMax / 4; ++k4) {
+                    float q[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (4 * k4 < a.Cn) ldv<4>(q, a.SG + (int64_t)r * a.Cn + 4 * k4);
+                    srow[4 * k4] = q[0]; srow[4 * k4 + 1] = q[1]; srow[4 * k4 + 2] = q[2]; srow[4 * k4 + 3] = q[3];
+                }
+            }
             for (int cv = c_first; cv < wv; cv += cp) {
                 float zv[VEC], gv[VEC], tv[VEC];
                 ldv<VEC>(zv, a.Zl + base + cv * VEC);
-                ldv<VEC>(gv, a.gradZ + base + cv * VEC);
                 ldv<VEC>(tv, a.Tl + base + cv * VEC);
+                if constexpr (LR == 1) lowrank_grad(gv, zv, tv, srow, wt, a.Cn, a.sp.nu);
+                else ldv<VEC>(gv, a.gradZ + base + cv * VEC);
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
                     const double z = (double)zv[v], gz = (double)gv[v], t = (double)tv[v];
@@ -465,6 +500,43 @@ __global__ __launch_bounds__(256) void z_step_kernel(float* __restrict__ Zl, con
             for (int v = 0; v < VEC; ++v) z[v] = (float)((double)z[v] - (double)g[v] * inv);
             stv<VEC>(Zl + base + cv * VEC, z);
         }
+    }
+}
+
+__global__ __launch_bounds__(256) void z_step_lowrank_kernel(float* __restrict__ Zl, const float* __restrict__ Tl,
+                                                             const float* __restrict__ SG, const float* __restrict__ Wt,
+                                                             float nu, const int32_t* __restrict__ row_comm, int64_t N,
+                                                             int Cl, int Cn, const Unit* __restrict__ units) {
+    const int wv = Cl / 4;
+    int cshift = 0;
+    while ((1 << cshift) < wv && cshift < 8) ++cshift;
+    const int c_first = threadIdx.x & ((1 << cshift) - 1);
+    float wt[kLowRankMax][4];
+#pragma unroll
+    for (int k = 0; k < kLowRankMax; ++k) {
+        if (k < Cn && c_first < wv) ldv<4>(wt[k], Wt + (int64_t)k * Cl + c_first * 4);
+        else { wt[k][0] = 0.f; wt[k][1] = 0.f; wt[k][2] = 0.f; wt[k][3] = 0.f; }
+    }
+    const int64_t r_step = (int64_t)gridDim.x * (256 >> cshift);
+    for (int64_t r = (int64_t)blockIdx.x * (256 >> cshift) + (threadIdx.x >> cshift); r < N; r += r_step) {
+        const Unit* u = units + row_comm[r];
+        if (u->skip || c_first >= wv) continue;
+        const double inv = 1.0 / u->step;
+        float sg[kLowRankMax];
+#pragma unroll
+        for (int k4 = 0; k4 < kLowRankMax / 4; ++k4) {
+            float q[4] = {0.f, 0.f, 0.f, 0.f};
+            if (4 * k4 < Cn) ldv<4>(q, SG + r * Cn + 4 * k4);
+            sg[4 * k4] = q[0]; sg[4 * k4 + 1] = q[1]; sg[4 * k4 + 2] = q[2]; sg[4 * k4 + 3] = q[3];
+        }
+        const int64_t o = r * Cl + c_first * 4;
+        float z[4], t[4], g[4];
+        ldv<4>(z, Zl + o);
+        ldv<4>(t, Tl + o);
+        lowrank_grad(g, z, t, sg, wt, Cn, nu);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) z[v] = (float)((double)z[v] - (double)g[v] * inv);
+        stv<4>(Zl + o, z);
     }
 }
 
@@ -730,13 +802,16 @@ void launch_z_trial(hipStream_t s, const ZTrialArgs& a0) {
     ZTrialArgs a = a0;
     if (a.n_chunks > 0) {
         const bool v4 = (a.Cl % 4) == 0 && (a.Cn % 4) == 0;
+        const bool lr = a.gradZ == nullptr;           // low-rank gradient (the caller checked the shape limits)
         if (a.ncand == 1) {
-            if (v4) hipLaunchKernelGGL((z_trial_kernel<1, 4>), dim3(a.n_chunks), dim3(256), 0, s, a);
-            else hipLaunchKernelGGL((z_trial_kernel<1, 1>), dim3(a.n_chunks), dim3(256), 0, s, a);
+            if (lr) hipLaunchKernelGGL((z_trial_kernel<1, 4, 1>), dim3(a.n_chunks), dim3(256), 0, s, a);
+            else if (v4) hipLaunchKernelGGL((z_trial_kernel<1, 4, 0>), dim3(a.n_chunks), dim3(256), 0, s, a);
+            else hipLaunchKernelGGL((z_trial_kernel<1, 1, 0>), dim3(a.n_chunks), dim3(256), 0, s, a);
         } else {
             a.ncand = kMaxCand;
-            if (v4) hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 4>), dim3(a.n_chunks), dim3(256), 0, s, a);
-            else hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 1>), dim3(a.n_chunks), dim3(256), 0, s, a);
+            if (lr) hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 4, 1>), dim3(a.n_chunks), dim3(256), 0, s, a);
+            else if (v4) hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 4, 0>), dim3(a.n_chunks), dim3(256), 0, s, a);
+            else hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 1, 0>), dim3(a.n_chunks), dim3(256), 0, s, a);
         }
     }
     hipLaunchKernelGGL(z_trial_finish_kernel, dim3(a.M), dim3(256), 0, s, a);
@@ -747,6 +822,12 @@ void launch_z_step(hipStream_t s, float* Zl, const float* gradZ, const int32_t* 
     const int nb = flat_grid(N * (int64_t)Cl);
     if (Cl % 4 == 0) hipLaunchKernelGGL((z_step_kernel<4>), dim3(nb), dim3(256), 0, s, Zl, gradZ, row_comm, N, Cl, units);
     else hipLaunchKernelGGL((z_step_kernel<1>), dim3(nb), dim3(256), 0, s, Zl, gradZ, row_comm, N, Cl, units);
+}
+
+void launch_z_step_lowrank(hipStream_t s, float* Zl, const float* Tl, const float* SG, const float* Wt, float nu,
+                           const int32_t* row_comm, int64_t N, int Cl, int Cn, const Unit* units) {
+    const int nb = flat_grid(N * (int64_t)Cl);
+    hipLaunchKernelGGL(z_step_lowrank_kernel, dim3(nb), dim3(256), 0, s, Zl, Tl, SG, Wt, nu, row_comm, N, Cl, Cn, units);
 }
 
 void launch_t_carry(hipStream_t s, float* Tn, const float* P, const int64_t* row_seg_ptr, const int32_t* seg_comm,

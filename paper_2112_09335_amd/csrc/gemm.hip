@@ -151,6 +151,93 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
         }
 }
 
+// out[n x C] = [ nu (Z - relu(T)) | SG ] * Bcat  with Bcat = [ W (K1 x C) ; S (K2 x C) ],  C <= 32.
+// This is (grad_Z psi) W for grad = nu (Z - relu(T)) + SG W^T and S = W^T W, without ever storing the gradient:
+// the left operand is formed while its tile is loaded.  K1 and K2 are multiples of four.
+__global__ __launch_bounds__(256) void gemm_nn_gradz_kernel(const float* __restrict__ Zl, const float* __restrict__ Tl,
+                                                            const float* __restrict__ SG, const float* __restrict__ Bcat,
+                                                            float* __restrict__ out, int64_t n, int K1, int K2, int C,
+                                                            float nu) {
+    constexpr int BN = 32;
+    constexpr int LDA = BK + 1;
+    constexpr int LDB = BN + 4;
+    __shared__ __align__(16) float As[BM * LDA];
+    __shared__ __align__(16) float Bs[BK * LDB];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wm = tid >> 6;
+    const int64_t m0 = (int64_t)blockIdx.x * BM;
+    const int K = K1 + K2;
+    const bool b_al = (C % 4) == 0;
+    floatx16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    float4 ra[2], rb;
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int f = tid + 256 * i;
+            const int row = f >> 2, kq = f & 3;
+            const int64_t gr = m0 + row;
+            const int k = k0 + 4 * kq;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (gr < n) {
+                if (k < K1) {
+                    const float4 z = *reinterpret_cast<const float4*>(Zl + gr * K1 + k);
+                    const float4 t = *reinterpret_cast<const float4*>(Tl + gr * K1 + k);
+                    v.x = nu * (z.x - fmaxf(t.x, 0.f));
+                    v.y = nu * (z.y - fmaxf(t.y, 0.f));
+                    v.z = nu * (z.z - fmaxf(t.z, 0.f));
+                    v.w = nu * (z.w - fmaxf(t.w, 0.f));
+                } else if (k < K) {
+                    v = *reinterpret_cast<const float4*>(SG + gr * K2 + (k - K1));
+                }
+            }
+            ra[i] = v;
+        }
+        if (tid < BK * BN / 4) {
+            const int kr = tid / (BN / 4), cq = tid % (BN / 4);
+            const int k = k0 + kr, c = 4 * cq;
+            rb = ld4_guard(Bcat, (int64_t)k * C + c, k < K, b_al, C - c);
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int f = tid + 256 * i;
+            const int row = f >> 2, kq = f & 3;
+            float* d = As + row * LDA + 4 * kq;
+            d[0] = ra[i].x; d[1] = ra[i].y; d[2] = ra[i].z; d[3] = ra[i].w;
+        }
+        if (tid < BK * BN / 4) {
+            const int kr = tid / (BN / 4), cq = tid % (BN / 4);
+            *reinterpret_cast<float4*>(Bs + kr * LDB + 4 * cq) = rb;
+        }
+    };
+    const int nk = (K + BK - 1) / BK;
+    const int li = lane & 31, lk = lane >> 5;
+    fetch(0);
+    for (int kt = 0; kt < nk; ++kt) {
+        __syncthreads();
+        stash();
+        __syncthreads();
+        if (kt + 1 < nk) fetch((kt + 1) * BK);
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            const float a = As[(wm * 32 + li) * LDA + kk + lk];
+            const float b = Bs[(kk + lk) * LDB + li];
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+        }
+    }
+    if (li < C) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = m0 + wm * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+            if (row < n) out[row * C + li] = acc[r];
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------------------ TN
 // Block (chunk, ktile, ctile): partial[chunk][k][c] = sum_{rows of chunk} A[row][k] G[row][c].
 template <int BN>
@@ -335,6 +422,13 @@ void launch_gemm_nn(hipStream_t s, const float* A, const float* B, float* out, i
         else
             hipLaunchKernelGGL((gemm_nn_kernel<32, 0>), grid, dim3(256), 0, s, A, B, out, n, K, C, nullptr, nullptr, 0.f);
     }
+}
+
+void launch_gemm_nn_gradz(hipStream_t s, const float* Zl, const float* Tl, const float* SG, const float* Bcat,
+                          float* out, int64_t n, int K1, int K2, int C, float nu) {
+    if (n <= 0) return;
+    hipLaunchKernelGGL(gemm_nn_gradz_kernel, dim3((unsigned)((n + BM - 1) / BM)), dim3(256), 0, s, Zl, Tl, SG, Bcat, out,
+                       n, K1, K2, C, nu);
 }
 
 size_t gemm_tn_scratch_floats(int64_t n, int K, int C) {

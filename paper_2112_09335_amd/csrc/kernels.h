@@ -50,6 +50,10 @@ struct GemmEpilogue {
 };
 void launch_gemm_nn(hipStream_t s, const float* A, const float* B, float* out, int64_t n, int K, int C,
                     const GemmEpilogue& epi = GemmEpilogue());
+// out[n x C] = [nu (Zl - relu(Tl)) | SG] * Bcat, Bcat = [W (K1 x C); S (K2 x C)], C <= 32, K1 % 4 == K2 % 4 == 0:
+// the product (grad_Z psi) W with grad = nu (Zl - relu(Tl)) + SG W^T, S = W^T W, the gradient never stored.
+void launch_gemm_nn_gradz(hipStream_t s, const float* Zl, const float* Tl, const float* SG, const float* Bcat,
+                          float* out, int64_t n, int K1, int K2, int C, float nu);
 // out[K x C] = A[n x K]^T * G[n x C]; partial: scratch of gemm_tn_scratch_floats(n,K,C) floats.
 size_t gemm_tn_scratch_floats(int64_t n, int K, int C);
 void launch_gemm_tn(hipStream_t s, const float* A, const float* G, float* out, int64_t n, int K, int C,
@@ -60,6 +64,7 @@ void launch_transpose(hipStream_t s, const float* in, float* out, int K, int C);
 // ---------------------------------------------------------------- fused elementwise + reductions (elementwise.hip)
 constexpr int kReduceBlocks = 2048;      // grid of the flat reducing kernels
 constexpr int kMaxCand = 16;             // step-size candidates evaluated per pass
+constexpr int kLowRankMax = 16;          // widest next layer for which the Z gradient is kept in low-rank form
 constexpr int kChunkRows = 128;          // rows / segments per reduction chunk of the Z search
 
 // One step-size search ("unit"): a layer's tau, or a (layer, community)'s theta.
@@ -115,6 +120,9 @@ struct ZTrialArgs {
     const int32_t* unit_chunk_ptr; int32_t M;
     const int32_t* segc_row;
     const float* Zl; const float* gradZ; const float* Tl; int Cl;       // own term, rows of the community
+    // low-rank form of the gradient (gradZ == nullptr): grad = nu (Zl - relu(Tl)) + SG Wt, SG is N x Cn with
+    // Cn <= kLowRankMax, Wt is Cn x Cl; it is recomputed per element instead of being read
+    const float* SG = nullptr; const float* Wt = nullptr;
     const float* Tn; const float* Zn; const float* U; const float* P; int Cn;   // next layer, per segment
     int next_is_last;
     int first_pass;        // also accumulate ||gradZ_m||^2 and ||Z_m||^2, apply the step floor
@@ -128,6 +136,9 @@ void launch_z_trial(hipStream_t s, const ZTrialArgs& a);
 // Z_l[i,:] -= gradZ[i,:] / theta[comm(i)]
 void launch_z_step(hipStream_t s, float* Zl, const float* gradZ, const int32_t* row_comm, int64_t N, int Cl,
                    const Unit* units);
+// the same step with the gradient in its low-rank form nu (Zl - relu(Tl)) + SG Wt (SG: N x Cn, Wt: Cn x Cl)
+void launch_z_step_lowrank(hipStream_t s, float* Zl, const float* Tl, const float* SG, const float* Wt, float nu,
+                           const int32_t* row_comm, int64_t N, int Cl, int Cn, const Unit* units);
 // Tn[i,:] -= sum over the segments (i,c) of row i of P[(i,c),:] / theta_c  (communities whose step was skipped
 // contribute nothing): the pre-activation of the next layer after the Z step, without a new aggregation.
 void launch_t_carry(hipStream_t s, float* Tn, const float* P, const int64_t* row_seg_ptr, const int32_t* seg_comm,

@@ -166,3 +166,24 @@ def test_dual_ascent_on_new_iterates_variant():
     w = synth.config(3, 0.005)
     w.hyper["dual_form"] = 1
     run_case(w, 5, "dual-form-1/3-layer")
+
+
+def test_low_rank_gradient_path_and_its_stored_twin():
+    """Narrow next layers (multiples of four up to 16 units) keep the Z gradient in low-rank form; both that
+    path and the stored-gradient path must match the oracle, three layers so that both hidden layers use it."""
+    from paper_2112_09335_amd import binding
+    w = synth.make_workload("lowrank", 21, 1500, 6, [36, 48, 12, 4], 4, 6, graph="sbm", features="gaussian",
+                            avg_degree=9, frac_intra=0.8)
+    run_case(w, 6, "low-rank")
+    a = binding.Solver.from_workload(w, 0)
+    b = binding.Solver.from_workload(w, 0)
+    b.tune("use_lowrank", 0)
+    a.run(5)
+    b.run(5)
+    for l in range(1, w.L + 1):
+        za, zb = a.get_Z(l), b.get_Z(l)
+        assert np.abs(za - zb).max() <= 1e-5 * np.abs(zb).max()
+    ta, tb = a.get_steps(), b.get_steps()
+    assert np.array_equal(ta[0], tb[0]) and np.array_equal(ta[1], tb[1]) and np.array_equal(ta[2], tb[2])
+    a.close()
+    b.close()
