@@ -80,6 +80,7 @@ struct cadmm_ctx {
     LayerScalars* scalars = nullptr;   // [L+1]
     int32_t* status = nullptr;
     bool base_valid = false, have_prev = false, dual_valid = false;
+    bool phi_valid = false;      // the penalties of the hidden layers whose gradient is not stored are evaluated too
     int iter = 0;
     // The pre-activations T_l = A~ Z_{l-1} W_l are carried from one iteration to the next instead of being
     // formed anew: the W step leaves T_l - Q/tau = A~ Z_{l-1}^k W_l^{k+1}, and the Z step of layer l-1 changes
@@ -332,26 +333,39 @@ void compute_T(cadmm_ctx* c, int l) {
     }
 }
 
-// H_l, T_l = H_l W_l, phi_l and G_l for every layer at the current iterate.  This is both the start
-// of a sweep and the readout of the previous one, so it is computed once per iterate.
-void base_eval(cadmm_ctx* c) {
-    if (c->base_valid) return;
+// H_l, T_l = H_l W_l, phi_l and G_l at the current iterate.  This is both the start of a sweep and the readout of
+// the previous one, so it is computed once per iterate (need_phi: also the penalties a sweep does not need).
+// A hidden layer in the (A~ Z) W association feeds its pre-activation gradient to the W gradient only, where
+// it is formed on the fly from T_l and Z_l; a sweep therefore skips phi_G for it (phi_l is a readout).
+bool gradient_on_the_fly(const cadmm_ctx* c, int l) { return l < c->L && !c->agg_first[l]; }
+
+void base_eval(cadmm_ctx* c, bool need_phi) {
     const int L = c->L;
     const int64_t N = c->hg.N;
-    for (int l = 1; l <= L; ++l) {
-        compute_T(c, l);
+    auto run_phi_G = [&](int l) {
         const double cnt = (double)N * c->C[l];
         timed(c, P_PHI_G, 4.0 * cnt * (l == L ? 6 : 3), 0.0, [&] {
             launch_phi_G(c->stream, c->T[l], c->Z[l], c->U, c->G[l], l == L ? c->TLprev : nullptr,
                          c->have_prev ? 1 : 0, (l == L && c->u_pending) ? 1 : 0, N * c->C[l], l == L, c->nu, c->rho,
                          c->partials, c->scalars + l);
         });
+    };
+    if (!c->base_valid) {
+        for (int l = 1; l <= L; ++l) {
+            compute_T(c, l);
+            if (!gradient_on_the_fly(c, l) || need_phi) run_phi_G(l);
+        }
+        if (!t1_reusable(c)) c->t1_age = 0;                // every T_l was just formed exactly
+        c->u_pending = false;
+        c->dual_valid = c->have_prev;
+        c->have_prev = true;
+        c->base_valid = true;
+        c->phi_valid = need_phi;
+    } else if (need_phi && !c->phi_valid) {
+        for (int l = 1; l <= L; ++l)
+            if (gradient_on_the_fly(c, l)) run_phi_G(l);
+        c->phi_valid = true;
     }
-    if (!t1_reusable(c)) c->t1_age = 0;                // every T_l was just formed exactly
-    c->u_pending = false;
-    c->dual_valid = c->have_prev;
-    c->have_prev = true;
-    c->base_valid = true;
 }
 
 // T_l <- A~ Z_{l-1}^{k+1} W_l^{k+1}, from the segment products P of layer l-1 and its accepted theta.
@@ -372,7 +386,7 @@ void sweep(cadmm_ctx* c) {
     hipStream_t s = c->stream;
     const SearchParams sp = search_params(c);
     const int more_passes = (c->max_bt + kMaxCand - 1) / kMaxCand;
-    base_eval(c);
+    base_eval(c, false);
 
     // ---- W-update, every layer from (W^k, Z^k, U^k)   (Section 3.1)
     for (int l = 1; l <= L; ++l) {
@@ -388,8 +402,12 @@ void sweep(cadmm_ctx* c) {
             left = c->Z[l - 1];
             right = c->H[l];
         }
-        timed(c, P_GEMM_TN, 4.0 * ((double)N * K + (double)N * Cl + (double)K * Cl), 2.0 * (double)N * K * Cl,
-              [&] { launch_gemm_tn(s, left, right, c->gradW, N, K, Cl, c->tn_partial); });
+        const bool fly = gradient_on_the_fly(c, l);    // G_l = nu (relu(T_l) - Z_l) 1[T_l > 0] formed inside the product
+        timed(c, P_GEMM_TN, 4.0 * ((double)N * K + (double)N * Cl * (fly ? 2 : 1) + (double)K * Cl), 2.0 * (double)N * K * Cl,
+              [&] {
+                  if (fly) launch_gemm_tn(s, left, c->T[l], c->gradW, N, K, Cl, c->tn_partial, c->Z[l], c->nu);
+                  else launch_gemm_tn(s, left, right, c->gradW, N, K, Cl, c->tn_partial);
+              });
         timed(c, P_OTHER, 8.0 * K * Cl, 0.0, [&] { launch_w_norms(s, c->gradW, c->W[l], K * Cl, unit, c->partials); });
         float* Q = c->G[l];                                                          // G_l is no longer needed
         // T(W - g/tau) = T - Q/tau with Q = A~ Z_{l-1} gradW
@@ -777,7 +795,7 @@ int cadmm_eval(cadmm_ctx* c, cadmm_stats* out, double* layer_penalty) {
     if (!c || !out) return CADMM_EINVAL;
     if (!c->has_init) return fail(c, CADMM_EORDER, "init first");
     const int L = c->L;
-    base_eval(c);
+    base_eval(c, true);
     launch_risk(c->stream, c->Z[L], c->d_labels, c->hg.N, c->C[L], c->risk, c->partials, c->scalars + L);
     std::vector<LayerScalars> sc(L + 1);
     int32_t st[4] = {0, 0, 0, 0};
@@ -861,7 +879,7 @@ int cadmm_get_Z(cadmm_ctx* c, int32_t l, float* dst) {
 int cadmm_get_U(cadmm_ctx* c, float* dst) {
     if (!c || !dst) return CADMM_EINVAL;
     if (!c->has_init) return fail(c, CADMM_EORDER, "init first");
-    if (c->u_pending) base_eval(c);      // dual_form 1: the step of the last sweep rides on the base evaluation
+    if (c->u_pending) base_eval(c, false);   // dual_form 1: the step of the last sweep rides on the base evaluation
     return download_rows(c, c->U, c->C[c->L], dst);
 }
 
@@ -893,7 +911,7 @@ int cadmm_set_state(cadmm_ctx* c, const float* const* W, const float* const* Z, 
     if (!c->has_init) return fail(c, CADMM_EORDER, "init first");
     const int L = c->L, M = c->hg.M;
     hipStream_t s = c->stream;
-    if (c->u_pending) base_eval(c);      // finish the pending dual step before anything is overwritten
+    if (c->u_pending) base_eval(c, false);   // finish the pending dual step before anything is overwritten
     c->t1_age = -1;
     if (W)
         for (int l = 1; l <= L; ++l)

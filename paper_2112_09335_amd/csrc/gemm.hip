@@ -240,8 +240,11 @@ __global__ __launch_bounds__(256) void gemm_nn_gradz_kernel(const float* __restr
 
 // ------------------------------------------------------------------------------------------------ TN
 // Block (chunk, ktile, ctile): partial[chunk][k][c] = sum_{rows of chunk} A[row][k] G[row][c].
-template <int BN>
+// PRO 1: the right operand is the hidden-layer pre-activation gradient nu (relu(T) - Z) 1[T > 0], formed from
+// T (passed as G) and Z while the tile is loaded, so that it is never stored.
+template <int BN, int PRO>
 __global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ A, const float* __restrict__ G,
+                                                      const float* __restrict__ Zl, float nu,
                                                       float* __restrict__ partial, int64_t n, int K, int C,
                                                       int64_t rows_per_chunk) {
     constexpr int WN = (BN == 128) ? 2 : 1;
@@ -297,6 +300,14 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ 
                 const int64_t gr = r0 + rr;
                 const int c = c0 + 4 * cq;
                 rg[i] = ld4_guard(G, gr * C + c, gr < r_end, g_al, C - c);
+                if constexpr (PRO == 1) {
+                    const float4 t = rg[i];
+                    const float4 z = ld4_guard(Zl, gr * C + c, gr < r_end, g_al, C - c);
+                    rg[i].x = (t.x > 0.f) ? nu * (t.x - z.x) : 0.f;
+                    rg[i].y = (t.y > 0.f) ? nu * (t.y - z.y) : 0.f;
+                    rg[i].z = (t.z > 0.f) ? nu * (t.z - z.z) : 0.f;
+                    rg[i].w = (t.w > 0.f) ? nu * (t.w - z.w) : 0.f;
+                }
             }
         }
     };
@@ -437,14 +448,21 @@ size_t gemm_tn_scratch_floats(int64_t n, int K, int C) {
 }
 
 void launch_gemm_tn(hipStream_t s, const float* A, const float* G, float* out, int64_t n, int K, int C,
-                    float* partial) {
+                    float* partial, const float* Zl, float nu) {
     if (K <= 0 || C <= 0) return;
     TnPlan p = tn_plan(n, K, C);
-    const unsigned nb = (unsigned)((int64_t)p.nchunks * p.tiles);
-    if (p.bn == 128)
-        hipLaunchKernelGGL((gemm_tn_kernel<128>), dim3(nb), dim3(256), 0, s, A, G, partial, n, K, C, p.rows_per_chunk);
-    else
-        hipLaunchKernelGGL((gemm_tn_kernel<32>), dim3(nb), dim3(256), 0, s, A, G, partial, n, K, C, p.rows_per_chunk);
+    const dim3 grid((unsigned)((int64_t)p.nchunks * p.tiles)), block(256);
+    if (Zl) {
+        if (p.bn == 128)
+            hipLaunchKernelGGL((gemm_tn_kernel<128, 1>), grid, block, 0, s, A, G, Zl, nu, partial, n, K, C, p.rows_per_chunk);
+        else
+            hipLaunchKernelGGL((gemm_tn_kernel<32, 1>), grid, block, 0, s, A, G, Zl, nu, partial, n, K, C, p.rows_per_chunk);
+    } else {
+        if (p.bn == 128)
+            hipLaunchKernelGGL((gemm_tn_kernel<128, 0>), grid, block, 0, s, A, G, Zl, nu, partial, n, K, C, p.rows_per_chunk);
+        else
+            hipLaunchKernelGGL((gemm_tn_kernel<32, 0>), grid, block, 0, s, A, G, Zl, nu, partial, n, K, C, p.rows_per_chunk);
+    }
     const int64_t count = (int64_t)K * C;
     hipLaunchKernelGGL(gemm_tn_reduce_kernel, dim3((unsigned)((count * 8 + 255) / 256)), dim3(256), 0, s, partial, out,
                        count, p.nchunks);

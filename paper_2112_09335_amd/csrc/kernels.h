@@ -56,8 +56,10 @@ void launch_gemm_nn_gradz(hipStream_t s, const float* Zl, const float* Tl, const
                           float* out, int64_t n, int K1, int K2, int C, float nu);
 // out[K x C] = A[n x K]^T * G[n x C]; partial: scratch of gemm_tn_scratch_floats(n,K,C) floats.
 size_t gemm_tn_scratch_floats(int64_t n, int K, int C);
+// With Zl != nullptr, G holds the pre-activation T of a hidden layer and the right operand is
+// nu (relu(T) - Zl) 1[T > 0], formed on the fly.
 void launch_gemm_tn(hipStream_t s, const float* A, const float* G, float* out, int64_t n, int K, int C,
-                    float* partial);
+                    float* partial, const float* Zl = nullptr, float nu = 0.f);
 // out[C x K] = in[K x C]^T (small)
 void launch_transpose(hipStream_t s, const float* in, float* out, int K, int C);
 
