@@ -158,9 +158,14 @@ def main():
                                                    ("bound", "achieved", "peak", "unit", "frac", "traffic")},
         "dominant_kernel": None if dominant is None else dominant["kernel"],
         "kernels": entries,
+        # all aggregation launches of the timed steps together.  achieved_GBs uses the algorithmic minimum (every
+        # row of the gathered matrix read once); gather_volume_GBs counts what the kernel actually requests from
+        # the memory system, nnz gathers of 4*width bytes (2 flops per gathered float) plus the entries
         "spmm": {"achieved_GBs": spmm_bytes / (spmm_ms * 1e-3) / 1e9 if spmm_ms > 0 else None,
                  "frac_of_hbm_peak": spmm_bytes / (spmm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if spmm_ms > 0 else None,
-                 "edges_features_per_s": 0.5 * spmm_flops / (spmm_ms * 1e-3) if spmm_ms > 0 else None},
+                 "edges_features_per_s": 0.5 * spmm_flops / (spmm_ms * 1e-3) if spmm_ms > 0 else None,
+                 "gather_volume_GBs": (2.0 * spmm_flops + 8.0 * nnz * sum(prof[k]["records"] for k in spmm_keys))
+                 / (spmm_ms * 1e-3) / 1e9 if spmm_ms > 0 else None},
         "ms_per_step_with_event_timing": 1e3 * dt_prof / args.steps,
         "objective": stats["objective"], "primal_res": stats["primal_res"], "status": stats["status"],
     }
