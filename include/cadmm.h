@@ -186,7 +186,7 @@ int  cadmm_op_wgrad(cadmm_ctx* ctx, const float* A, const float* G, int64_t n, i
  * number of timed launch groups, and the algorithmic bytes and flops booked for them (what the
  * operation must move / compute: operands read once, results written once).
  */
-#define CADMM_PROFILE_CLASSES 17
+#define CADMM_PROFILE_CLASSES 18
 int  cadmm_profile(cadmm_ctx* ctx, int enable);
 int  cadmm_get_profile(cadmm_ctx* ctx, double* ms, int64_t* records, double* bytes, double* flops);
 const char* cadmm_profile_class_name(int32_t cls);

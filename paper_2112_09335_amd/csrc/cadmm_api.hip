@@ -230,12 +230,13 @@ hipError_t upload(hipStream_t s, T* dst, const std::vector<T>& src) {
 // One class per kernel symbol (and role, where one symbol serves two), so that the live timings can be
 // set beside a profiler's per-kernel averages.
 enum ProfClass {
-    P_SPMM = 0, P_SPMM_GRADZ, P_SPMM_SEG, P_GEMM_NN_128, P_GEMM_NN_128_GRADZ, P_GEMM_NN_32, P_GEMM_TN, P_PHI_G,
+    P_SPMM = 0, P_SPMM_GRADZ, P_SPMM_SEG, P_GEMM_NN_128, P_GEMM_NN_128_GRADZ, P_GEMM_NN_32, P_GEMM_TN, P_GEMM_TN_32, P_PHI_G,
     P_G_ONLY, P_W_TRIAL, P_Z_TRIAL, P_W_STEP, P_Z_STEP, P_LAST_LAYER, P_T_CARRY, P_GEMM_GRADZ, P_OTHER
 };
 const char* kProfNames[CADMM_PROFILE_CLASSES] = {
     "spmm_rows_kernel[rows]", "spmm_rows_kernel[rows,gradz]", "spmm_rows_kernel[segments]", "gemm_nn_kernel<128,0>",
-    "gemm_nn_kernel<128,1>", "gemm_nn_kernel<32>", "gemm_tn_kernel+reduce", "phi_G_kernel", "G_only_kernel",
+    "gemm_nn_kernel<128,1>", "gemm_nn_kernel<32>", "gemm_tn_kernel<128>+reduce", "gemm_tn_kernel<32>+reduce",
+    "phi_G_kernel", "G_only_kernel",
     "w_trial_kernel", "z_trial_kernel", "w_step_kernel", "z_step_kernel", "last_layer_kernel", "t_carry_kernel",
     "gemm_nn_gradz_kernel", "other"};
 
@@ -403,7 +404,8 @@ void sweep(cadmm_ctx* c) {
             right = c->H[l];
         }
         const bool fly = gradient_on_the_fly(c, l);    // G_l = nu (relu(T_l) - Z_l) 1[T_l > 0] formed inside the product
-        timed(c, P_GEMM_TN, 4.0 * ((double)N * K + (double)N * Cl * (fly ? 2 : 1) + (double)K * Cl), 2.0 * (double)N * K * Cl,
+        timed(c, Cl > 32 ? P_GEMM_TN : P_GEMM_TN_32,
+              4.0 * ((double)N * K + (double)N * Cl * (fly ? 2 : 1) + (double)K * Cl), 2.0 * (double)N * K * Cl,
               [&] {
                   if (fly) launch_gemm_tn(s, left, c->T[l], c->gradW, N, K, Cl, c->tn_partial, c->Z[l], c->nu);
                   else launch_gemm_tn(s, left, right, c->gradW, N, K, Cl, c->tn_partial);
@@ -1006,6 +1008,7 @@ int cadmm_tune(cadmm_ctx* c, const char* key, int32_t value) {
     if (std::strcmp(key, "spmm_tile_cols") == 0) { set_spmm_tile_cols(value); return CADMM_OK; }
     if (std::strcmp(key, "spmm_xcd_remap") == 0) { set_spmm_xcd_remap(value); return CADMM_OK; }
     if (std::strcmp(key, "spmm_groups_log2") == 0) { set_spmm_groups_log2(value); return CADMM_OK; }
+    if (std::strcmp(key, "spmm_unroll") == 0) { set_spmm_unroll(value); return CADMM_OK; }
     return fail(c, CADMM_EINVAL, "unknown tuning key");
 }
 
@@ -1038,8 +1041,8 @@ int cadmm_op_wgrad(cadmm_ctx* c, const float* A, const float* G, int64_t n, int3
     if (!c || !A || !G || !out || n < 1 || K < 1 || C < 1) return CADMM_EINVAL;
     if (!c->has_ws) return fail(c, CADMM_EORDER, "set_workspace first");
     if (gemm_tn_scratch_floats(n, K, C) > c->tn_partial_floats) return fail(c, CADMM_ENOMEM, "shape needs more scratch than the model reserved");
-    timed(c, P_GEMM_TN, 4.0 * ((double)n * K + (double)n * C + (double)K * C), 2.0 * (double)n * K * C,
-          [&] { launch_gemm_tn(c->stream, A, G, out, n, K, C, c->tn_partial); });
+    timed(c, C > 32 ? P_GEMM_TN : P_GEMM_TN_32, 4.0 * ((double)n * K + (double)n * C + (double)K * C),
+          2.0 * (double)n * K * C, [&] { launch_gemm_tn(c->stream, A, G, out, n, K, C, c->tn_partial); });
     return check_launch(c, "op_wgrad");
 }
 

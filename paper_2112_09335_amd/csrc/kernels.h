@@ -39,6 +39,8 @@ void set_spmm_tile_cols(int cols);
 void set_spmm_xcd_remap(int on);
 // lane groups per output row as a power of two (-1 = from the mean row length)
 void set_spmm_groups_log2(int v);
+// gathers in flight per lane group: 8 (default, single-repeat shapes only) or 4
+void set_spmm_unroll(int v);
 
 // ---------------------------------------------------------------- dense contractions (gemm.hip)
 // out[n x C] = A[n x K] * B[K x C];  epilogue 1: out = nu * (Zl - relu(Tl)) + A B

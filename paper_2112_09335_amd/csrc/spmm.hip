@@ -44,7 +44,7 @@ __device__ __forceinline__ void store_vec(float* p, const float (&src)[VEC]) {
     }
 }
 
-template <int VEC, int R, int EPI>
+template <int VEC, int R, int EPI, int U>
 __global__ __launch_bounds__(256) void spmm_rows_kernel(
     const int64_t* __restrict__ lo, const int64_t* __restrict__ hi, const int64_t* __restrict__ part_lo,
     const int64_t* __restrict__ part_hi, int64_t nrows, int64_t nparts, const int32_t* __restrict__ col,
@@ -86,20 +86,20 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[r][v] = 0.f;
 
-    // the groups of a row take entries p+grp, p+grp+gpr, ...; four of them in flight per group
-    for (int64_t q = p + grp; q < e; q += 4 * gpr) {
-        int32_t c[4];
-        float a[4];
+    // the groups of a row take entries p+grp, p+grp+gpr, ...; U of them in flight per group
+    for (int64_t q = p + grp; q < e; q += U * gpr) {
+        int32_t c[U];
+        float a[U];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < U; ++u) {
             const int64_t qu = q + u * gpr;
             const bool ok = qu < e;
             c[u] = ok ? col[qu] : -1;
             a[u] = ok ? val[qu] : 0.f;
         }
-        float x[4][R][VEC];
+        float x[U][R][VEC];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int cc = cbase + r * cstride;
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(
             }
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -147,6 +147,7 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(
 int g_tile_cols = 0;
 int g_xcd_remap = 0;
 int g_gpr_log2 = -1;      // -1: chosen from the mean row length
+int g_unroll = 8;
 
 // Adds the parts of every split row in part order and applies the epilogue.  One lane group per row.
 template <int VEC, int EPI>
@@ -192,14 +193,11 @@ void launch_cfg(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32
     nb = (nb + 7) / 8 * 8;
     dim3 grid((unsigned)nb), block(256);
     const int max_len = split ? lg.max_len : 0;
-    if (epi.kind == 1)
-        hipLaunchKernelGGL((spmm_rows_kernel<VEC, R, 1>), grid, block, 0, s, lo, hi, lg.part_lo, lg.part_hi, nrows,
-                           nparts, col, val, X, Y, lg.side, width, lpr_log2, gpr_log2, col0, col1, max_len,
-                           g_xcd_remap, epi.Zl, epi.Tl, epi.nu);
-    else
-        hipLaunchKernelGGL((spmm_rows_kernel<VEC, R, 0>), grid, block, 0, s, lo, hi, lg.part_lo, lg.part_hi, nrows,
-                           nparts, col, val, X, Y, lg.side, width, lpr_log2, gpr_log2, col0, col1, max_len,
-                           g_xcd_remap, nullptr, nullptr, 0.f);
+    const bool deep = g_unroll == 8 && R == 1;       // eight gathers in flight per lane group
+#define CADMM_SPMM(E_, U_, Z_, T_, NU_) hipLaunchKernelGGL((spmm_rows_kernel<VEC, R, E_, U_>), grid, block, 0, s, lo, hi, lg.part_lo, lg.part_hi, nrows, nparts, col, val, X, Y, lg.side, width, lpr_log2, gpr_log2, col0, col1, max_len, g_xcd_remap, Z_, T_, NU_)
+    if (epi.kind == 1) { if (deep) CADMM_SPMM(1, 8, epi.Zl, epi.Tl, epi.nu); else CADMM_SPMM(1, 4, epi.Zl, epi.Tl, epi.nu); }
+    else { if (deep) CADMM_SPMM(0, 8, nullptr, nullptr, 0.f); else CADMM_SPMM(0, 4, nullptr, nullptr, 0.f); }
+#undef CADMM_SPMM
 }
 
 template <int VEC>
@@ -215,10 +213,12 @@ void launch_vec(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32
         int lpr_log2 = 0;
         while ((1 << lpr_log2) < lanes_needed && lpr_log2 < 6) ++lpr_log2;
         const int reps = (lanes_needed + (1 << lpr_log2) - 1) >> lpr_log2;
-        // lane groups per row: as many as the wavefront allows, but not more than about half the mean row length
+        // lane groups per row: as many as the wavefront allows, but only until one trip of the entry loop
+        // (groups x gathers in flight per group) covers a row of mean length
         int gpr_log2 = 0;
         const int mean_len = lg.mean_len > 0 ? lg.mean_len : 1;
-        while (lpr_log2 + gpr_log2 < 6 && (2 << gpr_log2) < mean_len / 2) ++gpr_log2;
+        const int in_flight = (reps <= 1) ? g_unroll : 4;
+        while (lpr_log2 + gpr_log2 < 6 && (in_flight << gpr_log2) < mean_len) ++gpr_log2;
         if (g_gpr_log2 >= 0) gpr_log2 = (lpr_log2 + g_gpr_log2 <= 6) ? g_gpr_log2 : 6 - lpr_log2;
         if (reps <= 1) launch_cfg<VEC, 1>(s, lo, hi, col, val, X, Y, nrows, width, lpr_log2, gpr_log2, col0, col1, epi, lg, split);
         else if (reps <= 2) launch_cfg<VEC, 2>(s, lo, hi, col, val, X, Y, nrows, width, lpr_log2, gpr_log2, col0, col1, epi, lg, split);
@@ -240,6 +240,7 @@ void launch_vec(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32
 void set_spmm_tile_cols(int cols) { g_tile_cols = cols > 0 ? cols : 0; }
 void set_spmm_xcd_remap(int on) { g_xcd_remap = on ? 1 : 0; }
 void set_spmm_groups_log2(int v) { g_gpr_log2 = v; }
+void set_spmm_unroll(int v) { g_unroll = (v == 8) ? 8 : 4; }
 
 void launch_spmm(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32_t* col, const float* val,
                  const float* X, float* Y, int64_t nrows, int width, const SpmmEpilogue& epi, const SpmmLong& lg) {
