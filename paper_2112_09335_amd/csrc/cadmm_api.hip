@@ -334,12 +334,12 @@ void compute_T(cadmm_ctx* c, int l) {
     }
 }
 
-// H_l, T_l = H_l W_l, phi_l and G_l at the current iterate.  This is both the start of a sweep and the readout of
-// the previous one, so it is computed once per iterate (need_phi: also the penalties a sweep does not need).
 // A hidden layer in the (A~ Z) W association feeds its pre-activation gradient to the W gradient only, where
 // it is formed on the fly from T_l and Z_l; a sweep therefore skips phi_G for it (phi_l is a readout).
 bool gradient_on_the_fly(const cadmm_ctx* c, int l) { return l < c->L && !c->agg_first[l]; }
 
+// H_l, T_l = H_l W_l, phi_l and G_l at the current iterate.  This is both the start of a sweep and the readout of
+// the previous one, so it is computed once per iterate (need_phi: also the penalties a sweep does not need).
 void base_eval(cadmm_ctx* c, bool need_phi) {
     const int L = c->L;
     const int64_t N = c->hg.N;
@@ -444,10 +444,10 @@ void sweep(cadmm_ctx* c) {
         });
         timed(c, P_OTHER, 8.0 * Cl * Cn, 0.0, [&] { launch_transpose(s, c->W[l + 1], c->Wt, Cl, Cn); });
         // grad psi (all communities at once) = nu (Z_l - relu(T_l)) + A~ G_{l+1} W_{l+1}^T; aggregate on the
-        // narrower of the two widths, the penalty term rides in the epilogue of whichever kernel comes last
-        // With a very narrow next layer the gradient nu (Z_l - relu(T_l)) + (A~ G_{l+1}) W_{l+1}^T is never
-        // stored: its consumers (the product with W_{l+1}, the search, the step) rebuild it per element from
-        // Z_l, T_l and the N x C_{l+1} factor, which removes a full write and two full reads of an N x C_l matrix.
+        // narrower of the two widths, the penalty term rides in the epilogue of whichever kernel comes last.
+        // With a very narrow next layer the gradient is never stored: its consumers (the product with
+        // W_{l+1}, the search, the step) rebuild it per element from Z_l, T_l and the N x C_{l+1} factor
+        // A~ G_{l+1}, which removes a full write and two full reads of an N x C_l matrix.
         const bool lowrank = c->use_lowrank && Cn <= kLowRankMax && Cn < Cl && Cn % 4 == 0 && Cl % 4 == 0 && Cl <= 1024;
         if (lowrank) {
             aggregate(c, c->G[l + 1], c->tmpA, Cn, SpmmEpilogue());                  // A~ G_{l+1}
