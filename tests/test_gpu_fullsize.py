@@ -161,3 +161,47 @@ def test_readout_and_iteration_properties_at_full_size(full):
         gsq = th * th * sqnorm(dZ)
         assert abs(gsq - sq[L + m]) <= 1e-4 * sq[L + m]
         assert val <= base - gsq / (2 * th) + 1e-7 * abs(base), (m, val, base, gsq / (2 * th))
+
+
+@pytest.mark.parametrize("index", [3, 5])
+def test_readout_and_dual_step_at_full_size_of_the_other_large_configs(index):
+    """Configs 3 (three layers, 32 communities) and 5 (eight layers of 512): after a few iterations the library's
+    readout must equal the oracle's full-graph forms evaluated on the library's own state, the last-layer step
+    must match the oracle's row solver and the dual step must satisfy Eq. 2 on every row."""
+    import torch  # noqa: F401
+    from paper_2112_09335_amd import binding
+    w = synth.config(index)
+    say(f"config {index}: N={w.N} E={w.E} dims={w.dims}")
+    s = binding.Solver.from_workload(w, 0)
+    g = OracleGraph(w.N, w.src, w.dst, w.M, w.comm, split=False)
+    h = w.hyper
+    o = AdmmOracle(g, w.dims, nu=h["nu"], rho=h["rho"], tau0=h["tau0"], theta0=h["theta0"], eta=h["eta"],
+                   max_backtrack=h["max_backtrack"], fista_iters=h["fista_iters"], risk=h["risk"])
+    o.set_data(w.X, w.labels)
+    L = w.L
+
+    def pull():
+        W = [None] + [s.get_W(l).astype(np.float64) for l in range(1, L + 1)]
+        Z = [o.Z[0]] + [g.to_new(s.get_Z(l).astype(np.float64)) for l in range(1, L + 1)]
+        return W, Z, g.to_new(s.get_U().astype(np.float64))
+
+    s.run(4)
+    W0, Z0, U0 = pull()
+    sg = s.eval()
+    so = o.stats_full_graph(W0, Z0, U0)
+    for key in ("objective", "lagrangian", "risk", "primal_res"):
+        assert abs(sg[key] - so[key]) <= REL * abs(so[key]), (key, sg[key], so[key])
+    for a, b in zip(sg["layer_penalty"], so["layer_penalty"]):
+        assert abs(a - b) <= REL * abs(b) + 1e-12 * so["objective"]
+    assert sg["status"] == 0
+    s.run(1)
+    WL1 = s.get_W(L).astype(np.float64)
+    ZL1 = g.to_new(s.get_Z(L).astype(np.float64))
+    U1 = g.to_new(s.get_U().astype(np.float64))
+    TL = g.A @ (Z0[L - 1] @ WL1)
+    want = U0 + o.rho * (Z0[L] - TL)
+    assert np.abs(U1 - want).max() <= REL * np.abs(want).max()
+    rows = np.random.default_rng(index).integers(0, g.N, 2000)
+    zref = fista_rows(Z0[L][rows], TL[rows], U0[rows], o.Y[rows], o.labelled[rows], o.rho, o.J, o.risk)
+    assert np.abs(ZL1[rows] - zref).max() <= REL * np.abs(zref).max()
+    s.close()
