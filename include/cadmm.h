@@ -186,7 +186,7 @@ int  cadmm_op_wgrad(cadmm_ctx* ctx, const float* A, const float* G, int64_t n, i
  * number of timed launch groups, and the algorithmic bytes and flops booked for them (what the
  * operation must move / compute: operands read once, results written once).
  */
-#define CADMM_PROFILE_CLASSES 18
+#define CADMM_PROFILE_CLASSES 19
 int  cadmm_profile(cadmm_ctx* ctx, int enable);
 int  cadmm_get_profile(cadmm_ctx* ctx, double* ms, int64_t* records, double* bytes, double* flops);
 const char* cadmm_profile_class_name(int32_t cls);
@@ -195,6 +195,8 @@ const char* cadmm_profile_class_name(int32_t cls);
  * captured HIP graph when the context's stream is not the default stream (default), 0 = plain launches.
  * "use_lowrank" (per context): 1 = with a next layer of at most 16 units the Z gradient is kept as
  * nu (Z_l - relu(T_l)) + (A~ G_{l+1}) W_{l+1}^T and rebuilt per element by its consumers (default), 0 = stored.
+ * "use_speculative" (per context): 1 = in a wide hidden layer the product Q = A~ Z_{l-1} grad W also evaluates the
+ * first candidate of the tau search and takes the step on the pre-activation speculatively (default), 0 = separate passes.
  * "t1_refresh" (per context): the pre-activations A~ Z_{l-1} W_l are carried from one iteration to the
  * next (through the W step, and through the segment products of the Z step) and formed anew every
  * this many iterations (default 16; 0 = always form them anew).

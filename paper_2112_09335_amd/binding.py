@@ -24,7 +24,7 @@ EXPORTS = [
     "cadmm_op_aggregate_segments", "cadmm_op_transform", "cadmm_op_wgrad",
     "cadmm_profile", "cadmm_get_profile", "cadmm_profile_class_name", "cadmm_tune", "cadmm_predict",
 ]
-PROFILE_CLASSES = 18
+PROFILE_CLASSES = 19
 
 
 class CadmmError(RuntimeError):

@@ -94,6 +94,7 @@ struct cadmm_ctx {
     // default stream; launch-bound problem sizes gain most.
     bool use_graph = true;
     bool use_lowrank = true;
+    bool use_speculative = true;
     struct GraphSlot { hipGraphExec_t exec = nullptr; bool tried = false; };
     GraphSlot graphs[2][2][2][2];
     // optional per-kernel-class timing with HIP events on the context's stream
@@ -212,8 +213,13 @@ size_t layout(cadmm_ctx* c, char* base) {
     c->tn_partial = b.take<float>(tnmax);
     c->tn_partial_floats = tnmax;
     size_t np = (size_t)kReduceBlocks * kMaxCand;
-    size_t np2 = nch * (kMaxCand + 2);
-    c->partials = b.take<double>(np > np2 ? np : np2);
+    const size_t np2 = nch * (kMaxCand + 2);
+    np = np > np2 ? np : np2;
+    for (int l = 1; l <= L; ++l) {               // block results of the products that also evaluate a candidate
+        const size_t np3 = (size_t)gemm_nn_blocks(N, c->C[l]) * kMaxCand;
+        np = np > np3 ? np : np3;
+    }
+    c->partials = b.take<double>(np);
     c->unitsW = b.take<Unit>(L);
     c->unitsZ = b.take<Unit>((size_t)(L - 1) * g.M);
     c->scalars = b.take<LayerScalars>(L + 1);
@@ -230,12 +236,12 @@ hipError_t upload(hipStream_t s, T* dst, const std::vector<T>& src) {
 // One class per kernel symbol (and role, where one symbol serves two), so that the live timings can be
 // set beside a profiler's per-kernel averages.
 enum ProfClass {
-    P_SPMM = 0, P_SPMM_GRADZ, P_SPMM_SEG, P_GEMM_NN_128, P_GEMM_NN_128_GRADZ, P_GEMM_NN_32, P_GEMM_TN, P_GEMM_TN_32, P_PHI_G,
+    P_SPMM = 0, P_SPMM_GRADZ, P_SPMM_SEG, P_GEMM_NN_128, P_GEMM_NN_128_GRADZ, P_GEMM_NN_128_TRIAL, P_GEMM_NN_32, P_GEMM_TN, P_GEMM_TN_32, P_PHI_G,
     P_G_ONLY, P_W_TRIAL, P_Z_TRIAL, P_W_STEP, P_Z_STEP, P_LAST_LAYER, P_T_CARRY, P_GEMM_GRADZ, P_OTHER
 };
 const char* kProfNames[CADMM_PROFILE_CLASSES] = {
     "spmm_rows_kernel[rows]", "spmm_rows_kernel[rows,gradz]", "spmm_rows_kernel[segments]", "gemm_nn_kernel<128,0>",
-    "gemm_nn_kernel<128,1>", "gemm_nn_kernel<32>", "gemm_tn_kernel<128>+reduce", "gemm_tn_kernel<32>+reduce",
+    "gemm_nn_kernel<128,1>", "gemm_nn_kernel<128,2>+finish", "gemm_nn_kernel<32>", "gemm_tn_kernel<128>+reduce", "gemm_tn_kernel<32>+reduce",
     "phi_G_kernel", "G_only_kernel",
     "w_trial_kernel", "z_trial_kernel", "w_step_kernel", "z_step_kernel", "last_layer_kernel", "t_carry_kernel",
     "gemm_nn_gradz_kernel", "other"};
@@ -413,20 +419,33 @@ void sweep(cadmm_ctx* c) {
         timed(c, P_OTHER, 8.0 * K * Cl, 0.0, [&] { launch_w_norms(s, c->gradW, c->W[l], K * Cl, unit, c->partials); });
         float* Q = c->G[l];                                                          // G_l is no longer needed
         // T(W - g/tau) = T - Q/tau with Q = A~ Z_{l-1} gradW
+        // In a wide hidden layer the product that forms Q also evaluates the first candidate of the search and
+        // takes the step on T_l speculatively (tau rarely changes once found); later kernels repair it if needed.
+        const bool spec = c->use_speculative && !c->agg_first[l] && !last && Cl > 32;
         if (c->agg_first[l]) {
             gemm_nn(c, c->Z[l - 1], c->gradW, c->tmpV, N, K, Cl);
             aggregate(c, c->tmpV, Q, Cl, SpmmEpilogue());
+        } else if (spec) {
+            GemmEpilogue ge;
+            ge.kind = 2; ge.Zl = c->Z[l]; ge.nu = c->nu; ge.Tio = c->T[l]; ge.unit = unit; ge.partials = c->partials;
+            timed(c, P_GEMM_NN_128_TRIAL, 4.0 * ((double)N * K + (double)K * Cl + 4.0 * (double)count), 2.0 * (double)N * K * Cl,
+                  [&] {
+                      launch_gemm_nn(s, c->H[l], c->gradW, Q, N, K, Cl, ge);
+                      launch_w_trial_finish(s, c->partials, (int)gemm_nn_blocks(N, Cl), sp, unit, c->status);
+                  });
         } else {
             gemm_nn(c, c->H[l], c->gradW, Q, N, K, Cl);
         }
         // one pass reads T0, Q, Z_l (and U for the last layer); passes after an accepted one return at once
-        timed(c, P_W_TRIAL, 4.0 * (double)count * (last ? 4 : 3), 0.0, [&] {
-            launch_w_trial(s, c->T[l], Q, c->Z[l], c->U, count, last, 1, sp, unit, c->partials, c->status);
+        timed(c, P_W_TRIAL, spec ? 0.0 : 4.0 * (double)count * (last ? 4 : 3), 0.0, [&] {
+            if (!spec) launch_w_trial(s, c->T[l], Q, c->Z[l], c->U, count, last, 1, sp, unit, c->partials, c->status);
             for (int p = 0; p < more_passes; ++p)
-                launch_w_trial(s, c->T[l], Q, c->Z[l], c->U, count, last, kMaxCand, sp, unit, c->partials, c->status);
+                launch_w_trial(s, c->T[l], Q, c->Z[l], c->U, count, last, kMaxCand, sp, unit, c->partials, c->status,
+                               spec ? 1 : 0);
         });
-        timed(c, P_W_STEP, 4.0 * (3.0 * (double)count + 3.0 * K * Cl), 0.0, [&] {
-            launch_w_step(s, c->W[l], c->gradW, K * Cl, c->T[l], Q, count, unit);    // W^{k+1}; T_l = A~ Z^k W^{k+1}
+        timed(c, P_W_STEP, 4.0 * ((spec ? 0.0 : 3.0) * (double)count + 3.0 * K * Cl), 0.0, [&] {
+            // W^{k+1}; T_l = A~ Z^k W^{k+1}
+            launch_w_step(s, c->W[l], c->gradW, K * Cl, c->T[l], Q, count, unit, spec ? 1 : 0);
         });
 
     }
@@ -992,8 +1011,10 @@ const char* cadmm_profile_class_name(int32_t cls) {
 int cadmm_tune(cadmm_ctx* c, const char* key, int32_t value) {
     if (!c || !key) return CADMM_EINVAL;
     if (std::strcmp(key, "use_graph") == 0) { c->use_graph = value != 0; return CADMM_OK; }
-    if (std::strcmp(key, "use_lowrank") == 0) {
-        c->use_lowrank = value != 0;
+    const bool k_lowrank = std::strcmp(key, "use_lowrank") == 0, k_spec = std::strcmp(key, "use_speculative") == 0;
+    if (k_lowrank || k_spec) {
+        if (k_lowrank) c->use_lowrank = value != 0;
+        else c->use_speculative = value != 0;
         for (auto& cube : c->graphs)
             for (auto& plane : cube)
                 for (auto& row : plane)

@@ -70,7 +70,9 @@ __device__ __forceinline__ void decide(Unit* u, const double* D, int ncand, Sear
 __device__ __forceinline__ void floor_or_start(Unit* u, double g, double bnorm) {
     u->g = g;
     u->bnorm = bnorm;
+    u->spec = (u->ntrials == 1) ? 1 : 0;     // last search: first candidate accepted
     u->ntrials = 0;
+    u->step0 = u->step;
     const double lim = kStepFloor * u->step;
     if (g <= lim * lim * bnorm) { u->done = 1; u->skip = 1; }
     else { u->done = 0; u->skip = 0; }
@@ -236,9 +238,10 @@ template <int LAST, int NC, int VEC>
 __global__ __launch_bounds__(256) void w_trial_kernel(const float* __restrict__ T0, const float* __restrict__ Q,
                                                       const float* __restrict__ Z, const float* __restrict__ U,
                                                       int64_t count, SearchParams sp, const Unit* unit,
-                                                      double* __restrict__ partials) {
+                                                      double* __restrict__ partials, int speculated) {
     __shared__ double sm[4];
     if (unit->done) return;
+    const double spec_inv = (speculated && unit->spec) ? 1.0 / unit->step0 : 0.0;      // T0 holds T0 - Q/step0: undo
     double inv[NC];
     {
         double step = unit->step;
@@ -257,7 +260,8 @@ __global__ __launch_bounds__(256) void w_trial_kernel(const float* __restrict__ 
         if (LAST) ldv<VEC>(uv, U + i);
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
-            const double t0 = (double)t0v[v], q = (double)qv[v], z = (double)zv[v];
+            const double q = (double)qv[v], z = (double)zv[v];
+            const double t0 = (double)t0v[v] + q * spec_inv;
             if (LAST) {
                 const double u = (double)uv[v];
                 const double r0 = z - t0;
@@ -301,17 +305,22 @@ __global__ __launch_bounds__(256) void w_trial_finish_kernel(const double* __res
 template <int VEC>
 __global__ __launch_bounds__(256) void w_step_kernel(float* __restrict__ W, const float* __restrict__ gradW,
                                                      int count_w, float* __restrict__ T, const float* __restrict__ Q,
-                                                     int64_t count_t, const Unit* unit) {
+                                                     int64_t count_t, const Unit* unit, int speculated) {
     if (unit->skip) return;
     const double inv = 1.0 / unit->step;
     const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t nthreads = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = gtid * VEC; i < count_t; i += nthreads * VEC) {
+    // T already holds T0 - Q/step0 when the step was taken speculatively: nothing to do if step0 was accepted,
+    // otherwise T0 - Q/step = T + Q (1/step0 - 1/step)
+    const bool spec = speculated && unit->spec;
+    const double tinv = spec ? inv - 1.0 / unit->step0 : inv;
+    const bool t_done = spec && unit->step == unit->step0;
+    for (int64_t i = gtid * VEC; !t_done && i < count_t; i += nthreads * VEC) {
         float t[VEC], q[VEC];
         ldv<VEC>(t, T + i);
         ldv<VEC>(q, Q + i);
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) t[v] = (float)((double)t[v] - (double)q[v] * inv);
+        for (int v = 0; v < VEC; ++v) t[v] = (float)((double)t[v] - (double)q[v] * tinv);
         stv<VEC>(T + i, t);
     }
     for (int64_t i = gtid; i < count_w; i += nthreads) W[i] = (float)((double)W[i] - (double)gradW[i] * inv);
@@ -701,7 +710,7 @@ __global__ void fill_units_kernel(Unit* units, int n, double step) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     Unit u;
-    u.step = step; u.g = 0.0; u.bnorm = 0.0; u.done = 0; u.skip = 0; u.ntrials = 0; u.pad = 0;
+    u.step = step; u.step0 = step; u.g = 0.0; u.bnorm = 0.0; u.done = 0; u.skip = 0; u.ntrials = 0; u.spec = 0;
     units[i] = u;
 }
 
@@ -773,12 +782,17 @@ void launch_w_norms(hipStream_t s, const float* gradW, const float* W, int count
     hipLaunchKernelGGL(w_norms_finish_kernel, dim3(1), dim3(64), 0, s, partials, nb, unit);
 }
 
+void launch_w_trial_finish(hipStream_t s, double* partials, int n_partials, SearchParams sp, Unit* unit,
+                           int32_t* status) {
+    hipLaunchKernelGGL(w_trial_finish_kernel, dim3(1), dim3(256), 0, s, partials, n_partials, 1, sp, unit, status);
+}
+
 void launch_w_trial(hipStream_t s, const float* T0, const float* Q, const float* Z, const float* U,
                     int64_t count, int last, int ncand, SearchParams sp, Unit* unit, double* partials,
-                    int32_t* status) {
+                    int32_t* status, int speculated) {
     const int nb = flat_grid(count);
     const bool v4 = (count % 4) == 0;
-#define CADMM_W_TRIAL(L_, N_, V_) hipLaunchKernelGGL((w_trial_kernel<L_, N_, V_>), dim3(nb), dim3(256), 0, s, T0, Q, Z, U, count, sp, unit, partials)
+#define CADMM_W_TRIAL(L_, N_, V_) hipLaunchKernelGGL((w_trial_kernel<L_, N_, V_>), dim3(nb), dim3(256), 0, s, T0, Q, Z, U, count, sp, unit, partials, speculated)
     if (ncand == 1) {
         if (last) { if (v4) CADMM_W_TRIAL(1, 1, 4); else CADMM_W_TRIAL(1, 1, 1); }
         else { if (v4) CADMM_W_TRIAL(0, 1, 4); else CADMM_W_TRIAL(0, 1, 1); }
@@ -792,10 +806,10 @@ void launch_w_trial(hipStream_t s, const float* T0, const float* Q, const float*
 }
 
 void launch_w_step(hipStream_t s, float* W, const float* gradW, int count_w, float* T, const float* Q,
-                   int64_t count_t, const Unit* unit) {
+                   int64_t count_t, const Unit* unit, int speculated) {
     const int nb = flat_grid(count_t > count_w ? count_t : count_w);
-    if (count_t % 4 == 0) hipLaunchKernelGGL((w_step_kernel<4>), dim3(nb), dim3(256), 0, s, W, gradW, count_w, T, Q, count_t, unit);
-    else hipLaunchKernelGGL((w_step_kernel<1>), dim3(nb), dim3(256), 0, s, W, gradW, count_w, T, Q, count_t, unit);
+    if (count_t % 4 == 0) hipLaunchKernelGGL((w_step_kernel<4>), dim3(nb), dim3(256), 0, s, W, gradW, count_w, T, Q, count_t, unit, speculated);
+    else hipLaunchKernelGGL((w_step_kernel<1>), dim3(nb), dim3(256), 0, s, W, gradW, count_w, T, Q, count_t, unit, speculated);
 }
 
 void launch_z_trial(hipStream_t s, const ZTrialArgs& a0) {

@@ -37,11 +37,13 @@ __device__ __forceinline__ float4 ld4_guard(const float* base, int64_t off, bool
 
 // ------------------------------------------------------------------------------------------------ NN
 // EPI 1: out = nu * (Zl - relu(Tl)) + A B   (gradient of the Z subproblem, Appendix A)
+// EPI 2: out = Q = A B; first candidate of the W search and speculative step on Tio (Section 3.1), see kernels.h
 template <int BN, int EPI>
 __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ A, const float* __restrict__ B,
                                                       float* __restrict__ out, int64_t n, int K, int C,
                                                       const float* __restrict__ Zl, const float* __restrict__ Tl,
-                                                      float nu) {
+                                                      float nu, float* __restrict__ Tio, const Unit* unit,
+                                                      double* __restrict__ partials) {
     constexpr int WN = (BN == 128) ? 2 : 1;       // waves along columns
     constexpr int WM = 4 / WN;                    // waves along rows
     constexpr int TM = BM / (WM * 32);            // 32x32 tiles per wave along rows
@@ -133,6 +135,12 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
         }
     }
     const int li = lane & 31, lk = lane >> 5;
+    double inv0 = 0.0, dsum = 0.0;
+    bool take = false;
+    if constexpr (EPI == 2) {
+        inv0 = unit->skip ? 0.0 : 1.0 / unit->step0;
+        take = unit->spec != 0 && !unit->skip;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -145,10 +153,25 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
                 if (row < n) {
                     float v = acc[i][j][r];
                     if constexpr (EPI == 1) v = nu * (Zl[row * C + c] - fmaxf(Tl[row * C + c], 0.f)) + v;
+                    if constexpr (EPI == 2) {
+                        const double t0 = (double)Tio[row * C + c], z = (double)Zl[row * C + c];
+                        const double t1 = t0 - (double)v * inv0;
+                        const double e0 = fmax(t0, 0.0) - z, e1 = fmax(t1, 0.0) - z;
+                        dsum += (e1 - e0) * (e1 + e0);
+                        if (take) Tio[row * C + c] = (float)t1;
+                    }
                     out[row * C + c] = v;
                 }
             }
         }
+    if constexpr (EPI == 2) {
+        __shared__ double red[4];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
+        if (lane == 0) red[wave] = dsum;
+        __syncthreads();
+        if (tid == 0) partials[(int64_t)blockIdx.x * kMaxCand] = 0.5 * (double)nu * (red[0] + red[1] + red[2] + red[3]);
+    }
 }
 
 // out[n x C] = [ nu (Z - relu(T)) | SG ] * Bcat  with Bcat = [ W (K1 x C) ; S (K2 x C) ],  C <= 32.
@@ -422,16 +445,23 @@ void launch_gemm_nn(hipStream_t s, const float* A, const float* B, float* out, i
     if (C > 32) {
         const int ct = (C + 127) / 128;
         dim3 grid((unsigned)(mt * ct));
-        if (epi.kind == 1)
-            hipLaunchKernelGGL((gemm_nn_kernel<128, 1>), grid, dim3(256), 0, s, A, B, out, n, K, C, epi.Zl, epi.Tl, epi.nu);
+        if (epi.kind == 2)
+            hipLaunchKernelGGL((gemm_nn_kernel<128, 2>), grid, dim3(256), 0, s, A, B, out, n, K, C, epi.Zl, nullptr, epi.nu,
+                               epi.Tio, epi.unit, epi.partials);
+        else if (epi.kind == 1)
+            hipLaunchKernelGGL((gemm_nn_kernel<128, 1>), grid, dim3(256), 0, s, A, B, out, n, K, C, epi.Zl, epi.Tl, epi.nu,
+                               nullptr, nullptr, nullptr);
         else
-            hipLaunchKernelGGL((gemm_nn_kernel<128, 0>), grid, dim3(256), 0, s, A, B, out, n, K, C, nullptr, nullptr, 0.f);
+            hipLaunchKernelGGL((gemm_nn_kernel<128, 0>), grid, dim3(256), 0, s, A, B, out, n, K, C, nullptr, nullptr, 0.f,
+                               nullptr, nullptr, nullptr);
     } else {
         dim3 grid((unsigned)mt);
         if (epi.kind == 1)
-            hipLaunchKernelGGL((gemm_nn_kernel<32, 1>), grid, dim3(256), 0, s, A, B, out, n, K, C, epi.Zl, epi.Tl, epi.nu);
+            hipLaunchKernelGGL((gemm_nn_kernel<32, 1>), grid, dim3(256), 0, s, A, B, out, n, K, C, epi.Zl, epi.Tl, epi.nu,
+                               nullptr, nullptr, nullptr);
         else
-            hipLaunchKernelGGL((gemm_nn_kernel<32, 0>), grid, dim3(256), 0, s, A, B, out, n, K, C, nullptr, nullptr, 0.f);
+            hipLaunchKernelGGL((gemm_nn_kernel<32, 0>), grid, dim3(256), 0, s, A, B, out, n, K, C, nullptr, nullptr, 0.f,
+                               nullptr, nullptr, nullptr);
     }
 }
 
@@ -440,6 +470,11 @@ void launch_gemm_nn_gradz(hipStream_t s, const float* Zl, const float* Tl, const
     if (n <= 0) return;
     hipLaunchKernelGGL(gemm_nn_gradz_kernel, dim3((unsigned)((n + BM - 1) / BM)), dim3(256), 0, s, Zl, Tl, SG, Bcat, out,
                        n, K1, K2, C, nu);
+}
+
+int64_t gemm_nn_blocks(int64_t n, int C) {
+    const int64_t mt = (n + BM - 1) / BM;
+    return C > 32 ? mt * ((C + 127) / 128) : mt;
 }
 
 size_t gemm_tn_scratch_floats(int64_t n, int K, int C) {

@@ -43,15 +43,26 @@ void set_spmm_groups_log2(int v);
 void set_spmm_unroll(int v);
 
 // ---------------------------------------------------------------- dense contractions (gemm.hip)
-// out[n x C] = A[n x K] * B[K x C];  epilogue 1: out = nu * (Zl - relu(Tl)) + A B
+struct Unit;
+// out[n x C] = A[n x K] * B[K x C];  epilogue 1: out = nu * (Zl - relu(Tl)) + A B.
+// epilogue 2 (hidden layer, W search): out = Q = A B is stored, and in the same pass the first candidate of
+// the search is evaluated and the step taken speculatively: with t0 = Tio, t1 = t0 - Q / unit->step0,
+// partials[block * kMaxCand] = nu/2 sum ((relu(t1) - Zl)^2 - (relu(t0) - Zl)^2) and, if unit->spec, Tio = t1.
+// If the search later accepts another value, w_step repairs Tio from Q.  The step is only taken ahead of the
+// decision when the previous search accepted its first candidate: then Q/step0 is small against Tio and
+// undoing it costs one rounding; with a step0 far too small (first iterations) it would wipe out Tio.
 struct GemmEpilogue {
     int kind = 0;
     const float* Zl = nullptr;
     const float* Tl = nullptr;
     float nu = 0.f;
+    float* Tio = nullptr;
+    const Unit* unit = nullptr;
+    double* partials = nullptr;
 };
 void launch_gemm_nn(hipStream_t s, const float* A, const float* B, float* out, int64_t n, int K, int C,
                     const GemmEpilogue& epi = GemmEpilogue());
+int64_t gemm_nn_blocks(int64_t n, int C);      // grid size of that launch (= block results of epilogue 2)
 // out[n x C] = [nu (Zl - relu(Tl)) | SG] * Bcat, Bcat = [W (K1 x C); S (K2 x C)], C <= 32, K1 % 4 == K2 % 4 == 0:
 // the product (grad_Z psi) W with grad = nu (Zl - relu(Tl)) + SG W^T, S = W^T W, the gradient never stored.
 void launch_gemm_nn_gradz(hipStream_t s, const float* Zl, const float* Tl, const float* SG, const float* Bcat,
@@ -74,12 +85,13 @@ constexpr int kChunkRows = 128;          // rows / segments per reduction chunk 
 // One step-size search ("unit"): a layer's tau, or a (layer, community)'s theta.
 struct Unit {
     double step;       // current first candidate / accepted value
+    double step0;      // first candidate of this iteration's search (the value the speculative step used)
     double g;          // squared gradient norm
     double bnorm;      // squared norm of the block that moves
     int32_t done;      // search finished
     int32_t skip;      // step below resolution: block stays
     int32_t ntrials;   // candidates tested this iteration
-    int32_t pad;
+    int32_t spec;      // the previous search accepted its first candidate: a speculative step with step0 is safe
 };
 
 // Readout scalars of one layer's base evaluation.
@@ -110,12 +122,17 @@ void launch_risk(hipStream_t s, const float* ZL, const int32_t* labels, int64_t 
 // unit.g = ||gradW||^2, unit.bnorm = ||W||^2, applies the step floor, resets the search state.
 void launch_w_norms(hipStream_t s, const float* gradW, const float* W, int count, Unit* unit, double* partials);
 // One pass of the W search: candidates step*eta^j, j < ncand, on phi_l(T0 - Q/step).
+// speculated != 0: T0 already holds the speculative step T0 - Q/step0; the pass rebuilds T0 = T0 + Q/step0.
 void launch_w_trial(hipStream_t s, const float* T0, const float* Q, const float* Z, const float* U,
                     int64_t count, int last, int ncand, SearchParams sp, Unit* unit, double* partials,
-                    int32_t* status);
+                    int32_t* status, int speculated = 0);
+// Sums n_partials block results of an epilogue-2 product (candidate 0 only) and takes the search decision.
+void launch_w_trial_finish(hipStream_t s, double* partials, int n_partials, SearchParams sp, Unit* unit,
+                           int32_t* status);
 // W -= gradW/step (count_w entries), T = T0 - Q/step (count_t entries); no-op if unit.skip.
+// speculated != 0: T already holds T0 - Q/step0 and is only repaired if the accepted step differs.
 void launch_w_step(hipStream_t s, float* W, const float* gradW, int count_w, float* T, const float* Q,
-                   int64_t count_t, const Unit* unit);
+                   int64_t count_t, const Unit* unit, int speculated = 0);
 
 // Z search, layer l (widths Cl, Cn = C_{l+1}).  Device arrays of the graph:
 struct ZTrialArgs {
