@@ -53,8 +53,10 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
     constexpr int B_F4 = BK * BN / 4;             // float4 loads for the B tile
     constexpr int B_PER_T = (B_F4 + 255) / 256;
 
-    __shared__ __align__(16) float As[BM * LDA];
-    __shared__ __align__(16) float Bs[BK * LDB];
+    // one buffer: the operand tiles during the product, a 32-row slab of the result tile afterwards
+    __shared__ __align__(16) float smem[BM * LDA + BK * LDB];
+    float* const As = smem;
+    float* const Bs = smem + BM * LDA;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -141,29 +143,96 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
         inv0 = unit->skip ? 0.0 : 1.0 / unit->step0;
         take = unit->spec != 0 && !unit->skip;
     }
+    // one result element: returns what goes to out, updates t (EPI 2) and the candidate's sum
+    auto finish = [&](float v, float z, float& t) -> float {
+        if constexpr (EPI == 1) v = nu * (z - fmaxf(t, 0.f)) + v;
+        if constexpr (EPI == 2) {
+            const double t0 = (double)t, zd = (double)z;
+            const double t1 = t0 - (double)v * inv0;
+            const double e0 = fmax(t0, 0.0) - zd, e1 = fmax(t1, 0.0) - zd;
+            dsum += (e1 - e0) * (e1 + e0);
+            t = (float)t1;
+        }
+        return v;
+    };
+    if constexpr (BN == 128) {
+        // The accumulators hold 32 consecutive columns per row and lane group; passing each 32-row slab of the
+        // tile through LDS turns every global access of the epilogue into float4 pieces of a 512-byte row.
+        constexpr int LDC = BN + 4;
+        static_assert(32 * LDC <= BM * LDA + BK * LDB, "result slab must fit the operand buffer");
+        float* const Cs = smem;
+        const float* tin = (EPI == 2) ? Tio : Tl;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int q = 0; q < BM / 32; ++q) {
+            __syncthreads();
+            if (wm == q / TM) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int c = c0 + wn * TN * 32 + j * 32 + li;
-            if (c >= C) continue;
+                for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t row = m0 + wm * TM * 32 + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
-                if (row < n) {
-                    float v = acc[i][j][r];
-                    if constexpr (EPI == 1) v = nu * (Zl[row * C + c] - fmaxf(Tl[row * C + c], 0.f)) + v;
-                    if constexpr (EPI == 2) {
-                        const double t0 = (double)Tio[row * C + c], z = (double)Zl[row * C + c];
-                        const double t1 = t0 - (double)v * inv0;
-                        const double e0 = fmax(t0, 0.0) - z, e1 = fmax(t1, 0.0) - z;
-                        dsum += (e1 - e0) * (e1 + e0);
-                        if (take) Tio[row * C + c] = (float)t1;
+                    for (int r = 0; r < 16; ++r)
+                        Cs[(8 * (r >> 2) + 4 * lk + (r & 3)) * LDC + wn * TN * 32 + j * 32 + li] = acc[q % TM][j][r];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int f = tid + 256 * u;
+                const int rl = f >> 5, cq = f & 31;
+                const int64_t row = m0 + 32 * q + rl;
+                const int c = c0 + 4 * cq;
+                if (row >= n || c >= C) continue;
+                const float4 v4 = *reinterpret_cast<const float4*>(Cs + rl * LDC + 4 * cq);
+                float v[4] = {v4.x, v4.y, v4.z, v4.w};
+                const int64_t o = row * C + c;
+                if (b_al) {
+                    float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f), t4 = z4;
+                    if constexpr (EPI != 0) {
+                        z4 = *reinterpret_cast<const float4*>(Zl + o);
+                        t4 = *reinterpret_cast<const float4*>(tin + o);
                     }
-                    out[row * C + c] = v;
+                    v[0] = finish(v[0], z4.x, t4.x);
+                    v[1] = finish(v[1], z4.y, t4.y);
+                    v[2] = finish(v[2], z4.z, t4.z);
+                    v[3] = finish(v[3], z4.w, t4.w);
+                    if constexpr (EPI == 2) {
+                        if (take) *reinterpret_cast<float4*>(Tio + o) = t4;
+                    }
+                    *reinterpret_cast<float4*>(out + o) = make_float4(v[0], v[1], v[2], v[3]);
+                } else {
+                    for (int e = 0; e < 4 && c + e < C; ++e) {
+                        float z = 0.f, t = 0.f;
+                        if constexpr (EPI != 0) { z = Zl[o + e]; t = tin[o + e]; }
+                        const float w = finish(v[e], z, t);
+                        if constexpr (EPI == 2) {
+                            if (take) Tio[o + e] = t;
+                        }
+                        out[o + e] = w;
+                    }
                 }
             }
         }
+    } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int c = c0 + wn * TN * 32 + j * 32 + li;
+                if (c >= C) continue;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t row = m0 + wm * TM * 32 + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+                    if (row < n) {
+                        float z = 0.f, t = 0.f;
+                        if constexpr (EPI == 1) { z = Zl[row * C + c]; t = Tl[row * C + c]; }
+                        if constexpr (EPI == 2) { z = Zl[row * C + c]; t = Tio[row * C + c]; }
+                        const float v = finish(acc[i][j][r], z, t);
+                        if constexpr (EPI == 2) {
+                            if (take) Tio[row * C + c] = t;
+                        }
+                        out[row * C + c] = v;
+                    }
+                }
+            }
+    }
     if constexpr (EPI == 2) {
         __shared__ double red[4];
 #pragma unroll
