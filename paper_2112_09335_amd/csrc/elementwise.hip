@@ -288,13 +288,22 @@ __global__ __launch_bounds__(256) void w_trial_kernel(const float* __restrict__ 
 }
 
 __global__ __launch_bounds__(256) void w_trial_finish_kernel(const double* __restrict__ partials, int nblocks,
-                                                             int ncand, SearchParams sp, Unit* unit, int32_t* status) {
+                                                             int stride, int ncand, SearchParams sp, Unit* unit,
+                                                             int32_t* status) {
     __shared__ double sm[4];
     __shared__ double D[kMaxCand];
     if (unit->done) return;
     for (int j = 0; j < ncand; ++j) {
-        double a = 0.0;
-        for (int i = threadIdx.x; i < nblocks; i += blockDim.x) a += partials[i * kMaxCand + j];
+        double a = 0.0, b = 0.0, c = 0.0, d = 0.0;     // four independent loads in flight per thread
+        int i = threadIdx.x;
+        for (; i + 768 < nblocks; i += 1024) {
+            a += partials[(int64_t)i * stride + j];
+            b += partials[(int64_t)(i + 256) * stride + j];
+            c += partials[(int64_t)(i + 512) * stride + j];
+            d += partials[(int64_t)(i + 768) * stride + j];
+        }
+        for (; i < nblocks; i += 256) a += partials[(int64_t)i * stride + j];
+        a = (a + b) + (c + d);
         a = block_sum(a, sm);
         if (threadIdx.x == 0) D[j] = a;
     }
@@ -348,9 +357,7 @@ __device__ __forceinline__ void lowrank_grad(float (&g)[4], const float (&z)[4],
 }
 
 template <int NC, int VEC, int LR>
-__global__ __launch_bounds__(256) void z_trial_kernel(ZTrialArgs a) {
-    __shared__ double sm[4];
-    const int ch = blockIdx.x;
+__device__ __forceinline__ void z_trial_chunk(const ZTrialArgs& a, int ch, double* sm) {
     const int unit = a.chunk_unit[ch];
     const Unit* u = a.units + unit;
     if (u->done) return;
@@ -458,6 +465,22 @@ __global__ __launch_bounds__(256) void z_trial_kernel(ZTrialArgs a) {
         sg = block_sum(sg, sm);
         sb = block_sum(sb, sm);
         if (threadIdx.x == 0) { out[kMaxCand] = sg; out[kMaxCand + 1] = sb; }
+    }
+}
+
+// The first pass (one candidate) runs one block per chunk.  A later pass (NC candidates) usually finds every
+// community done: each block first looks at all the done flags at once and leaves if nothing is pending,
+// otherwise a small grid strides over the chunks.
+template <int NC, int VEC, int LR>
+__global__ __launch_bounds__(256) void z_trial_kernel(ZTrialArgs a) {
+    __shared__ double sm[4];
+    if constexpr (NC == 1) {
+        z_trial_chunk<NC, VEC, LR>(a, blockIdx.x, sm);
+    } else {
+        int pending = 0;
+        for (int i = threadIdx.x; i < a.M; i += 256) pending |= (a.units[i].done == 0);
+        if (!__syncthreads_or(pending)) return;
+        for (int ch = blockIdx.x; ch < a.n_chunks; ch += gridDim.x) z_trial_chunk<NC, VEC, LR>(a, ch, sm);
     }
 }
 
@@ -784,7 +807,7 @@ void launch_w_norms(hipStream_t s, const float* gradW, const float* W, int count
 
 void launch_w_trial_finish(hipStream_t s, double* partials, int n_partials, SearchParams sp, Unit* unit,
                            int32_t* status) {
-    hipLaunchKernelGGL(w_trial_finish_kernel, dim3(1), dim3(256), 0, s, partials, n_partials, 1, sp, unit, status);
+    hipLaunchKernelGGL(w_trial_finish_kernel, dim3(1), dim3(256), 0, s, partials, n_partials, 1, 1, sp, unit, status);
 }
 
 void launch_w_trial(hipStream_t s, const float* T0, const float* Q, const float* Z, const float* U,
@@ -802,7 +825,7 @@ void launch_w_trial(hipStream_t s, const float* T0, const float* Q, const float*
         else { if (v4) CADMM_W_TRIAL(0, kMaxCand, 4); else CADMM_W_TRIAL(0, kMaxCand, 1); }
     }
 #undef CADMM_W_TRIAL
-    hipLaunchKernelGGL(w_trial_finish_kernel, dim3(1), dim3(256), 0, s, partials, nb, ncand, sp, unit, status);
+    hipLaunchKernelGGL(w_trial_finish_kernel, dim3(1), dim3(256), 0, s, partials, nb, kMaxCand, ncand, sp, unit, status);
 }
 
 void launch_w_step(hipStream_t s, float* W, const float* gradW, int count_w, float* T, const float* Q,
@@ -823,9 +846,10 @@ void launch_z_trial(hipStream_t s, const ZTrialArgs& a0) {
             else hipLaunchKernelGGL((z_trial_kernel<1, 1, 0>), dim3(a.n_chunks), dim3(256), 0, s, a);
         } else {
             a.ncand = kMaxCand;
-            if (lr) hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 4, 1>), dim3(a.n_chunks), dim3(256), 0, s, a);
-            else if (v4) hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 4, 0>), dim3(a.n_chunks), dim3(256), 0, s, a);
-            else hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 1, 0>), dim3(a.n_chunks), dim3(256), 0, s, a);
+            const int nb = a.n_chunks < kReduceBlocks ? a.n_chunks : kReduceBlocks;
+            if (lr) hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 4, 1>), dim3(nb), dim3(256), 0, s, a);
+            else if (v4) hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 4, 0>), dim3(nb), dim3(256), 0, s, a);
+            else hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 1, 0>), dim3(nb), dim3(256), 0, s, a);
         }
     }
     hipLaunchKernelGGL(z_trial_finish_kernel, dim3(a.M), dim3(256), 0, s, a);

@@ -239,7 +239,7 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
         for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
         if (lane == 0) red[wave] = dsum;
         __syncthreads();
-        if (tid == 0) partials[(int64_t)blockIdx.x * kMaxCand] = 0.5 * (double)nu * (red[0] + red[1] + red[2] + red[3]);
+        if (tid == 0) partials[blockIdx.x] = 0.5 * (double)nu * (red[0] + red[1] + red[2] + red[3]);
     }
 }
 
