@@ -505,11 +505,12 @@ void sweep(cadmm_ctx* c) {
         a.Zl = c->Z[l]; a.gradZ = lowrank ? nullptr : c->tmpB; a.Tl = c->T[l]; a.Cl = Cl;
         a.SG = c->tmpA; a.Wt = c->Wt;
         a.Tn = c->T[l + 1]; a.Zn = c->Z[l + 1]; a.U = c->U; a.P = c->P; a.Cn = Cn;
+        a.Gn = c->G[l + 1];
         a.next_is_last = next_last;
         a.sp = sp; a.units = units; a.partials = c->partials; a.status = c->status;
-        // one pass reads Z_l, grad, T_l over the rows and T_{l+1}, Z_{l+1} (U), P over the segments
+        // one pass reads Z_l, grad, T_l over the rows and P with T_{l+1}, Z_{l+1} (or G_L alone) over the segments
         const double zt_bytes = 4.0 * ((lowrank ? 2.0 : 3.0) * (double)N * Cl + (lowrank ? (double)N * Cn : 0.0) +
-                                       (next_last ? 4.0 : 3.0) * (double)c->hg.n_seg * Cn) + 4.0 * (double)c->hg.n_seg;
+                                       (next_last ? 2.0 : 3.0) * (double)c->hg.n_seg * Cn) + 4.0 * (double)c->hg.n_seg;
         timed(c, P_Z_TRIAL, zt_bytes, 0.0, [&] {
             a.first_pass = 1; a.ncand = 1;
             launch_z_trial(s, a);

@@ -427,21 +427,24 @@ __device__ __forceinline__ void z_trial_chunk(const ZTrialArgs& a, int ch, doubl
             const int64_t row = a.segc_row[s];
             const int64_t base = row * width, pbase = (int64_t)s * width;
             for (int cv = c_first; cv < wv; cv += cp) {
-                float tv[VEC], zv[VEC], pv[VEC], uv[VEC];
-                ldv<VEC>(tv, a.Tn + base + cv * VEC);
-                ldv<VEC>(zv, a.Zn + base + cv * VEC);
+                float tv[VEC], zv[VEC], pv[VEC];
                 ldv<VEC>(pv, a.P + pbase + cv * VEC);
-                if (a.next_is_last) ldv<VEC>(uv, a.U + base + cv * VEC);
+                if (a.next_is_last) {
+                    // the change of <U, Z_L - T> + rho/2 |Z_L - T|^2 under T -> T - p/theta is
+                    // (p/theta) (u + rho (z - t)) + rho/2 (p/theta)^2, and u + rho (z - t) = -G_L is at hand
+                    ldv<VEC>(tv, a.Gn + base + cv * VEC);
+                } else {
+                    ldv<VEC>(tv, a.Tn + base + cv * VEC);
+                    ldv<VEC>(zv, a.Zn + base + cv * VEC);
+                }
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
                     const double t0 = (double)tv[v], z = (double)zv[v], p = (double)pv[v];
                     if (a.next_is_last) {
-                        const double uu = (double)uv[v];
-                        const double r0 = z - t0;
 #pragma unroll
                         for (int j = 0; j < NC; ++j) {
                             const double dq = p * inv[j];
-                            D[j] += dq * (uu + hrho * (2.0 * r0 + dq));
+                            D[j] += dq * (hrho * dq - t0);
                         }
                     } else {
                         const double e0 = fmax(t0, 0.0) - z;

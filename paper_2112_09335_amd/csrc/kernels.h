@@ -145,6 +145,7 @@ struct ZTrialArgs {
     // Cn <= kLowRankMax, Wt is Cn x Cl; it is recomputed per element instead of being read
     const float* SG = nullptr; const float* Wt = nullptr;
     const float* Tn; const float* Zn; const float* U; const float* P; int Cn;   // next layer, per segment
+    const float* Gn = nullptr;   // last next layer: G_L = -(U + rho (Z_L - T_L)), read in place of Tn, Zn and U
     int next_is_last;
     int first_pass;        // also accumulate ||gradZ_m||^2 and ||Z_m||^2, apply the step floor
     int ncand;
