@@ -35,6 +35,22 @@ __device__ __forceinline__ float4 ld4_guard(const float* base, int64_t off, bool
     return v;
 }
 
+// Consecutive workgroups go round-robin to the eight XCDs, each with an L2 of its own.  Workgroups that read the
+// same operand tile (the `inner` column tiles of one row tile, the tiles of one row chunk) are therefore given
+// indices 8 apart, so that they run at about the same time on ONE XCD and the shared tile comes from its L2.
+// The last, incomplete set of 8 * inner workgroups keeps the plain order.  (outer, in) is a bijection of blockIdx.
+__device__ __forceinline__ void xcd_group(unsigned b, unsigned nb, unsigned inner, int64_t& outer, int& in) {
+    const unsigned set = 8u * inner;
+    if (b < nb / set * set) {
+        const unsigned w = b % set;
+        outer = (int64_t)(b / set) * 8 + (w & 7u);
+        in = (int)(w >> 3);
+    } else {
+        outer = b / inner;
+        in = (int)(b % inner);
+    }
+}
+
 // ------------------------------------------------------------------------------------------------ NN
 // EPI 1: out = nu * (Zl - relu(Tl)) + A B   (gradient of the Z subproblem, Appendix A)
 // EPI 2: out = Q = A B; first candidate of the W search and speculative step on Tio (Section 3.1), see kernels.h
@@ -48,13 +64,18 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
     constexpr int WM = 4 / WN;                    // waves along rows
     constexpr int TM = BM / (WM * 32);            // 32x32 tiles per wave along rows
     constexpr int TN = BN / (WN * 32);
-    constexpr int LDA = BK + 1;
+    // columns of A per step: the narrow variant is bound by reading A, and takes a whole 128-byte line of a
+    // row per step so that no half line has to survive in the L2 until the next step
+    constexpr int BKK = (BN == 32) ? 32 : BK;
+    constexpr int LDA = BKK + 1;
     constexpr int LDB = BN + 4;
-    constexpr int B_F4 = BK * BN / 4;             // float4 loads for the B tile
+    constexpr int A_Q = BKK / 4;                  // float4 per row of the A tile
+    constexpr int A_PER_T = BM * A_Q / 256;
+    constexpr int B_F4 = BKK * BN / 4;            // float4 loads for the B tile
     constexpr int B_PER_T = (B_F4 + 255) / 256;
 
     // one buffer: the operand tiles during the product, a 32-row slab of the result tile afterwards
-    __shared__ __align__(16) float smem[BM * LDA + BK * LDB];
+    __shared__ __align__(16) float smem[BM * LDA + BKK * LDB];
     float* const As = smem;
     float* const Bs = smem + BM * LDA;
 
@@ -63,8 +84,11 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
     const int wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int ctiles = (C + BN - 1) / BN;
-    const int64_t m0 = (int64_t)(blockIdx.x / ctiles) * BM;
-    const int c0 = (blockIdx.x % ctiles) * BN;
+    int64_t mtile;
+    int ctile;
+    xcd_group(blockIdx.x, gridDim.x, (unsigned)ctiles, mtile, ctile);
+    const int64_t m0 = mtile * BM;
+    const int c0 = ctile * BN;
     const bool a_al = (K % 4) == 0;
     const bool b_al = (C % 4) == 0;
 
@@ -76,12 +100,12 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    float4 ra[2], rb[B_PER_T];
+    float4 ra[A_PER_T], rb[B_PER_T];
     auto fetch = [&](int k0) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < A_PER_T; ++i) {
             const int f = tid + 256 * i;
-            const int row = f >> 2, kq = f & 3;
+            const int row = f / A_Q, kq = f % A_Q;
             const int64_t gr = m0 + row;
             const int k = k0 + 4 * kq;
             ra[i] = ld4_guard(A, gr * K + k, gr < n, a_al, K - k);
@@ -98,9 +122,9 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
     };
     auto stash = [&]() {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < A_PER_T; ++i) {
             const int f = tid + 256 * i;
-            const int row = f >> 2, kq = f & 3;
+            const int row = f / A_Q, kq = f % A_Q;
             float* d = As + row * LDA + 4 * kq;
             d[0] = ra[i].x; d[1] = ra[i].y; d[2] = ra[i].z; d[3] = ra[i].w;
         }
@@ -114,16 +138,16 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
         }
     };
 
-    const int nk = (K + BK - 1) / BK;
+    const int nk = (K + BKK - 1) / BKK;
     fetch(0);
     for (int kt = 0; kt < nk; ++kt) {
         __syncthreads();            // previous tile fully consumed
         stash();
         __syncthreads();
-        if (kt + 1 < nk) fetch((kt + 1) * BK);
+        if (kt + 1 < nk) fetch((kt + 1) * BKK);
         const int li = lane & 31, lk = lane >> 5;
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 2) {
+        for (int kk = 0; kk < BKK; kk += 2) {
             float a[TM], b[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i) a[i] = As[(wm * TM * 32 + i * 32 + li) * LDA + kk + lk];
@@ -159,7 +183,7 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
         // The accumulators hold 32 consecutive columns per row and lane group; passing each 32-row slab of the
         // tile through LDS turns every global access of the epilogue into float4 pieces of a 512-byte row.
         constexpr int LDC = BN + 4;
-        static_assert(32 * LDC <= BM * LDA + BK * LDB, "result slab must fit the operand buffer");
+        static_assert(32 * LDC <= BM * LDA + BKK * LDB, "result slab must fit the operand buffer");
         float* const Cs = smem;
         const float* tin = (EPI == 2) ? Tio : Tl;
 #pragma unroll
@@ -251,10 +275,13 @@ __global__ __launch_bounds__(256) void gemm_nn_gradz_kernel(const float* __restr
                                                             float* __restrict__ out, int64_t n, int K1, int K2, int C,
                                                             float nu) {
     constexpr int BN = 32;
-    constexpr int LDA = BK + 1;
+    // 32 columns of Z_l and T_l per step: every row then gives a whole 128-byte line of each matrix to one step.
+    // With half lines the second half had left the L2 before its step came (twice the traffic, measured).
+    constexpr int GBK = 32;
+    constexpr int LDA = GBK + 1;
     constexpr int LDB = BN + 4;
     __shared__ __align__(16) float As[BM * LDA];
-    __shared__ __align__(16) float Bs[BK * LDB];
+    __shared__ __align__(16) float Bs[GBK * LDB];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wm = tid >> 6;
@@ -264,12 +291,12 @@ __global__ __launch_bounds__(256) void gemm_nn_gradz_kernel(const float* __restr
     floatx16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    float4 ra[2], rb;
+    float4 ra[4], rb;
     auto fetch = [&](int k0) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < 4; ++i) {
             const int f = tid + 256 * i;
-            const int row = f >> 2, kq = f & 3;
+            const int row = f >> 3, kq = f & 7;
             const int64_t gr = m0 + row;
             const int k = k0 + 4 * kq;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -287,35 +314,35 @@ __global__ __launch_bounds__(256) void gemm_nn_gradz_kernel(const float* __restr
             }
             ra[i] = v;
         }
-        if (tid < BK * BN / 4) {
-            const int kr = tid / (BN / 4), cq = tid % (BN / 4);
+        {
+            const int kr = tid / (BN / 4), cq = tid % (BN / 4);      // 32 x 8 float4, one per thread
             const int k = k0 + kr, c = 4 * cq;
             rb = ld4_guard(Bcat, (int64_t)k * C + c, k < K, b_al, C - c);
         }
     };
     auto stash = [&]() {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < 4; ++i) {
             const int f = tid + 256 * i;
-            const int row = f >> 2, kq = f & 3;
+            const int row = f >> 3, kq = f & 7;
             float* d = As + row * LDA + 4 * kq;
             d[0] = ra[i].x; d[1] = ra[i].y; d[2] = ra[i].z; d[3] = ra[i].w;
         }
-        if (tid < BK * BN / 4) {
+        {
             const int kr = tid / (BN / 4), cq = tid % (BN / 4);
             *reinterpret_cast<float4*>(Bs + kr * LDB + 4 * cq) = rb;
         }
     };
-    const int nk = (K + BK - 1) / BK;
+    const int nk = (K + GBK - 1) / GBK;
     const int li = lane & 31, lk = lane >> 5;
     fetch(0);
     for (int kt = 0; kt < nk; ++kt) {
         __syncthreads();
         stash();
         __syncthreads();
-        if (kt + 1 < nk) fetch((kt + 1) * BK);
+        if (kt + 1 < nk) fetch((kt + 1) * GBK);
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 2) {
+        for (int kk = 0; kk < GBK; kk += 2) {
             const float a = As[(wm * 32 + li) * LDA + kk + lk];
             const float b = Bs[(kk + lk) * LDB + li];
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
@@ -357,8 +384,9 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ 
     const int wm = wave / WN, wn = wave % WN;
     const int ktiles = (K + BM - 1) / BM;
     const int ctiles = (C + BN - 1) / BN;
-    const int tile = blockIdx.x % (ktiles * ctiles);
-    const int64_t chunk = blockIdx.x / (ktiles * ctiles);
+    int tile;
+    int64_t chunk;
+    xcd_group(blockIdx.x, gridDim.x, (unsigned)(ktiles * ctiles), chunk, tile);
     const int k0 = (tile / ctiles) * BM;
     const int c0 = (tile % ctiles) * BN;
     const int64_t r_begin = chunk * rows_per_chunk;
