@@ -26,14 +26,22 @@ MFMA_FP32_PEAK_TFLOPS = 157.3
 # algorithmic byte over the timed region) is above the machine balance, else against HBM bandwidth.
 MACHINE_BALANCE = MFMA_FP32_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)      # flop per byte
 
-# Bytes per launch that crossed the L2 -> fabric boundary (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of
-# known size), measured once with rocprofv3 --pmc on the single kernels of the default workload at full size;
-# the summary with the commands is profiles/kernel_memory_traffic_powerlaw_dcsbm_2M.txt.
+# Bytes per launch group that crossed the L2 -> fabric boundary (FETCH_SIZE + WRITE_SIZE, each scaled by what a plain
+# copy of known size reads), measured with rocprofv3 --pmc on this program at the default workload (steady-state
+# sweeps); the summary with the commands is profiles/sweep_memory_traffic_powerlaw_dcsbm_2M.txt.
 MEASURED_TRAFFIC = {
-    (4, "gemm_nn_kernel<128,0>"): 2.238e9 + 2.048e9,          # out[N x 256] = A[N x 128] B
-    (4, "spmm_rows_kernel[rows]"): 3.333e9 + 0.129e9,         # width 16
-    (4, "spmm_rows_kernel[segments]"): 5.299e9 + 0.659e9,     # width 16
-    (4, "gemm_nn_kernel<32>"): 2.629e9 + 0.128e9,             # out[N x 16] = A[N x 256] B
+    (4, "gemm_nn_kernel<128,2>+finish"): 5.19e9 + 4.10e9,     # Q = H_1 gradW_1, first candidate, speculative step on T_1
+    (4, "spmm_rows_kernel[rows]"): 3.454e9 + 0.129e9,         # width 16
+    (4, "spmm_rows_kernel[segments]"): 5.277e9 + 0.659e9,     # width 16
+    (4, "gemm_tn_kernel<128>+reduce"): 5.43e9 + 0.038e9 + 0.067e9,
+    (4, "z_trial_kernel"): 6.126e9 + 0.006e9,
+    (4, "z_step_kernel"): 4.297e9 + 2.048e9,
+    (4, "gemm_nn_gradz_kernel"): 4.226e9 + 0.128e9,
+    (4, "t_carry_kernel"): 1.296e9 + 0.128e9,
+    (4, "gemm_nn_kernel<32>"): 2.049e9 + 0.128e9,             # out[N x 16] = A[N x 256] B
+    (4, "gemm_tn_kernel<32>+reduce"): 2.188e9 + 0.008e9,
+    (4, "last_layer_kernel"): 0.392e9 + 0.256e9,
+    (4, "gemm_nn_kernel<128,0>"): 1.114e9 + 2.048e9,          # out[N x 256] = A[N x 128] B
 }
 
 # CPU-oracle sample: (scale of N, iterations) per workload, sized for about 10-30 s of host time
