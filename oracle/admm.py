@@ -30,7 +30,12 @@ only oracle <-> GPU agreement and the invariants in the tests hold them):
   * dual step with the superscripts as printed (Eq. 2): Z_L^k and p^k (p uses W^{k+1}); dual_form = 1
     selects the usual ADMM dual ascent on the new iterates (Z_L^{k+1}, Z_{L-1}^{k+1}, W_L^{k+1}) instead;
   * updates are Jacobi: W^{k+1} from (W^k, Z^k, U^k); every Z^{k+1}_{l,m} from
-    (W^{k+1}, Z^k, U^k).
+    (W^{k+1}, Z^k, U^k)  (schedule 0, Algorithm 1 as printed);
+  * schedule 1 is the serial baseline of Section 4.1 ("layers trained sequentially"), read as a
+    Gauss-Seidel pass over the layers: for l = 1..L first W_l, then Z_l (all communities of the layer
+    together), each from the newest values of everything else, i.e. W_l from (Z_{l-1}^{k+1}, Z_l^k),
+    Z_l from (W_l^{k+1}, Z_{l-1}^{k+1}, W_{l+1}^k, Z_{l+1}^k); the dual step closes the pass and
+    follows dual_form, where "Z_{L-1}^k" of form 0 is the Z_{L-1} the last-layer update saw.
 """
 from __future__ import annotations
 
@@ -97,7 +102,7 @@ class AdmmOracle:
     STEP_FLOOR = 1e-12
 
     def __init__(self, graph: OracleGraph, dims, *, nu, rho, tau0, theta0, eta, max_backtrack,
-                 fista_iters, risk=0, dual_form=0):
+                 fista_iters, risk=0, dual_form=0, schedule=0):
         self.g = graph
         self.M = graph.M
         self.N = graph.N
@@ -116,6 +121,10 @@ class AdmmOracle:
         self.dual_form = int(dual_form)
         if self.dual_form not in (0, 1):
             raise ValueError("dual_form must be 0 (Eq. 2 as printed) or 1 (new iterates)")
+        self.schedule = int(schedule)
+        if self.schedule not in (0, 1):
+            raise ValueError("schedule must be 0 (Algorithm 1) or 1 (layer by layer)")
+        self.block_trace = None       # a list here receives (name, l, L_rho) after every primal block update of schedule 1
         self.k = 0
         self.status = 0
         self.trials_W = [0] * (self.L + 1)
@@ -347,7 +356,46 @@ class AdmmOracle:
     # ------------------------------------------------------------------ one iteration of Algorithm 1
     def iterate(self, k=1):
         for _ in range(k):
-            self._sweep()
+            if self.schedule == 0:
+                self._sweep()
+            else:
+                self._sweep_layer_by_layer()
+
+    def _sweep_layer_by_layer(self):
+        """Serial baseline (Section 4.1): one pass over the layers, W_l then Z_l, newest values everywhere."""
+        L, M = self.L, self.M
+        W, Z, U = list(self.W), list(self.Z), self.U
+        T_seen = None
+        for l in range(1, L + 1):
+            W[l] = self.update_W(l, W, Z, U)
+            self._trace("W", l, W, Z, U)
+            p_prev = self.first_order(l - 1, Z[l - 1], W[l])
+            Znew = np.empty_like(Z[l])
+            if l < L:
+                p_cur = self.first_order(l, Z[l], W[l + 1])
+                s_cur = self.second_order(l, p_cur, Z[l + 1], U)
+                for m in range(M):
+                    Znew[self.g.rows(m)] = self.update_Z_hidden(l, m, Z, W, U, p_prev, p_cur, s_cur)
+            else:
+                T_seen = np.vstack([sum(p_prev[(r, m)] for r in self.g.nbr_and_self(m)) for m in range(M)])
+                for m in range(M):
+                    Znew[self.g.rows(m)] = self.update_Z_last(m, Z, U, p_prev)
+            Z_L_old = Z[L]
+            Z[l] = Znew
+            self._trace("Z", l, W, Z, U)
+        if self.dual_form == 0:
+            Un = U + self.rho * (Z_L_old - T_seen)
+        else:
+            Un = U + self.rho * (Z[L] - T_seen)     # Z_{L-1}, W_L did not change after the last-layer update
+        self.TL_prev = np.vstack([self.g.aggregate_block(m, self.Z[L - 1]) @ self.W[L] for m in range(M)])
+        self.W, self.Z, self.U = W, Z, Un
+        self.k += 1
+        if not all(np.all(np.isfinite(a)) for a in self.W[1:] + self.Z[1:] + [self.U]):
+            self.status |= self.STATUS_NONFINITE
+
+    def _trace(self, name, l, W, Z, U):
+        if self.block_trace is not None:
+            self.block_trace.append((name, l, self.stats_full_graph(W, Z, U)["lagrangian"]))
 
     def _sweep(self):
         L, M = self.L, self.M
@@ -486,7 +534,7 @@ def make_oracle(w, iters=None):
     h = w.hyper
     o = AdmmOracle(g, w.dims, nu=h["nu"], rho=h["rho"], tau0=h["tau0"], theta0=h["theta0"], eta=h["eta"],
                    max_backtrack=h["max_backtrack"], fista_iters=h["fista_iters"], risk=h["risk"],
-                   dual_form=h["dual_form"])
+                   dual_form=h["dual_form"], schedule=h.get("schedule", 0))
     o.set_data(w.X, w.labels)
     o.init(w.W0)
     return o

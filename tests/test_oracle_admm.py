@@ -448,3 +448,66 @@ def test_empty_graph_reduces_to_a_plain_multilayer_perceptron_penalty():
     o.Z[1] = rng.standard_normal((N, 4))
     assert o.phi(1, o.W[1], o.Z[0], o.Z[1]) == pytest.approx(
         0.5 * o.nu * np.sum((o.Z[1] - relu(o.Z[0] @ o.W[1])) ** 2), rel=1e-13)
+
+
+# ---------------------------------------------------------------- serial baseline: layer by layer (Section 4.1)
+def test_layer_by_layer_pass_descends_the_lagrangian_at_every_W_and_hidden_Z_block():
+    # one community: every block update is then an exact Gauss-Seidel step on Eq. 1, and backtracking on a
+    # majorising model cannot increase it (the FISTA block carries momentum and is not checked)
+    o, _ = tiny_problem(31, M=1, hyper=dict(schedule=1))
+    for _ in range(3):
+        before = dense_lagrangian(o, o.W, o.Z, o.U)
+        o.block_trace = []
+        o.iterate(1)
+        assert [(n, l) for n, l, _ in o.block_trace] == [("W", 1), ("Z", 1), ("W", 2), ("Z", 2), ("W", 3), ("Z", 3)]
+        prev = before
+        for name, l, val in o.block_trace:
+            if not (name == "Z" and l == o.L):
+                assert val <= prev + 1e-10 * abs(prev), (name, l, val, prev)
+            prev = val
+        assert o.block_trace[-2][2] < before - 1e-6 * abs(before)      # and the pass does move
+    assert o.status == 0
+
+
+def test_layer_by_layer_feeds_each_block_the_newest_values():
+    o, _ = tiny_problem(32, hyper=dict(schedule=1))
+    j, _ = tiny_problem(32)                          # Algorithm 1 from the same point
+    A = o.g.A.toarray()
+    W_old = [None] + [w.copy() for w in o.W[1:]]
+    Z_old = [z.copy() for z in o.Z]
+    U_old = o.U.copy()
+    o.iterate(1)
+    j.iterate(1)
+    # the first block sees the same inputs in both schedules
+    np.testing.assert_array_equal(o.W[1], j.W[1])
+    # W_2 is a gradient step of phi_2 taken at Z_1^{k+1}: rebuild it densely with the accepted tau_2
+    H = A @ o.Z[1]
+    T = H @ W_old[2]
+    G = o.nu * (np.maximum(T, 0.0) - Z_old[2]) * (T > 0)
+    np.testing.assert_allclose(o.W[2], W_old[2] - (H.T @ G) / o.tau[2], rtol=1e-11, atol=1e-13)
+    assert np.abs(o.W[2] - j.W[2]).max() > 1e-6       # Algorithm 1 took it at Z_1^k
+    # Z_2 saw W_2^{k+1}, Z_1^{k+1} (through T_2) and the old W_3, Z_3
+    for m in range(o.M):
+        rows = o.g.rows(m)
+        def psi_dense(Zm):
+            Z2 = Z_old[2].copy()
+            Z2[rows] = Zm
+            own = 0.5 * o.nu * np.sum((Zm - np.maximum(A[rows] @ o.Z[1] @ o.W[2], 0.0)) ** 2)
+            r = Z_old[3] - A @ Z2 @ W_old[3]          # rows not adjacent to V_m only add a constant
+            return own + np.sum(U_old * r) + 0.5 * o.rho * np.sum(r * r)
+        eps = 1e-6
+        rng = np.random.default_rng(5 + m)
+        D = rng.standard_normal(Z_old[2][rows].shape)
+        g_fd = (psi_dense(Z_old[2][rows] + eps * D) - psi_dense(Z_old[2][rows] - eps * D)) / (2 * eps)
+        step = (Z_old[2][rows] - o.Z[2][rows]) * o.theta[2][m]          # = grad psi at the old block
+        assert np.sum(step * D) == pytest.approx(g_fd, rel=1e-5, abs=1e-8)
+    # dual step of form 0: Z_L^k and the T_L the last-layer update saw
+    np.testing.assert_allclose(o.U - U_old, o.rho * (Z_old[3] - A @ o.Z[2] @ o.W[3]), rtol=1e-10, atol=1e-12)
+
+
+def test_layer_by_layer_with_dual_form_1_uses_the_new_last_layer():
+    o, _ = tiny_problem(33, hyper=dict(schedule=1, dual_form=1))
+    A = o.g.A.toarray()
+    U_old = o.U.copy()
+    o.iterate(1)
+    np.testing.assert_allclose(o.U - U_old, o.rho * (o.Z[3] - A @ o.Z[2] @ o.W[3]), rtol=1e-10, atol=1e-12)
