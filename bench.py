@@ -45,7 +45,7 @@ MEASURED_TRAFFIC = {
 }
 
 # CPU-oracle sample: (scale of N, iterations) per workload, sized for about 10-30 s of host time
-ORACLE_SAMPLE = {1: (1.0, 10), 2: (0.25, 4), 3: (0.02, 3), 4: (0.004, 3), 5: (0.004, 2)}
+ORACLE_SAMPLE = {1: (1.0, 10), 2: (0.25, 4), 3: (0.02, 3), 4: (0.004, 3), 5: (0.004, 2), 6: (0.1, 3), 7: (0.2, 3)}
 
 
 def roofline_entry(name, p):
@@ -63,13 +63,14 @@ def roofline_entry(name, p):
                 traffic=None, avg_launch_ms=per_launch_ms, launches=p["records"], share_of_step=None)
 
 
-def cpu_baseline(index, full_N, full_nnz):
+def cpu_baseline(index, full_N, full_nnz, communities=None, schedule=0):
     """The oracle as it stands, on a smaller instance of the same recipe, extrapolated linearly in nnz."""
     from threadpoolctl import threadpool_info
     from oracle.admm import make_oracle
     from paper_2112_09335_amd import synth
     scale, iters = ORACLE_SAMPLE[index]
-    w = synth.config(index, scale)
+    w = synth.config(index, scale, communities)
+    w.hyper["schedule"] = schedule
     orc = make_oracle(w)
     orc.iterate(1)                       # first iteration is atypical (zero gradients at the forward-pass start)
     t0 = time.perf_counter()
@@ -92,7 +93,10 @@ def main():
     # timed region holds its share of them
     ap.add_argument("--steps", type=int, default=32)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", type=int, default=4, help="benchmark configuration 1..5 (synth.config)")
+    ap.add_argument("--workload", type=int, default=4, help="benchmark configuration 1..5; 6, 7: shapes of the "
+                    "paper's speed-up experiment (synth.config)")
+    ap.add_argument("--communities", type=int, default=None, help="override the number of communities M")
+    ap.add_argument("--schedule", type=int, default=0, help="0 = Algorithm 1, 1 = layer by layer (serial baseline)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink N (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -105,7 +109,8 @@ def main():
     from paper_2112_09335_amd import binding, synth
 
     t0 = time.perf_counter()
-    w = synth.config(args.workload, args.scale)
+    w = synth.config(args.workload, args.scale, args.communities)
+    w.hyper["schedule"] = args.schedule
     t_gen = time.perf_counter() - t0
     t0 = time.perf_counter()
     solver = binding.Solver.from_workload(w, 0)
@@ -163,7 +168,8 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"configs[{args.workload - 1}] {w.name}", "N": w.N, "communities": w.M,
-                   "edges": w.E, "nnz": nnz, "layers": w.L, "widths": w.dims, "scale": args.scale},
+                   "edges": w.E, "nnz": nnz, "layers": w.L, "widths": w.dims, "scale": args.scale,
+                   "schedule": args.schedule},
         "roofline": None if dominant is None else {k: dominant[k] for k in
                                                    ("bound", "achieved", "peak", "unit", "frac", "traffic")},
         "dominant_kernel": None if dominant is None else dominant["kernel"],
@@ -180,7 +186,7 @@ def main():
         "objective": stats["objective"], "primal_res": stats["primal_res"], "status": stats["status"],
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.workload, w.N, nnz)
+        out["cpu_baseline"] = cpu_baseline(args.workload, w.N, nnz, args.communities, args.schedule)
     print(json.dumps(out))
 
 

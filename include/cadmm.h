@@ -97,6 +97,9 @@ int  cadmm_get_segment_order(cadmm_ctx* ctx, int64_t* order /* host [n_segments]
  *   last-layer solver (Appendix A, Eq. 5); dual_form: 0 = dual step with the superscripts as
  *   printed in Eq. 2 (Z_L^k, W_L^{k+1}); 1 = dual ascent on the new iterates,
  *   U^{k+1} = U^k + rho (Z_L^{k+1} - A~ Z_{L-1}^{k+1} W_L^{k+1}).
+ *   schedule: 0 = Algorithm 1 (every W_l, then every Z_{l,m}, all from the values of iteration k);
+ *   1 = the serial baseline of Section 4.1, layers one after the other: for l = 1..L first W_l, then
+ *   Z_l (its communities together), each from the newest values of everything else.
  */
 typedef struct {
     int32_t L;
@@ -104,6 +107,7 @@ typedef struct {
     int32_t risk;
     float nu, rho, tau0, theta0, eta;
     int32_t max_backtrack, fista_iters, dual_form;
+    int32_t schedule;
 } cadmm_model;
 int  cadmm_set_model(cadmm_ctx* ctx, const cadmm_model* model);
 

@@ -28,7 +28,7 @@ struct cadmm_ctx {
     // (A~ Z_{l-1}) W_l.  Its W-update then needs three aggregations of width C_l, so it pays if
     // 3 C_l < C_{l-1}.  In those layers the slot H[l] holds A~ G_l (N x C_l).
     std::vector<char> agg_first;
-    int risk = 0, max_bt = 60, J = 10, dual_form = 0;
+    int risk = 0, max_bt = 60, J = 10, dual_form = 0, schedule = 0;
     bool u_pending = false;      // dual_form 1: the dual step of the last sweep is still to be applied
     float nu = 0, rho = 0, tau0 = 0, theta0 = 0, eta = 2;
     // workspace
@@ -326,9 +326,9 @@ bool t1_reusable(const cadmm_ctx* c) { return c->t1_age >= 0 && c->t1_age < c->t
 
 // T_l = A~ Z_{l-1} W_l in the association chosen for the layer.  Used by the initial forward pass and
 // by every base evaluation, so that re-evaluating an unchanged point reproduces T_l bit for bit.
-void compute_T(cadmm_ctx* c, int l) {
+void compute_T(cadmm_ctx* c, int l, bool force = false) {
     const int64_t N = c->hg.N;
-    const bool carried = t1_reusable(c);               // T[l] already holds A~ Z_{l-1} W_l for the current state
+    const bool carried = !force && t1_reusable(c);     // T[l] already holds A~ Z_{l-1} W_l for the current state
     if (c->agg_first[l]) {
         if (carried) return;
         gemm_nn(c, c->Z[l - 1], c->W[l], c->tmpV, N, c->C[l - 1], c->C[l]);
@@ -386,17 +386,15 @@ void carry_T(cadmm_ctx* c, int l) {
     });
 }
 
-void sweep(cadmm_ctx* c) {
+// W_l <- W_l - grad phi_l / tau_l with backtracking on tau_l (Section 3.1), from the T_l, H_l (or Z_{l-1}) and G_l
+// in memory; leaves T_l = A~ Z_{l-1} W_l^{new}.
+void w_update(cadmm_ctx* c, int l) {
     const int L = c->L;
     const int64_t N = c->hg.N;
-    const int M = c->hg.M;
     hipStream_t s = c->stream;
     const SearchParams sp = search_params(c);
     const int more_passes = (c->max_bt + kMaxCand - 1) / kMaxCand;
-    base_eval(c, false);
-
-    // ---- W-update, every layer from (W^k, Z^k, U^k)   (Section 3.1)
-    for (int l = 1; l <= L; ++l) {
+    {
         const int K = c->C[l - 1], Cl = c->C[l];
         const int64_t count = N * Cl;
         const int last = (l == L);
@@ -447,13 +445,19 @@ void sweep(cadmm_ctx* c) {
             // W^{k+1}; T_l = A~ Z^k W^{k+1}
             launch_w_step(s, c->W[l], c->gradW, K * Cl, c->T[l], Q, count, unit, spec ? 1 : 0);
         });
-
     }
+}
 
-    // ---- Z-update, hidden layers, every community from (W^{k+1}, Z^k, U^k)   (Appendix A, Eqs. 3, 4, 6-8)
-    // Ascending l keeps the update Jacobi although Z_l is overwritten in place: layer l reads Z_{l+1}^k
-    // (not yet touched) and T_l, T_{l+1}, which were formed from Z^k before any Z changed.
-    for (int l = 1; l <= L - 1; ++l) {
+// Z_{l,m} <- Z_{l,m} - grad psi_{l,m} / theta_{l,m} for every community of hidden layer l (Appendix A, Eqs. 3, 4, 6-8),
+// from T_l, T_{l+1}, Z_{l+1}, U, W_{l+1} in memory.  Leaves the segment products in Pbuf[l & 1].
+void z_update_hidden(cadmm_ctx* c, int l) {
+    const int L = c->L;
+    const int64_t N = c->hg.N;
+    const int M = c->hg.M;
+    hipStream_t s = c->stream;
+    const SearchParams sp = search_params(c);
+    const int more_passes = (c->max_bt + kMaxCand - 1) / kMaxCand;
+    {
         const int Cl = c->C[l], Cn = c->C[l + 1];
         const int next_last = (l + 1 == L);
         Unit* units = c->unitsZ + (size_t)(l - 1) * M;
@@ -523,15 +527,57 @@ void sweep(cadmm_ctx* c) {
             else
                 launch_z_step(s, c->Z[l], c->tmpB, c->d_row_comm, N, Cl, units);
         });
+    }
+}
+
+// last layer Z_L (Eq. 5) and, for dual_form 0, the dual step (Eq. 2), both from Z_L^k, U^k and the T_L in memory
+void last_layer_update(cadmm_ctx* c) {
+    const int L = c->L;
+    const int64_t N = c->hg.N;
+    timed(c, P_LAST_LAYER, 4.0 * (5.0 * (double)N * c->C[L] + (double)N), 0.0, [&] {
+        launch_last_layer(c->stream, c->Z[L], c->U, c->T[L], c->d_labels, N, c->C[L], c->risk, c->rho, c->J,
+                          c->dual_form == 0 ? 1 : 0);
+    });
+}
+
+// Serial baseline of Section 4.1 read as a Gauss-Seidel pass: for l = 1..L first W_l, then Z_l, each from the newest
+// values.  T_l is formed anew once Z_{l-1} has changed; T_{l+1} = A~ Z_l^k W_{l+1}^k comes from the base evaluation.
+void sweep_layer_by_layer(cadmm_ctx* c) {
+    const int L = c->L;
+    const int64_t N = c->hg.N;
+    base_eval(c, false);
+    for (int l = 1; l <= L; ++l) {
+        if (l >= 2) {
+            compute_T(c, l, true);
+            if (!gradient_on_the_fly(c, l))
+                timed(c, P_G_ONLY, 4.0 * (double)N * c->C[l] * (l == L ? 4 : 3), 0.0, [&] {
+                    launch_G_only(c->stream, c->T[l], c->Z[l], c->U, c->G[l], N * c->C[l], l == L, c->nu, c->rho);
+                });
+        }
+        w_update(c, l);
+        if (l < L) z_update_hidden(c, l);
+        else last_layer_update(c);
+    }
+    if (c->t1_age >= 0) c->t1_age++;
+    if (c->dual_form == 1) c->u_pending = true;
+    c->iter++;
+    c->base_valid = false;
+}
+
+// Algorithm 1: every W_l from (W^k, Z^k, U^k), then every Z_{l,m} from (W^{k+1}, Z^k, U^k), then U.
+void sweep(cadmm_ctx* c) {
+    if (c->schedule == 1) { sweep_layer_by_layer(c); return; }
+    const int L = c->L;
+    base_eval(c, false);
+    for (int l = 1; l <= L; ++l) w_update(c, l);
+    // Ascending l keeps the Z update Jacobi although Z_l is overwritten in place: layer l reads Z_{l+1}^k
+    // (not yet touched) and T_l, T_{l+1}, which were formed from Z^k before any Z changed.
+    for (int l = 1; l <= L - 1; ++l) {
+        z_update_hidden(c, l);
         // T_l is not read again in this sweep: bring it to the new Z_{l-1} (P and theta of layer l-1)
         if (l >= 2) carry_T(c, l);
     }
-
-    // ---- last layer Z_L (Eq. 5) and the dual step (Eq. 2), both from Z_L^k, U^k and T_L = A~ Z_{L-1}^k W_L^{k+1}
-    timed(c, P_LAST_LAYER, 4.0 * (5.0 * (double)N * c->C[L] + (double)N), 0.0, [&] {
-        launch_last_layer(s, c->Z[L], c->U, c->T[L], c->d_labels, N, c->C[L], c->risk, c->rho, c->J,
-                          c->dual_form == 0 ? 1 : 0);
-    });
+    last_layer_update(c);
     carry_T(c, L);
     if (c->t1_age >= 0) c->t1_age++;
     if (c->dual_form == 1) c->u_pending = true;      // applied by the next base evaluation, on the new iterates
@@ -651,6 +697,7 @@ int cadmm_set_model(cadmm_ctx* c, const cadmm_model* m) {
     if (m->max_backtrack < 0 || m->max_backtrack > 64) return fail(c, CADMM_EINVAL, "max_backtrack must be in [0, 64]");
     if (m->fista_iters < 0) return fail(c, CADMM_EINVAL, "fista_iters must be non-negative");
     if (m->dual_form != 0 && m->dual_form != 1) return fail(c, CADMM_EINVAL, "dual_form must be 0 or 1");
+    if (m->schedule != 0 && m->schedule != 1) return fail(c, CADMM_EINVAL, "schedule must be 0 or 1");
     c->L = m->L;
     c->C.assign(m->C, m->C + m->L + 1);
     c->risk = m->risk;
@@ -658,6 +705,7 @@ int cadmm_set_model(cadmm_ctx* c, const cadmm_model* m) {
     c->max_bt = m->max_backtrack;
     c->J = m->fista_iters;
     c->dual_form = m->dual_form;
+    c->schedule = m->schedule;
     c->agg_first.assign(c->L + 1, 0);
     for (int l = 2; l <= c->L; ++l) c->agg_first[l] = (3 * c->C[l] < c->C[l - 1]) ? 1 : 0;
     c->has_model = true;

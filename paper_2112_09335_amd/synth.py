@@ -45,7 +45,7 @@ class Workload:
 
 
 DEFAULT_HYPER = dict(nu=1e-3, rho=1e-3, tau0=1e-3, theta0=1e-3, eta=2.0,
-                     max_backtrack=60, fista_iters=10, risk=0, dual_form=0)
+                     max_backtrack=60, fista_iters=10, risk=0, dual_form=0, schedule=0)
 
 
 def _dedup_pairs(a: np.ndarray, b: np.ndarray, N: int):
@@ -195,7 +195,7 @@ def make_workload(name, seed, N, M, dims, n_classes, iters, *, graph, features,
     return Workload(name, N, M, src, dst, comm, X, labels, list(dims), W0, iters, h)
 
 
-# The five benchmark configurations (index = seed).  `scale` shrinks N (and keeps degree,
+# The five benchmark configurations (index = seed), and two more for the serial-versus-community comparison.  `scale` shrinks N (and keeps degree,
 # community count, widths) for CPU-sized samples of the same recipe.
 def config(index: int, scale: float = 1.0, M: Optional[int] = None) -> Workload:
     def n(v):
@@ -216,4 +216,14 @@ def config(index: int, scale: float = 1.0, M: Optional[int] = None) -> Workload:
     if index == 5:
         return make_workload("deep_wide_sbm", 5, n(500000), M or 16, [512] * 8 + [10], 10, 10, graph="sbm",
                              features="gaussian", avg_degree=12, frac_intra=0.85)
-    raise ValueError("config index must be 1..5")
+    # Shapes of the two graphs of the paper's speed-up experiment (Section 4.1, Tables 2 and 3: node, feature and
+    # class counts as printed; two layers with 1000 hidden units; 3 communities).  The paper prints no edge counts:
+    # the average degree is an assumption of this recipe, and the graphs are SBM stand-ins, not the datasets.
+    if index == 6:
+        return make_workload("computers_shape_sbm", 6, n(13752), M or 3, [767, 1000, 10], 10, 50, graph="sbm",
+                             features="bernoulli", avg_degree=36, frac_intra=0.90)
+    if index == 7:
+        return make_workload("photo_shape_sbm", 7, n(7650), M or 3, [745, 1000, 8], 8, 50, graph="sbm",
+                             features="bernoulli", avg_degree=31, frac_intra=0.90,
+                             hyper=dict(nu=1e-4, rho=1e-4))
+    raise ValueError("config index must be 1..7")

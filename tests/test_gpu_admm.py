@@ -187,3 +187,21 @@ def test_low_rank_gradient_path_and_its_stored_twin():
     assert np.array_equal(ta[0], tb[0]) and np.array_equal(ta[1], tb[1]) and np.array_equal(ta[2], tb[2])
     a.close()
     b.close()
+
+
+def test_layer_by_layer_schedule_matches_the_oracle():
+    """Serial baseline of Section 4.1 (schedule 1): W_l then Z_l, layer after layer, newest values everywhere."""
+    w = synth.config(1, 0.5)
+    w.hyper["schedule"] = 1
+    run_case(w, 8, "layer-by-layer/config1")
+    w = synth.config(3, 0.01)                       # three layers: both kinds of hidden Z update
+    w.hyper["schedule"] = 1
+    run_case(w, 6, "layer-by-layer/config3")
+    w = synth.config(4, 0.002)                      # narrow-side association, low-rank gradient, hub rows
+    w.hyper["schedule"] = 1
+    w.hyper["dual_form"] = 1
+    run_case(w, 6, "layer-by-layer/config4/dual-form-1")
+    w = synth.make_workload("serial", 14, 900, 1, [24, 40, 12, 5], 5, 5, graph="sbm", features="gaussian",
+                            avg_degree=8, frac_intra=1.0)
+    w.hyper["schedule"] = 1                         # the paper's serial run: one community
+    run_case(w, 6, "layer-by-layer/one-community")
