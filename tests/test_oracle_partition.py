@@ -60,23 +60,64 @@ def test_cap_formula_and_participation_rule():
 
 
 def test_one_round_by_hand_on_a_path():
-    # path 0-1-2-3, every node its own label, cap 2.  Whoever takes part asks for the smaller neighbour label
-    # (every neighbour label occurs once, its own label never); requests are granted in node order while the
-    # target had room at the start of the round (cap - 1 = 1 each).
-    nb = [[1], [0, 2], [1, 3], [2]]
+    # path 0-1-2-3, unit weights, every node its own label, cap 2.  Whoever takes part asks for the smaller
+    # neighbour label (every neighbour label pulls with weight 1, its own label with 0); requests are granted in
+    # node order while the target had room at the start of the round (cap - 1 = 1 each).
+    nb = [{1: 1}, {0: 1, 2: 1}, {1: 1, 3: 1}, {2: 1}]
     label, size = [0, 1, 2, 3], {0: 1, 1: 1, 2: 1, 3: 1}
     r = 0
-    moved = propagation_round(nb, label, size, 2, r)
+    moved = propagation_round(nb, [1, 1, 1, 1], label, size, 2, r)
     expect = [0, 1, 2, 3]
     room = {c: 1 for c in range(4)}
     for v in range(4):
         if takes_part(v, r):
-            want = min(u for u in nb[v])               # neighbour labels are the neighbour ids here
+            want = min(nb[v])                          # neighbour labels are the neighbour ids here
             if room[want] > 0:
                 room[want] -= 1
                 expect[v] = want
     assert label == expect and moved == sum(1 for v in range(4) if expect[v] != v)
     assert sorted(size.items()) == sorted((c, expect.count(c)) for c in range(4))
+
+
+def test_one_weighted_round_by_hand():
+    # star: centre 0 (label 9, weight 1) with four leaves of weights 5, 2, 4, 1 (in node order), each labelled by its own
+    # number and pulled towards label 9 only.  cap 8: the room of label 9 is 8 - 1 = 7.  In node order: the first
+    # leaf (5) fits -> room 2, the second (2) fits -> room 0, the third (4) and the fourth (1) do not.
+    r = 2
+    assert not takes_part(0, r)
+    leaves = [v for v in range(1, 40) if takes_part(v, r)][:4]
+    n = leaves[-1] + 1
+    pulls = dict(zip(leaves, (3, 1, 1, 1)))
+    nb = [dict() for _ in range(n)]
+    for v, w in pulls.items():
+        nb[0][v] = w
+        nb[v][0] = w
+    weight = [1] * n
+    for v, w in zip(leaves, (5, 2, 4, 1)):
+        weight[v] = w
+    label = list(range(n))
+    label[0] = 9 + n
+    size = {label[v]: weight[v] for v in range(n)}
+    assert propagation_round(nb, weight, label, size, 8, r) == 2
+    assert [label[v] for v in leaves] == [9 + n, 9 + n, leaves[2], leaves[3]] and size[9 + n] == 8
+    assert size[leaves[0]] == 0 and size[leaves[1]] == 0 and size[leaves[2]] == 4 and size[leaves[3]] == 1
+    # the centre, when it takes part, follows the heaviest pull, not the most neighbours
+    r0 = next(r for r in range(100000) if takes_part(0, r) and not any(takes_part(v, r) for v in leaves))
+    a, b = leaves[0], leaves[1]
+    def fresh():
+        lab = list(range(n))
+        lab[0] = 9 + n
+        for v in leaves[1:]:
+            lab[v] = b                                      # three leaves share label b: pull 1 + 1 + 1 = 3
+        return lab, {9 + n: 1, a: 5, b: 7}
+    lab, size = fresh()
+    assert propagation_round(nb, weight, lab, size, 8, r0) == 1 and lab[0] == a     # 3 against 3: the smaller label, a
+    nb[0][b] = 2
+    nb[b][0] = 2                                            # now label b pulls with 4, but 1 + 7 fits cap 8 exactly
+    lab, size = fresh()
+    assert propagation_round(nb, weight, lab, size, 8, r0) == 1 and lab[0] == b and size[b] == 8
+    lab, size = fresh()
+    assert propagation_round(nb, weight, lab, size, 7, r0) == 0                     # and with cap 7 it does not
 
 
 @pytest.mark.parametrize("idx,scale,slack", [(1, 1.0, 1.15), (2, 0.25, 1.15), (3, 0.025, 1.02), (4, 0.0025, 1.10)])
