@@ -97,6 +97,8 @@ def main():
                     "paper's speed-up experiment (synth.config)")
     ap.add_argument("--communities", type=int, default=None, help="override the number of communities M")
     ap.add_argument("--schedule", type=int, default=0, help="0 = Algorithm 1, 1 = layer by layer (serial baseline)")
+    ap.add_argument("--partition", choices=["planted", "builtin"], default="planted",
+                    help="communities: the generator's planted blocks, or the library's own partitioner")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink N (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -112,6 +114,12 @@ def main():
     w = synth.config(args.workload, args.scale, args.communities)
     w.hyper["schedule"] = args.schedule
     t_gen = time.perf_counter() - t0
+    if args.partition == "builtin":
+        t0 = time.perf_counter()
+        host = binding.Solver(device=-1)
+        w.comm = host.partition(w.N, w.src, w.dst, w.M)
+        host.close()
+        print(f"# built-in partitioner: {time.perf_counter() - t0:.2f} s on the host", file=sys.stderr, flush=True)
     t0 = time.perf_counter()
     solver = binding.Solver.from_workload(w, 0)
     torch.cuda.synchronize()
@@ -169,7 +177,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"configs[{args.workload - 1}] {w.name}", "N": w.N, "communities": w.M,
                    "edges": w.E, "nnz": nnz, "layers": w.L, "widths": w.dims, "scale": args.scale,
-                   "schedule": args.schedule},
+                   "schedule": args.schedule, "partition": args.partition},
         "roofline": None if dominant is None else {k: dominant[k] for k in
                                                    ("bound", "achieved", "peak", "unit", "frac", "traffic")},
         "dominant_kernel": None if dominant is None else dominant["kernel"],

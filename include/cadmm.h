@@ -56,6 +56,20 @@ void cadmm_destroy(cadmm_ctx* ctx);
 const char* cadmm_last_error(cadmm_ctx* ctx);
 
 /*
+ * Communities for a graph that comes without them (paper, Section 2: the graph is divided into M
+ * communities; the paper uses METIS there, this is the library's own deterministic stand-in).
+ *   src,dst  host int32[n_edges] as for cadmm_build_graph (repeats, both orientations and self pairs
+ *            are normalised away);  comm  host int32[N], out: community of every node, in [0,M).
+ * Size-capped label propagation from one cluster per node, merging of clusters along the connection
+ * with the most edges until M are left, a few more propagation rounds; every tie is broken by node
+ * or cluster number, so the result depends on the input only.  No community exceeds
+ * ceil(N/M) + floor(N/M)/20 + 1 nodes unless clusters had to be merged regardless of size; some
+ * communities may stay empty.  Host work only: valid on a context created with device = -1.
+ */
+int  cadmm_partition(cadmm_ctx* ctx, int64_t N, int64_t n_edges, const int32_t* src, const int32_t* dst,
+                     int32_t M, int32_t* comm);
+
+/*
  * Graph and communities (paper, Section 2: undirected unweighted graph G(V,E), normalised
  * adjacency A~ = (D+I)^(-1/2)(A+I)(D+I)^(-1/2), partition into M communities V_m, neighbour
  * sets N_m, blocks A~_{m,r}).

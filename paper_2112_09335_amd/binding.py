@@ -23,6 +23,7 @@ EXPORTS = [
     "cadmm_get_Z", "cadmm_get_U", "cadmm_get_steps", "cadmm_set_state", "cadmm_op_aggregate",
     "cadmm_op_aggregate_segments", "cadmm_op_transform", "cadmm_op_wgrad",
     "cadmm_profile", "cadmm_get_profile", "cadmm_profile_class_name", "cadmm_tune", "cadmm_predict",
+    "cadmm_partition",
 ]
 PROFILE_CLASSES = 19
 
@@ -66,6 +67,7 @@ def load_library():
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
     lib.cadmm_create.argtypes = [C.POINTER(vp), C.c_int, vp]
     lib.cadmm_build_graph.argtypes = [vp, i64, i64, vp, vp, i32, vp]
+    lib.cadmm_partition.argtypes = [vp, i64, i64, vp, vp, i32, vp]
     lib.cadmm_graph_sizes.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
     lib.cadmm_get_graph.argtypes = [vp] * 10
     lib.cadmm_get_segment_order.argtypes = [vp, vp]
@@ -150,6 +152,17 @@ class Solver:
             raise CadmmError(f"{what} failed ({rc}): {msg.decode() if msg else ''}")
 
     # ---- graph
+    def partition(self, N, src, dst, M):
+        """Communities for a graph without them: int32 [N] in [0, M) (host work, any context)."""
+        src = np.ascontiguousarray(src, dtype=np.int32)
+        dst = np.ascontiguousarray(dst, dtype=np.int32)
+        if src.shape != dst.shape:
+            raise CadmmError("edge array size mismatch")
+        comm = np.empty(int(N), np.int32)
+        self._check(self.lib.cadmm_partition(self.h, N, src.shape[0], _ptr(src), _ptr(dst), M, _ptr(comm)),
+                    "cadmm_partition")
+        return comm
+
     def build_graph(self, N, src, dst, M, comm=None):
         src = np.ascontiguousarray(src, dtype=np.int32)
         dst = np.ascontiguousarray(dst, dtype=np.int32)

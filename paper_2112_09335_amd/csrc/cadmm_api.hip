@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "host_graph.h"
+#include "host_partition.h"
 #include "kernels.h"
 
 using namespace cadmm;
@@ -645,6 +646,14 @@ void cadmm_destroy(cadmm_ctx* ctx) {
 }
 
 const char* cadmm_last_error(cadmm_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int cadmm_partition(cadmm_ctx* c, int64_t N, int64_t n_edges, const int32_t* src, const int32_t* dst, int32_t M,
+                    int32_t* comm) {
+    if (!c) return CADMM_EINVAL;
+    std::string e = partition_graph(N, n_edges, src, dst, M, comm);
+    if (!e.empty()) return fail(c, CADMM_EINVAL, e);
+    return CADMM_OK;
+}
 
 int cadmm_build_graph(cadmm_ctx* c, int64_t N, int64_t n_edges, const int32_t* src, const int32_t* dst, int32_t M,
                       const int32_t* comm) {
