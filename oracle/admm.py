@@ -16,6 +16,8 @@ only oracle <-> GPU agreement and the invariants in the tests hold them):
   * backtracking: start from the last accepted value (tau0 / theta0 at k = 0), multiply
     by eta until  model >= objective  holds (equality accepts), at most max_backtrack
     multiplications (then the step is taken anyway and a status bit is raised);
+  * step_policy 1 lets the parameters shrink again: a search then starts from (last accepted value) / eta
+    instead of the last accepted value itself (policy 0, the monotone choice above);
   * a step below resolution is not taken: if the first candidate would move the block by
     less than 1e-12 of its own norm, i.e. ||grad||^2 <= (1e-12 * tau)^2 * ||block||^2, the
     block keeps its value and its step parameter and no trial is counted (at the
@@ -102,7 +104,7 @@ class AdmmOracle:
     STEP_FLOOR = 1e-12
 
     def __init__(self, graph: OracleGraph, dims, *, nu, rho, tau0, theta0, eta, max_backtrack,
-                 fista_iters, risk=0, dual_form=0, schedule=0):
+                 fista_iters, risk=0, dual_form=0, schedule=0, step_policy=0):
         self.g = graph
         self.M = graph.M
         self.N = graph.N
@@ -121,6 +123,9 @@ class AdmmOracle:
         self.dual_form = int(dual_form)
         if self.dual_form not in (0, 1):
             raise ValueError("dual_form must be 0 (Eq. 2 as printed) or 1 (new iterates)")
+        self.step_policy = int(step_policy)
+        if self.step_policy not in (0, 1):
+            raise ValueError("step_policy must be 0 (start from the last accepted value) or 1 (from that / eta)")
         self.schedule = int(schedule)
         if self.schedule not in (0, 1):
             raise ValueError("schedule must be 0 (Algorithm 1) or 1 (layer by layer)")
@@ -213,7 +218,7 @@ class AdmmOracle:
         W = Wk[l]
         phi0 = self.phi(l, W, Zk[l - 1], Zk[l], Uk)
         grad = self.grad_phi_W(l, W, Zk[l - 1], Zk[l], Uk)
-        tau = self.tau[l]
+        tau = self.tau[l] / self.eta if self.step_policy == 1 else self.tau[l]
         trials = 0
         if sqnorm(grad) <= (self.STEP_FLOOR * tau) ** 2 * sqnorm(W):
             self.trials_W[l] = 0
@@ -318,7 +323,7 @@ class AdmmOracle:
         args = (Wn[l + 1], Zk[l + 1], Uk, p_prev, p_cur, s_cur)
         psi0 = self.psi(l, m, Z, *args)
         grad = self.grad_psi(l, m, Z, *args)
-        theta = self.theta[l][m]
+        theta = self.theta[l][m] / self.eta if self.step_policy == 1 else self.theta[l][m]
         trials = 0
         if sqnorm(grad) <= (self.STEP_FLOOR * theta) ** 2 * sqnorm(Z):
             self.trials_Z[l][m] = 0
@@ -534,7 +539,7 @@ def make_oracle(w, iters=None):
     h = w.hyper
     o = AdmmOracle(g, w.dims, nu=h["nu"], rho=h["rho"], tau0=h["tau0"], theta0=h["theta0"], eta=h["eta"],
                    max_backtrack=h["max_backtrack"], fista_iters=h["fista_iters"], risk=h["risk"],
-                   dual_form=h["dual_form"], schedule=h.get("schedule", 0))
+                   dual_form=h["dual_form"], schedule=h.get("schedule", 0), step_policy=h.get("step_policy", 0))
     o.set_data(w.X, w.labels)
     o.init(w.W0)
     return o

@@ -511,3 +511,38 @@ def test_layer_by_layer_with_dual_form_1_uses_the_new_last_layer():
     U_old = o.U.copy()
     o.iterate(1)
     np.testing.assert_allclose(o.U - U_old, o.rho * (o.Z[3] - A @ o.Z[2] @ o.W[3]), rtol=1e-10, atol=1e-12)
+
+
+# ---------------------------------------------------------------- step parameters that may shrink again
+def test_step_policy_1_starts_a_search_one_notch_lower_and_still_meets_the_conditions():
+    o, _ = tiny_problem(41, hyper=dict(step_policy=1))
+    m, _ = tiny_problem(41)                                       # monotone policy from the same point
+    for _ in range(6):
+        o.iterate(1)
+        m.iterate(1)
+    assert o.status == 0
+    # the first search of a run starts at tau0 / eta, so an accepted value below tau0 * eta^j of the monotone run shows up
+    taus_o, taus_m = np.array(o.tau[1:]), np.array(m.tau[1:])
+    assert np.all(np.log2(taus_o / o.tau[1]) % 1 == 0)            # still powers of eta apart
+    assert np.any(taus_o < taus_m)                                # some parameter ended lower than the monotone one
+    # an accepted tau satisfies the model condition at the point it was taken from: redo the last W step densely
+    A = o.g.A.toarray()
+    snap = o.snapshot()
+    W_old, Z_old = [None] + [w.copy() for w in o.W[1:]], [z.copy() for z in o.Z]
+    tau_before = list(o.tau)
+    o.iterate(1)
+    l = 1
+    H = A @ Z_old[0]
+    T = H @ W_old[1]
+    G = o.nu * (np.maximum(T, 0.0) - Z_old[1]) * (T > 0)
+    grad = H.T @ G
+    tau = o.tau[1]
+    assert tau >= tau_before[1] / o.eta * (1 - 1e-12)             # never below the first candidate
+    Wn = W_old[1] - grad / tau
+    phi = lambda W: 0.5 * o.nu * np.sum((Z_old[1] - np.maximum(H @ W, 0.0)) ** 2)
+    assert phi(Wn) <= phi(W_old[1]) - np.sum(grad * grad) / (2 * tau) + 1e-12 * abs(phi(W_old[1]))
+    np.testing.assert_allclose(o.W[1], Wn, rtol=1e-11, atol=1e-13)
+    if tau > tau_before[1] / o.eta * (1 + 1e-12):                 # then the candidate before it failed the condition
+        Wp = W_old[1] - grad / (tau / o.eta)
+        assert phi(Wp) > phi(W_old[1]) - np.sum(grad * grad) / (2 * tau / o.eta)
+    o.restore(snap)
