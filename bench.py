@@ -63,7 +63,7 @@ def roofline_entry(name, p):
                 traffic=None, avg_launch_ms=per_launch_ms, launches=p["records"], share_of_step=None)
 
 
-def cpu_baseline(index, full_N, full_nnz, communities=None, schedule=0):
+def cpu_baseline(index, full_N, full_nnz, communities=None, schedule=0, step_policy=0):
     """The oracle as it stands, on a smaller instance of the same recipe, extrapolated linearly in nnz."""
     from threadpoolctl import threadpool_info
     from oracle.admm import make_oracle
@@ -71,6 +71,7 @@ def cpu_baseline(index, full_N, full_nnz, communities=None, schedule=0):
     scale, iters = ORACLE_SAMPLE[index]
     w = synth.config(index, scale, communities)
     w.hyper["schedule"] = schedule
+    w.hyper["step_policy"] = step_policy
     orc = make_oracle(w)
     orc.iterate(1)                       # first iteration is atypical (zero gradients at the forward-pass start)
     t0 = time.perf_counter()
@@ -97,6 +98,8 @@ def main():
                     "paper's speed-up experiment (synth.config)")
     ap.add_argument("--communities", type=int, default=None, help="override the number of communities M")
     ap.add_argument("--schedule", type=int, default=0, help="0 = Algorithm 1, 1 = layer by layer (serial baseline)")
+    ap.add_argument("--step-policy", type=int, default=0, help="0 = step parameters never shrink, 1 = a search "
+                    "starts one notch below the last accepted value")
     ap.add_argument("--partition", choices=["planted", "builtin"], default="planted",
                     help="communities: the generator's planted blocks, or the library's own partitioner")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink N (debugging only)")
@@ -113,6 +116,7 @@ def main():
     t0 = time.perf_counter()
     w = synth.config(args.workload, args.scale, args.communities)
     w.hyper["schedule"] = args.schedule
+    w.hyper["step_policy"] = args.step_policy
     t_gen = time.perf_counter() - t0
     if args.partition == "builtin":
         t0 = time.perf_counter()
@@ -177,7 +181,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"configs[{args.workload - 1}] {w.name}", "N": w.N, "communities": w.M,
                    "edges": w.E, "nnz": nnz, "layers": w.L, "widths": w.dims, "scale": args.scale,
-                   "schedule": args.schedule, "partition": args.partition},
+                   "schedule": args.schedule, "step_policy": args.step_policy, "partition": args.partition},
         "roofline": None if dominant is None else {k: dominant[k] for k in
                                                    ("bound", "achieved", "peak", "unit", "frac", "traffic")},
         "dominant_kernel": None if dominant is None else dominant["kernel"],
@@ -194,7 +198,7 @@ def main():
         "objective": stats["objective"], "primal_res": stats["primal_res"], "status": stats["status"],
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.workload, w.N, nnz, args.communities, args.schedule)
+        out["cpu_baseline"] = cpu_baseline(args.workload, w.N, nnz, args.communities, args.schedule, args.step_policy)
     print(json.dumps(out))
 
 

@@ -114,6 +114,8 @@ int  cadmm_get_segment_order(cadmm_ctx* ctx, int64_t* order /* host [n_segments]
  *   schedule: 0 = Algorithm 1 (every W_l, then every Z_{l,m}, all from the values of iteration k);
  *   1 = the serial baseline of Section 4.1, layers one after the other: for l = 1..L first W_l, then
  *   Z_l (its communities together), each from the newest values of everything else.
+ *   step_policy: 0 = a search for tau_l / theta_{l,m} starts from the value accepted last time, so the
+ *   parameters never shrink; 1 = it starts from that value divided by eta, so they can.
  */
 typedef struct {
     int32_t L;
@@ -122,6 +124,7 @@ typedef struct {
     float nu, rho, tau0, theta0, eta;
     int32_t max_backtrack, fista_iters, dual_form;
     int32_t schedule;
+    int32_t step_policy;
 } cadmm_model;
 int  cadmm_set_model(cadmm_ctx* ctx, const cadmm_model* model);
 
@@ -221,7 +224,8 @@ const char* cadmm_profile_class_name(int32_t cls);
  * Process-wide: "spmm_tile_cols": feature columns handled per
  * aggregation launch (0 = all at once); "spmm_xcd_remap": 1 = each XCD walks one contiguous eighth of
  * the rows, 0 = blocks in plain order (default); "spmm_groups_log2": lane groups that share one output
- * row, as a power of two (-1 = chosen from the mean row length). */
+ * row, as a power of two (-1 = chosen from the mean row length); "spmm_unroll": gathers in flight per lane
+ * group, 8 (default) or 4. */
 int  cadmm_tune(cadmm_ctx* ctx, const char* key, int32_t value);
 
 #ifdef __cplusplus

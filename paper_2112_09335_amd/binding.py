@@ -36,7 +36,7 @@ class _Model(C.Structure):
     _fields_ = [("L", C.c_int32), ("C", C.POINTER(C.c_int32)), ("risk", C.c_int32),
                 ("nu", C.c_float), ("rho", C.c_float), ("tau0", C.c_float), ("theta0", C.c_float),
                 ("eta", C.c_float), ("max_backtrack", C.c_int32), ("fista_iters", C.c_int32),
-                ("dual_form", C.c_int32), ("schedule", C.c_int32)]
+                ("dual_form", C.c_int32), ("schedule", C.c_int32), ("step_policy", C.c_int32)]
 
 
 class _Stats(C.Structure):
@@ -199,11 +199,12 @@ class Solver:
 
     # ---- model / workspace / data
     def set_model(self, dims, *, nu, rho, tau0, theta0, eta, max_backtrack, fista_iters, risk=0, dual_form=0,
-                  schedule=0):
+                  schedule=0, step_policy=0):
         self.dims = [int(d) for d in dims]
         self.L = len(self.dims) - 1
         arr = (C.c_int32 * len(self.dims))(*self.dims)
-        m = _Model(self.L, arr, risk, nu, rho, tau0, theta0, eta, max_backtrack, fista_iters, dual_form, schedule)
+        m = _Model(self.L, arr, risk, nu, rho, tau0, theta0, eta, max_backtrack, fista_iters, dual_form, schedule,
+                   step_policy)
         self._check(self.lib.cadmm_set_model(self.h, C.byref(m)), "cadmm_set_model")
 
     def workspace_bytes(self):
@@ -369,7 +370,8 @@ class Solver:
         h = w.hyper
         s.set_model(w.dims, nu=h["nu"], rho=h["rho"], tau0=h["tau0"], theta0=h["theta0"], eta=h["eta"],
                     max_backtrack=h["max_backtrack"], fista_iters=h["fista_iters"], risk=h["risk"],
-                    dual_form=h["dual_form"], schedule=h.get("schedule", 0))
+                    dual_form=h["dual_form"], schedule=h.get("schedule", 0),
+                    step_policy=h.get("step_policy", 0))
         s.set_workspace()
         s.set_data(w.X, w.labels)
         s.init(w.W0)

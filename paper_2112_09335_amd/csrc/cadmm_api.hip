@@ -29,7 +29,7 @@ struct cadmm_ctx {
     // (A~ Z_{l-1}) W_l.  Its W-update then needs three aggregations of width C_l, so it pays if
     // 3 C_l < C_{l-1}.  In those layers the slot H[l] holds A~ G_l (N x C_l).
     std::vector<char> agg_first;
-    int risk = 0, max_bt = 60, J = 10, dual_form = 0, schedule = 0;
+    int risk = 0, max_bt = 60, J = 10, dual_form = 0, schedule = 0, step_policy = 0;
     bool u_pending = false;      // dual_form 1: the dual step of the last sweep is still to be applied
     float nu = 0, rho = 0, tau0 = 0, theta0 = 0, eta = 2;
     // workspace
@@ -312,6 +312,7 @@ SearchParams search_params(const cadmm_ctx* c) {
     sp.rho = c->rho;
     sp.eta = c->eta;
     sp.max_backtrack = c->max_bt;
+    sp.relax = c->step_policy == 1 ? 1 : 0;
     return sp;
 }
 
@@ -415,7 +416,7 @@ void w_update(cadmm_ctx* c, int l) {
                   if (fly) launch_gemm_tn(s, left, c->T[l], c->gradW, N, K, Cl, c->tn_partial, c->Z[l], c->nu);
                   else launch_gemm_tn(s, left, right, c->gradW, N, K, Cl, c->tn_partial);
               });
-        timed(c, P_OTHER, 8.0 * K * Cl, 0.0, [&] { launch_w_norms(s, c->gradW, c->W[l], K * Cl, unit, c->partials); });
+        timed(c, P_OTHER, 8.0 * K * Cl, 0.0, [&] { launch_w_norms(s, c->gradW, c->W[l], K * Cl, unit, c->partials, sp); });
         float* Q = c->G[l];                                                          // G_l is no longer needed
         // T(W - g/tau) = T - Q/tau with Q = A~ Z_{l-1} gradW
         // In a wide hidden layer the product that forms Q also evaluates the first candidate of the search and
@@ -500,7 +501,7 @@ void z_update_hidden(cadmm_ctx* c, int l) {
             launch_spmm(s, c->d_segc_lo, c->d_segc_hi, c->d_col, c->d_val, c->tmpV, c->P, c->hg.n_seg, Cn,
                         SpmmEpilogue(), long_segs_of(c));                            // A~_{r,m} (grad W) per segment
         });
-        launch_reset_units(s, units, M);
+        launch_reset_units(s, units, M, sp);
         ZTrialArgs a;
         a.chunk_unit = c->d_chunk_unit; a.chunk_kind = c->d_chunk_kind;
         a.chunk_begin = c->d_chunk_begin; a.chunk_end = c->d_chunk_end;
@@ -707,6 +708,7 @@ int cadmm_set_model(cadmm_ctx* c, const cadmm_model* m) {
     if (m->fista_iters < 0) return fail(c, CADMM_EINVAL, "fista_iters must be non-negative");
     if (m->dual_form != 0 && m->dual_form != 1) return fail(c, CADMM_EINVAL, "dual_form must be 0 or 1");
     if (m->schedule != 0 && m->schedule != 1) return fail(c, CADMM_EINVAL, "schedule must be 0 or 1");
+    if (m->step_policy != 0 && m->step_policy != 1) return fail(c, CADMM_EINVAL, "step_policy must be 0 or 1");
     c->L = m->L;
     c->C.assign(m->C, m->C + m->L + 1);
     c->risk = m->risk;
@@ -715,6 +717,7 @@ int cadmm_set_model(cadmm_ctx* c, const cadmm_model* m) {
     c->J = m->fista_iters;
     c->dual_form = m->dual_form;
     c->schedule = m->schedule;
+    c->step_policy = m->step_policy;
     c->agg_first.assign(c->L + 1, 0);
     for (int l = 2; l <= c->L; ++l) c->agg_first[l] = (3 * c->C[l] < c->C[l - 1]) ? 1 : 0;
     c->has_model = true;

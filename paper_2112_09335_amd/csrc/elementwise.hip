@@ -67,15 +67,24 @@ __device__ __forceinline__ void decide(Unit* u, const double* D, int ncand, Sear
     u->ntrials = nt;
 }
 
-__device__ __forceinline__ void floor_or_start(Unit* u, double g, double bnorm) {
-    u->g = g;
-    u->bnorm = bnorm;
+// Start of a search, before its first trial: the first candidate is the last accepted value, or that divided by
+// eta if the parameters may shrink again.
+__device__ __forceinline__ void begin_search(Unit* u, SearchParams sp) {
     u->spec = (u->ntrials == 1) ? 1 : 0;     // last search: first candidate accepted
     u->ntrials = 0;
+    u->keep = u->step;
+    if (sp.relax) u->step = u->step / (double)sp.eta;
     u->step0 = u->step;
+    u->done = 0;
+    u->skip = 0;
+}
+
+// A step below resolution is not taken: the block and its step parameter stay as they were.
+__device__ __forceinline__ void floor_test(Unit* u, double g, double bnorm) {
+    u->g = g;
+    u->bnorm = bnorm;
     const double lim = kStepFloor * u->step;
-    if (g <= lim * lim * bnorm) { u->done = 1; u->skip = 1; }
-    else { u->done = 0; u->skip = 0; }
+    if (g <= lim * lim * bnorm) { u->done = 1; u->skip = 1; u->step = u->keep; }
 }
 
 // ------------------------------------------------------------------------------------------ phi and G
@@ -227,11 +236,12 @@ __global__ __launch_bounds__(256) void w_norms_kernel(const float* __restrict__ 
 }
 
 __global__ __launch_bounds__(64) void w_norms_finish_kernel(const double* __restrict__ partials, int nblocks,
-                                                            Unit* unit) {
+                                                            Unit* unit, SearchParams sp) {
     if (threadIdx.x != 0) return;
     double g = 0.0, b = 0.0;
     for (int i = 0; i < nblocks; ++i) { g += partials[2 * i]; b += partials[2 * i + 1]; }
-    floor_or_start(unit, g, b);
+    begin_search(unit, sp);
+    floor_test(unit, g, b);
 }
 
 template <int LAST, int NC, int VEC>
@@ -505,7 +515,7 @@ __global__ __launch_bounds__(256) void z_trial_finish_kernel(ZTrialArgs a) {
     __syncthreads();
     if (threadIdx.x == 0) {
         if (a.first_pass) {
-            floor_or_start(u, D[kMaxCand], D[kMaxCand + 1]);
+            floor_test(u, D[kMaxCand], D[kMaxCand + 1]);      // the search began in reset_units_kernel
             if (u->done) return;
         }
         decide(u, D, a.ncand, a.sp, a.status);
@@ -736,16 +746,15 @@ __global__ void fill_units_kernel(Unit* units, int n, double step) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     Unit u;
-    u.step = step; u.step0 = step; u.g = 0.0; u.bnorm = 0.0; u.done = 0; u.skip = 0; u.ntrials = 0; u.spec = 0;
+    u.step = step; u.step0 = step; u.keep = step; u.g = 0.0; u.bnorm = 0.0; u.done = 0; u.skip = 0; u.ntrials = 0;
+    u.spec = 0;
     units[i] = u;
 }
 
-__global__ void reset_units_kernel(Unit* units, int n) {
+__global__ void reset_units_kernel(Unit* units, int n, SearchParams sp) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
-    units[i].done = 0;
-    units[i].skip = 0;
-    units[i].ntrials = 0;
+    begin_search(units + i, sp);
 }
 
 __global__ __launch_bounds__(256) void permute_rows_kernel(const float* __restrict__ src, float* __restrict__ dst,
@@ -800,12 +809,13 @@ void launch_risk(hipStream_t s, const float* ZL, const int32_t* labels, int64_t 
     hipLaunchKernelGGL(risk_finish_kernel, dim3(1), dim3(256), 0, s, partials, nb, out);
 }
 
-void launch_w_norms(hipStream_t s, const float* gradW, const float* W, int count, Unit* unit, double* partials) {
+void launch_w_norms(hipStream_t s, const float* gradW, const float* W, int count, Unit* unit, double* partials,
+                    SearchParams sp) {
     int nb = (count + 2047) / 2048;
     if (nb > 64) nb = 64;
     if (nb < 1) nb = 1;
     hipLaunchKernelGGL(w_norms_kernel, dim3(nb), dim3(256), 0, s, gradW, W, count, partials);
-    hipLaunchKernelGGL(w_norms_finish_kernel, dim3(1), dim3(64), 0, s, partials, nb, unit);
+    hipLaunchKernelGGL(w_norms_finish_kernel, dim3(1), dim3(64), 0, s, partials, nb, unit, sp);
 }
 
 void launch_w_trial_finish(hipStream_t s, double* partials, int n_partials, SearchParams sp, Unit* unit,
@@ -901,8 +911,8 @@ void launch_fill_units(hipStream_t s, Unit* units, int n, double step) {
     hipLaunchKernelGGL(fill_units_kernel, dim3((n + 255) / 256), dim3(256), 0, s, units, n, step);
 }
 
-void launch_reset_units(hipStream_t s, Unit* units, int n) {
-    hipLaunchKernelGGL(reset_units_kernel, dim3((n + 255) / 256), dim3(256), 0, s, units, n);
+void launch_reset_units(hipStream_t s, Unit* units, int n, SearchParams sp) {
+    hipLaunchKernelGGL(reset_units_kernel, dim3((n + 255) / 256), dim3(256), 0, s, units, n, sp);
 }
 
 void launch_permute_rows(hipStream_t s, const float* src, float* dst, const int32_t* idx, int64_t N, int C,

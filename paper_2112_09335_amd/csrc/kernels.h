@@ -86,6 +86,7 @@ constexpr int kChunkRows = 128;          // rows / segments per reduction chunk 
 struct Unit {
     double step;       // current first candidate / accepted value
     double step0;      // first candidate of this iteration's search (the value the speculative step used)
+    double keep;       // value accepted by the previous search (restored if this one takes no step)
     double g;          // squared gradient norm
     double bnorm;      // squared norm of the block that moves
     int32_t done;      // search finished
@@ -105,6 +106,7 @@ struct LayerScalars {
 struct SearchParams {
     float nu, rho, eta;
     int32_t max_backtrack;
+    int32_t relax;       // 1: a search starts from (last accepted value) / eta, 0: from the last accepted value
 };
 
 // phi_l and G_l at T (hidden: G = nu (relu(T)-Z) 1[T>0]; last: G = -(U + rho (Z - T))).
@@ -120,7 +122,8 @@ void launch_G_only(hipStream_t s, const float* T, const float* Z, const float* U
 void launch_risk(hipStream_t s, const float* ZL, const int32_t* labels, int64_t N, int CL, int risk,
                  double* partials, LayerScalars* out);
 // unit.g = ||gradW||^2, unit.bnorm = ||W||^2, applies the step floor, resets the search state.
-void launch_w_norms(hipStream_t s, const float* gradW, const float* W, int count, Unit* unit, double* partials);
+void launch_w_norms(hipStream_t s, const float* gradW, const float* W, int count, Unit* unit, double* partials,
+                    SearchParams sp);
 // One pass of the W search: candidates step*eta^j, j < ncand, on phi_l(T0 - Q/step).
 // speculated != 0: T0 already holds the speculative step T0 - Q/step0; the pass rebuilds T0 = T0 + Q/step0.
 void launch_w_trial(hipStream_t s, const float* T0, const float* Q, const float* Z, const float* U,
@@ -173,7 +176,7 @@ void launch_last_layer(hipStream_t s, float* ZL, float* U, const float* TL, cons
 void launch_relu(hipStream_t s, const float* T, float* Z, int64_t count, int apply_relu);
 void launch_argmax_rows(hipStream_t s, const float* T, int32_t* pred, int64_t N, int C);
 void launch_fill_units(hipStream_t s, Unit* units, int n, double step);
-void launch_reset_units(hipStream_t s, Unit* units, int n);
+void launch_reset_units(hipStream_t s, Unit* units, int n, SearchParams sp);
 // gather / scatter rows between caller order and internal order: dst[r,:] = src[idx[r],:] or dst[idx[r],:] = src[r,:]
 void launch_permute_rows(hipStream_t s, const float* src, float* dst, const int32_t* idx, int64_t N, int C,
                          int scatter);

@@ -205,3 +205,17 @@ def test_layer_by_layer_schedule_matches_the_oracle():
                             avg_degree=8, frac_intra=1.0)
     w.hyper["schedule"] = 1                         # the paper's serial run: one community
     run_case(w, 6, "layer-by-layer/one-community")
+
+
+def test_step_parameters_that_may_shrink_again():
+    """step_policy 1: every search starts one notch below the value accepted last time."""
+    w = synth.config(1, 0.5)
+    w.hyper["step_policy"] = 1
+    run_case(w, 8, "step-policy-1/config1")
+    w = synth.config(3, 0.01)
+    w.hyper["step_policy"] = 1
+    run_case(w, 6, "step-policy-1/config3")
+    w = synth.config(4, 0.002)
+    w.hyper["step_policy"] = 1
+    w.hyper["schedule"] = 1
+    run_case(w, 6, "step-policy-1/config4/layer-by-layer")
