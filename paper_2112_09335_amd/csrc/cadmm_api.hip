@@ -428,10 +428,13 @@ void w_update(cadmm_ctx* c, int l) {
         } else if (spec) {
             GemmEpilogue ge;
             ge.kind = 2; ge.Zl = c->Z[l]; ge.nu = c->nu; ge.Tio = c->T[l]; ge.unit = unit; ge.partials = c->partials;
-            timed(c, P_GEMM_NN_128_TRIAL, 4.0 * ((double)N * K + (double)K * Cl + 4.0 * (double)count), 2.0 * (double)N * K * Cl,
+            timed(c, P_GEMM_NN_128_TRIAL, 4.0 * ((double)N * K + (double)K * Cl + 3.0 * (double)count), 2.0 * (double)N * K * Cl,
                   [&] {
                       launch_gemm_nn(s, c->H[l], c->gradW, Q, N, K, Cl, ge);
                       launch_w_trial_finish(s, c->partials, (int)gemm_nn_blocks(N, Cl), sp, unit, c->status);
+                      GemmEpilogue again;          // Q itself, only if the step was taken ahead and then rejected
+                      again.unit = unit;
+                      launch_gemm_nn(s, c->H[l], c->gradW, Q, N, K, Cl, again);
                   });
         } else {
             gemm_nn(c, c->H[l], c->gradW, Q, N, K, Cl);

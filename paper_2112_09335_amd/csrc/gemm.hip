@@ -84,6 +84,10 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
     const int wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int ctiles = (C + BN - 1) / BN;
+    if constexpr (EPI == 0) {
+        // gated plain product: Q again for a W search whose speculative step (epilogue 2, Q not stored) was rejected
+        if (unit != nullptr && (!unit->spec || unit->skip || (unit->done && unit->step == unit->step0))) return;
+    }
     int64_t mtile;
     int ctile;
     xcd_group(blockIdx.x, gridDim.x, (unsigned)ctiles, mtile, ctile);
@@ -219,8 +223,10 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
                     v[3] = finish(v[3], z4.w, t4.w);
                     if constexpr (EPI == 2) {
                         if (take) *reinterpret_cast<float4*>(Tio + o) = t4;
+                        else *reinterpret_cast<float4*>(out + o) = make_float4(v[0], v[1], v[2], v[3]);
+                    } else {
+                        *reinterpret_cast<float4*>(out + o) = make_float4(v[0], v[1], v[2], v[3]);
                     }
-                    *reinterpret_cast<float4*>(out + o) = make_float4(v[0], v[1], v[2], v[3]);
                 } else {
                     for (int e = 0; e < 4 && c + e < C; ++e) {
                         float z = 0.f, t = 0.f;
@@ -228,8 +234,10 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
                         const float w = finish(v[e], z, t);
                         if constexpr (EPI == 2) {
                             if (take) Tio[o + e] = t;
+                            else out[o + e] = w;
+                        } else {
+                            out[o + e] = w;
                         }
-                        out[o + e] = w;
                     }
                 }
             }
@@ -251,8 +259,10 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
                         const float v = finish(acc[i][j][r], z, t);
                         if constexpr (EPI == 2) {
                             if (take) Tio[row * C + c] = t;
+                            else out[row * C + c] = v;
+                        } else {
+                            out[row * C + c] = v;
                         }
-                        out[row * C + c] = v;
                     }
                 }
             }
@@ -550,7 +560,7 @@ void launch_gemm_nn(hipStream_t s, const float* A, const float* B, float* out, i
                                nullptr, nullptr, nullptr);
         else
             hipLaunchKernelGGL((gemm_nn_kernel<128, 0>), grid, dim3(256), 0, s, A, B, out, n, K, C, nullptr, nullptr, 0.f,
-                               nullptr, nullptr, nullptr);
+                               nullptr, epi.unit, nullptr);
     } else {
         dim3 grid((unsigned)mt);
         if (epi.kind == 1)

@@ -45,10 +45,11 @@ void set_spmm_unroll(int v);
 // ---------------------------------------------------------------- dense contractions (gemm.hip)
 struct Unit;
 // out[n x C] = A[n x K] * B[K x C];  epilogue 1: out = nu * (Zl - relu(Tl)) + A B.
-// epilogue 2 (hidden layer, W search): out = Q = A B is stored, and in the same pass the first candidate of
-// the search is evaluated and the step taken speculatively: with t0 = Tio, t1 = t0 - Q / unit->step0,
-// partials[block * kMaxCand] = nu/2 sum ((relu(t1) - Zl)^2 - (relu(t0) - Zl)^2) and, if unit->spec, Tio = t1.
-// If the search later accepts another value, w_step repairs Tio from Q.  The step is only taken ahead of the
+// epilogue 2 (hidden layer, W search): with Q = A B, t0 = Tio, t1 = t0 - Q / unit->step0 the first candidate of
+// the search is evaluated in the same pass, partials[block] = nu/2 sum ((relu(t1) - Zl)^2 - (relu(t0) - Zl)^2), and
+// either the step is taken ahead of the decision (unit->spec: Tio = t1, Q is not stored) or out = Q is stored.
+// If the search then rejects the first candidate, a plain product with kind 0 and `unit` set forms Q after all
+// (its workgroups leave at once otherwise) and w_step repairs Tio from it.  The step is only taken ahead of the
 // decision when the previous search accepted its first candidate: then Q/step0 is small against Tio and
 // undoing it costs one rounding; with a step0 far too small (first iterations) it would wipe out Tio.
 struct GemmEpilogue {
