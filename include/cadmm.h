@@ -200,6 +200,17 @@ int  cadmm_op_wgrad(cadmm_ctx* ctx, const float* A, const float* G, int64_t n, i
                     int32_t C, float* out);
 
 /*
+ * Machine calibration for the rooflines the benchmarks quote (no counterpart in the paper).  Runs `reps` timed
+ * launches (after one untimed) on the context's stream, synchronises, and returns the rate.
+ *   kind 0: plain copy of `count` floats (multiple of 4) from src to dst, both device; rate = GB/s read + written.
+ *   kind 1: dependent chains of fp32 MFMAs on registers, `count` steps of four 32x32x2 MFMAs per wavefront,
+ *           2048 workgroups of four wavefronts; dst: device scratch of at least 2048 * 256 floats (src unused);
+ *           rate = TFLOP/s.
+ */
+int  cadmm_op_calibrate(cadmm_ctx* ctx, int32_t kind, const float* src, float* dst, int64_t count, int32_t reps,
+                        double* rate);
+
+/*
  * Per-kernel-class timing for benchmarks (no counterpart in the paper).  cadmm_profile(ctx, 1) clears
  * the counters and makes every later launch group be bracketed by a pair of HIP events on the
  * context's stream; cadmm_profile(ctx, 0) stops that.  cadmm_get_profile synchronises and returns,

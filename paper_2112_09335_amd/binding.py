@@ -23,7 +23,7 @@ EXPORTS = [
     "cadmm_get_Z", "cadmm_get_U", "cadmm_get_steps", "cadmm_set_state", "cadmm_op_aggregate",
     "cadmm_op_aggregate_segments", "cadmm_op_transform", "cadmm_op_wgrad",
     "cadmm_profile", "cadmm_get_profile", "cadmm_profile_class_name", "cadmm_tune", "cadmm_predict",
-    "cadmm_partition",
+    "cadmm_partition", "cadmm_op_calibrate",
 ]
 PROFILE_CLASSES = 19
 
@@ -87,6 +87,7 @@ def load_library():
     lib.cadmm_op_aggregate_segments.argtypes = [vp, vp, i32, vp]
     lib.cadmm_op_transform.argtypes = [vp, vp, i64, i32, vp, i32, vp]
     lib.cadmm_op_wgrad.argtypes = [vp, vp, vp, i64, i32, i32, vp]
+    lib.cadmm_op_calibrate.argtypes = [vp, i32, vp, vp, i64, i32, C.POINTER(C.c_double)]
     lib.cadmm_tune.argtypes = [vp, C.c_char_p, i32]
     lib.cadmm_predict.argtypes = [vp, vp, vp, C.POINTER(C.c_double)]
     lib.cadmm_profile.argtypes = [vp, C.c_int]
@@ -333,6 +334,26 @@ class Solver:
                     "cadmm_op_transform")
         self._leave()
         return out
+
+    def op_calibrate(self, kind, count, reps=5):
+        """'copy': GB/s of a plain device copy of `count` floats; 'mfma': TFLOP/s of register-only fp32 MFMA chains."""
+        torch = self._torch
+        rate = C.c_double()
+        self._enter()
+        if kind == "copy":
+            src = torch.ones(count, dtype=torch.float32, device=f"cuda:{self.device}")
+            dst = torch.empty_like(src)
+            torch.cuda.current_stream().synchronize()
+            rc = self.lib.cadmm_op_calibrate(self.h, 0, C.c_void_p(src.data_ptr()), C.c_void_p(dst.data_ptr()), count,
+                                             reps, C.byref(rate))
+        elif kind == "mfma":
+            dst = torch.empty(2048 * 256, dtype=torch.float32, device=f"cuda:{self.device}")
+            rc = self.lib.cadmm_op_calibrate(self.h, 1, None, C.c_void_p(dst.data_ptr()), count, reps, C.byref(rate))
+        else:
+            raise CadmmError(f"unknown calibration {kind}")
+        self._check(rc, "cadmm_op_calibrate")
+        self._leave()
+        return float(rate.value)
 
     def op_wgrad(self, A, G):
         torch = self._torch

@@ -1131,4 +1131,34 @@ int cadmm_op_wgrad(cadmm_ctx* c, const float* A, const float* G, int64_t n, int3
     return check_launch(c, "op_wgrad");
 }
 
+int cadmm_op_calibrate(cadmm_ctx* c, int32_t kind, const float* src, float* dst, int64_t count, int32_t reps,
+                       double* rate) {
+    if (!c || !dst || !rate || count < 4 || reps < 1 || (kind != 0 && kind != 1)) return CADMM_EINVAL;
+    if (c->device < 0) return fail(c, CADMM_EUNSUPPORTED, "host-only context");
+    const int blocks = 2048;
+    if (kind == 0 && (!src || count % 4 != 0)) return fail(c, CADMM_EINVAL, "copy needs src and a multiple of four floats");
+    if (kind == 1 && count > (1 << 24)) return fail(c, CADMM_EINVAL, "at most 2^24 MFMA steps per launch");
+    hipEvent_t a = nullptr, b = nullptr;
+    HIP_TRY(c, hipEventCreate(&a));
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return fail(c, CADMM_EHIP, "hipEventCreate"); }
+    double work = 0.0;
+    auto once = [&] {
+        if (kind == 0) { launch_stream_copy(c->stream, src, dst, count); work += 8.0 * (double)count; }
+        else work += launch_mfma_chain(c->stream, dst, blocks, (int)count);
+    };
+    once();                                     // untimed first launch
+    work = 0.0;
+    (void)hipEventRecord(a, c->stream);
+    for (int i = 0; i < reps; ++i) once();
+    (void)hipEventRecord(b, c->stream);
+    hipError_t e = hipEventSynchronize(b);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    if (e != hipSuccess) return hip_fail(c, e, "op_calibrate");
+    *rate = ms > 0.f ? work / ((double)ms * 1e-3) / (kind == 0 ? 1e9 : 1e12) : 0.0;
+    return check_launch(c, "op_calibrate");
+}
+
 }  // extern "C"

@@ -518,6 +518,33 @@ __global__ __launch_bounds__(256) void transpose_kernel(const float* __restrict_
     out[c * K + k] = in[i];
 }
 
+// Machine calibration: nothing but dependent chains of fp32 MFMAs on registers, four chains per wavefront.
+__global__ __launch_bounds__(256) void mfma_chain_kernel(float* __restrict__ out, int iters, float seed) {
+    floatx16 acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    const float a = seed + (float)(threadIdx.x & 7), b = 0.5f * seed;
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[j], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[j][r];
+    out[(int64_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+// Machine calibration: dst = src, one float4 per thread and step.
+__global__ __launch_bounds__(256) void stream_copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
+                                                          int64_t n4) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) dst[i] = src[i];
+}
+
 struct TnPlan {
     int nchunks;
     int64_t rows_per_chunk;
@@ -608,6 +635,17 @@ void launch_gemm_tn(hipStream_t s, const float* A, const float* G, float* out, i
     const int64_t count = (int64_t)K * C;
     hipLaunchKernelGGL(gemm_tn_reduce_kernel, dim3((unsigned)((count * 8 + 255) / 256)), dim3(256), 0, s, partial, out,
                        count, p.nchunks);
+}
+
+double launch_mfma_chain(hipStream_t s, float* out, int blocks, int iters) {
+    hipLaunchKernelGGL(mfma_chain_kernel, dim3((unsigned)blocks), dim3(256), 0, s, out, iters, 1.0f);
+    return (double)blocks * 4.0 * iters * 4.0 * (32.0 * 32.0 * 2.0 * 2.0);      // flops
+}
+
+void launch_stream_copy(hipStream_t s, const float* src, float* dst, int64_t count) {
+    const int64_t n4 = count / 4;
+    hipLaunchKernelGGL(stream_copy_kernel, dim3(8192), dim3(256), 0, s, reinterpret_cast<const float4*>(src),
+                       reinterpret_cast<float4*>(dst), n4);
 }
 
 void launch_transpose(hipStream_t s, const float* in, float* out, int K, int C) {

@@ -63,6 +63,10 @@ struct GemmEpilogue {
 };
 void launch_gemm_nn(hipStream_t s, const float* A, const float* B, float* out, int64_t n, int K, int C,
                     const GemmEpilogue& epi = GemmEpilogue());
+// calibration kernels: chains of fp32 MFMAs on registers (returns the flops of the launch; out: blocks * 256 floats),
+// and a plain copy of count floats (count % 4 == 0)
+double launch_mfma_chain(hipStream_t s, float* out, int blocks, int iters);
+void launch_stream_copy(hipStream_t s, const float* src, float* dst, int64_t count);
 int64_t gemm_nn_blocks(int64_t n, int C);      // grid size of that launch (= block results of epilogue 2)
 // out[n x C] = [nu (Zl - relu(Tl)) | SG] * Bcat, Bcat = [W (K1 x C); S (K2 x C)], C <= 32, K1 % 4 == K2 % 4 == 0:
 // the product (grad_Z psi) W with grad = nu (Zl - relu(Tl)) + SG W^T, S = W^T W, the gradient never stored.

@@ -5,6 +5,8 @@
            transform:256:256 wgrad:128:256 --reps 5
 
 ops:  copy            a plain device copy of 1 GiB (torch), the calibration point for memory counters
+      stream          the library's own copy kernel on 1 GiB (cadmm_op_calibrate): what a streaming kernel can reach
+      mfma            register-only chains of fp32 MFMAs (cadmm_op_calibrate): what the matrix cores can reach
       aggregate:W     Y = A~ X, X of width W                    (cadmm_op_aggregate)
       segments:W      per-(row, community) aggregation          (cadmm_op_aggregate_segments)
       transform:K:C   out[N x C] = A[N x K] B[K x C]            (cadmm_op_transform)
@@ -55,6 +57,15 @@ def main():
     for op in args.ops:
         parts = op.split(":")
         kind = parts[0]
+        if kind in ("stream", "mfma"):
+            if kind == "stream":
+                rate = s.op_calibrate("copy", 1 << 28, args.reps)
+                print(f"{op:20s} library copy kernel, 1 GiB read + 1 GiB written: {rate:8.1f} GB/s", flush=True)
+            else:
+                rate = s.op_calibrate("mfma", 20000, args.reps)
+                print(f"{op:20s} fp32 MFMA chains on registers: {rate:7.2f} TFLOP/s "
+                      f"({rate / 157.3:.3f} of the published 157.3)", flush=True)
+            continue
         if kind == "copy":
             n = 1 << 28                                           # 1 GiB of fp32
             src = torch.randn(n, device="cuda")
