@@ -61,7 +61,7 @@ const char* cadmm_last_error(cadmm_ctx* ctx);
  *   src,dst  host int32[n_edges] as for cadmm_build_graph (repeats, both orientations and self pairs
  *            are normalised away);  comm  host int32[N], out: community of every node, in [0,M).
  * Size-capped label propagation from one cluster per node, merging of clusters along the connection
- * with the most edges until M are left, a few more propagation rounds; every tie is broken by node
+ * with the most edges until M are left, propagation on the original graph until it rests; every tie is broken by node
  * or cluster number, so the result depends on the input only.  No community exceeds
  * ceil(N/M) + floor(N/M)/20 + 1 nodes unless clusters had to be merged regardless of size; some
  * communities may stay empty.  Host work only: valid on a context created with device = -1.

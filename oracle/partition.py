@@ -32,8 +32,9 @@ Definition (all integer work):
             the two lightest nodes (ties: smaller number), the larger number into the smaller, whatever
             the cap.
   result    the nodes that are left become communities 0, 1, .. in increasing order of their number; every
-            original node gets the community of the chain of clusters it went into; eight more rounds
-            r = 0 .. 7 of the propagation on the finest graph polish the borders.
+            original node gets the community of the chain of clusters it went into; then the propagation
+            runs on the finest graph again, rounds r = 0, 1, .. until two rounds in a row moved nothing, at
+            most 100, which moves the borders where the coarse levels left them in the wrong place.
 Fewer than M communities may remain; the ones after the last are then empty.
 """
 from __future__ import annotations
@@ -41,7 +42,6 @@ from __future__ import annotations
 import numpy as np
 
 MAX_ROUNDS = 100
-REFINE_ROUNDS = 8
 MASK64 = (1 << 64) - 1
 
 
@@ -198,8 +198,11 @@ def partition(N, src, dst, M):
     for c in label:
         size[c] = size.get(c, 0) + 1
     unit = [1] * N
-    for r in range(REFINE_ROUNDS):
-        propagation_round(finest, unit, label, size, cap, r)
+    quiet = 0
+    for r in range(MAX_ROUNDS):
+        quiet = quiet + 1 if propagation_round(finest, unit, label, size, cap, r) == 0 else 0
+        if quiet == 2:
+            break
     return np.asarray(label, dtype=np.int32)
 
 

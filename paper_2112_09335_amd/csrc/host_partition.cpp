@@ -1,6 +1,6 @@
 // Deterministic multilevel partitioner: size-capped synchronous label propagation until it rests, contraction of
 // the clusters to the nodes of the next level, greedy merging on the last level along the heaviest connection,
-// and a few propagation rounds on the finest graph at the end.
+// and propagation on the finest graph at the end until it rests again.
 // The paper leaves the partition to METIS (Section 2); this is the library's own stand-in, every tie broken
 // by node or cluster number so that the result depends on nothing but the input.
 #include "host_partition.h"
@@ -282,7 +282,9 @@ std::string partition_graph(int64_t N, int64_t n_edges, const int32_t* src, cons
     size.assign(M, 0);
     granted.assign(M, 0);
     for (int64_t v = 0; v < N; ++v) size[label[v]]++;
-    for (int r = 0; r < kPartitionRefineRounds; ++r) propagation_round(finest, label, size, cap, r, want, granted);
+    int quiet = 0;
+    for (int r = 0; r < kPartitionMaxRounds && quiet < 2; ++r)
+        quiet = propagation_round(finest, label, size, cap, r, want, granted) == 0 ? quiet + 1 : 0;
     for (int64_t v = 0; v < N; ++v) comm[v] = label[v];
     return std::string();
 }

@@ -5,8 +5,8 @@
 
 namespace cadmm {
 
-constexpr int kPartitionMaxRounds = 100;    // propagation rounds per level, unless it comes to rest earlier
-constexpr int kPartitionRefineRounds = 8;   // propagation rounds on the finest graph at the end
+constexpr int kPartitionMaxRounds = 100;    // propagation rounds per level and in the final refinement, unless two
+                                            // rounds in a row move nothing before that
 
 // Cuts the simple undirected graph of the edge list into at most M communities of about equal size
 // (the paper uses METIS for this, Section 2).  Writes the community of every node to comm[N].
