@@ -405,19 +405,19 @@ class AdmmOracle:
     def _sweep(self):
         L, M = self.L, self.M
         Wk, Zk, Uk = self.W, self.Z, self.U
-        # Line 3: W_l^{k+1} for every l from (Z^k, U^k)
+        # Algorithm 1, the W step: W_l^{k+1} for every l from (Z^k, U^k)
         Wn = [None] + [self.update_W(l, Wk, Zk, Uk) for l in range(1, L + 1)]
         # messages with Z^k and W^{k+1}
         p = [self.first_order(l, Zk[l], Wn[l + 1]) for l in range(0, L)]
         s = [None] + [self.second_order(l, p[l], Zk[l + 1], Uk) for l in range(1, L)]
-        # Line 4: Z_{l,m}^{k+1} for every l, m from (W^{k+1}, Z^k, U^k)
+        # Algorithm 1, the Z step: Z_{l,m}^{k+1} for every l, m from (W^{k+1}, Z^k, U^k)
         Zn = [Zk[0]] + [np.empty_like(Zk[l]) for l in range(1, L + 1)]
         for l in range(1, L):
             for m in range(M):
                 Zn[l][self.g.rows(m)] = self.update_Z_hidden(l, m, Zk, Wn, Uk, p[l - 1], p[l], s[l])
         for m in range(M):
             Zn[L][self.g.rows(m)] = self.update_Z_last(m, Zk, Uk, p[L - 1])
-        # Line 5: U_m^{k+1} = U_m^k + rho (Z_{L,m}^k - sum_r p_{L-1,r->m}^k)       (Eq. 2 as printed)
+        # Algorithm 1, the dual step: U_m^{k+1} = U_m^k + rho (Z_{L,m}^k - sum_r p_{L-1,r->m}^k)   (Eq. 2 as printed)
         # dual_form 1 is the usual ADMM dual ascent on the new iterates instead:
         #         U_m^{k+1} = U_m^k + rho (Z_{L,m}^{k+1} - sum_r A~_{m,r} Z_{L-1,r}^{k+1} W_L^{k+1})
         Un = np.empty_like(Uk)
