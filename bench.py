@@ -21,6 +21,8 @@ if ROOT not in sys.path:
 # published MI355X peaks
 HBM_PEAK_GBS = 8000.0
 MFMA_FP32_PEAK_TFLOPS = 157.3
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+SPLIT_PRODUCTS = 6      # bf16 MFMA products issued per fp32 product in the gemm_nn_split kernels
 
 # A kernel class is priced against the MFMA roofline if its arithmetic intensity (algorithmic flops per
 # algorithmic byte over the timed region) is above the machine balance, else against HBM bandwidth.
@@ -30,7 +32,7 @@ MACHINE_BALANCE = MFMA_FP32_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)      # flo
 # copy of known size reads), measured with rocprofv3 --pmc on this program at the default workload (steady-state
 # sweeps); the summary with the commands is profiles/sweep_memory_traffic_powerlaw_dcsbm_2M.txt.
 MEASURED_TRAFFIC = {
-    (4, "gemm_nn_kernel<128,2>+finish"): 5.16e9 + 2.05e9,     # H_1 gradW_1, first candidate, step on T_1 ahead of the decision
+    (4, "gemm_nn_split_kernel<2>+finish"): 5.16e9 + 2.05e9,   # H_1 gradW_1, first candidate, step on T_1 ahead of the decision
     (4, "spmm_rows_kernel[rows]"): 3.454e9 + 0.129e9,         # width 16
     (4, "spmm_rows_kernel[segments]"): 5.277e9 + 0.659e9,     # width 16
     (4, "gemm_tn_kernel<128>+reduce"): 5.43e9 + 0.038e9 + 0.067e9,
@@ -41,7 +43,7 @@ MEASURED_TRAFFIC = {
     (4, "gemm_nn_kernel<32>"): 2.049e9 + 0.128e9,             # out[N x 16] = A[N x 256] B
     (4, "gemm_tn_kernel<32>+reduce"): 2.188e9 + 0.008e9,
     (4, "last_layer_kernel"): 0.392e9 + 0.256e9,
-    (4, "gemm_nn_kernel<128,0>"): 1.114e9 + 2.048e9,          # out[N x 256] = A[N x 128] B
+    (4, "gemm_nn_split_kernel<0>"): 1.114e9 + 2.048e9,        # out[N x 256] = A[N x 128] B
 }
 
 # CPU-oracle sample: (scale of N, iterations) per workload, sized for about 10-30 s of host time
@@ -53,6 +55,12 @@ def roofline_entry(name, p):
     if sec <= 0 or p["records"] == 0:
         return None
     per_launch_ms = p["ms"] / p["records"]
+    if name.startswith("gemm_nn_split") and p["bytes"] > 0 and p["flops"] / p["bytes"] > MACHINE_BALANCE:
+        # fp32-exact product issued as six bf16 MFMA products: priced in issued bf16 flops against the bf16 peak
+        ach = SPLIT_PRODUCTS * p["flops"] / sec / 1e12
+        return dict(kernel=name, bound="mfma", achieved=ach, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=ach / MFMA_BF16_PEAK_TFLOPS, traffic=None, avg_launch_ms=per_launch_ms,
+                    launches=p["records"], share_of_step=None, fp32_product_TFLOPs=p["flops"] / sec / 1e12)
     if name.startswith("gemm") and p["bytes"] > 0 and p["flops"] / p["bytes"] > MACHINE_BALANCE:
         ach = p["flops"] / sec / 1e12
         return dict(kernel=name, bound="mfma", achieved=ach, peak=MFMA_FP32_PEAK_TFLOPS, unit="TFLOP/s",

@@ -236,7 +236,9 @@ const char* cadmm_profile_class_name(int32_t cls);
  * aggregation launch (0 = all at once); "spmm_xcd_remap": 1 = each XCD walks one contiguous eighth of
  * the rows, 0 = blocks in plain order (default); "spmm_groups_log2": lane groups that share one output
  * row, as a power of two (-1 = chosen from the mean row length); "spmm_unroll": gathers in flight per lane
- * group, 8 (default) or 4. */
+ * group, 8 (default) or 4; "gemm_split": 1 = products with more than 32 result columns run on the bf16 matrix
+ * cores, both operands split exactly into three bf16 parts and the six largest cross products accumulated in fp32
+ * (default), 0 = on the fp32 matrix cores. */
 int  cadmm_tune(cadmm_ctx* ctx, const char* key, int32_t value);
 
 #ifdef __cplusplus

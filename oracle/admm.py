@@ -50,14 +50,15 @@ def relu(x):
     return np.maximum(x, 0.0)
 
 
-# ReLU'(x) = 1[x > RELU_TIE_SHIFT].  The value is 0 (the reading ReLU'(0) = 0).  Tests move it by a
-# few fp32 roundings to ask what the iterate would be had a pre-activation that is zero up to rounding
-# fallen on the other side: the derivative of the penalty jumps there, so both outcomes are valid.
-RELU_TIE_SHIFT = 0.0
+# ReLU'(x) = 1[x > shift], shift = 0 (the reading ReLU'(0) = 0).  Tests move it by a few fp32 roundings to ask
+# what the iterate would be had a pre-activation that is zero up to rounding fallen on the other side: the
+# derivative of the penalty jumps there, so both outcomes are valid.  The W step and the Z step of one iteration
+# look at different pre-activations (before and after the W step), so each has a shift of its own.
+RELU_TIE_SHIFT = {"W": 0.0, "Z": 0.0}
 
 
-def relu_grad(x):
-    return (x > RELU_TIE_SHIFT).astype(np.float64)
+def relu_grad(x, step="W"):
+    return (x > RELU_TIE_SHIFT[step]).astype(np.float64)
 
 
 def inner(a, b):
@@ -204,7 +205,7 @@ class AdmmOracle:
             H = self.g.aggregate_block(m, Zprev)
             T = H @ Wl
             if l < self.L:
-                G = self.nu * (relu(T) - self.blk(Zl, m)) * relu_grad(T)
+                G = self.nu * (relu(T) - self.blk(Zl, m)) * relu_grad(T, "W")
             else:
                 r = self.blk(Zl, m) - T
                 G = -(self.blk(U, m) + self.rho * r)
@@ -298,12 +299,12 @@ class AdmmOracle:
         for r in g.nbrs(m):
             a = a + p_cur[(r, m)]
         if l <= self.L - 2:
-            Gm = self.nu * (relu(a) - self.blk(Znext, m)) * relu_grad(a)
+            Gm = self.nu * (relu(a) - self.blk(Znext, m)) * relu_grad(a, "Z")
             grad = grad + g.block[(m, m)].T @ Gm @ Wnext.T
             for r in g.nbrs(m):
                 s1, s2 = s_cur[(r, m)]
                 b = g.block[(r, m)] @ Zlm @ Wnext + s2
-                Gr = self.nu * (relu(b) - s1) * relu_grad(b)
+                Gr = self.nu * (relu(b) - s1) * relu_grad(b, "Z")
                 grad = grad + g.block[(r, m)].T @ Gr @ Wnext.T
         else:
             res = self.blk(Znext, m) - a

@@ -1069,16 +1069,24 @@ int cadmm_get_profile(cadmm_ctx* c, double* ms, int64_t* records, double* bytes,
 }
 
 const char* cadmm_profile_class_name(int32_t cls) {
-    return (cls >= 0 && cls < CADMM_PROFILE_CLASSES) ? kProfNames[cls] : "";
+    if (cls < 0 || cls >= CADMM_PROFILE_CLASSES) return "";
+    if (get_gemm_split()) {                      // the wide products run as the bf16-split kernel: name that symbol
+        if (cls == P_GEMM_NN_128) return "gemm_nn_split_kernel<0>";
+        if (cls == P_GEMM_NN_128_GRADZ) return "gemm_nn_split_kernel<1>";
+        if (cls == P_GEMM_NN_128_TRIAL) return "gemm_nn_split_kernel<2>+finish";
+    }
+    return kProfNames[cls];
 }
 
 int cadmm_tune(cadmm_ctx* c, const char* key, int32_t value) {
     if (!c || !key) return CADMM_EINVAL;
     if (std::strcmp(key, "use_graph") == 0) { c->use_graph = value != 0; return CADMM_OK; }
     const bool k_lowrank = std::strcmp(key, "use_lowrank") == 0, k_spec = std::strcmp(key, "use_speculative") == 0;
-    if (k_lowrank || k_spec) {
+    const bool k_split = std::strcmp(key, "gemm_split") == 0;
+    if (k_lowrank || k_spec || k_split) {
         if (k_lowrank) c->use_lowrank = value != 0;
-        else c->use_speculative = value != 0;
+        else if (k_spec) c->use_speculative = value != 0;
+        else set_gemm_split(value);                  // process-wide; captured iterations of this context are dropped
         for (auto& cube : c->graphs)
             for (auto& plane : cube)
                 for (auto& row : plane)

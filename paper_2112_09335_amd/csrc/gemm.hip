@@ -51,6 +51,105 @@ __device__ __forceinline__ void xcd_group(unsigned b, unsigned nb, unsigned inne
     }
 }
 
+// Epilogue of a 128 x 128 result tile held as 2 x 2 accumulators per wavefront (2 x 2 wavefronts).
+// The accumulators hold 32 consecutive columns per row and lane group; passing each 32-row slab of the tile
+// through LDS (Cs: 32 x 132 floats, the operand buffer reused) turns every global access of the epilogue into
+// float4 pieces of a 512-byte row.
+// EPI 0: out = acc.  EPI 1: out = nu (Zl - relu(Tl)) + acc.  EPI 2: first candidate of the W search and the step
+// on Tio ahead of the decision, see GemmEpilogue.
+template <int EPI>
+__device__ __forceinline__ void tile128_epilogue(floatx16 (&acc)[2][2], float* Cs, int64_t m0, int c0, int64_t n, int C,
+                                                 float* __restrict__ out, const float* __restrict__ Zl,
+                                                 const float* __restrict__ Tl, float nu, float* __restrict__ Tio,
+                                                 const Unit* unit, double* __restrict__ partials) {
+    constexpr int LDC = 128 + 4;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int li = lane & 31, lk = lane >> 5;
+    const bool c_al = (C % 4) == 0;
+    double inv0 = 0.0, dsum = 0.0;
+    bool take = false;
+    if constexpr (EPI == 2) {
+        inv0 = unit->skip ? 0.0 : 1.0 / unit->step0;
+        take = unit->spec != 0 && !unit->skip;
+    }
+    // one result element: returns what goes to out, updates t (EPI 2) and the candidate's sum
+    auto finish = [&](float v, float z, float& t) -> float {
+        if constexpr (EPI == 1) v = nu * (z - fmaxf(t, 0.f)) + v;
+        if constexpr (EPI == 2) {
+            const double t0 = (double)t, zd = (double)z;
+            const double t1 = t0 - (double)v * inv0;
+            const double e0 = fmax(t0, 0.0) - zd, e1 = fmax(t1, 0.0) - zd;
+            dsum += (e1 - e0) * (e1 + e0);
+            t = (float)t1;
+        }
+        return v;
+    };
+    const float* tin = (EPI == 2) ? Tio : Tl;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        __syncthreads();
+        if (wm == q / 2) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    Cs[(8 * (r >> 2) + 4 * lk + (r & 3)) * LDC + wn * 64 + j * 32 + li] = acc[q % 2][j][r];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int f = tid + 256 * u;
+            const int rl = f >> 5, cq = f & 31;
+            const int64_t row = m0 + 32 * q + rl;
+            const int c = c0 + 4 * cq;
+            if (row >= n || c >= C) continue;
+            const float4 v4 = *reinterpret_cast<const float4*>(Cs + rl * LDC + 4 * cq);
+            float v[4] = {v4.x, v4.y, v4.z, v4.w};
+            const int64_t o = row * C + c;
+            if (c_al) {
+                float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f), t4 = z4;
+                if constexpr (EPI != 0) {
+                    z4 = *reinterpret_cast<const float4*>(Zl + o);
+                    t4 = *reinterpret_cast<const float4*>(tin + o);
+                }
+                v[0] = finish(v[0], z4.x, t4.x);
+                v[1] = finish(v[1], z4.y, t4.y);
+                v[2] = finish(v[2], z4.z, t4.z);
+                v[3] = finish(v[3], z4.w, t4.w);
+                if constexpr (EPI == 2) {
+                    if (take) *reinterpret_cast<float4*>(Tio + o) = t4;
+                    else *reinterpret_cast<float4*>(out + o) = make_float4(v[0], v[1], v[2], v[3]);
+                } else {
+                    *reinterpret_cast<float4*>(out + o) = make_float4(v[0], v[1], v[2], v[3]);
+                }
+            } else {
+                for (int e = 0; e < 4 && c + e < C; ++e) {
+                    float z = 0.f, t = 0.f;
+                    if constexpr (EPI != 0) { z = Zl[o + e]; t = tin[o + e]; }
+                    const float w = finish(v[e], z, t);
+                    if constexpr (EPI == 2) {
+                        if (take) Tio[o + e] = t;
+                        else out[o + e] = w;
+                    } else {
+                        out[o + e] = w;
+                    }
+                }
+            }
+        }
+    }
+    if constexpr (EPI == 2) {
+        __shared__ double red[4];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
+        if (lane == 0) red[wave] = dsum;
+        __syncthreads();
+        if (tid == 0) partials[blockIdx.x] = 0.5 * (double)nu * (red[0] + red[1] + red[2] + red[3]);
+    }
+}
+
 // ------------------------------------------------------------------------------------------------ NN
 // EPI 1: out = nu * (Zl - relu(Tl)) + A B   (gradient of the Z subproblem, Appendix A)
 // EPI 2: out = Q = A B; first candidate of the W search and speculative step on Tio (Section 3.1), see kernels.h
@@ -164,85 +263,12 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
         }
     }
-    const int li = lane & 31, lk = lane >> 5;
-    double inv0 = 0.0, dsum = 0.0;
-    bool take = false;
-    if constexpr (EPI == 2) {
-        inv0 = unit->skip ? 0.0 : 1.0 / unit->step0;
-        take = unit->spec != 0 && !unit->skip;
-    }
-    // one result element: returns what goes to out, updates t (EPI 2) and the candidate's sum
-    auto finish = [&](float v, float z, float& t) -> float {
-        if constexpr (EPI == 1) v = nu * (z - fmaxf(t, 0.f)) + v;
-        if constexpr (EPI == 2) {
-            const double t0 = (double)t, zd = (double)z;
-            const double t1 = t0 - (double)v * inv0;
-            const double e0 = fmax(t0, 0.0) - zd, e1 = fmax(t1, 0.0) - zd;
-            dsum += (e1 - e0) * (e1 + e0);
-            t = (float)t1;
-        }
-        return v;
-    };
     if constexpr (BN == 128) {
-        // The accumulators hold 32 consecutive columns per row and lane group; passing each 32-row slab of the
-        // tile through LDS turns every global access of the epilogue into float4 pieces of a 512-byte row.
-        constexpr int LDC = BN + 4;
-        static_assert(32 * LDC <= BM * LDA + BKK * LDB, "result slab must fit the operand buffer");
-        float* const Cs = smem;
-        const float* tin = (EPI == 2) ? Tio : Tl;
-#pragma unroll
-        for (int q = 0; q < BM / 32; ++q) {
-            __syncthreads();
-            if (wm == q / TM) {
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        Cs[(8 * (r >> 2) + 4 * lk + (r & 3)) * LDC + wn * TN * 32 + j * 32 + li] = acc[q % TM][j][r];
-            }
-            __syncthreads();
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int f = tid + 256 * u;
-                const int rl = f >> 5, cq = f & 31;
-                const int64_t row = m0 + 32 * q + rl;
-                const int c = c0 + 4 * cq;
-                if (row >= n || c >= C) continue;
-                const float4 v4 = *reinterpret_cast<const float4*>(Cs + rl * LDC + 4 * cq);
-                float v[4] = {v4.x, v4.y, v4.z, v4.w};
-                const int64_t o = row * C + c;
-                if (b_al) {
-                    float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f), t4 = z4;
-                    if constexpr (EPI != 0) {
-                        z4 = *reinterpret_cast<const float4*>(Zl + o);
-                        t4 = *reinterpret_cast<const float4*>(tin + o);
-                    }
-                    v[0] = finish(v[0], z4.x, t4.x);
-                    v[1] = finish(v[1], z4.y, t4.y);
-                    v[2] = finish(v[2], z4.z, t4.z);
-                    v[3] = finish(v[3], z4.w, t4.w);
-                    if constexpr (EPI == 2) {
-                        if (take) *reinterpret_cast<float4*>(Tio + o) = t4;
-                        else *reinterpret_cast<float4*>(out + o) = make_float4(v[0], v[1], v[2], v[3]);
-                    } else {
-                        *reinterpret_cast<float4*>(out + o) = make_float4(v[0], v[1], v[2], v[3]);
-                    }
-                } else {
-                    for (int e = 0; e < 4 && c + e < C; ++e) {
-                        float z = 0.f, t = 0.f;
-                        if constexpr (EPI != 0) { z = Zl[o + e]; t = tin[o + e]; }
-                        const float w = finish(v[e], z, t);
-                        if constexpr (EPI == 2) {
-                            if (take) Tio[o + e] = t;
-                            else out[o + e] = w;
-                        } else {
-                            out[o + e] = w;
-                        }
-                    }
-                }
-            }
-        }
+        static_assert(32 * (BN + 4) <= BM * LDA + BKK * LDB, "result slab must fit the operand buffer");
+        tile128_epilogue<EPI>(acc, smem, m0, c0, n, C, out, Zl, Tl, nu, Tio, unit, partials);
     } else {
+        static_assert(BN == 128 || EPI != 2, "the search epilogue exists for the wide tile only");
+        const int li = lane & 31, lk = lane >> 5;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -253,28 +279,148 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
                 for (int r = 0; r < 16; ++r) {
                     const int64_t row = m0 + wm * TM * 32 + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
                     if (row < n) {
-                        float z = 0.f, t = 0.f;
-                        if constexpr (EPI == 1) { z = Zl[row * C + c]; t = Tl[row * C + c]; }
-                        if constexpr (EPI == 2) { z = Zl[row * C + c]; t = Tio[row * C + c]; }
-                        const float v = finish(acc[i][j][r], z, t);
-                        if constexpr (EPI == 2) {
-                            if (take) Tio[row * C + c] = t;
-                            else out[row * C + c] = v;
-                        } else {
-                            out[row * C + c] = v;
-                        }
+                        float v = acc[i][j][r];
+                        if constexpr (EPI == 1) v = nu * (Zl[row * C + c] - fmaxf(Tl[row * C + c], 0.f)) + v;
+                        out[row * C + c] = v;
                     }
                 }
             }
     }
-    if constexpr (EPI == 2) {
-        __shared__ double red[4];
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
-        if (lane == 0) red[wave] = dsum;
-        __syncthreads();
-        if (tid == 0) partials[blockIdx.x] = 0.5 * (double)nu * (red[0] + red[1] + red[2] + red[3]);
+}
+
+// The same product out[n x C] = A[n x K] B[K x C] on the bf16 matrix cores, fp32-exact in its inputs: an fp32 number is the
+// exact sum of three bf16 numbers (8 + 8 + 8 significand bits, each part the truncated remainder of the one before), and of the
+// nine cross products the six largest are accumulated in fp32 (hi*hi, hi*mid, mid*hi, mid*mid, hi*lo, lo*hi; the three
+// that are left out are below 2^-24 of |a||b|).  Six v_mfma_f32_32x32x16_bf16 per 16 columns of K replace 32
+// v_mfma_f32_32x32x2_f32, at a sixteenth of the cycles per flop.  Operand layout of 32x32x16 (64 lanes): a lane holds
+// A[i = lane%32][k = 8*(lane/32) .. +7] and B[k = 8*(lane/32) .. +7][j = lane%32]; the accumulator as for 32x32x2.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// two fp32 numbers -> their three bf16 parts, each pair packed into one dword (low half = first number)
+__device__ __forceinline__ void split3_pair(float x0, float x1, unsigned& h, unsigned& m, unsigned& l) {
+    const unsigned u0 = __float_as_uint(x0), u1 = __float_as_uint(x1);
+    h = __builtin_amdgcn_perm(u1, u0, 0x07060302u);             // upper halves of u1 and u0
+    const float r0 = x0 - __uint_as_float(u0 & 0xFFFF0000u);    // exact
+    const float r1 = x1 - __uint_as_float(u1 & 0xFFFF0000u);
+    const unsigned v0 = __float_as_uint(r0), v1 = __float_as_uint(r1);
+    m = __builtin_amdgcn_perm(v1, v0, 0x07060302u);
+    const float s0 = r0 - __uint_as_float(v0 & 0xFFFF0000u);    // exact, at most 8 significant bits left
+    const float s1 = r1 - __uint_as_float(v1 & 0xFFFF0000u);
+    l = __builtin_amdgcn_perm(__float_as_uint(s1), __float_as_uint(s0), 0x07060302u);
+}
+
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_nn_split_kernel(const float* __restrict__ A, const float* __restrict__ B,
+                                                            float* __restrict__ out, int64_t n, int K, int C,
+                                                            const float* __restrict__ Zl, const float* __restrict__ Tl,
+                                                            float nu, float* __restrict__ Tio, const Unit* unit,
+                                                            double* __restrict__ partials) {
+    constexpr int BN = 128;
+    if constexpr (EPI == 0) {
+        // gated plain product, as in gemm_nn_kernel
+        if (unit != nullptr && (!unit->spec || unit->skip || (unit->done && unit->step == unit->step0))) return;
     }
+    constexpr int LDH = BK + 8;                   // bf16 per tile row: rows start 16-byte aligned
+    constexpr int PLANE = BM * LDH;               // BM == BN
+    __shared__ __align__(16) unsigned short smem[6 * PLANE];
+    unsigned short* const As = smem;              // [3][BM][LDH]: A tile, k contiguous per row
+    unsigned short* const Bs = smem + 3 * PLANE;  // [3][BN][LDH]: B tile transposed, k contiguous per column
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int li = lane & 31, lk = lane >> 5;
+    const int ctiles = (C + BN - 1) / BN;
+    int64_t mtile;
+    int ctile;
+    xcd_group(blockIdx.x, gridDim.x, (unsigned)ctiles, mtile, ctile);
+    const int64_t m0 = mtile * BM;
+    const int c0 = ctile * BN;
+    const bool a_al = (K % 4) == 0;
+    const bool b_al = (C % 4) == 0;
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // A: thread takes 4 consecutive k of two rows; B: 8 consecutive k of one column (coalesced across the columns)
+    float4 ra[2];
+    float rb[8];
+    const int bc = tid & 127, bkg = tid >> 7;
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int f = tid + 256 * i;
+            const int row = f >> 2, kq = f & 3;
+            const int64_t gr = m0 + row;
+            const int k = k0 + 4 * kq;
+            ra[i] = ld4_guard(A, gr * K + k, gr < n, a_al, K - k);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int k = k0 + 8 * bkg + e;
+            rb[e] = (k < K && c0 + bc < C) ? B[(int64_t)k * C + c0 + bc] : 0.f;
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int f = tid + 256 * i;
+            const int row = f >> 2, kq = f & 3;
+            unsigned h0, m0_, l0, h1, m1, l1;
+            split3_pair(ra[i].x, ra[i].y, h0, m0_, l0);
+            split3_pair(ra[i].z, ra[i].w, h1, m1, l1);
+            const int o = row * LDH + 4 * kq;
+            *reinterpret_cast<uint2*>(As + o) = make_uint2(h0, h1);
+            *reinterpret_cast<uint2*>(As + PLANE + o) = make_uint2(m0_, m1);
+            *reinterpret_cast<uint2*>(As + 2 * PLANE + o) = make_uint2(l0, l1);
+        }
+        {
+            unsigned h[4], m[4], l[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) split3_pair(rb[2 * e], rb[2 * e + 1], h[e], m[e], l[e]);
+            const int o = bc * LDH + 8 * bkg;
+            *reinterpret_cast<uint4*>(Bs + o) = make_uint4(h[0], h[1], h[2], h[3]);
+            *reinterpret_cast<uint4*>(Bs + PLANE + o) = make_uint4(m[0], m[1], m[2], m[3]);
+            *reinterpret_cast<uint4*>(Bs + 2 * PLANE + o) = make_uint4(l[0], l[1], l[2], l[3]);
+        }
+    };
+
+    const int nk = (K + BK - 1) / BK;
+    fetch(0);
+    for (int kt = 0; kt < nk; ++kt) {
+        __syncthreads();
+        stash();
+        __syncthreads();
+        if (kt + 1 < nk) fetch((kt + 1) * BK);
+        bf16x8 a[3][2], b[3][2];
+#pragma unroll
+        for (int p = 0; p < 3; ++p)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                a[p][i] = *reinterpret_cast<const bf16x8*>(As + p * PLANE + (wm * 64 + i * 32 + li) * LDH + 8 * lk);
+                b[p][i] = *reinterpret_cast<const bf16x8*>(Bs + p * PLANE + (wn * 64 + i * 32 + li) * LDH + 8 * lk);
+            }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                floatx16 c = acc[i][j];
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2][i], b[0][j], c, 0, 0, 0);   // small terms first
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[2][j], c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][i], b[1][j], c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][i], b[0][j], c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[1][j], c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[0][j], c, 0, 0, 0);
+                acc[i][j] = c;
+            }
+    }
+    static_assert(32 * (BN + 4) * 4 <= 6 * PLANE * 2, "result slab must fit the operand buffer");
+    tile128_epilogue<EPI>(acc, reinterpret_cast<float*>(smem), m0, c0, n, C, out, Zl, Tl, nu, Tio, unit, partials);
 }
 
 // out[n x C] = [ nu (Z - relu(T)) | SG ] * Bcat  with Bcat = [ W (K1 x C) ; S (K2 x C) ],  C <= 32.
@@ -545,6 +691,8 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(const float4* __restri
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) dst[i] = src[i];
 }
 
+int g_split = 1;      // 1: wide products run on the bf16 matrix cores with three-way split operands, 0: fp32 MFMA
+
 struct TnPlan {
     int nchunks;
     int64_t rows_per_chunk;
@@ -572,6 +720,9 @@ TnPlan tn_plan(int64_t n, int K, int C) {
 
 }  // namespace
 
+void set_gemm_split(int on) { g_split = on ? 1 : 0; }
+int get_gemm_split() { return g_split; }
+
 void launch_gemm_nn(hipStream_t s, const float* A, const float* B, float* out, int64_t n, int K, int C,
                     const GemmEpilogue& epi) {
     if (n <= 0 || C <= 0) return;
@@ -579,15 +730,22 @@ void launch_gemm_nn(hipStream_t s, const float* A, const float* B, float* out, i
     if (C > 32) {
         const int ct = (C + 127) / 128;
         dim3 grid((unsigned)(mt * ct));
-        if (epi.kind == 2)
-            hipLaunchKernelGGL((gemm_nn_kernel<128, 2>), grid, dim3(256), 0, s, A, B, out, n, K, C, epi.Zl, nullptr, epi.nu,
-                               epi.Tio, epi.unit, epi.partials);
-        else if (epi.kind == 1)
-            hipLaunchKernelGGL((gemm_nn_kernel<128, 1>), grid, dim3(256), 0, s, A, B, out, n, K, C, epi.Zl, epi.Tl, epi.nu,
-                               nullptr, nullptr, nullptr);
-        else
-            hipLaunchKernelGGL((gemm_nn_kernel<128, 0>), grid, dim3(256), 0, s, A, B, out, n, K, C, nullptr, nullptr, 0.f,
-                               nullptr, epi.unit, nullptr);
+#define CADMM_NN128(K2_, K1_, K0_) \
+        if (epi.kind == 2) \
+            hipLaunchKernelGGL(K2_, grid, dim3(256), 0, s, A, B, out, n, K, C, epi.Zl, nullptr, epi.nu, epi.Tio, epi.unit, \
+                               epi.partials); \
+        else if (epi.kind == 1) \
+            hipLaunchKernelGGL(K1_, grid, dim3(256), 0, s, A, B, out, n, K, C, epi.Zl, epi.Tl, epi.nu, nullptr, nullptr, \
+                               nullptr); \
+        else \
+            hipLaunchKernelGGL(K0_, grid, dim3(256), 0, s, A, B, out, n, K, C, nullptr, nullptr, 0.f, nullptr, epi.unit, \
+                               nullptr)
+        if (g_split) {
+            CADMM_NN128((gemm_nn_split_kernel<2>), (gemm_nn_split_kernel<1>), (gemm_nn_split_kernel<0>));
+        } else {
+            CADMM_NN128((gemm_nn_kernel<128, 2>), (gemm_nn_kernel<128, 1>), (gemm_nn_kernel<128, 0>));
+        }
+#undef CADMM_NN128
     } else {
         dim3 grid((unsigned)mt);
         if (epi.kind == 1)

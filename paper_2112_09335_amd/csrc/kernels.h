@@ -63,6 +63,9 @@ struct GemmEpilogue {
 };
 void launch_gemm_nn(hipStream_t s, const float* A, const float* B, float* out, int64_t n, int K, int C,
                     const GemmEpilogue& epi = GemmEpilogue());
+// 1: plain products wider than 32 columns use three-way bf16 splits of both operands on the bf16 matrix cores
+void set_gemm_split(int on);
+int get_gemm_split();
 // calibration kernels: chains of fp32 MFMAs on registers (returns the flops of the launch; out: blocks * 256 floats),
 // and a plain copy of count floats (count % 4 == 0)
 double launch_mfma_chain(hipStream_t s, float* out, int blocks, int iters);

@@ -32,8 +32,9 @@ def step_with_relu_ties(solver, orc, tag):
     it: the gradient of the penalty nu/2 ||Z - relu(T)||^2 jumps where a pre-activation T crosses 0, so
     an entry that is zero up to fp32 rounding may fall on either side.  The oracle's iteration is
     repeated from the same state with the threshold of ReLU' moved by +-delta (a few fp32 roundings of
-    the pre-activation scale); the GPU result must then match one of these equally valid outcomes to
-    the same tolerance.  Returns (worst relative error, tie used?)."""
+    the pre-activation scale), separately for the W step and the Z step, which look at different
+    pre-activations; the GPU result must then match one of these equally valid outcomes to the same
+    tolerance.  Returns (worst relative error, tie used?)."""
     import oracle.admm as oa
     snap = orc.snapshot()
     solver.run(1)
@@ -44,18 +45,20 @@ def step_with_relu_ties(solver, orc, tag):
         # fp32 rounding of a pre-activation of size ~scale is a few 1e-7 * scale; a finer-to-coarser ladder
         # so that only the entry nearest to zero changes side first
         scale = max(1.0, max(float(np.sqrt(np.mean(z * z))) for z in snap["Z"][1:]))
-        ladder = [sgn * m * 1e-7 * scale for m in (1, 2, 4, 8, 16, 32) for sgn in (+1, -1)]
-        for shift in ladder:
+        rungs = [0.0] + [sgn * m * 1e-7 * scale for m in (0.1, 0.3, 1, 2, 4, 8, 16, 32) for sgn in (+1, -1)]
+        pairs = sorted(((a, b) for a in rungs for b in rungs if (a, b) != (0.0, 0.0)),
+                       key=lambda p: ((p[0] != 0.0) + (p[1] != 0.0), abs(p[0]) + abs(p[1])))
+        for shift_w, shift_z in pairs:
             orc.restore(snap)
-            oa.RELU_TIE_SHIFT = shift
+            oa.RELU_TIE_SHIFT["W"], oa.RELU_TIE_SHIFT["Z"] = shift_w, shift_z
             try:
                 orc.iterate(1)
             finally:
-                oa.RELU_TIE_SHIFT = 0.0
+                oa.RELU_TIE_SHIFT["W"], oa.RELU_TIE_SHIFT["Z"] = 0.0, 0.0
             try:
-                worst = compare_iterate(solver, orc, tag + f" [relu tie shift {shift:+.1e}]")
-                say(f"{tag}: ReLU tie, matches the oracle with threshold {shift:+.2e}; first mismatch was: "
-                    f"{str(first).splitlines()[0][:160]}")
+                worst = compare_iterate(solver, orc, tag + f" [relu tie shifts {shift_w:+.1e} {shift_z:+.1e}]")
+                say(f"{tag}: ReLU tie, matches the oracle with thresholds W {shift_w:+.2e}, Z {shift_z:+.2e}; "
+                    f"first mismatch was: {str(first).splitlines()[0][:160]}")
                 return worst, True
             except AssertionError:
                 continue
