@@ -22,7 +22,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 MFMA_FP32_PEAK_TFLOPS = 157.3
 MFMA_BF16_PEAK_TFLOPS = 2500.0
-SPLIT_PRODUCTS = 6      # bf16 MFMA products issued per fp32 product in the gemm_nn_split kernels
+SPLIT_PRODUCTS = 6      # bf16 MFMA products issued per fp32 product in the split kernels
 
 # A kernel class is priced against the MFMA roofline if its arithmetic intensity (algorithmic flops per
 # algorithmic byte over the timed region) is above the machine balance, else against HBM bandwidth.
@@ -35,7 +35,7 @@ MEASURED_TRAFFIC = {
     (4, "gemm_nn_split_kernel<2>+finish"): 5.16e9 + 2.05e9,   # H_1 gradW_1, first candidate, step on T_1 ahead of the decision
     (4, "spmm_rows_kernel[rows]"): 3.454e9 + 0.129e9,         # width 16
     (4, "spmm_rows_kernel[segments]"): 5.277e9 + 0.659e9,     # width 16
-    (4, "gemm_tn_kernel<128>+reduce"): 5.43e9 + 0.038e9 + 0.067e9,
+    (4, "gemm_tn_split_kernel+reduce"): 5.43e9 + 0.038e9 + 0.067e9,
     (4, "z_trial_kernel"): 6.126e9 + 0.006e9,
     (4, "z_step_kernel"): 4.297e9 + 2.048e9,
     (4, "gemm_nn_gradz_kernel"): 4.226e9 + 0.128e9,
@@ -55,7 +55,7 @@ def roofline_entry(name, p):
     if sec <= 0 or p["records"] == 0:
         return None
     per_launch_ms = p["ms"] / p["records"]
-    if name.startswith("gemm_nn_split") and p["bytes"] > 0 and p["flops"] / p["bytes"] > MACHINE_BALANCE:
+    if name.startswith(("gemm_nn_split", "gemm_tn_split")) and p["bytes"] > 0 and p["flops"] / p["bytes"] > MACHINE_BALANCE:
         # fp32-exact product issued as six bf16 MFMA products: priced in issued bf16 flops against the bf16 peak
         ach = SPLIT_PRODUCTS * p["flops"] / sec / 1e12
         return dict(kernel=name, bound="mfma", achieved=ach, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",

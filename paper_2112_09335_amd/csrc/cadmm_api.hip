@@ -1074,6 +1074,7 @@ const char* cadmm_profile_class_name(int32_t cls) {
         if (cls == P_GEMM_NN_128) return "gemm_nn_split_kernel<0>";
         if (cls == P_GEMM_NN_128_GRADZ) return "gemm_nn_split_kernel<1>";
         if (cls == P_GEMM_NN_128_TRIAL) return "gemm_nn_split_kernel<2>+finish";
+        if (cls == P_GEMM_TN) return "gemm_tn_split_kernel+reduce";
     }
     return kProfNames[cls];
 }

@@ -1,4 +1,6 @@
-// Dense fp32 contractions of the sweep on the gfx950 matrix cores (v_mfma_f32_32x32x2_f32):
+// Dense fp32 contractions of the sweep on the gfx950 matrix cores: v_mfma_f32_32x32x2_f32, or (default for results
+// wider than 32 columns, the *_split_kernel variants) v_mfma_f32_32x32x16_bf16 on operands split exactly into
+// three bf16 parts each, which gives the same accuracy at a fraction of the matrix-core time:
 //   gemm_nn : out[n x C] = A[n x K] B[K x C]     (T_l = H_l W_l, Q = H_l gradW, G W^T, gradZ W;
 //                                                 paper Section 3.1 and Appendix A)
 //   gemm_tn : out[K x C] = A[n x K]^T G[n x C]   (gradient of phi with respect to W_l: a sum over all
@@ -309,8 +311,9 @@ __device__ __forceinline__ void split3_pair(float x0, float x1, unsigned& h, uns
     l = __builtin_amdgcn_perm(__float_as_uint(s1), __float_as_uint(s0), 0x07060302u);
 }
 
+// (four wavefronts per SIMD asked for: the few registers that spill cost less than the fourth wavefront gains)
 template <int EPI>
-__global__ __launch_bounds__(256) void gemm_nn_split_kernel(const float* __restrict__ A, const float* __restrict__ B,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void gemm_nn_split_kernel(const float* __restrict__ A, const float* __restrict__ B,
                                                             float* __restrict__ out, int64_t n, int K, int C,
                                                             const float* __restrict__ Zl, const float* __restrict__ Tl,
                                                             float nu, float* __restrict__ Tio, const Unit* unit,
@@ -390,6 +393,33 @@ __global__ __launch_bounds__(256) void gemm_nn_split_kernel(const float* __restr
         }
     };
 
+    auto multiply = [&]() {
+        bf16x8 a[3][2];
+#pragma unroll
+        for (int p = 0; p < 3; ++p)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                a[p][i] = *reinterpret_cast<const bf16x8*>(As + p * PLANE + (wm * 64 + i * 32 + li) * LDH + 8 * lk);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            bf16x8 b[3];                             // one column tile's parts at a time keeps the register count down
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+                b[p] = *reinterpret_cast<const bf16x8*>(Bs + p * PLANE + (wn * 64 + j * 32 + li) * LDH + 8 * lk);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                floatx16 c = acc[i][j];
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2][i], b[0], c, 0, 0, 0);   // small terms first
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[2], c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][i], b[1], c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][i], b[0], c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[1], c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[0], c, 0, 0, 0);
+                acc[i][j] = c;
+            }
+        }
+    };
+    // (fetching two steps ahead was tried: the second register set costs more occupancy than the latency it hides)
     const int nk = (K + BK - 1) / BK;
     fetch(0);
     for (int kt = 0; kt < nk; ++kt) {
@@ -397,27 +427,7 @@ __global__ __launch_bounds__(256) void gemm_nn_split_kernel(const float* __restr
         stash();
         __syncthreads();
         if (kt + 1 < nk) fetch((kt + 1) * BK);
-        bf16x8 a[3][2], b[3][2];
-#pragma unroll
-        for (int p = 0; p < 3; ++p)
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                a[p][i] = *reinterpret_cast<const bf16x8*>(As + p * PLANE + (wm * 64 + i * 32 + li) * LDH + 8 * lk);
-                b[p][i] = *reinterpret_cast<const bf16x8*>(Bs + p * PLANE + (wn * 64 + i * 32 + li) * LDH + 8 * lk);
-            }
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                floatx16 c = acc[i][j];
-                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2][i], b[0][j], c, 0, 0, 0);   // small terms first
-                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[2][j], c, 0, 0, 0);
-                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][i], b[1][j], c, 0, 0, 0);
-                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][i], b[0][j], c, 0, 0, 0);
-                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[1][j], c, 0, 0, 0);
-                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[0][j], c, 0, 0, 0);
-                acc[i][j] = c;
-            }
+        multiply();
     }
     static_assert(32 * (BN + 4) * 4 <= 6 * PLANE * 2, "result slab must fit the operand buffer");
     tile128_epilogue<EPI>(acc, reinterpret_cast<float*>(smem), m0, c0, n, C, out, Zl, Tl, nu, Tio, unit, partials);
@@ -640,6 +650,124 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ 
         }
 }
 
+// gemm_tn on the bf16 matrix cores, same three-way split as gemm_nn_split_kernel.  Both operands are contracted
+// over the rows, so both tiles are stored transposed (8 consecutive rows of one column per lane and MFMA): a thread
+// loads 8 rows of one column, which is coalesced across the threads of a wavefront (consecutive columns).
+// PRO 1 forms G = nu (relu(T) - Z) 1[T > 0] from T (passed as G) and Zl while loading.  128 x 128 result tile.
+template <int PRO>
+__global__ __launch_bounds__(256) void gemm_tn_split_kernel(const float* __restrict__ A, const float* __restrict__ G,
+                                                            const float* __restrict__ Zl, float nu,
+                                                            float* __restrict__ partial, int64_t n, int K, int C,
+                                                            int64_t rows_per_chunk) {
+    constexpr int LDH = BK + 8;
+    constexpr int PLANE = 128 * LDH;
+    __shared__ __align__(16) unsigned short smem[6 * PLANE];
+    unsigned short* const As = smem;              // [3][128 columns of A][LDH rows]
+    unsigned short* const Gs = smem + 3 * PLANE;  // [3][128 columns of G][LDH rows]
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int li = lane & 31, lk = lane >> 5;
+    const int ktiles = (K + 127) / 128;
+    const int ctiles = (C + 127) / 128;
+    int tile;
+    int64_t chunk;
+    xcd_group(blockIdx.x, gridDim.x, (unsigned)(ktiles * ctiles), chunk, tile);
+    const int k0 = (tile / ctiles) * 128;
+    const int c0 = (tile % ctiles) * 128;
+    const int64_t r_begin = chunk * rows_per_chunk;
+    const int64_t r_end = (r_begin + rows_per_chunk < n) ? (r_begin + rows_per_chunk) : n;
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int col = tid & 127, rg = tid >> 7;     // this thread: column `col` of both tiles, rows 8 rg .. 8 rg + 7
+    const bool a_on = k0 + col < K, g_on = c0 + col < C;
+    float ra[8], rgv[8];
+    auto fetch = [&](int64_t r0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int64_t r = r0 + 8 * rg + e;
+            const bool on = r < r_end;
+            ra[e] = (on && a_on) ? A[r * K + k0 + col] : 0.f;
+            float g = (on && g_on) ? G[r * C + c0 + col] : 0.f;
+            if constexpr (PRO == 1) {
+                const float z = (on && g_on) ? Zl[r * C + c0 + col] : 0.f;
+                g = (g > 0.f) ? nu * (g - z) : 0.f;
+            }
+            rgv[e] = g;
+        }
+    };
+    auto stash = [&]() {
+        unsigned h[4], m[4], l[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) split3_pair(ra[2 * e], ra[2 * e + 1], h[e], m[e], l[e]);
+        const int o = col * LDH + 8 * rg;
+        *reinterpret_cast<uint4*>(As + o) = make_uint4(h[0], h[1], h[2], h[3]);
+        *reinterpret_cast<uint4*>(As + PLANE + o) = make_uint4(m[0], m[1], m[2], m[3]);
+        *reinterpret_cast<uint4*>(As + 2 * PLANE + o) = make_uint4(l[0], l[1], l[2], l[3]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) split3_pair(rgv[2 * e], rgv[2 * e + 1], h[e], m[e], l[e]);
+        *reinterpret_cast<uint4*>(Gs + o) = make_uint4(h[0], h[1], h[2], h[3]);
+        *reinterpret_cast<uint4*>(Gs + PLANE + o) = make_uint4(m[0], m[1], m[2], m[3]);
+        *reinterpret_cast<uint4*>(Gs + 2 * PLANE + o) = make_uint4(l[0], l[1], l[2], l[3]);
+    };
+
+    auto multiply = [&]() {
+        bf16x8 a[3][2];
+#pragma unroll
+        for (int p = 0; p < 3; ++p)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                a[p][i] = *reinterpret_cast<const bf16x8*>(As + p * PLANE + (wm * 64 + i * 32 + li) * LDH + 8 * lk);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            bf16x8 b[3];                             // one column tile's parts at a time keeps the register count down
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+                b[p] = *reinterpret_cast<const bf16x8*>(Gs + p * PLANE + (wn * 64 + j * 32 + li) * LDH + 8 * lk);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                floatx16 c = acc[i][j];
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2][i], b[0], c, 0, 0, 0);   // small terms first
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[2], c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][i], b[1], c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][i], b[0], c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[1], c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[0], c, 0, 0, 0);
+                acc[i][j] = c;
+            }
+        }
+    };
+    if (r_begin < r_end) fetch(r_begin);
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += BK) {
+        __syncthreads();
+        stash();
+        __syncthreads();
+        if (r0 + BK < r_end) fetch(r0 + BK);
+        multiply();
+    }
+    float* dst = partial + chunk * (int64_t)K * C;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int c = c0 + wn * 64 + j * 32 + li;
+            if (c >= C) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int k = k0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+                if (k < K) dst[(int64_t)k * C + c] = acc[i][j][r];
+            }
+        }
+}
+
 // Eight lanes share one output entry: lane j adds chunks j, j+8, ... in order, then the eight partial
 // sums are added in lane order by a shuffle tree (fixed order, so the result is reproducible).
 __global__ __launch_bounds__(256) void gemm_tn_reduce_kernel(const float* __restrict__ partial,
@@ -779,7 +907,10 @@ void launch_gemm_tn(hipStream_t s, const float* A, const float* G, float* out, i
     if (K <= 0 || C <= 0) return;
     TnPlan p = tn_plan(n, K, C);
     const dim3 grid((unsigned)((int64_t)p.nchunks * p.tiles)), block(256);
-    if (Zl) {
+    if (g_split && p.bn == 128) {
+        if (Zl) hipLaunchKernelGGL((gemm_tn_split_kernel<1>), grid, block, 0, s, A, G, Zl, nu, partial, n, K, C, p.rows_per_chunk);
+        else hipLaunchKernelGGL((gemm_tn_split_kernel<0>), grid, block, 0, s, A, G, Zl, nu, partial, n, K, C, p.rows_per_chunk);
+    } else if (Zl) {
         if (p.bn == 128)
             hipLaunchKernelGGL((gemm_tn_kernel<128, 1>), grid, block, 0, s, A, G, Zl, nu, partial, n, K, C, p.rows_per_chunk);
         else
