@@ -32,10 +32,10 @@ MACHINE_BALANCE = MFMA_FP32_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)      # flo
 # copy of known size reads), measured with rocprofv3 --pmc on this program at the default workload (steady-state
 # sweeps); the summary with the commands is profiles/sweep_memory_traffic_powerlaw_dcsbm_2M.txt.
 MEASURED_TRAFFIC = {
-    (4, "gemm_nn_split_kernel<2>+finish"): 5.16e9 + 2.05e9,   # H_1 gradW_1, first candidate, step on T_1 ahead of the decision
+    (4, "gemm_nn_split_kernel<2>+finish"): 5.15e9 + 2.05e9,   # H_1 gradW_1, first candidate, step on T_1 ahead of the decision
     (4, "spmm_rows_kernel[rows]"): 3.454e9 + 0.129e9,         # width 16
     (4, "spmm_rows_kernel[segments]"): 5.277e9 + 0.659e9,     # width 16
-    (4, "gemm_tn_split_kernel+reduce"): 5.43e9 + 0.038e9 + 0.067e9,
+    (4, "gemm_tn_split_kernel+reduce"): 5.16e9 + 0.038e9 + 0.067e9,
     (4, "z_trial_kernel"): 6.126e9 + 0.006e9,
     (4, "z_step_kernel"): 4.297e9 + 2.048e9,
     (4, "gemm_nn_gradz_kernel"): 4.226e9 + 0.128e9,
