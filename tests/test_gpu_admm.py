@@ -222,3 +222,16 @@ def test_step_parameters_that_may_shrink_again():
     w.hyper["step_policy"] = 1
     w.hyper["schedule"] = 1
     run_case(w, 6, "step-policy-1/config4/layer-by-layer")
+
+
+def test_fp32_matrix_core_path_matches_the_oracle_too():
+    """The sweep with the wide products on the fp32 MFMA kernels (gemm_split = 0) instead of the bf16-split ones."""
+    from paper_2112_09335_amd import binding
+    w = synth.config(3, 0.01)
+    probe = binding.Solver(device=-1)
+    try:
+        probe.tune("gemm_split", 0)              # process-wide switch
+        run_case(w, 5, "fp32-mfma/config3")
+    finally:
+        probe.tune("gemm_split", 1)
+        probe.close()

@@ -142,3 +142,36 @@ def test_wgrad_matches_fp64_product(ctx, n, K, C):
     out = s.op_wgrad(torch.from_numpy(A).cuda(), torch.from_numpy(G).cuda()).cpu().numpy().astype(np.float64)
     ref = A.astype(np.float64).T @ G.astype(np.float64)
     assert rel_err(out, ref) < 1e-5
+
+
+@pytest.mark.parametrize("n,K,C", [(3000, 512, 512), (1031, 500, 200), (2000, 128, 256), (640, 37, 129)])
+def test_products_agree_on_the_fp32_and_the_bf16_split_matrix_core_paths(ctx, n, K, C):
+    """Results wider than 32 columns run on the bf16 matrix cores with both operands split exactly into three bf16
+    parts; the fp32 MFMA kernels stay selectable.  Both must sit at fp32 rounding of the fp64 product, also for
+    operands whose rows span many orders of magnitude."""
+    s, g, torch = ctx
+    say("split products", n, K, C)
+    rng = np.random.default_rng(n * 7 + K + C)
+    A = (rng.standard_normal((n, K)) * np.exp(3.0 * rng.standard_normal((n, 1)))).astype(np.float32)
+    B = (rng.standard_normal((K, C)) * np.exp(2.0 * rng.standard_normal((1, C)))).astype(np.float32)
+    G = (rng.standard_normal((n, C)) * np.exp(3.0 * rng.standard_normal((n, 1)))).astype(np.float32)
+    ref_nn = A.astype(np.float64) @ B.astype(np.float64)
+    mag_nn = np.abs(A).astype(np.float64) @ np.abs(B).astype(np.float64)
+    ref_tn = A.astype(np.float64).T @ G.astype(np.float64)
+    mag_tn = np.abs(A).astype(np.float64).T @ np.abs(G).astype(np.float64)
+    At, Bt, Gt = (torch.from_numpy(x).cuda() for x in (A, B, G))
+    try:
+        for split in (0, 1):
+            s.tune("gemm_split", split)
+            nn = s.op_transform(At, Bt).cpu().numpy().astype(np.float64)
+            tn = s.op_wgrad(At, Gt).cpu().numpy().astype(np.float64)
+            assert (np.abs(nn - ref_nn) / mag_nn).max() < 2e-6, split
+            assert (np.abs(tn - ref_tn) / mag_tn).max() < 2e-6, split
+    finally:
+        s.tune("gemm_split", 1)
+
+
+def test_calibration_kernels_report_a_rate(ctx):
+    s, g, torch = ctx
+    assert s.op_calibrate("copy", 1 << 22, 3) > 10.0        # GB/s
+    assert s.op_calibrate("mfma", 200, 3) > 1.0             # TFLOP/s
