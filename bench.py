@@ -47,7 +47,7 @@ MEASURED_TRAFFIC = {
 }
 
 # CPU-oracle sample: (scale of N, iterations) per workload, sized for about 10-30 s of host time
-ORACLE_SAMPLE = {1: (1.0, 10), 2: (0.25, 4), 3: (0.02, 3), 4: (0.004, 3), 5: (0.004, 2), 6: (0.1, 3), 7: (0.2, 3)}
+ORACLE_SAMPLE = {1: (1.0, 10), 2: (0.25, 4), 3: (0.02, 3), 4: (0.004, 8), 5: (0.004, 2), 6: (0.1, 3), 7: (0.2, 3)}
 
 
 def roofline_entry(name, p):
