@@ -35,7 +35,7 @@ void launch_spmm(hipStream_t s, const int64_t* lo, const int64_t* hi, const int3
 // columns of the feature matrix handled per launch (0 = all); smaller tiles keep a community's share of
 // the gathered matrix inside one XCD's L2 at the price of re-reading the entries once per tile
 void set_spmm_tile_cols(int cols);
-// 1: every XCD walks one contiguous eighth of the rows (default); 0: blocks in plain order
+// 1: every XCD walks one contiguous eighth of the rows; 0: blocks in plain order (default: measured faster)
 void set_spmm_xcd_remap(int on);
 // lane groups per output row as a power of two (-1 = from the mean row length)
 void set_spmm_groups_log2(int v);

@@ -8,13 +8,13 @@
 //
 // Mapping: a group of LPR lanes (a power of two, up to the 64-lane wavefront) reads one gathered
 // neighbour row with one fully coalesced VEC*4-byte load per lane and keeps VEC*R accumulators per lane.
-// GPR such groups share one output row and take its entries round-robin, four entries in flight per
+// GPR such groups share one output row and take its entries round-robin, eight (or four) entries in flight per
 // group; their partial sums are added by a wavefront-level xor-shuffle reduction.  GPR follows the mean
 // row length, so short rows (segments) pack several rows into a wavefront and long rows spread over it.
 // Rows beyond a length threshold (power-law hubs) are cut into parts that run as extra rows of the same
 // launch into a side buffer; a small kernel adds a row's parts in order.  Everything is order-fixed:
 // no atomics, results are reproducible.  The bound is the L2 / HBM traffic of the gathers.
-// Blocks can be renumbered so that each XCD (blockIdx mod 8) walks one contiguous eighth of the rows.
+// Blocks can be renumbered so that each XCD (blockIdx mod 8) walks one contiguous eighth of the rows (off by default).
 #include "kernels.h"
 
 namespace cadmm {
