@@ -588,6 +588,7 @@ __global__ __launch_bounds__(256) void z_step_lowrank_kernel(float* __restrict__
 // After Z_{l,m} <- Z_{l,m} - grad/theta_{l,m} the next layer's pre-activation A~ Z_l W_{l+1} of row i changes by
 // - sum over the segments (i, c) of P_{(i,c)} / theta_{l,c}  (P = A~_{., c} grad W_{l+1}, already formed for the
 // search).  Applying that keeps T_{l+1} valid for the next iteration without a new aggregation and product.
+constexpr int kCarryBatch = 4;
 template <int VEC>
 __global__ __launch_bounds__(256) void t_carry_kernel(float* __restrict__ Tn, const float* __restrict__ P,
                                                       const int64_t* __restrict__ row_seg_ptr,
@@ -607,15 +608,34 @@ __global__ __launch_bounds__(256) void t_carry_kernel(float* __restrict__ Tn, co
 #pragma unroll
             for (int v = 0; v < VEC; ++v) acc[v] = 0.0;
             bool any = false;
-            for (int64_t sgm = s0; sgm < s1; ++sgm) {
-                const Unit* u = units + seg_comm[sgm];
-                if (u->skip) continue;
-                any = true;
-                const double inv = 1.0 / u->step;
-                float p[VEC];
-                ldv<VEC>(p, P + (int64_t)seg_pos[sgm] * Cn + cv * VEC);
+            // kCarryBatch segments at a time: their index, unit and row loads do not depend on each other, so they
+            // are in flight together; the sums are still taken in segment order.
+            for (int64_t sgm = s0; sgm < s1; sgm += kCarryBatch) {
+                int cm[kCarryBatch], ps[kCarryBatch];
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) acc[v] += (double)p[v] * inv;
+                for (int j = 0; j < kCarryBatch; ++j) {
+                    const int64_t sj = sgm + j < s1 ? sgm + j : s1 - 1;
+                    cm[j] = seg_comm[sj];
+                    ps[j] = seg_pos[sj];
+                }
+                double st[kCarryBatch];
+                bool use[kCarryBatch];
+                float p[kCarryBatch][VEC];
+#pragma unroll
+                for (int j = 0; j < kCarryBatch; ++j) {
+                    const Unit* u = units + cm[j];
+                    st[j] = u->step;
+                    use[j] = sgm + j < s1 && !u->skip;
+                    ldv<VEC>(p[j], P + (int64_t)ps[j] * Cn + cv * VEC);
+                }
+#pragma unroll
+                for (int j = 0; j < kCarryBatch; ++j) {
+                    if (!use[j]) continue;
+                    any = true;
+                    const double inv = 1.0 / st[j];
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[v] += (double)p[j][v] * inv;
+                }
             }
             if (!any) continue;
             float t[VEC];
