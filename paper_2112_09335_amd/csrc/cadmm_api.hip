@@ -41,8 +41,10 @@ struct cadmm_ctx {
     float* d_val = nullptr;
     int32_t* d_row_comm = nullptr;
     int32_t* d_perm = nullptr;
-    int64_t* d_segc_lo = nullptr;
-    int64_t* d_segc_hi = nullptr;
+    int32_t* d_segc_col = nullptr;
+    float* d_segc_val = nullptr;
+    int32_t* d_seg1_pos = nullptr; int32_t* d_seg1_col = nullptr; float* d_seg1_val = nullptr;
+    int64_t* d_segm_ptr = nullptr; int64_t* d_segm_end = nullptr; int32_t* d_segm_pos = nullptr;
     int32_t* d_segc_row = nullptr;
     int32_t* d_chunk_unit = nullptr;
     int32_t* d_chunk_kind = nullptr;
@@ -155,8 +157,14 @@ size_t layout(cadmm_ctx* c, char* base) {
     c->d_val = b.take<float>(g.nnz);
     c->d_row_comm = b.take<int32_t>(N);
     c->d_perm = b.take<int32_t>(N);
-    c->d_segc_lo = b.take<int64_t>(g.n_seg);
-    c->d_segc_hi = b.take<int64_t>(g.n_seg);
+    c->d_segc_col = b.take<int32_t>(g.nnz);
+    c->d_segc_val = b.take<float>(g.nnz);
+    c->d_seg1_pos = b.take<int32_t>(g.seg1_pos.size());
+    c->d_seg1_col = b.take<int32_t>(g.seg1_pos.size());
+    c->d_seg1_val = b.take<float>(g.seg1_pos.size());
+    c->d_segm_ptr = b.take<int64_t>(g.segm_pos.size());
+    c->d_segm_end = b.take<int64_t>(g.segm_pos.size());
+    c->d_segm_pos = b.take<int32_t>(g.segm_pos.size());
     c->d_segc_row = b.take<int32_t>(g.n_seg);
     const size_t nch = g.chunks.size();
     c->d_chunk_unit = b.take<int32_t>(nch);
@@ -289,7 +297,8 @@ SpmmLong long_segs_of(const cadmm_ctx* c) {
     lg.n_parts = c->hg.long_segs.n_parts(); lg.part_lo = c->d_ls_part_lo; lg.part_hi = c->d_ls_part_hi;
     lg.n_long = c->hg.long_segs.n_long(); lg.long_row = c->d_ls_row; lg.long_part_ptr = c->d_ls_ptr;
     lg.side = c->side;
-    lg.mean_len = (int)(c->hg.nnz / (c->hg.n_seg > 0 ? c->hg.n_seg : 1));
+    const int64_t n1 = (int64_t)c->hg.seg1_pos.size(), nm = (int64_t)c->hg.segm_pos.size();
+    lg.mean_len = (int)((c->hg.nnz - n1) / (nm > 0 ? nm : 1));
     return lg;
 }
 
@@ -322,6 +331,17 @@ void aggregate(cadmm_ctx* c, const float* X, float* Y, int width, const SpmmEpil
               launch_spmm(c->stream, c->d_row_ptr, c->d_row_ptr + 1, c->d_col, c->d_val, X, Y, c->hg.N, width, epi,
                           long_rows_of(c));
           });
+}
+
+// P_{(i,c)} = sum over the entries of row i in community c of A~_ij V_j, one output row per segment, in the
+// (community, row) order: the segments with several entries as a row list, those with one entry as scaled copies.
+void aggregate_segments(cadmm_ctx* c, const float* V, float* P, int width) {
+    timed(c, P_SPMM_SEG, spmm_bytes(c, c->hg.n_seg, width, 0), 2.0 * (double)c->hg.nnz * width, [&] {
+        launch_spmm(c->stream, c->d_segm_ptr, c->d_segm_end, c->d_segc_col, c->d_segc_val, V, P,
+                    (int64_t)c->hg.segm_pos.size(), width, SpmmEpilogue(), long_segs_of(c), c->d_segm_pos);
+        launch_spmm_single(c->stream, c->d_seg1_pos, c->d_seg1_col, c->d_seg1_val, V, P, (int64_t)c->hg.seg1_pos.size(),
+                           width);
+    });
 }
 
 bool t1_reusable(const cadmm_ctx* c) { return c->t1_age >= 0 && c->t1_age < c->t1_refresh; }
@@ -500,10 +520,7 @@ void z_update_hidden(cadmm_ctx* c, int l) {
             });
         else
             gemm_nn(c, c->tmpB, c->W[l + 1], c->tmpV, N, Cl, Cn);                    // grad W_{l+1}
-        timed(c, P_SPMM_SEG, spmm_bytes(c, c->hg.n_seg, Cn, 0), 2.0 * (double)c->hg.nnz * Cn, [&] {
-            launch_spmm(s, c->d_segc_lo, c->d_segc_hi, c->d_col, c->d_val, c->tmpV, c->P, c->hg.n_seg, Cn,
-                        SpmmEpilogue(), long_segs_of(c));                            // A~_{r,m} (grad W) per segment
-        });
+        aggregate_segments(c, c->tmpV, c->P, Cn);                                    // A~_{r,m} (grad W) per segment
         launch_reset_units(s, units, M, sp);
         ZTrialArgs a;
         a.chunk_unit = c->d_chunk_unit; a.chunk_kind = c->d_chunk_kind;
@@ -754,8 +771,14 @@ int cadmm_set_workspace(cadmm_ctx* c, void* dev_ptr, size_t bytes) {
     HIP_TRY(c, upload(s, c->d_val, g.val));
     HIP_TRY(c, upload(s, c->d_row_comm, g.row_comm));
     HIP_TRY(c, upload(s, c->d_perm, g.perm));
-    HIP_TRY(c, upload(s, c->d_segc_lo, g.segc_lo));
-    HIP_TRY(c, upload(s, c->d_segc_hi, g.segc_hi));
+    HIP_TRY(c, upload(s, c->d_segc_col, g.segc_col));
+    HIP_TRY(c, upload(s, c->d_segc_val, g.segc_val));
+    HIP_TRY(c, upload(s, c->d_seg1_pos, g.seg1_pos));
+    HIP_TRY(c, upload(s, c->d_seg1_col, g.seg1_col));
+    HIP_TRY(c, upload(s, c->d_seg1_val, g.seg1_val));
+    HIP_TRY(c, upload(s, c->d_segm_ptr, g.segm_ptr));
+    HIP_TRY(c, upload(s, c->d_segm_end, g.segm_end));
+    HIP_TRY(c, upload(s, c->d_segm_pos, g.segm_pos));
     HIP_TRY(c, upload(s, c->d_segc_row, g.segc_row));
     std::vector<int32_t> cu, ck, cb, ce;
     for (const Chunk& ch : g.chunks) { cu.push_back(ch.unit); ck.push_back(ch.kind); cb.push_back(ch.begin); ce.push_back(ch.end); }
@@ -1118,10 +1141,7 @@ int cadmm_op_aggregate_segments(cadmm_ctx* c, const float* V, int32_t width, flo
     if (!c || !V || !P || width < 1) return CADMM_EINVAL;
     if (!c->has_ws) return fail(c, CADMM_EORDER, "set_workspace first");
     if (width > max_of(c->C, 0, c->L)) return fail(c, CADMM_ENOMEM, "width exceeds the widest layer the workspace was sized for");
-    timed(c, P_SPMM_SEG, spmm_bytes(c, c->hg.n_seg, width, 0), 2.0 * (double)c->hg.nnz * width, [&] {
-        launch_spmm(c->stream, c->d_segc_lo, c->d_segc_hi, c->d_col, c->d_val, V, P, c->hg.n_seg, width, SpmmEpilogue(),
-                    long_segs_of(c));
-    });
+    aggregate_segments(c, V, P, width);
     return check_launch(c, "op_aggregate_segments");
 }
 

@@ -182,26 +182,54 @@ std::string build_host_graph(HostGraph& g, int64_t N, int64_t n_edges, const int
     for (int64_t s = 0; s < g.n_seg; ++s) g.segc_comm_ptr[g.seg_comm[(size_t)s] + 1]++;
     for (int32_t m = 0; m < M; ++m) g.segc_comm_ptr[m + 1] += g.segc_comm_ptr[m];
     g.segc_order.resize((size_t)g.n_seg);
-    g.segc_lo.resize((size_t)g.n_seg);
-    g.segc_hi.resize((size_t)g.n_seg);
     g.segc_row.resize((size_t)g.n_seg);
     {
         std::vector<int64_t> cur(g.segc_comm_ptr.begin(), g.segc_comm_ptr.end() - 1);
         for (int64_t s = 0; s < g.n_seg; ++s) {
             int64_t j = cur[g.seg_comm[(size_t)s]]++;
             g.segc_order[(size_t)j] = s;
-            g.segc_lo[(size_t)j] = g.seg_ptr[(size_t)s];
-            g.segc_hi[(size_t)j] = g.seg_ptr[(size_t)s + 1];
             g.segc_row[(size_t)j] = g.seg_row[(size_t)s];
         }
     }
+    // The entries once more, in this order: a pass over the segments of a community then reads its column
+    // indices and values front to back instead of one short piece out of every row.
+    g.segc_ptr.assign((size_t)g.n_seg + 1, 0);
+    for (int64_t j = 0; j < g.n_seg; ++j) {
+        const int64_t s = g.segc_order[(size_t)j];
+        g.segc_ptr[(size_t)j + 1] = g.segc_ptr[(size_t)j] + (g.seg_ptr[(size_t)s + 1] - g.seg_ptr[(size_t)s]);
+    }
+    g.segc_col.resize((size_t)g.nnz);
+    g.segc_val.resize((size_t)g.nnz);
+    parallel_rows(g.n_seg, [&](int64_t j0, int64_t j1) {
+        for (int64_t j = j0; j < j1; ++j) {
+            const int64_t s = g.segc_order[(size_t)j];
+            const int64_t from = g.seg_ptr[(size_t)s], n = g.seg_ptr[(size_t)s + 1] - from, to = g.segc_ptr[(size_t)j];
+            for (int64_t k = 0; k < n; ++k) {
+                g.segc_col[(size_t)(to + k)] = g.col[(size_t)(from + k)];
+                g.segc_val[(size_t)(to + k)] = g.val[(size_t)(from + k)];
+            }
+        }
+    });
 
     g.row_seg_ptr.assign(seg_cnt.begin(), seg_cnt.end());
     g.seg_pos.resize((size_t)g.n_seg);
     for (int64_t j = 0; j < g.n_seg; ++j) g.seg_pos[(size_t)g.segc_order[(size_t)j]] = (int32_t)j;
 
     split_long(g.long_rows, g.row_ptr.data(), g.row_ptr.data() + 1, N);
-    split_long(g.long_segs, g.segc_lo.data(), g.segc_hi.data(), g.n_seg);
+    for (int64_t j = 0; j < g.n_seg; ++j) {
+        const int64_t lo = g.segc_ptr[(size_t)j], hi = g.segc_ptr[(size_t)j + 1];
+        if (hi - lo == 1) {
+            g.seg1_pos.push_back((int32_t)j);
+            g.seg1_col.push_back(g.segc_col[(size_t)lo]);
+            g.seg1_val.push_back(g.segc_val[(size_t)lo]);
+        } else {
+            g.segm_ptr.push_back(lo);
+            g.segm_end.push_back(hi);
+            g.segm_pos.push_back((int32_t)j);
+        }
+    }
+    split_long(g.long_segs, g.segm_ptr.data(), g.segm_end.data(), (int64_t)g.segm_ptr.size());
+    for (auto& r : g.long_segs.long_row) r = g.segm_pos[(size_t)r];
 
     // reduction chunks: for every community its own rows, then its segments
     g.unit_chunk_ptr.assign(M + 1, 0);

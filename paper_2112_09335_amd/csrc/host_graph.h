@@ -46,14 +46,23 @@ struct HostGraph {
     std::vector<uint8_t> neighbour;     // [M*M]
     // segments, (community, row) order
     std::vector<int64_t> segc_order;    // [n_seg] index into the (row, community) order
-    std::vector<int64_t> segc_lo;       // [n_seg] first entry in col/val
-    std::vector<int64_t> segc_hi;       // [n_seg] one past the last entry
+    std::vector<int64_t> segc_ptr;      // [n_seg+1] entry range of a segment in segc_col / segc_val
+    std::vector<int32_t> segc_col;      // [nnz] the entries of col, regrouped so that this order reads them front to back
+    std::vector<float>   segc_val;      // [nnz] likewise for val
     std::vector<int32_t> segc_row;      // [n_seg]
     std::vector<int64_t> segc_comm_ptr; // [M+1]
     std::vector<int64_t> row_seg_ptr;   // [N+1] segments of a row in the (row, community) order
     std::vector<int32_t> seg_pos;       // [n_seg] position of that segment in the (community, row) order
+    // the same segments by length, each list in (community, row) order: a segment with a single entry is a
+    // scaled copy of one gathered row; the others are aggregated like rows
+    std::vector<int32_t> seg1_pos;      // [n_seg1] position of the segment in the (community, row) order
+    std::vector<int32_t> seg1_col;      // [n_seg1] its entry
+    std::vector<float>   seg1_val;      // [n_seg1]
+    std::vector<int64_t> segm_ptr;      // [n_segm] first entry in segc_col / segc_val
+    std::vector<int64_t> segm_end;      // [n_segm] one past the last
+    std::vector<int32_t> segm_pos;      // [n_segm] position of the segment in the (community, row) order
     LongRows long_rows;                 // of the CSR rows
-    LongRows long_segs;                 // of the segments in (community, row) order
+    LongRows long_segs;                 // of the segm list; long_row holds the segment's position, not its list index
     // reduction chunks for the Z search, grouped by community
     std::vector<Chunk>   chunks;
     std::vector<int32_t> unit_chunk_ptr; // [M+1]

@@ -28,10 +28,15 @@ struct SpmmLong {
     const int32_t* long_row = nullptr;
     const int32_t* long_part_ptr = nullptr;
     float* side = nullptr;
+    int xcd_remap = -1;              // 1 / 0: XCD k walks the k-th eighth of the rows / plain order; -1: the global setting
 };
+// Row r of the list goes to row out_index[r] of Y (to row r if out_index is null; the epilogue needs null).
 void launch_spmm(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32_t* col, const float* val,
                  const float* X, float* Y, int64_t nrows, int width, const SpmmEpilogue& epi,
-                 const SpmmLong& lg);
+                 const SpmmLong& lg, const int32_t* out_index = nullptr);
+// Y[pos[k], :] = val[k] * X[col[k], :] for k < n: the output rows that have a single entry.
+void launch_spmm_single(hipStream_t s, const int32_t* pos, const int32_t* col, const float* val, const float* X,
+                        float* Y, int64_t n, int width);
 // columns of the feature matrix handled per launch (0 = all); smaller tiles keep a community's share of
 // the gathered matrix inside one XCD's L2 at the price of re-reading the entries once per tile
 void set_spmm_tile_cols(int cols);

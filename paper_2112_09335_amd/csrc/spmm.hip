@@ -50,15 +50,26 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(
     const int64_t* __restrict__ part_hi, int64_t nrows, int64_t nparts, const int32_t* __restrict__ col,
     const float* __restrict__ val, const float* __restrict__ X, float* __restrict__ Y, float* __restrict__ side,
     int width, int lpr_log2, int gpr_log2, int col0, int col1, int max_len, int xcd_remap,
-    const float* __restrict__ Zl, const float* __restrict__ Tl, float nu) {
-    // optional XCD-aware renumbering: gridDim.x is a multiple of 8
-    const int per_xcd = gridDim.x >> 3;
-    const int64_t lb = xcd_remap ? (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3) : (int64_t)blockIdx.x;
+    const float* __restrict__ Zl, const float* __restrict__ Tl, float nu, const int32_t* __restrict__ out_index,
+    int64_t part_blocks) {
+    // The first part_blocks workgroups (a multiple of 8) take the parts of split rows, the longest pieces of work,
+    // so that they do not form the tail of the launch; the other workgroups cover the rows.  Optional XCD-aware
+    // renumbering of the latter: XCD k (blockIdx mod 8) walks the k-th contiguous eighth of the rows.
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int span_log2 = lpr_log2 + gpr_log2;          // lanes that share one output row
-    const int64_t vrow = ((lb * 4 + wave) << (6 - span_log2)) + (lane >> span_log2);
-    if (vrow >= nrows + nparts) return;                 // uniform over the row's lane span
+    int64_t vrow;
+    if ((int64_t)blockIdx.x < part_blocks) {
+        vrow = (((int64_t)blockIdx.x * 4 + wave) << (6 - span_log2)) + (lane >> span_log2);
+        if (vrow >= nparts) return;
+        vrow += nrows;
+    } else {
+        int64_t lb = (int64_t)blockIdx.x - part_blocks;
+        const int64_t row_blocks = (int64_t)gridDim.x - part_blocks;     // a multiple of 8
+        if (xcd_remap) lb = (lb & 7) * (row_blocks >> 3) + (lb >> 3);
+        vrow = ((lb * 4 + wave) << (6 - span_log2)) + (lane >> span_log2);
+        if (vrow >= nrows) return;                      // uniform over the row's lane span
+    }
     const int lpr = 1 << lpr_log2;
     const int gpr = 1 << gpr_log2;
     const int grp = (lane >> lpr_log2) & (gpr - 1);
@@ -72,8 +83,8 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(
     if (!is_part) {
         p = lo[vrow];
         e = hi[vrow];
-        if (max_len > 0 && e - p > max_len) return;     // split row: its parts follow in the same launch
-        dst = Y + vrow * (int64_t)width;
+        if (max_len > 0 && e - p > max_len) return;     // split row: the first workgroups take its parts
+        dst = Y + (out_index ? (int64_t)out_index[vrow] : vrow) * (int64_t)width;
     } else {
         p = part_lo[vrow - nrows];
         e = part_hi[vrow - nrows];
@@ -86,7 +97,16 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[r][v] = 0.f;
 
-    // the groups of a row take entries p+grp, p+grp+gpr, ...; U of them in flight per group
+    // the groups of a row take entries p+grp, p+grp+gpr, ...; U of them in flight per group.  Every load is
+    // unconditional: a slot past the end of the row reads the row's last entry again with weight zero, and a lane
+    // past the last column reads the last columns again without storing them.  (Loads under a branch would make
+    // the compiler wait for each gather before it issues the next.)
+    int ccl[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int cc = cbase + r * cstride;
+        ccl[r] = cc < col1 ? cc : col1 - VEC;
+    }
     for (int64_t q = p + grp; q < e; q += U * gpr) {
         int32_t c[U];
         float a[U];
@@ -94,22 +114,16 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(
         for (int u = 0; u < U; ++u) {
             const int64_t qu = q + u * gpr;
             const bool ok = qu < e;
-            c[u] = ok ? col[qu] : -1;
-            a[u] = ok ? val[qu] : 0.f;
+            const int64_t qc = ok ? qu : e - 1;
+            c[u] = col[qc];
+            const float av = val[qc];
+            a[u] = ok ? av : 0.f;
         }
         float x[U][R][VEC];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
+        for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const int cc = cbase + r * cstride;
-                if (c[u] >= 0 && cc < col1) load_vec<VEC>(x[u][r], X + (int64_t)c[u] * width + cc);
-                else {
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) x[u][r][v] = 0.f;
-                }
-            }
-        }
+            for (int r = 0; r < R; ++r) load_vec<VEC>(x[u][r], X + (int64_t)c[u] * width + ccl[r]);
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -140,6 +154,43 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(
                 }
             }
             store_vec<VEC>(dst + cc, acc[r]);
+        }
+    }
+}
+
+// Output rows with a single entry (most (row, neighbour community) segments of a sparse graph): row pos[k] of Y is
+// val[k] times row col[k] of X.  A lane group takes kSingleBatch consecutive k, so that their index loads, their
+// gathers and their stores are in flight together; the lists are read front to back.
+constexpr int kSingleBatch = 4;
+template <int VEC>
+__global__ __launch_bounds__(256) void spmm_single_kernel(const int32_t* __restrict__ pos,
+                                                          const int32_t* __restrict__ col,
+                                                          const float* __restrict__ val, const float* __restrict__ X,
+                                                          float* __restrict__ Y, int64_t n, int width, int lpr_log2) {
+    const int lpr = 1 << lpr_log2;
+    const int sub = threadIdx.x & (lpr - 1);
+    const int64_t group = (int64_t)blockIdx.x * (256 >> lpr_log2) + (threadIdx.x >> lpr_log2);
+    const int64_t k0 = group * kSingleBatch;
+    if (k0 >= n) return;
+    int32_t o[kSingleBatch], c[kSingleBatch];
+    float a[kSingleBatch];
+#pragma unroll
+    for (int j = 0; j < kSingleBatch; ++j) {
+        const int64_t k = k0 + j < n ? k0 + j : n - 1;
+        o[j] = pos[k];
+        c[j] = col[k];
+        a[j] = val[k];
+    }
+    for (int cc = sub * VEC; cc < width; cc += lpr * VEC) {
+        float x[kSingleBatch][VEC];
+#pragma unroll
+        for (int j = 0; j < kSingleBatch; ++j) load_vec<VEC>(x[j], X + (int64_t)c[j] * width + cc);
+#pragma unroll
+        for (int j = 0; j < kSingleBatch; ++j) {
+            if (k0 + j >= n) break;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) x[j][v] *= a[j];
+            store_vec<VEC>(Y + (int64_t)o[j] * width + cc, x[j]);
         }
     }
 }
@@ -186,15 +237,17 @@ __global__ __launch_bounds__(256) void spmm_combine_kernel(const float* __restri
 template <int VEC, int R>
 void launch_cfg(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32_t* col, const float* val,
                 const float* X, float* Y, int64_t nrows, int width, int lpr_log2, int gpr_log2, int col0, int col1,
-                const SpmmEpilogue& epi, const SpmmLong& lg, bool split) {
+                const SpmmEpilogue& epi, const SpmmLong& lg, bool split, const int32_t* out_index) {
     const int64_t nparts = split ? lg.n_parts : 0;
     const int rows_per_block = 4 * (64 >> (lpr_log2 + gpr_log2));
-    int64_t nb = (nrows + nparts + rows_per_block - 1) / rows_per_block;
-    nb = (nb + 7) / 8 * 8;
+    const int64_t row_blocks = ((nrows + rows_per_block - 1) / rows_per_block + 7) / 8 * 8;
+    const int64_t part_blocks = ((nparts + rows_per_block - 1) / rows_per_block + 7) / 8 * 8;
+    const int64_t nb = part_blocks + row_blocks;
     dim3 grid((unsigned)nb), block(256);
+    const int xcd_remap = (lg.xcd_remap >= 0) ? lg.xcd_remap : g_xcd_remap;
     const int max_len = split ? lg.max_len : 0;
     const bool deep = g_unroll == 8 && R == 1;       // eight gathers in flight per lane group
-#define CADMM_SPMM(E_, U_, Z_, T_, NU_) hipLaunchKernelGGL((spmm_rows_kernel<VEC, R, E_, U_>), grid, block, 0, s, lo, hi, lg.part_lo, lg.part_hi, nrows, nparts, col, val, X, Y, lg.side, width, lpr_log2, gpr_log2, col0, col1, max_len, g_xcd_remap, Z_, T_, NU_)
+#define CADMM_SPMM(E_, U_, Z_, T_, NU_) hipLaunchKernelGGL((spmm_rows_kernel<VEC, R, E_, U_>), grid, block, 0, s, lo, hi, lg.part_lo, lg.part_hi, nrows, nparts, col, val, X, Y, lg.side, width, lpr_log2, gpr_log2, col0, col1, max_len, xcd_remap, Z_, T_, NU_, out_index, part_blocks)
     if (epi.kind == 1) { if (deep) CADMM_SPMM(1, 8, epi.Zl, epi.Tl, epi.nu); else CADMM_SPMM(1, 4, epi.Zl, epi.Tl, epi.nu); }
     else { if (deep) CADMM_SPMM(0, 8, nullptr, nullptr, 0.f); else CADMM_SPMM(0, 4, nullptr, nullptr, 0.f); }
 #undef CADMM_SPMM
@@ -202,7 +255,8 @@ void launch_cfg(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32
 
 template <int VEC>
 void launch_vec(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32_t* col, const float* val,
-                const float* X, float* Y, int64_t nrows, int width, const SpmmEpilogue& epi, const SpmmLong& lg) {
+                const float* X, float* Y, int64_t nrows, int width, const SpmmEpilogue& epi, const SpmmLong& lg,
+                const int32_t* out_index) {
     // column tiles of at most 64 lanes * VEC * 4 repeats; a smaller tile can be requested
     int tile = 64 * VEC * 4;
     if (g_tile_cols > 0 && g_tile_cols < tile) tile = (g_tile_cols + VEC - 1) / VEC * VEC;
@@ -220,9 +274,9 @@ void launch_vec(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32
         const int in_flight = (reps <= 1) ? g_unroll : 4;
         while (lpr_log2 + gpr_log2 < 6 && (in_flight << gpr_log2) < mean_len) ++gpr_log2;
         if (g_gpr_log2 >= 0) gpr_log2 = (lpr_log2 + g_gpr_log2 <= 6) ? g_gpr_log2 : 6 - lpr_log2;
-        if (reps <= 1) launch_cfg<VEC, 1>(s, lo, hi, col, val, X, Y, nrows, width, lpr_log2, gpr_log2, col0, col1, epi, lg, split);
-        else if (reps <= 2) launch_cfg<VEC, 2>(s, lo, hi, col, val, X, Y, nrows, width, lpr_log2, gpr_log2, col0, col1, epi, lg, split);
-        else launch_cfg<VEC, 4>(s, lo, hi, col, val, X, Y, nrows, width, lpr_log2, gpr_log2, col0, col1, epi, lg, split);
+        if (reps <= 1) launch_cfg<VEC, 1>(s, lo, hi, col, val, X, Y, nrows, width, lpr_log2, gpr_log2, col0, col1, epi, lg, split, out_index);
+        else if (reps <= 2) launch_cfg<VEC, 2>(s, lo, hi, col, val, X, Y, nrows, width, lpr_log2, gpr_log2, col0, col1, epi, lg, split, out_index);
+        else launch_cfg<VEC, 4>(s, lo, hi, col, val, X, Y, nrows, width, lpr_log2, gpr_log2, col0, col1, epi, lg, split, out_index);
         if (split) {
             dim3 grid((unsigned)lg.n_long), block(64);
             if (epi.kind == 1)
@@ -243,10 +297,25 @@ void set_spmm_groups_log2(int v) { g_gpr_log2 = v; }
 void set_spmm_unroll(int v) { g_unroll = (v == 8) ? 8 : 4; }
 
 void launch_spmm(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32_t* col, const float* val,
-                 const float* X, float* Y, int64_t nrows, int width, const SpmmEpilogue& epi, const SpmmLong& lg) {
+                 const float* X, float* Y, int64_t nrows, int width, const SpmmEpilogue& epi, const SpmmLong& lg,
+                 const int32_t* out_index) {
     if (nrows <= 0 || width <= 0) return;
-    if (width % 4 == 0) launch_vec<4>(s, lo, hi, col, val, X, Y, nrows, width, epi, lg);
-    else launch_vec<1>(s, lo, hi, col, val, X, Y, nrows, width, epi, lg);
+    if (width % 4 == 0) launch_vec<4>(s, lo, hi, col, val, X, Y, nrows, width, epi, lg, out_index);
+    else launch_vec<1>(s, lo, hi, col, val, X, Y, nrows, width, epi, lg, out_index);
+}
+
+void launch_spmm_single(hipStream_t s, const int32_t* pos, const int32_t* col, const float* val, const float* X,
+                        float* Y, int64_t n, int width) {
+    if (n <= 0 || width <= 0) return;
+    const int vec = (width % 4 == 0) ? 4 : 1;
+    const int lanes_needed = (width + vec - 1) / vec;
+    int lpr_log2 = 0;
+    while ((1 << lpr_log2) < lanes_needed && lpr_log2 < 6) ++lpr_log2;
+    const int64_t groups = (n + kSingleBatch - 1) / kSingleBatch;
+    const int64_t per_block = 256 >> lpr_log2;
+    const int64_t nb = (groups + per_block - 1) / per_block;
+    if (vec == 4) hipLaunchKernelGGL((spmm_single_kernel<4>), dim3((unsigned)nb), dim3(256), 0, s, pos, col, val, X, Y, n, width, lpr_log2);
+    else hipLaunchKernelGGL((spmm_single_kernel<1>), dim3((unsigned)nb), dim3(256), 0, s, pos, col, val, X, Y, n, width, lpr_log2);
 }
 
 }  // namespace cadmm
