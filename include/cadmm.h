@@ -234,8 +234,8 @@ const char* cadmm_profile_class_name(int32_t cls);
  * this many iterations (default 16; 0 = always form them anew).
  * Process-wide: "spmm_tile_cols": feature columns handled per
  * aggregation launch (0 = all at once); "spmm_xcd_remap": 1 = each XCD walks one contiguous eighth of
- * the rows, 0 = blocks in plain order (default); "spmm_groups_log2": lane groups that share one output
- * row, as a power of two (-1 = chosen from the mean row length); "spmm_unroll": gathers in flight per lane
+ * the rows of a length class (default), 0 = blocks in plain order; "spmm_groups_log2": lane groups that share one
+ * output row, as a power of two (-1 = chosen per length class of the rows); "spmm_unroll": gathers in flight per lane
  * group, 8 (default) or 4; "gemm_split": 1 = products with more than 32 result columns run on the bf16 matrix
  * cores, both operands split exactly into three bf16 parts and the six largest cross products accumulated in fp32
  * (default), 0 = on the fp32 matrix cores. */

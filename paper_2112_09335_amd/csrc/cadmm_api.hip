@@ -36,15 +36,9 @@ struct cadmm_ctx {
     char* ws = nullptr;
     size_t ws_bytes = 0;
     // graph on the device
-    int64_t* d_row_ptr = nullptr;
-    int32_t* d_col = nullptr;
-    float* d_val = nullptr;
     int32_t* d_row_comm = nullptr;
     int32_t* d_perm = nullptr;
-    int32_t* d_segc_col = nullptr;
-    float* d_segc_val = nullptr;
     int32_t* d_seg1_pos = nullptr; int32_t* d_seg1_col = nullptr; float* d_seg1_val = nullptr;
-    int64_t* d_segm_ptr = nullptr; int64_t* d_segm_end = nullptr; int32_t* d_segm_pos = nullptr;
     int32_t* d_segc_row = nullptr;
     int32_t* d_chunk_unit = nullptr;
     int32_t* d_chunk_kind = nullptr;
@@ -58,10 +52,11 @@ struct cadmm_ctx {
     int32_t* d_seg_pos = nullptr;
     std::vector<int32_t> h_labels;     // internal row order
     // split rows of the CSR row list and of the segment list; side buffer for their parts
-    int64_t* d_lr_part_lo = nullptr; int64_t* d_lr_part_hi = nullptr;
-    int32_t* d_lr_row = nullptr; int32_t* d_lr_ptr = nullptr;
-    int64_t* d_ls_part_lo = nullptr; int64_t* d_ls_part_hi = nullptr;
-    int32_t* d_ls_row = nullptr; int32_t* d_ls_ptr = nullptr;
+    struct DevSchedule {               // device copy of a RowSchedule
+        int64_t* ptr = nullptr; int32_t* out = nullptr; int32_t* col = nullptr; float* val = nullptr;
+        int64_t* part_lo = nullptr; int64_t* part_hi = nullptr; int32_t* long_row = nullptr; int32_t* long_ptr = nullptr;
+    };
+    DevSchedule d_rows, d_segs;
     float* side = nullptr;
     // state and per-layer buffers, index l = 0..L (unused slots stay null)
     std::vector<float*> Z, W, H, T, G;
@@ -152,19 +147,23 @@ size_t layout(cadmm_ctx* c, char* base) {
     const int L = c->L;
     const int64_t N = g.N;
     Bump b{base};
-    c->d_row_ptr = b.take<int64_t>(N + 1);
-    c->d_col = b.take<int32_t>(g.nnz);
-    c->d_val = b.take<float>(g.nnz);
     c->d_row_comm = b.take<int32_t>(N);
     c->d_perm = b.take<int32_t>(N);
-    c->d_segc_col = b.take<int32_t>(g.nnz);
-    c->d_segc_val = b.take<float>(g.nnz);
+    auto take_schedule = [&](cadmm_ctx::DevSchedule& d, const RowSchedule& rs) {
+        d.ptr = b.take<int64_t>(rs.ptr.size());
+        d.out = b.take<int32_t>(rs.out.size());
+        d.col = b.take<int32_t>(rs.col.size());
+        d.val = b.take<float>(rs.val.size());
+        d.part_lo = b.take<int64_t>(rs.longs.n_parts());
+        d.part_hi = b.take<int64_t>(rs.longs.n_parts());
+        d.long_row = b.take<int32_t>(rs.longs.n_long());
+        d.long_ptr = b.take<int32_t>(rs.longs.n_long() + 1);
+    };
+    take_schedule(c->d_rows, g.row_sched);
+    take_schedule(c->d_segs, g.seg_sched);
     c->d_seg1_pos = b.take<int32_t>(g.seg1_pos.size());
     c->d_seg1_col = b.take<int32_t>(g.seg1_pos.size());
     c->d_seg1_val = b.take<float>(g.seg1_pos.size());
-    c->d_segm_ptr = b.take<int64_t>(g.segm_pos.size());
-    c->d_segm_end = b.take<int64_t>(g.segm_pos.size());
-    c->d_segm_pos = b.take<int32_t>(g.segm_pos.size());
     c->d_segc_row = b.take<int32_t>(g.n_seg);
     const size_t nch = g.chunks.size();
     c->d_chunk_unit = b.take<int32_t>(nch);
@@ -177,16 +176,8 @@ size_t layout(cadmm_ctx* c, char* base) {
     c->d_row_seg_ptr = b.take<int64_t>(N + 1);
     c->d_seg_comm = b.take<int32_t>(g.n_seg);
     c->d_seg_pos = b.take<int32_t>(g.n_seg);
-    c->d_lr_part_lo = b.take<int64_t>(g.long_rows.n_parts());
-    c->d_lr_part_hi = b.take<int64_t>(g.long_rows.n_parts());
-    c->d_lr_row = b.take<int32_t>(g.long_rows.n_long());
-    c->d_lr_ptr = b.take<int32_t>(g.long_rows.n_long() + 1);
-    c->d_ls_part_lo = b.take<int64_t>(g.long_segs.n_parts());
-    c->d_ls_part_hi = b.take<int64_t>(g.long_segs.n_parts());
-    c->d_ls_row = b.take<int32_t>(g.long_segs.n_long());
-    c->d_ls_ptr = b.take<int32_t>(g.long_segs.n_long() + 1);
     {
-        const int64_t np_ = g.long_rows.n_parts() > g.long_segs.n_parts() ? g.long_rows.n_parts() : g.long_segs.n_parts();
+        const int64_t np_ = g.row_sched.longs.n_parts() > g.seg_sched.longs.n_parts() ? g.row_sched.longs.n_parts() : g.seg_sched.longs.n_parts();
         c->side = b.take<float>((size_t)np_ * max_of(c->C, 0, L));
     }
     c->Z.assign(L + 1, nullptr);
@@ -281,24 +272,14 @@ void timed(cadmm_ctx* c, int cls, double bytes, double flops, F body) {
     }
 }
 
-SpmmLong long_rows_of(const cadmm_ctx* c) {
+SpmmLong schedule_of(const cadmm_ctx* c, const cadmm_ctx::DevSchedule& d, const RowSchedule& rs) {
     SpmmLong lg;
     lg.max_len = kSplitThreshold;
-    lg.n_parts = c->hg.long_rows.n_parts(); lg.part_lo = c->d_lr_part_lo; lg.part_hi = c->d_lr_part_hi;
-    lg.n_long = c->hg.long_rows.n_long(); lg.long_row = c->d_lr_row; lg.long_part_ptr = c->d_lr_ptr;
+    lg.n_parts = rs.longs.n_parts(); lg.part_lo = d.part_lo; lg.part_hi = d.part_hi;
+    lg.n_long = rs.longs.n_long(); lg.long_row = d.long_row; lg.long_part_ptr = d.long_ptr;
     lg.side = c->side;
-    lg.mean_len = (int)(c->hg.nnz / (c->hg.N > 0 ? c->hg.N : 1));
-    return lg;
-}
-
-SpmmLong long_segs_of(const cadmm_ctx* c) {
-    SpmmLong lg;
-    lg.max_len = kSplitThreshold;
-    lg.n_parts = c->hg.long_segs.n_parts(); lg.part_lo = c->d_ls_part_lo; lg.part_hi = c->d_ls_part_hi;
-    lg.n_long = c->hg.long_segs.n_long(); lg.long_row = c->d_ls_row; lg.long_part_ptr = c->d_ls_ptr;
-    lg.side = c->side;
-    const int64_t n1 = (int64_t)c->hg.seg1_pos.size(), nm = (int64_t)c->hg.segm_pos.size();
-    lg.mean_len = (int)((c->hg.nnz - n1) / (nm > 0 ? nm : 1));
+    lg.mean_len = (int)((int64_t)rs.col.size() / (rs.n_rows() > 0 ? rs.n_rows() : 1));
+    lg.class_start = rs.class_start;
     return lg;
 }
 
@@ -328,8 +309,8 @@ SearchParams search_params(const cadmm_ctx* c) {
 void aggregate(cadmm_ctx* c, const float* X, float* Y, int width, const SpmmEpilogue& epi) {
     timed(c, epi.kind ? P_SPMM_GRADZ : P_SPMM, spmm_bytes(c, c->hg.N, width, epi.kind ? 2 : 0),
           2.0 * (double)c->hg.nnz * width, [&] {
-              launch_spmm(c->stream, c->d_row_ptr, c->d_row_ptr + 1, c->d_col, c->d_val, X, Y, c->hg.N, width, epi,
-                          long_rows_of(c));
+              launch_spmm(c->stream, c->d_rows.ptr, c->d_rows.ptr + 1, c->d_rows.col, c->d_rows.val, X, Y,
+                          c->hg.row_sched.n_rows(), width, epi, schedule_of(c, c->d_rows, c->hg.row_sched), c->d_rows.out);
           });
 }
 
@@ -337,8 +318,8 @@ void aggregate(cadmm_ctx* c, const float* X, float* Y, int width, const SpmmEpil
 // (community, row) order: the segments with several entries as a row list, those with one entry as scaled copies.
 void aggregate_segments(cadmm_ctx* c, const float* V, float* P, int width) {
     timed(c, P_SPMM_SEG, spmm_bytes(c, c->hg.n_seg, width, 0), 2.0 * (double)c->hg.nnz * width, [&] {
-        launch_spmm(c->stream, c->d_segm_ptr, c->d_segm_end, c->d_segc_col, c->d_segc_val, V, P,
-                    (int64_t)c->hg.segm_pos.size(), width, SpmmEpilogue(), long_segs_of(c), c->d_segm_pos);
+        launch_spmm(c->stream, c->d_segs.ptr, c->d_segs.ptr + 1, c->d_segs.col, c->d_segs.val, V, P,
+                    c->hg.seg_sched.n_rows(), width, SpmmEpilogue(), schedule_of(c, c->d_segs, c->hg.seg_sched), c->d_segs.out);
         launch_spmm_single(c->stream, c->d_seg1_pos, c->d_seg1_col, c->d_seg1_val, V, P, (int64_t)c->hg.seg1_pos.size(),
                            width);
     });
@@ -766,19 +747,24 @@ int cadmm_set_workspace(cadmm_ctx* c, void* dev_ptr, size_t bytes) {
     c->ws_bytes = need;
     const HostGraph& g = c->hg;
     hipStream_t s = c->stream;
-    HIP_TRY(c, upload(s, c->d_row_ptr, g.row_ptr));
-    HIP_TRY(c, upload(s, c->d_col, g.col));
-    HIP_TRY(c, upload(s, c->d_val, g.val));
     HIP_TRY(c, upload(s, c->d_row_comm, g.row_comm));
     HIP_TRY(c, upload(s, c->d_perm, g.perm));
-    HIP_TRY(c, upload(s, c->d_segc_col, g.segc_col));
-    HIP_TRY(c, upload(s, c->d_segc_val, g.segc_val));
+    auto upload_schedule = [&](const cadmm_ctx::DevSchedule& d, const RowSchedule& rs) -> hipError_t {
+        hipError_t e;
+        if ((e = upload(s, d.ptr, rs.ptr)) != hipSuccess) return e;
+        if ((e = upload(s, d.out, rs.out)) != hipSuccess) return e;
+        if ((e = upload(s, d.col, rs.col)) != hipSuccess) return e;
+        if ((e = upload(s, d.val, rs.val)) != hipSuccess) return e;
+        if ((e = upload(s, d.part_lo, rs.longs.part_lo)) != hipSuccess) return e;
+        if ((e = upload(s, d.part_hi, rs.longs.part_hi)) != hipSuccess) return e;
+        if ((e = upload(s, d.long_row, rs.longs.long_row)) != hipSuccess) return e;
+        return upload(s, d.long_ptr, rs.longs.long_part_ptr);
+    };
+    HIP_TRY(c, upload_schedule(c->d_rows, g.row_sched));
+    HIP_TRY(c, upload_schedule(c->d_segs, g.seg_sched));
     HIP_TRY(c, upload(s, c->d_seg1_pos, g.seg1_pos));
     HIP_TRY(c, upload(s, c->d_seg1_col, g.seg1_col));
     HIP_TRY(c, upload(s, c->d_seg1_val, g.seg1_val));
-    HIP_TRY(c, upload(s, c->d_segm_ptr, g.segm_ptr));
-    HIP_TRY(c, upload(s, c->d_segm_end, g.segm_end));
-    HIP_TRY(c, upload(s, c->d_segm_pos, g.segm_pos));
     HIP_TRY(c, upload(s, c->d_segc_row, g.segc_row));
     std::vector<int32_t> cu, ck, cb, ce;
     for (const Chunk& ch : g.chunks) { cu.push_back(ch.unit); ck.push_back(ch.kind); cb.push_back(ch.begin); ce.push_back(ch.end); }
@@ -790,14 +776,6 @@ int cadmm_set_workspace(cadmm_ctx* c, void* dev_ptr, size_t bytes) {
     HIP_TRY(c, upload(s, c->d_row_seg_ptr, g.row_seg_ptr));
     HIP_TRY(c, upload(s, c->d_seg_comm, g.seg_comm));
     HIP_TRY(c, upload(s, c->d_seg_pos, g.seg_pos));
-    HIP_TRY(c, upload(s, c->d_lr_part_lo, g.long_rows.part_lo));
-    HIP_TRY(c, upload(s, c->d_lr_part_hi, g.long_rows.part_hi));
-    HIP_TRY(c, upload(s, c->d_lr_row, g.long_rows.long_row));
-    HIP_TRY(c, upload(s, c->d_lr_ptr, g.long_rows.long_part_ptr));
-    HIP_TRY(c, upload(s, c->d_ls_part_lo, g.long_segs.part_lo));
-    HIP_TRY(c, upload(s, c->d_ls_part_hi, g.long_segs.part_hi));
-    HIP_TRY(c, upload(s, c->d_ls_row, g.long_segs.long_row));
-    HIP_TRY(c, upload(s, c->d_ls_ptr, g.long_segs.long_part_ptr));
     HIP_TRY(c, hipMemsetAsync(c->status, 0, 4 * sizeof(int32_t), s));
     HIP_TRY(c, hipStreamSynchronize(s));     // the host vectors above must outlive the copies
     c->has_ws = true;

@@ -25,19 +25,100 @@ void parallel_rows(int64_t n, F f) {
     for (auto& x : th) x.join();
 }
 
-void split_long(LongRows& lr, const int64_t* lo, const int64_t* hi, int64_t nrows) {
-    lr = LongRows();
-    lr.long_part_ptr.push_back(0);
+// Stored class of a row with len entries (see RowSchedule): -1 = split.
+int stored_class(int64_t len) {
+    if (len > kSplitThreshold) return -1;
+    int k = 0;
+    while (k < kLengthClasses - 1 && (int64_t)(4 << k) < len) ++k;     // smallest k with 4 * 2^k >= len, at most 7
+    return kLengthClasses - 1 - k;
+}
+
+// Row r of the list has the entries [lo[r], hi[r]) of col / val and goes to output row out[r] (r if out is null).
+void make_schedule(RowSchedule& rs, int64_t nrows, const int64_t* lo, const int64_t* hi, const int32_t* out,
+                   const int32_t* col, const float* val) {
+    rs = RowSchedule();
+    int64_t count[kLengthClasses + 1] = {};
+    int64_t n_long = 0, total = 0;
     for (int64_t r = 0; r < nrows; ++r) {
-        const int64_t len = hi[r] - lo[r];
-        if (len <= kSplitThreshold) continue;
-        for (int64_t p = lo[r]; p < hi[r]; p += kSplitPart) {
-            lr.part_lo.push_back(p);
-            lr.part_hi.push_back(p + kSplitPart < hi[r] ? p + kSplitPart : hi[r]);
-        }
-        lr.long_row.push_back((int32_t)r);
-        lr.long_part_ptr.push_back((int32_t)lr.part_lo.size());
+        const int j = stored_class(hi[r] - lo[r]);
+        if (j < 0) ++n_long; else ++count[j + 1];
+        total += hi[r] - lo[r];
     }
+    for (int j = 0; j < kLengthClasses; ++j) count[j + 1] += count[j];
+    for (int j = 0; j <= kLengthClasses; ++j) rs.class_start[j] = count[j];
+    const int64_t n_sched = nrows - n_long;
+    std::vector<int64_t> src((size_t)n_sched);                 // list row of scheduled row i
+    std::vector<int64_t> long_src;
+    {
+        int64_t cur[kLengthClasses];
+        for (int j = 0; j < kLengthClasses; ++j) cur[j] = count[j];
+        for (int64_t r = 0; r < nrows; ++r) {
+            const int j = stored_class(hi[r] - lo[r]);
+            if (j < 0) long_src.push_back(r); else src[(size_t)cur[j]++] = r;
+        }
+    }
+    rs.ptr.assign((size_t)n_sched + 1, 0);
+    rs.out.resize((size_t)n_sched);
+    for (int64_t i = 0; i < n_sched; ++i) {
+        const int64_t r = src[(size_t)i];
+        rs.ptr[(size_t)i + 1] = rs.ptr[(size_t)i] + (hi[r] - lo[r]);
+        rs.out[(size_t)i] = out ? out[r] : (int32_t)r;
+    }
+    rs.col.resize((size_t)total);
+    rs.val.resize((size_t)total);
+    parallel_rows(n_sched, [&](int64_t i0, int64_t i1) {
+        for (int64_t i = i0; i < i1; ++i) {
+            const int64_t r = src[(size_t)i], to = rs.ptr[(size_t)i], n = hi[r] - lo[r];
+            for (int64_t k = 0; k < n; ++k) {
+                rs.col[(size_t)(to + k)] = col[lo[r] + k];
+                rs.val[(size_t)(to + k)] = val[lo[r] + k];
+            }
+        }
+    });
+    int64_t to = rs.ptr[(size_t)n_sched];
+    rs.longs.long_part_ptr.push_back(0);
+    for (int64_t r : long_src) {
+        const int64_t n = hi[r] - lo[r];
+        for (int64_t k = 0; k < n; ++k) {
+            rs.col[(size_t)(to + k)] = col[lo[r] + k];
+            rs.val[(size_t)(to + k)] = val[lo[r] + k];
+        }
+        for (int64_t p = to; p < to + n; p += kSplitPart) {
+            rs.longs.part_lo.push_back(p);
+            rs.longs.part_hi.push_back(p + kSplitPart < to + n ? p + kSplitPart : to + n);
+        }
+        rs.longs.long_row.push_back(out ? out[r] : (int32_t)r);
+        rs.longs.long_part_ptr.push_back((int32_t)rs.longs.part_lo.size());
+        to += n;
+    }
+}
+
+// What the aggregation kernel relies on: every scheduled row and every part is an in-range, non-negative entry
+// range, a row sits in the class that bounds its length, outputs are in range.
+bool schedule_ok(const RowSchedule& rs, int64_t n_out) {
+    const int64_t n = rs.n_rows(), total = (int64_t)rs.col.size();
+    if ((int64_t)rs.ptr.size() != n + 1 || rs.val.size() != rs.col.size()) return false;
+    if (rs.class_start[0] != 0 || rs.class_start[kLengthClasses] != n) return false;
+    for (int j = 0; j < kLengthClasses; ++j) {
+        if (rs.class_start[j] > rs.class_start[j + 1]) return false;
+        const int64_t cap = j == 0 ? kSplitThreshold : (int64_t)(4 << (kLengthClasses - 1 - j));
+        for (int64_t i = rs.class_start[j]; i < rs.class_start[j + 1]; ++i) {
+            const int64_t len = rs.ptr[(size_t)i + 1] - rs.ptr[(size_t)i];
+            if (len < 0 || len > cap) return false;
+        }
+    }
+    if (n > 0 && (rs.ptr[0] != 0 || rs.ptr[(size_t)n] > total)) return false;
+    for (int64_t i = 0; i < n; ++i)
+        if (rs.out[(size_t)i] < 0 || rs.out[(size_t)i] >= n_out) return false;
+    const LongRows& lr = rs.longs;
+    if (lr.part_lo.size() != lr.part_hi.size() || lr.long_part_ptr.size() != lr.long_row.size() + 1) return false;
+    for (size_t p = 0; p < lr.part_lo.size(); ++p)
+        if (lr.part_lo[p] < 0 || lr.part_lo[p] >= lr.part_hi[p] || lr.part_hi[p] > total ||
+            lr.part_hi[p] - lr.part_lo[p] > kSplitPart) return false;
+    for (size_t i = 0; i < lr.long_row.size(); ++i)
+        if (lr.long_row[i] < 0 || lr.long_row[i] >= n_out || lr.long_part_ptr[i] >= lr.long_part_ptr[i + 1] ||
+            lr.long_part_ptr[i + 1] > (int32_t)lr.part_lo.size()) return false;
+    return true;
 }
 
 }  // namespace
@@ -191,45 +272,31 @@ std::string build_host_graph(HostGraph& g, int64_t N, int64_t n_edges, const int
             g.segc_row[(size_t)j] = g.seg_row[(size_t)s];
         }
     }
-    // The entries once more, in this order: a pass over the segments of a community then reads its column
-    // indices and values front to back instead of one short piece out of every row.
-    g.segc_ptr.assign((size_t)g.n_seg + 1, 0);
-    for (int64_t j = 0; j < g.n_seg; ++j) {
-        const int64_t s = g.segc_order[(size_t)j];
-        g.segc_ptr[(size_t)j + 1] = g.segc_ptr[(size_t)j] + (g.seg_ptr[(size_t)s + 1] - g.seg_ptr[(size_t)s]);
-    }
-    g.segc_col.resize((size_t)g.nnz);
-    g.segc_val.resize((size_t)g.nnz);
-    parallel_rows(g.n_seg, [&](int64_t j0, int64_t j1) {
-        for (int64_t j = j0; j < j1; ++j) {
-            const int64_t s = g.segc_order[(size_t)j];
-            const int64_t from = g.seg_ptr[(size_t)s], n = g.seg_ptr[(size_t)s + 1] - from, to = g.segc_ptr[(size_t)j];
-            for (int64_t k = 0; k < n; ++k) {
-                g.segc_col[(size_t)(to + k)] = g.col[(size_t)(from + k)];
-                g.segc_val[(size_t)(to + k)] = g.val[(size_t)(from + k)];
-            }
-        }
-    });
-
     g.row_seg_ptr.assign(seg_cnt.begin(), seg_cnt.end());
     g.seg_pos.resize((size_t)g.n_seg);
     for (int64_t j = 0; j < g.n_seg; ++j) g.seg_pos[(size_t)g.segc_order[(size_t)j]] = (int32_t)j;
 
-    split_long(g.long_rows, g.row_ptr.data(), g.row_ptr.data() + 1, N);
-    for (int64_t j = 0; j < g.n_seg; ++j) {
-        const int64_t lo = g.segc_ptr[(size_t)j], hi = g.segc_ptr[(size_t)j + 1];
-        if (hi - lo == 1) {
-            g.seg1_pos.push_back((int32_t)j);
-            g.seg1_col.push_back(g.segc_col[(size_t)lo]);
-            g.seg1_val.push_back(g.segc_val[(size_t)lo]);
-        } else {
-            g.segm_ptr.push_back(lo);
-            g.segm_end.push_back(hi);
-            g.segm_pos.push_back((int32_t)j);
+    make_schedule(g.row_sched, N, g.row_ptr.data(), g.row_ptr.data() + 1, nullptr, g.col.data(), g.val.data());
+    {
+        std::vector<int64_t> mlo, mhi;
+        std::vector<int32_t> mpos;
+        for (int64_t j = 0; j < g.n_seg; ++j) {
+            const int64_t s = g.segc_order[(size_t)j];
+            const int64_t lo = g.seg_ptr[(size_t)s], hi = g.seg_ptr[(size_t)s + 1];
+            if (hi - lo == 1) {
+                g.seg1_pos.push_back((int32_t)j);
+                g.seg1_col.push_back(g.col[(size_t)lo]);
+                g.seg1_val.push_back(g.val[(size_t)lo]);
+            } else {
+                mlo.push_back(lo);
+                mhi.push_back(hi);
+                mpos.push_back((int32_t)j);
+            }
         }
+        make_schedule(g.seg_sched, (int64_t)mpos.size(), mlo.data(), mhi.data(), mpos.data(), g.col.data(), g.val.data());
     }
-    split_long(g.long_segs, g.segm_ptr.data(), g.segm_end.data(), (int64_t)g.segm_ptr.size());
-    for (auto& r : g.long_segs.long_row) r = g.segm_pos[(size_t)r];
+
+    if (!schedule_ok(g.row_sched, N) || !schedule_ok(g.seg_sched, g.n_seg)) return "internal error: row schedule";
 
     // reduction chunks: for every community its own rows, then its segments
     g.unit_chunk_ptr.assign(M + 1, 0);

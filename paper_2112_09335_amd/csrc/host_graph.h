@@ -29,6 +29,23 @@ struct LongRows {
 constexpr int kSplitThreshold = 384;   // rows with more entries are split ...
 constexpr int kSplitPart = 256;        // ... into parts of at most this many entries
 
+// A row list laid out for the aggregation kernel.  The rows that are not split are grouped into kLengthClasses
+// length classes, the longest class first, in the list's order inside a class: stored class j holds the rows
+// with at most 4 * 2^(kLengthClasses-1-j) entries that fit no later class (stored class 0: everything longer, up to
+// the split threshold).  A launch can then give every class as many lanes per row as its rows can use, so that
+// few lanes of a gather instruction stay idle.  The entries are copied in the same order, those of the split
+// rows after them, so that a launch reads col and val front to back.
+constexpr int kLengthClasses = 8;
+struct RowSchedule {
+    std::vector<int64_t> ptr;                    // [n_rows+1] entries of scheduled row i: [ptr[i], ptr[i+1])
+    std::vector<int32_t> out;                    // [n_rows] output row of scheduled row i
+    std::vector<int32_t> col;                    // [entries of the list]
+    std::vector<float>   val;
+    int64_t class_start[kLengthClasses + 1] = {};   // scheduled rows of stored class j: [class_start[j], class_start[j+1])
+    LongRows longs;                              // split rows: part ranges in col / val, long_row = the output row
+    int64_t n_rows() const { return (int64_t)out.size(); }
+};
+
 struct HostGraph {
     int64_t N = 0, E = 0, nnz = 0, n_seg = 0, n_halo_rows = 0;
     int32_t M = 0;
@@ -46,23 +63,17 @@ struct HostGraph {
     std::vector<uint8_t> neighbour;     // [M*M]
     // segments, (community, row) order
     std::vector<int64_t> segc_order;    // [n_seg] index into the (row, community) order
-    std::vector<int64_t> segc_ptr;      // [n_seg+1] entry range of a segment in segc_col / segc_val
-    std::vector<int32_t> segc_col;      // [nnz] the entries of col, regrouped so that this order reads them front to back
-    std::vector<float>   segc_val;      // [nnz] likewise for val
     std::vector<int32_t> segc_row;      // [n_seg]
     std::vector<int64_t> segc_comm_ptr; // [M+1]
     std::vector<int64_t> row_seg_ptr;   // [N+1] segments of a row in the (row, community) order
     std::vector<int32_t> seg_pos;       // [n_seg] position of that segment in the (community, row) order
-    // the same segments by length, each list in (community, row) order: a segment with a single entry is a
-    // scaled copy of one gathered row; the others are aggregated like rows
+    // the same segments by length: one with a single entry is a scaled copy of one gathered row (listed in the
+    // (community, row) order); the others are aggregated like rows (seg_sched)
     std::vector<int32_t> seg1_pos;      // [n_seg1] position of the segment in the (community, row) order
     std::vector<int32_t> seg1_col;      // [n_seg1] its entry
     std::vector<float>   seg1_val;      // [n_seg1]
-    std::vector<int64_t> segm_ptr;      // [n_segm] first entry in segc_col / segc_val
-    std::vector<int64_t> segm_end;      // [n_segm] one past the last
-    std::vector<int32_t> segm_pos;      // [n_segm] position of the segment in the (community, row) order
-    LongRows long_rows;                 // of the CSR rows
-    LongRows long_segs;                 // of the segm list; long_row holds the segment's position, not its list index
+    RowSchedule row_sched;              // the CSR rows; output row = the row
+    RowSchedule seg_sched;              // the segments with several entries; output row = position in the (community, row) order
     // reduction chunks for the Z search, grouped by community
     std::vector<Chunk>   chunks;
     std::vector<int32_t> unit_chunk_ptr; // [M+1]

@@ -29,7 +29,12 @@ struct SpmmLong {
     const int32_t* long_part_ptr = nullptr;
     float* side = nullptr;
     int xcd_remap = -1;              // 1 / 0: XCD k walks the k-th eighth of the rows / plain order; -1: the global setting
+    // Host array of kSpmmClasses + 1 row indices, or null.  Rows [class_start[j], class_start[j+1]) hold at most
+    // 4 * 2^(kSpmmClasses-1-j) entries each (j = 0: any length up to max_len); each class then gets the lane groups
+    // per row that its rows can fill.  Null: one class, lane groups from mean_len.
+    const int64_t* class_start = nullptr;
 };
+constexpr int kSpmmClasses = 8;
 // Row r of the list goes to row out_index[r] of Y (to row r if out_index is null; the epilogue needs null).
 void launch_spmm(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32_t* col, const float* val,
                  const float* X, float* Y, int64_t nrows, int width, const SpmmEpilogue& epi,
@@ -40,7 +45,7 @@ void launch_spmm_single(hipStream_t s, const int32_t* pos, const int32_t* col, c
 // columns of the feature matrix handled per launch (0 = all); smaller tiles keep a community's share of
 // the gathered matrix inside one XCD's L2 at the price of re-reading the entries once per tile
 void set_spmm_tile_cols(int cols);
-// 1: every XCD walks one contiguous eighth of the rows; 0: blocks in plain order (default: measured faster)
+// 1: inside a length class every XCD walks one contiguous eighth of the rows (default); 0: blocks in plain order
 void set_spmm_xcd_remap(int on);
 // lane groups per output row as a power of two (-1 = from the mean row length)
 void set_spmm_groups_log2(int v);

@@ -2,19 +2,22 @@
 // is A~_{m,m} X_m + sum_{r in N_m} A~_{m,r} X_r; Appendix A: the same sum restricted to one
 // neighbour community per output row, the "segments").
 //
-// Layout: CSR with sorted columns in the community-contiguous numbering, so one row's entries are
-// grouped by community and a (row, community) segment is a contiguous entry range [lo, hi).
+// Layout: a row list (the CSR rows, or the (row, community) segments with several entries) laid out by the host
+// for this kernel: rows grouped into length classes, the longest class first and community-contiguous inside a
+// class, with a copy of the column indices and values in that order and the output row of every list row.
 // Features are row-major fp32.
 //
 // Mapping: a group of LPR lanes (a power of two, up to the 64-lane wavefront) reads one gathered
 // neighbour row with one fully coalesced VEC*4-byte load per lane and keeps VEC*R accumulators per lane.
 // GPR such groups share one output row and take its entries round-robin, eight (or four) entries in flight per
-// group; their partial sums are added by a wavefront-level xor-shuffle reduction.  GPR follows the mean
-// row length, so short rows (segments) pack several rows into a wavefront and long rows spread over it.
-// Rows beyond a length threshold (power-law hubs) are cut into parts that run as extra rows of the same
-// launch into a side buffer; a small kernel adds a row's parts in order.  Everything is order-fixed:
-// no atomics, results are reproducible.  The bound is the L2 / HBM traffic of the gathers.
-// Blocks can be renumbered so that each XCD (blockIdx mod 8) walks one contiguous eighth of the rows (off by default).
+// group; their partial sums are added by a wavefront-level xor-shuffle reduction.  GPR is chosen per length
+// class so that one trip of the entry loop covers the class's longest row: short rows pack many rows into a
+// wavefront, long rows spread over it, and the rows of a wavefront need the same number of trips.
+// Rows beyond a length threshold (power-law hubs) are cut into parts that run first in the same launch, into a
+// side buffer; a small kernel adds a row's parts in order.  Segments with a single entry are scaled copies of a
+// gathered row and have a kernel of their own.  Everything is order-fixed: no atomics, results are reproducible.
+// The bound is the L2 / fabric traffic of the gathers.  Inside a class XCD k (blockIdx mod 8) walks the k-th
+// contiguous eighth of the rows (a few communities), so that the rows it gathers stay in its L2.
 #include "kernels.h"
 
 namespace cadmm {
@@ -44,31 +47,48 @@ __device__ __forceinline__ void store_vec(float* p, const float (&src)[VEC]) {
     }
 }
 
+// Which rows a workgroup takes: class j covers the rows [row_start[j], row_start[j+1]) with 2^g[j] lane groups per
+// row, in the workgroups [block_start[j], block_start[j+1]) after those of the parts.
+struct ClassMap {
+    int n;
+    int part_g;
+    int g[kSpmmClasses];
+    long long row_start[kSpmmClasses + 1];
+    long long block_start[kSpmmClasses + 1];
+};
+
 template <int VEC, int R, int EPI, int U>
 __global__ __launch_bounds__(256) void spmm_rows_kernel(
     const int64_t* __restrict__ lo, const int64_t* __restrict__ hi, const int64_t* __restrict__ part_lo,
     const int64_t* __restrict__ part_hi, int64_t nrows, int64_t nparts, const int32_t* __restrict__ col,
     const float* __restrict__ val, const float* __restrict__ X, float* __restrict__ Y, float* __restrict__ side,
-    int width, int lpr_log2, int gpr_log2, int col0, int col1, int max_len, int xcd_remap,
+    int width, int lpr_log2, ClassMap cm, int col0, int col1, int max_len, int xcd_remap,
     const float* __restrict__ Zl, const float* __restrict__ Tl, float nu, const int32_t* __restrict__ out_index,
     int64_t part_blocks) {
     // The first part_blocks workgroups (a multiple of 8) take the parts of split rows, the longest pieces of work,
-    // so that they do not form the tail of the launch; the other workgroups cover the rows.  Optional XCD-aware
-    // renumbering of the latter: XCD k (blockIdx mod 8) walks the k-th contiguous eighth of the rows.
+    // so that they do not form the tail of the launch; then come the workgroups of each length class in turn (each
+    // count a multiple of 8).  Optional XCD-aware renumbering inside a class: XCD k (blockIdx mod 8) walks the
+    // k-th contiguous eighth of its rows.
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int span_log2 = lpr_log2 + gpr_log2;          // lanes that share one output row
+    int gpr_log2;
     int64_t vrow;
     if ((int64_t)blockIdx.x < part_blocks) {
+        gpr_log2 = cm.part_g;
+        const int span_log2 = lpr_log2 + gpr_log2;      // lanes that share one output row
         vrow = (((int64_t)blockIdx.x * 4 + wave) << (6 - span_log2)) + (lane >> span_log2);
         if (vrow >= nparts) return;
         vrow += nrows;
     } else {
-        int64_t lb = (int64_t)blockIdx.x - part_blocks;
-        const int64_t row_blocks = (int64_t)gridDim.x - part_blocks;     // a multiple of 8
-        if (xcd_remap) lb = (lb & 7) * (row_blocks >> 3) + (lb >> 3);
-        vrow = ((lb * 4 + wave) << (6 - span_log2)) + (lane >> span_log2);
-        if (vrow >= nrows) return;                      // uniform over the row's lane span
+        const int64_t b = (int64_t)blockIdx.x - part_blocks;
+        int j = 0;
+        while (j + 1 < cm.n && b >= cm.block_start[j + 1]) ++j;
+        gpr_log2 = cm.g[j];
+        const int span_log2 = lpr_log2 + gpr_log2;
+        int64_t lb = b - cm.block_start[j];
+        if (xcd_remap) lb = (lb & 7) * ((cm.block_start[j + 1] - cm.block_start[j]) >> 3) + (lb >> 3);
+        vrow = cm.row_start[j] + (((lb * 4 + wave) << (6 - span_log2)) + (lane >> span_log2));
+        if (vrow >= cm.row_start[j + 1]) return;        // uniform over the row's lane span
     }
     const int lpr = 1 << lpr_log2;
     const int gpr = 1 << gpr_log2;
@@ -145,7 +165,7 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(
         if (cc < col1) {
             if constexpr (EPI == 1) {
                 if (!is_part) {
-                    const int64_t o = vrow * (int64_t)width + cc;
+                    const int64_t o = (out_index ? (int64_t)out_index[vrow] : vrow) * (int64_t)width + cc;
                     float z[VEC], t[VEC];
                     load_vec<VEC>(z, Zl + o);
                     load_vec<VEC>(t, Tl + o);
@@ -196,7 +216,7 @@ __global__ __launch_bounds__(256) void spmm_single_kernel(const int32_t* __restr
 }
 
 int g_tile_cols = 0;
-int g_xcd_remap = 0;
+int g_xcd_remap = 1;
 int g_gpr_log2 = -1;      // -1: chosen from the mean row length
 int g_unroll = 8;
 
@@ -239,15 +259,49 @@ void launch_cfg(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32
                 const float* X, float* Y, int64_t nrows, int width, int lpr_log2, int gpr_log2, int col0, int col1,
                 const SpmmEpilogue& epi, const SpmmLong& lg, bool split, const int32_t* out_index) {
     const int64_t nparts = split ? lg.n_parts : 0;
-    const int rows_per_block = 4 * (64 >> (lpr_log2 + gpr_log2));
-    const int64_t row_blocks = ((nrows + rows_per_block - 1) / rows_per_block + 7) / 8 * 8;
-    const int64_t part_blocks = ((nparts + rows_per_block - 1) / rows_per_block + 7) / 8 * 8;
-    const int64_t nb = part_blocks + row_blocks;
+    constexpr int U = (R == 1) ? 8 : 4;              // gathers in flight per lane group when g_unroll allows
+    const bool deep = g_unroll == 8 && R == 1;
+    const int in_flight = deep ? U : 4;
+    const int g_max = 6 - lpr_log2;
+    ClassMap cm;
+    if (lg.class_start && g_gpr_log2 < 0) {
+        // class j holds rows of at most 4 * 2^(kSpmmClasses-1-j) entries (j = 0: up to the split threshold): the
+        // fewest lane groups whose gathers in flight cover such a row in one trip of the entry loop
+        cm.n = kSpmmClasses;
+        for (int j = 0; j < kSpmmClasses; ++j) {
+            int g = 0;
+            if (j == 0) g = g_max;
+            else while (g < g_max && (in_flight << g) < (4 << (kSpmmClasses - 1 - j))) ++g;
+            cm.g[j] = g;
+            cm.row_start[j] = lg.class_start[j];
+        }
+        cm.row_start[kSpmmClasses] = lg.class_start[kSpmmClasses];
+    } else {
+        cm.n = 1;
+        cm.g[0] = gpr_log2;
+        cm.row_start[0] = 0;
+        cm.row_start[1] = nrows;
+    }
+    cm.part_g = (g_gpr_log2 >= 0) ? gpr_log2 : g_max;
+    cm.block_start[0] = 0;
+    for (int j = 0; j < cm.n; ++j) {
+        const int64_t per_block = 4 * (64 >> (lpr_log2 + cm.g[j]));
+        const int64_t n = cm.row_start[j + 1] - cm.row_start[j];
+        cm.block_start[j + 1] = cm.block_start[j] + ((n + per_block - 1) / per_block + 7) / 8 * 8;
+    }
+    for (int j = cm.n; j < kSpmmClasses; ++j) {
+        cm.g[j] = 0;
+        cm.row_start[j + 1] = cm.row_start[cm.n];
+        cm.block_start[j + 1] = cm.block_start[cm.n];
+    }
+    const int64_t part_per_block = 4 * (64 >> (lpr_log2 + cm.part_g));
+    const int64_t part_blocks = ((nparts + part_per_block - 1) / part_per_block + 7) / 8 * 8;
+    const int64_t nb = part_blocks + cm.block_start[cm.n];
+    if (nb <= 0) return;
     dim3 grid((unsigned)nb), block(256);
     const int xcd_remap = (lg.xcd_remap >= 0) ? lg.xcd_remap : g_xcd_remap;
     const int max_len = split ? lg.max_len : 0;
-    const bool deep = g_unroll == 8 && R == 1;       // eight gathers in flight per lane group
-#define CADMM_SPMM(E_, U_, Z_, T_, NU_) hipLaunchKernelGGL((spmm_rows_kernel<VEC, R, E_, U_>), grid, block, 0, s, lo, hi, lg.part_lo, lg.part_hi, nrows, nparts, col, val, X, Y, lg.side, width, lpr_log2, gpr_log2, col0, col1, max_len, xcd_remap, Z_, T_, NU_, out_index, part_blocks)
+#define CADMM_SPMM(E_, U_, Z_, T_, NU_) hipLaunchKernelGGL((spmm_rows_kernel<VEC, R, E_, U_>), grid, block, 0, s, lo, hi, lg.part_lo, lg.part_hi, nrows, nparts, col, val, X, Y, lg.side, width, lpr_log2, cm, col0, col1, max_len, xcd_remap, Z_, T_, NU_, out_index, part_blocks)
     if (epi.kind == 1) { if (deep) CADMM_SPMM(1, 8, epi.Zl, epi.Tl, epi.nu); else CADMM_SPMM(1, 4, epi.Zl, epi.Tl, epi.nu); }
     else { if (deep) CADMM_SPMM(0, 8, nullptr, nullptr, 0.f); else CADMM_SPMM(0, 4, nullptr, nullptr, 0.f); }
 #undef CADMM_SPMM
@@ -299,7 +353,7 @@ void set_spmm_unroll(int v) { g_unroll = (v == 8) ? 8 : 4; }
 void launch_spmm(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32_t* col, const float* val,
                  const float* X, float* Y, int64_t nrows, int width, const SpmmEpilogue& epi, const SpmmLong& lg,
                  const int32_t* out_index) {
-    if (nrows <= 0 || width <= 0) return;
+    if ((nrows <= 0 && lg.n_parts <= 0) || width <= 0) return;
     if (width % 4 == 0) launch_vec<4>(s, lo, hi, col, val, X, Y, nrows, width, epi, lg, out_index);
     else launch_vec<1>(s, lo, hi, col, val, X, Y, nrows, width, epi, lg, out_index);
 }
