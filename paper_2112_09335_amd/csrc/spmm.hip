@@ -38,12 +38,16 @@ __device__ __forceinline__ void load_vec(float (&dst)[VEC], const float* p) {
     }
 }
 
+typedef float float_x4 __attribute__((ext_vector_type(4)));
+
+// results are written once and read by a later kernel: streamed past the L2's resident lines
 template <int VEC>
 __device__ __forceinline__ void store_vec(float* p, const float (&src)[VEC]) {
     if constexpr (VEC == 4) {
-        *reinterpret_cast<float4*>(p) = make_float4(src[0], src[1], src[2], src[3]);
+        float_x4 v = {src[0], src[1], src[2], src[3]};
+        __builtin_nontemporal_store(v, reinterpret_cast<float_x4*>(p));
     } else {
-        *p = src[0];
+        __builtin_nontemporal_store(src[0], p);
     }
 }
 
