@@ -33,13 +33,13 @@ MACHINE_BALANCE = MFMA_FP32_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)      # flo
 # sweeps); the summary with the commands is profiles/sweep_memory_traffic_powerlaw_dcsbm_2M.txt.
 MEASURED_TRAFFIC = {
     (4, "gemm_nn_split_kernel<2>+finish"): 5.15e9 + 2.05e9,   # H_1 gradW_1, first candidate, step on T_1 ahead of the decision
-    (4, "spmm_rows_kernel[rows]"): 3.454e9 + 0.129e9,         # width 16
-    (4, "spmm_rows_kernel[segments]"): 5.277e9 + 0.659e9,     # width 16
+    (4, "spmm_rows_kernel[rows]"): 2.927e9 + 0.131e9,         # width 16
+    (4, "spmm_rows_kernel[segments]"): 1.684e9 + 0.184e9 + 0.601e9 + 0.510e9,   # width 16: several entries + single entry
     (4, "gemm_tn_split_kernel+reduce"): 5.16e9 + 0.038e9 + 0.067e9,
     (4, "z_trial_kernel"): 6.126e9 + 0.006e9,
     (4, "z_step_kernel"): 4.297e9 + 2.048e9,
     (4, "gemm_nn_gradz_kernel"): 4.226e9 + 0.128e9,
-    (4, "t_carry_kernel"): 1.296e9 + 0.128e9,
+    (4, "t_carry_kernel"): 1.280e9 + 0.114e9,
     (4, "gemm_nn_kernel<32>"): 2.049e9 + 0.128e9,             # out[N x 16] = A[N x 256] B
     (4, "gemm_tn_kernel<32>+reduce"): 2.188e9 + 0.008e9,
     (4, "last_layer_kernel"): 0.392e9 + 0.256e9,

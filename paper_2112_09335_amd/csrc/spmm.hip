@@ -224,28 +224,42 @@ int g_xcd_remap = 1;
 int g_gpr_log2 = -1;      // -1: chosen from the mean row length
 int g_unroll = 8;
 
-// Adds the parts of every split row in part order and applies the epilogue.  One lane group per row.
+// Adds the parts of every split row and applies the epilogue.  One wavefront per row: 2^lpr_log2 lanes cover the
+// columns of the tile; where that leaves lanes over, the 64 >> lpr_log2 lane groups take the parts round-robin and
+// their sums are added by xor-shuffles, so that a hub with a hundred parts is not one chain of dependent loads.
+// The order of the additions is fixed by the part count alone.
 template <int VEC, int EPI>
-__global__ __launch_bounds__(256) void spmm_combine_kernel(const float* __restrict__ side,
-                                                           const int32_t* __restrict__ long_row,
-                                                           const int32_t* __restrict__ long_part_ptr, int64_t n_long,
-                                                           float* __restrict__ Y, int width, int col0, int col1,
-                                                           const float* __restrict__ Zl, const float* __restrict__ Tl,
-                                                           float nu) {
+__global__ __launch_bounds__(64) void spmm_combine_kernel(const float* __restrict__ side,
+                                                          const int32_t* __restrict__ long_row,
+                                                          const int32_t* __restrict__ long_part_ptr, int64_t n_long,
+                                                          float* __restrict__ Y, int width, int col0, int col1,
+                                                          const float* __restrict__ Zl, const float* __restrict__ Tl,
+                                                          float nu, int lpr_log2) {
     const int64_t i = blockIdx.x;
     if (i >= n_long) return;
     const int64_t row = long_row[i];
     const int p0 = long_part_ptr[i], p1 = long_part_ptr[i + 1];
-    for (int c = col0 + threadIdx.x * VEC; c < col1; c += blockDim.x * VEC) {
+    const int lpr = 1 << lpr_log2, groups = 64 >> lpr_log2;
+    const int sub = threadIdx.x & (lpr - 1), grp = threadIdx.x >> lpr_log2;
+    for (int cb = col0; cb < col1; cb += lpr * VEC) {           // same trip count in every lane
+        const int c = cb + sub * VEC;
+        const bool ok = c < col1;
         float acc[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
-        for (int p = p0; p < p1; ++p) {
-            float x[VEC];
-            load_vec<VEC>(x, side + (int64_t)p * width + c);
+        if (ok) {
+            for (int p = p0 + grp; p < p1; p += groups) {
+                float x[VEC];
+                load_vec<VEC>(x, side + (int64_t)p * width + c);
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) acc[v] += x[v];
+                for (int v = 0; v < VEC; ++v) acc[v] += x[v];
+            }
         }
+        for (int off = lpr; off < 64; off <<= 1) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[v] += __shfl_xor(acc[v], off, 64);
+        }
+        if (!ok || grp != 0) continue;
         const int64_t o = row * (int64_t)width + c;
         if constexpr (EPI == 1) {
             float z[VEC], t[VEC];
@@ -339,10 +353,10 @@ void launch_vec(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32
             dim3 grid((unsigned)lg.n_long), block(64);
             if (epi.kind == 1)
                 hipLaunchKernelGGL((spmm_combine_kernel<VEC, 1>), grid, block, 0, s, lg.side, lg.long_row,
-                                   lg.long_part_ptr, lg.n_long, Y, width, col0, col1, epi.Zl, epi.Tl, epi.nu);
+                                   lg.long_part_ptr, lg.n_long, Y, width, col0, col1, epi.Zl, epi.Tl, epi.nu, lpr_log2);
             else
                 hipLaunchKernelGGL((spmm_combine_kernel<VEC, 0>), grid, block, 0, s, lg.side, lg.long_row,
-                                   lg.long_part_ptr, lg.n_long, Y, width, col0, col1, nullptr, nullptr, 0.f);
+                                   lg.long_part_ptr, lg.n_long, Y, width, col0, col1, nullptr, nullptr, 0.f, lpr_log2);
         }
     }
 }
