@@ -200,6 +200,21 @@ int  cadmm_op_wgrad(cadmm_ctx* ctx, const float* A, const float* G, int64_t n, i
                     int32_t C, float* out);
 
 /*
+ * cadmm_op_wgrad for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and the same result bit for bit as
+ * cadmm_op_wgrad (out = A^T G, A device n x K, G device n x C, out device K x C, enqueued on the context's stream),
+ * but the per-chunk partial matrices of the product live in a static device array inside the library (72 MiB on every
+ * GPU the library runs on, held until the process ends) instead of the workspace, so the call works on a context
+ * that has no graph, model or workspace yet and calls no allocating routine.  Shapes whose partial matrices need more
+ * than 18 * 2^20 floats (about (1024 + tiles) * 16384 floats for tiles = ceil(K/128) * ceil(C/128) result tiles when
+ * C > 32; all widths up to 1024 x 1024 fit) return CADMM_ENOMEM.  All calls on one GPU share that array: two calls
+ * that overlap on one GPU (different streams or contexts) race; calls on one stream are ordered and safe.  Nothing in
+ * the array has to be cleared between calls: the product writes every entry the reduction reads.
+ */
+int  cadmm_op_wgrad_noalloc(cadmm_ctx* ctx, const float* A, const float* G, int64_t n, int32_t K, int32_t C,
+                            float* out);
+
+/*
  * Machine calibration for the rooflines the benchmarks quote (no counterpart in the paper).  Runs `reps` timed
  * launches (after one untimed) on the context's stream, synchronises, and returns the rate.
  *   kind 0: plain copy of `count` floats (multiple of 4) from src to dst, both device; rate = GB/s read + written.

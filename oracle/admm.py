@@ -50,15 +50,44 @@ def relu(x):
     return np.maximum(x, 0.0)
 
 
-# ReLU'(x) = 1[x > shift], shift = 0 (the reading ReLU'(0) = 0).  Tests move it by a few fp32 roundings to ask
-# what the iterate would be had a pre-activation that is zero up to rounding fallen on the other side: the
-# derivative of the penalty jumps there, so both outcomes are valid.  The W step and the Z step of one iteration
-# look at different pre-activations (before and after the W step), so each has a shift of its own.
-RELU_TIE_SHIFT = {"W": 0.0, "Z": 0.0}
+# ReLU'(x) = 1[x > 0] (the reading ReLU'(0) = 0).  The derivative of the penalty nu/2 ||Z - relu(T)||^2 jumps where a
+# pre-activation T crosses 0, so an entry whose fp64 value is zero up to the fp32 rounding of the contraction that
+# forms it may fall on either side in an fp32 implementation, and both outcomes are valid iterates.  The tests use
+# this hook to make such a tie checkable entry by entry: with ``band`` > 0 every evaluation of ReLU' records the
+# entries with |T| <= band * rms(T of that block), keyed by (step, layer of T, row, column); ``flips`` names entries
+# whose derivative is to be taken on the other side, and only entries inside the band may be named.  The W step
+# and the Z step of one iteration look at different pre-activations (before and after the W step), hence the step
+# in the key.  With band = 0 and no flips (the default) this is the plain definition.
+class ReluTieHook:
+    def __init__(self):
+        self.reset()
+
+    def reset(self):
+        self.band = 0.0
+        self.found = {}       # key -> (|T| / rms, T): the candidates seen with band > 0
+        self.flips = set()    # keys whose derivative is flipped
+        self.flipped = {}     # key -> |T| / rms of the flips that were applied
 
 
-def relu_grad(x, step="W"):
-    return (x > RELU_TIE_SHIFT[step]).astype(np.float64)
+RELU_TIES = ReluTieHook()
+
+
+def relu_grad(x, step="W", layer=0, rows=None):
+    mask = (x > 0.0).astype(np.float64)
+    hook = RELU_TIES
+    if hook.band <= 0.0 or x.size == 0:
+        return mask
+    scale = float(np.sqrt(np.mean(x * x)))
+    r0 = 0 if rows is None else rows.start
+    near = np.argwhere(np.abs(x) <= hook.band * scale)
+    for i, j in near:
+        key = (step, int(layer), int(r0 + i), int(j))
+        rel = abs(float(x[i, j])) / scale if scale > 0 else 0.0
+        hook.found[key] = (rel, float(x[i, j]))
+        if key in hook.flips:
+            mask[i, j] = 1.0 - mask[i, j]
+            hook.flipped[key] = rel
+    return mask
 
 
 def inner(a, b):
@@ -205,7 +234,7 @@ class AdmmOracle:
             H = self.g.aggregate_block(m, Zprev)
             T = H @ Wl
             if l < self.L:
-                G = self.nu * (relu(T) - self.blk(Zl, m)) * relu_grad(T, "W")
+                G = self.nu * (relu(T) - self.blk(Zl, m)) * relu_grad(T, "W", l, self.g.rows(m))
             else:
                 r = self.blk(Zl, m) - T
                 G = -(self.blk(U, m) + self.rho * r)
@@ -299,12 +328,12 @@ class AdmmOracle:
         for r in g.nbrs(m):
             a = a + p_cur[(r, m)]
         if l <= self.L - 2:
-            Gm = self.nu * (relu(a) - self.blk(Znext, m)) * relu_grad(a, "Z")
+            Gm = self.nu * (relu(a) - self.blk(Znext, m)) * relu_grad(a, "Z", l + 1, g.rows(m))
             grad = grad + g.block[(m, m)].T @ Gm @ Wnext.T
             for r in g.nbrs(m):
                 s1, s2 = s_cur[(r, m)]
                 b = g.block[(r, m)] @ Zlm @ Wnext + s2
-                Gr = self.nu * (relu(b) - s1) * relu_grad(b, "Z")
+                Gr = self.nu * (relu(b) - s1) * relu_grad(b, "Z", l + 1, g.rows(r))
                 grad = grad + g.block[(r, m)].T @ Gr @ Wnext.T
         else:
             res = self.blk(Znext, m) - a

@@ -23,7 +23,7 @@ EXPORTS = [
     "cadmm_get_Z", "cadmm_get_U", "cadmm_get_steps", "cadmm_set_state", "cadmm_op_aggregate",
     "cadmm_op_aggregate_segments", "cadmm_op_transform", "cadmm_op_wgrad",
     "cadmm_profile", "cadmm_get_profile", "cadmm_profile_class_name", "cadmm_tune", "cadmm_predict",
-    "cadmm_partition", "cadmm_op_calibrate",
+    "cadmm_partition", "cadmm_op_calibrate", "cadmm_op_wgrad_noalloc",
 ]
 PROFILE_CLASSES = 19
 
@@ -87,6 +87,7 @@ def load_library():
     lib.cadmm_op_aggregate_segments.argtypes = [vp, vp, i32, vp]
     lib.cadmm_op_transform.argtypes = [vp, vp, i64, i32, vp, i32, vp]
     lib.cadmm_op_wgrad.argtypes = [vp, vp, vp, i64, i32, i32, vp]
+    lib.cadmm_op_wgrad_noalloc.argtypes = [vp, vp, vp, i64, i32, i32, vp]
     lib.cadmm_op_calibrate.argtypes = [vp, i32, vp, vp, i64, i32, C.POINTER(C.c_double)]
     lib.cadmm_tune.argtypes = [vp, C.c_char_p, i32]
     lib.cadmm_predict.argtypes = [vp, vp, vp, C.POINTER(C.c_double)]
@@ -362,6 +363,19 @@ class Solver:
         self._enter()
         self._check(self.lib.cadmm_op_wgrad(self.h, C.c_void_p(A.data_ptr()), C.c_void_p(G.data_ptr()), A.shape[0],
                                             A.shape[1], G.shape[1], C.c_void_p(out.data_ptr())), "cadmm_op_wgrad")
+        self._leave()
+        return out
+
+    def op_wgrad_noalloc(self, A, G, out=None):
+        """out = A^T G through the entry point that allocates nothing; `out` may be a preallocated tensor."""
+        torch = self._torch
+        assert A.is_cuda and G.is_cuda and A.is_contiguous() and G.is_contiguous() and A.shape[0] == G.shape[0]
+        if out is None:
+            out = torch.empty((A.shape[1], G.shape[1]), dtype=torch.float32, device=A.device)
+        self._enter()
+        self._check(self.lib.cadmm_op_wgrad_noalloc(self.h, C.c_void_p(A.data_ptr()), C.c_void_p(G.data_ptr()),
+                                                    A.shape[0], A.shape[1], G.shape[1], C.c_void_p(out.data_ptr())),
+                    "cadmm_op_wgrad_noalloc")
         self._leave()
         return out
 

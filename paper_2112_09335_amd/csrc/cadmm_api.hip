@@ -7,6 +7,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -15,6 +16,15 @@
 #include "kernels.h"
 
 using namespace cadmm;
+
+// Scratch of cadmm_op_wgrad_noalloc: the per-chunk partial matrices of the W-gradient product, for callers that cannot
+// allocate.  Every GPU the library runs on holds its own copy of this array until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; kernels get the per-device address looked up below.
+constexpr size_t kStaticScratchFloats = (size_t)18 << 20;          // 72 MiB
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+constexpr int kMaxDevices = 64;
+static float* g_scratch_ptr[kMaxDevices] = {};                     // device address of `scratch` on GPU d, once looked up
+static std::mutex g_scratch_mutex;
 
 struct cadmm_ctx {
     int device = 0;
@@ -612,6 +622,17 @@ int upload_rows(cadmm_ctx* c, const float* src, int on_device, int C, float* dst
     return check_launch(c, "upload_rows");
 }
 
+void drop_graphs(cadmm_ctx* c) {
+    for (auto& cube : c->graphs)
+        for (auto& plane : cube)
+            for (auto& row : plane)
+                for (auto& slot : row) {
+                    if (slot.exec) (void)hipGraphExecDestroy(slot.exec);
+                    slot.exec = nullptr;
+                    slot.tried = false;
+                }
+}
+
 }  // namespace
 
 extern "C" {
@@ -638,11 +659,7 @@ void cadmm_destroy(cadmm_ctx* ctx) {
         (void)hipStreamSynchronize(ctx->stream);
         for (auto& r : ctx->prof_recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
         for (auto e : ctx->prof_pool) (void)hipEventDestroy(e);
-        for (auto& cube : ctx->graphs)
-            for (auto& plane : cube)
-                for (auto& row : plane)
-                    for (auto& slot : row)
-                        if (slot.exec) (void)hipGraphExecDestroy(slot.exec);
+        drop_graphs(ctx);
     }
     delete ctx;
 }
@@ -1084,22 +1101,16 @@ int cadmm_tune(cadmm_ctx* c, const char* key, int32_t value) {
     if (!c || !key) return CADMM_EINVAL;
     if (std::strcmp(key, "use_graph") == 0) { c->use_graph = value != 0; return CADMM_OK; }
     const bool k_lowrank = std::strcmp(key, "use_lowrank") == 0, k_spec = std::strcmp(key, "use_speculative") == 0;
-    const bool k_split = std::strcmp(key, "gemm_split") == 0;
-    if (k_lowrank || k_spec || k_split) {
+    const bool k_split = std::strcmp(key, "gemm_split") == 0, k_refresh = std::strcmp(key, "t1_refresh") == 0;
+    if (k_lowrank || k_spec || k_split || k_refresh) {
+        // each of these changes the launch sequence of an iteration: captured iterations of this context are dropped
         if (k_lowrank) c->use_lowrank = value != 0;
         else if (k_spec) c->use_speculative = value != 0;
-        else set_gemm_split(value);                  // process-wide; captured iterations of this context are dropped
-        for (auto& cube : c->graphs)
-            for (auto& plane : cube)
-                for (auto& row : plane)
-                    for (auto& slot : row) {
-                        if (slot.exec) (void)hipGraphExecDestroy(slot.exec);
-                        slot.exec = nullptr;
-                        slot.tried = false;
-                    }
+        else if (k_refresh) { c->t1_refresh = value; c->t1_age = -1; }
+        else set_gemm_split(value);                  // process-wide
+        drop_graphs(c);
         return CADMM_OK;
     }
-    if (std::strcmp(key, "t1_refresh") == 0) { c->t1_refresh = value; c->t1_age = -1; return CADMM_OK; }
     if (std::strcmp(key, "spmm_tile_cols") == 0) { set_spmm_tile_cols(value); return CADMM_OK; }
     if (std::strcmp(key, "spmm_xcd_remap") == 0) { set_spmm_xcd_remap(value); return CADMM_OK; }
     if (std::strcmp(key, "spmm_groups_log2") == 0) { set_spmm_groups_log2(value); return CADMM_OK; }
@@ -1125,6 +1136,7 @@ int cadmm_op_aggregate_segments(cadmm_ctx* c, const float* V, int32_t width, flo
 
 int cadmm_op_transform(cadmm_ctx* c, const float* A, int64_t n, int32_t K, const float* B, int32_t C, float* out) {
     if (!c || !A || !B || !out || n < 1 || K < 1 || C < 1) return CADMM_EINVAL;
+    if (c->device < 0) return fail(c, CADMM_EUNSUPPORTED, "host-only context (device -1) has no device path");
     gemm_nn(c, A, B, out, n, K, C);
     return check_launch(c, "op_transform");
 }
@@ -1136,6 +1148,39 @@ int cadmm_op_wgrad(cadmm_ctx* c, const float* A, const float* G, int64_t n, int3
     timed(c, C > 32 ? P_GEMM_TN : P_GEMM_TN_32, 4.0 * ((double)n * K + (double)n * C + (double)K * C),
           2.0 * (double)n * K * C, [&] { launch_gemm_tn(c->stream, A, G, out, n, K, C, c->tn_partial); });
     return check_launch(c, "op_wgrad");
+}
+
+int cadmm_op_wgrad_noalloc(cadmm_ctx* c, const float* A, const float* G, int64_t n, int32_t K, int32_t C, float* out) {
+    if (!c || !A || !G || !out || n < 1 || K < 1 || C < 1) return CADMM_EINVAL;
+    if (c->device < 0) return fail(c, CADMM_EUNSUPPORTED, "host-only context (device -1) has no device path");
+    if (c->device >= kMaxDevices) return fail(c, CADMM_EUNSUPPORTED, "device index beyond the static scratch table");
+    const size_t need = gemm_tn_scratch_floats(n, K, C);
+    if (need > kStaticScratchFloats)
+        return fail(c, CADMM_ENOMEM, "shape needs " + std::to_string(need) + " floats of scratch, the static scratch holds " +
+                                         std::to_string(kStaticScratchFloats) + "; use cadmm_op_wgrad with a workspace");
+    int current = -1;
+    HIP_TRY(c, hipGetDevice(&current));
+    if (current != c->device) HIP_TRY(c, hipSetDevice(c->device));
+    float* ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[c->device]) {
+            // once per device, with that device current: every GPU has its own copy of the array at its own address
+            void* p = nullptr;
+            hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !p) {
+                if (current != c->device) (void)hipSetDevice(current);
+                return hip_fail(c, e, "hipGetSymbolAddress(scratch)");
+            }
+            g_scratch_ptr[c->device] = static_cast<float*>(p);
+        }
+        ptr = g_scratch_ptr[c->device];
+    }
+    // every entry of the partial matrices that the reduction reads is written by the product first: nothing to clear
+    launch_gemm_tn(c->stream, A, G, out, n, K, C, ptr);
+    int rc = check_launch(c, "op_wgrad_noalloc");
+    if (current != c->device) (void)hipSetDevice(current);
+    return rc;
 }
 
 int cadmm_op_calibrate(cadmm_ctx* c, int32_t kind, const float* src, float* dst, int64_t count, int32_t reps,

@@ -196,6 +196,30 @@ def make_workload(name, seed, N, M, dims, n_classes, iters, *, graph, features,
     return Workload(name, N, M, src, dst, comm, X, labels, list(dims), W0, iters, h)
 
 
+def add_hubs(w: Workload, seed: int, hubs: int, degree: int, concentrate: float = 0.0) -> Workload:
+    """Give `hubs` nodes about `degree` extra neighbours each, as the heaviest nodes of a power-law graph have at full
+    size (config 4: up to 3 * 10^4) and a scaled-down sample of the recipe does not.  A share `concentrate` of a hub's
+    new neighbours is drawn inside ONE other community, so that this (row, community) segment is long too; the rest
+    uniformly over all nodes.  Returns a new workload; features, labels and weights are kept."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    N = w.N
+    hub_ids = rng.choice(N, size=hubs, replace=False)
+    a, b = [w.src.astype(np.int64)], [w.dst.astype(np.int64)]
+    for h in hub_ids:
+        n_one = int(round(concentrate * degree))
+        others = np.flatnonzero(w.comm != w.comm[h])
+        target = w.comm[others[rng.integers(others.shape[0])]] if others.shape[0] else w.comm[h]
+        pool = np.flatnonzero(w.comm == target)
+        picks = [rng.choice(pool, size=min(n_one, pool.shape[0]), replace=False)] if n_one else []
+        picks.append(rng.choice(N, size=degree - n_one, replace=False))
+        nb = np.concatenate(picks)
+        a.append(np.full(nb.shape[0], h, np.int64))
+        b.append(nb.astype(np.int64))
+    src, dst = _dedup_pairs(np.concatenate(a), np.concatenate(b), N)
+    return Workload(w.name + "+hubs", N, w.M, np.ascontiguousarray(src), np.ascontiguousarray(dst), w.comm, w.X,
+                    w.labels, list(w.dims), w.W0, w.iters, dict(w.hyper))
+
+
 # The five benchmark configurations (index = seed), and two more for the serial-versus-community comparison.  `scale` shrinks N (and keeps degree,
 # community count, widths) for CPU-sized samples of the same recipe.
 def config(index: int, scale: float = 1.0, M: Optional[int] = None) -> Workload:

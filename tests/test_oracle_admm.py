@@ -546,3 +546,117 @@ def test_step_policy_1_starts_a_search_one_notch_lower_and_still_meets_the_condi
         Wp = W_old[1] - grad / (tau / o.eta)
         assert phi(Wp) > phi(W_old[1]) - np.sum(grad * grad) / (2 * tau / o.eta)
     o.restore(snap)
+
+
+# ---------------------------------------------------------------- a step below resolution is not taken
+def _floor_case(seed):
+    o, _ = tiny_problem(seed)
+    o.iterate(2)                      # a generic state with step parameters that have been searched
+    return o
+
+
+def test_step_floor_of_the_W_update_has_its_boundary_where_the_reading_puts_it():
+    """Reading: if the first candidate would move W_l by less than 1e-12 of its norm, ||grad||^2 <= (1e-12 tau)^2 ||W||^2,
+    the block and tau_l stay and no trial is counted.  tau is placed just above and just below ||grad|| / (1e-12 ||W||)
+    for a gradient that is far from zero."""
+    o = _floor_case(21)
+    for l in range(1, o.L + 1):
+        W = o.W[l].copy()
+        grad = o.grad_phi_W(l, W, o.Z[l - 1], o.Z[l], o.U)
+        gn, wn = np.sqrt(np.sum(grad ** 2)), np.sqrt(np.sum(W ** 2))
+        assert gn > 1e-6 * wn                                  # nothing like a zero gradient
+        edge = gn / (AdmmOracle.STEP_FLOOR * wn)               # tau at which the first step has relative size 1e-12
+        # at or beyond the edge: nothing moves, nothing is counted, tau is kept
+        for tau in (edge * (1 + 1e-9), edge * 4.0):
+            o.tau[l], o.trials_W[l] = tau, -7
+            Wn = o.update_W(l, o.W, o.Z, o.U)
+            assert np.array_equal(Wn, W) and Wn is not o.W[l]
+            assert o.tau[l] == tau and o.trials_W[l] == 0
+        # just inside: the step is taken, with at least one trial, and it is the model's minimiser for the tau it ends with
+        o.tau[l] = edge * (1 - 1e-6)
+        Wn = o.update_W(l, o.W, o.Z, o.U)
+        assert o.trials_W[l] >= 1 and o.tau[l] >= edge * (1 - 1e-6)
+        assert not np.array_equal(Wn, W)
+        np.testing.assert_allclose(Wn, W - grad / o.tau[l], rtol=0, atol=0)
+        moved = np.sqrt(np.sum((Wn - W) ** 2)) / wn
+        assert 0 < moved <= 1.01e-12
+
+
+def test_step_floor_of_the_Z_update_has_its_boundary_where_the_reading_puts_it():
+    o = _floor_case(22)
+    p, s = messages(o, o.W)
+    checked = 0
+    for l in range(1, o.L):
+        for m in range(o.M):
+            rows = o.g.rows(m)
+            if rows.stop == rows.start:
+                continue
+            Z = o.Z[l][rows].copy()
+            args = (o.W[l + 1], o.Z[l + 1], o.U, p[l - 1], p[l], s[l])
+            grad = o.grad_psi(l, m, Z, *args)
+            gn, zn = np.sqrt(np.sum(grad ** 2)), np.sqrt(np.sum(Z ** 2))
+            assert gn > 1e-6 * zn
+            edge = gn / (AdmmOracle.STEP_FLOOR * zn)
+            o.theta[l][m], o.trials_Z[l][m] = edge * (1 + 1e-9), -7
+            Zn = o.update_Z_hidden(l, m, o.Z, o.W, o.U, p[l - 1], p[l], s[l])
+            assert np.array_equal(Zn, Z) and o.theta[l][m] == edge * (1 + 1e-9) and o.trials_Z[l][m] == 0
+            o.theta[l][m] = edge * (1 - 1e-6)
+            Zn = o.update_Z_hidden(l, m, o.Z, o.W, o.U, p[l - 1], p[l], s[l])
+            assert o.trials_Z[l][m] >= 1 and not np.array_equal(Zn, Z)
+            np.testing.assert_allclose(Zn, Z - grad / o.theta[l][m], rtol=0, atol=0)
+            checked += 1
+    assert checked >= 2
+
+
+def test_step_floor_uses_the_first_candidate_of_the_search_under_step_policy_1():
+    """With step_policy 1 the first candidate is tau / eta, and the floor is taken at that value."""
+    o, _ = tiny_problem(23, hyper=dict(step_policy=1))
+    o.iterate(2)
+    l = 1
+    W = o.W[l].copy()
+    grad = o.grad_phi_W(l, W, o.Z[l - 1], o.Z[l], o.U)
+    edge = np.sqrt(np.sum(grad ** 2)) / (AdmmOracle.STEP_FLOOR * np.sqrt(np.sum(W ** 2)))
+    o.tau[l] = edge * o.eta * (1 + 1e-9)           # first candidate just beyond the edge
+    assert np.array_equal(o.update_W(l, o.W, o.Z, o.U), W) and o.trials_W[l] == 0
+    o.tau[l] = edge * o.eta * (1 - 1e-6)
+    assert not np.array_equal(o.update_W(l, o.W, o.Z, o.U), W) and o.trials_W[l] >= 1
+
+
+# ---------------------------------------------------------------- the ReLU-tie hook of the parity tests
+def test_relu_tie_hook_flips_only_named_entries_inside_the_band_and_is_off_by_default():
+    import oracle.admm as oa
+    hook = oa.RELU_TIES
+    o, rng = tiny_problem(24)
+    l = 1
+    # plant a pre-activation that is zero up to 1e-9 of the block's rms: solve for one entry of Z_0... simpler, shift
+    # one column of W_1 so that T_1[i, j] of community m's block lands at +1e-9 rms
+    m = max(range(o.M), key=lambda q: o.g.rows(q).stop - o.g.rows(q).start)
+    rows = o.g.rows(m)
+    H = o.g.aggregate_block(m, o.Z[0])
+    T = H @ o.W[l]
+    i, j = 1, 2
+    rms = np.sqrt(np.mean(T * T))
+    k = int(np.argmax(np.abs(H[i])))
+    o.W[l][k, j] += (1e-9 * rms - T[i, j]) / H[i, k]
+    T = H @ o.W[l]
+    assert 0 < T[i, j] < 1e-8 * rms
+    key = ("W", l, rows.start + i, j)
+    try:
+        g_plain = o.grad_phi_W(l, o.W[l], o.Z[0], o.Z[l])
+        assert hook.found == {} and hook.flipped == {}                      # off by default: nothing recorded
+        hook.band = 4e-6
+        g_probe = o.grad_phi_W(l, o.W[l], o.Z[0], o.Z[l])
+        assert np.array_equal(g_probe, g_plain)                             # recording changes nothing
+        assert list(hook.found) == [key]                                    # and finds exactly the planted entry
+        far = ("W", l, rows.start, 0)
+        hook.flips = {key, far}                                             # an entry outside the band cannot be flipped
+        g_flip = o.grad_phi_W(l, o.W[l], o.Z[0], o.Z[l])
+        assert set(hook.flipped) == {key}
+        # the flipped derivative is 0 instead of 1 at that entry: the gradient loses exactly H_i^T G_ij
+        Gij = o.nu * (max(T[i, j], 0.0) - o.Z[l][rows][i, j])
+        expect = g_plain.copy()
+        expect[:, j] -= H[i] * Gij
+        np.testing.assert_allclose(g_flip, expect, rtol=1e-12, atol=1e-15)
+    finally:
+        hook.reset()
+    assert np.array_equal(o.grad_phi_W(l, o.W[l], o.Z[0], o.Z[l]), g_plain)
