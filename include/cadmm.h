@@ -221,6 +221,12 @@ int  cadmm_op_wgrad_noalloc(cadmm_ctx* ctx, const float* A, const float* G, int6
  *   kind 1: dependent chains of fp32 MFMAs on registers, `count` steps of four 32x32x2 MFMAs per wavefront,
  *           2048 workgroups of four wavefronts; dst: device scratch of at least 2048 * 256 floats (src unused);
  *           rate = TFLOP/s.
+ *   kind 2 / 3: the gathers of the aggregation and nothing else, driven by the column stream of the graph's rows (2) or
+ *           of its (row, community) segments with several entries (3), in the order the aggregation reads it: every
+ *           eight-entry chunk is loaded and the eight rows of `count` floats (4, 8, ... 256) it names are gathered from
+ *           src (device, N x count) and added up; no row bounds, no reduction, no result rows.  dst as for kind 1.
+ *           rate = GB/s of entry pairs plus gathered rows: what the memory system serves to this access pattern, the
+ *           ceiling for cadmm_op_aggregate / _aggregate_segments at that width.  Needs the workspace.
  */
 int  cadmm_op_calibrate(cadmm_ctx* ctx, int32_t kind, const float* src, float* dst, int64_t count, int32_t reps,
                         double* rate);
@@ -248,10 +254,9 @@ const char* cadmm_profile_class_name(int32_t cls);
  * next (through the W step, and through the segment products of the Z step) and formed anew every
  * this many iterations (default 16; 0 = always form them anew).
  * Process-wide: "spmm_tile_cols": feature columns handled per
- * aggregation launch (0 = all at once); "spmm_xcd_remap": 1 = each XCD walks one contiguous eighth of
- * the rows of a length class (default), 0 = blocks in plain order; "spmm_groups_log2": lane groups that share one
- * output row, as a power of two (-1 = chosen per length class of the rows); "spmm_unroll": gathers in flight per lane
- * group, 8 (default) or 4; "gemm_split": 1 = products with more than 32 result columns run on the bf16 matrix
+ * aggregation launch (0 = all at once); "spmm_xcd_remap": 1 = each XCD walks one contiguous slice of the aggregation's
+ * work list, whole communities one after the other (default), 0 = workgroups in plain order;
+ * "gemm_split": 1 = products with more than 32 result columns run on the bf16 matrix
  * cores, both operands split exactly into three bf16 parts and the six largest cross products accumulated in fp32
  * (default), 0 = on the fp32 matrix cores. */
 int  cadmm_tune(cadmm_ctx* ctx, const char* key, int32_t value);

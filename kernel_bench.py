@@ -1,12 +1,14 @@
 #!/usr/bin/env python3
 """Time single kernels of the library on a synthetic workload (for profiling under rocprofv3).
 
-    python paper_2112_09335_amd/kernel_bench.py --workload 4 --ops copy aggregate:256 segments:16 \
+    python kernel_bench.py --workload 4 --ops copy aggregate:256 segments:16 \
            transform:256:256 wgrad:128:256 --reps 5
 
 ops:  copy            a plain device copy of 1 GiB (torch), the calibration point for memory counters
       stream          the library's own copy kernel on 1 GiB (cadmm_op_calibrate): what a streaming kernel can reach
       mfma            register-only chains of fp32 MFMAs (cadmm_op_calibrate): what the matrix cores can reach
+      gather:W        only the gathers of the row aggregation at width W, no row structure (cadmm_op_calibrate):
+                      what the memory system serves to the graph's column stream; gatherseg:W the same for the segments
       aggregate:W     Y = A~ X, X of width W                    (cadmm_op_aggregate)
       segments:W      per-(row, community) aggregation          (cadmm_op_aggregate_segments)
       transform:K:C   out[N x C] = A[N x K] B[K x C]            (cadmm_op_transform)
@@ -17,7 +19,7 @@ import argparse
 import os
 import sys
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -57,6 +59,12 @@ def main():
     for op in args.ops:
         parts = op.split(":")
         kind = parts[0]
+        if kind in ("gather", "gatherseg"):
+            W = int(parts[1])
+            rate = s.op_calibrate("gather" if kind == "gather" else "gather_segments", W, args.reps)
+            print(f"{op:20s} gathers of {4 * W}-byte rows along the real column stream: {rate:8.1f} GB/s requested "
+                  f"(pairs + rows) = {rate / (8.0 + 4.0 * W):7.2f} G gathers/s", flush=True)
+            continue
         if kind in ("stream", "mfma"):
             if kind == "stream":
                 rate = s.op_calibrate("copy", 1 << 28, args.reps)

@@ -337,7 +337,8 @@ class Solver:
         return out
 
     def op_calibrate(self, kind, count, reps=5):
-        """'copy': GB/s of a plain device copy of `count` floats; 'mfma': TFLOP/s of register-only fp32 MFMA chains."""
+        """'copy': GB/s of a plain device copy of `count` floats; 'mfma': TFLOP/s of register-only fp32 MFMA chains;
+        'gather' / 'gather_segments': GB/s of the aggregation's gathers alone at a row width of `count` floats."""
         torch = self._torch
         rate = C.c_double()
         self._enter()
@@ -350,6 +351,12 @@ class Solver:
         elif kind == "mfma":
             dst = torch.empty(2048 * 256, dtype=torch.float32, device=f"cuda:{self.device}")
             rc = self.lib.cadmm_op_calibrate(self.h, 1, None, C.c_void_p(dst.data_ptr()), count, reps, C.byref(rate))
+        elif kind in ("gather", "gather_segments"):
+            src = torch.randn(self.N, count, dtype=torch.float32, device=f"cuda:{self.device}")
+            dst = torch.empty(2048 * 256, dtype=torch.float32, device=f"cuda:{self.device}")
+            torch.cuda.current_stream().synchronize()
+            rc = self.lib.cadmm_op_calibrate(self.h, 2 if kind == "gather" else 3, C.c_void_p(src.data_ptr()),
+                                             C.c_void_p(dst.data_ptr()), count, reps, C.byref(rate))
         else:
             raise CadmmError(f"unknown calibration {kind}")
         self._check(rc, "cadmm_op_calibrate")

@@ -63,8 +63,10 @@ struct cadmm_ctx {
     std::vector<int32_t> h_labels;     // internal row order
     // split rows of the CSR row list and of the segment list; side buffer for their parts
     struct DevSchedule {               // device copy of a RowSchedule
-        int64_t* ptr = nullptr; int32_t* out = nullptr; int32_t* col = nullptr; float* val = nullptr;
-        int64_t* part_lo = nullptr; int64_t* part_hi = nullptr; int32_t* long_row = nullptr; int32_t* long_ptr = nullptr;
+        int4* rec = nullptr; int2* ent = nullptr; int32_t* long_row = nullptr; int32_t* long_ptr = nullptr;
+        int4* blocks[7] = {};          // workgroup -> rows table per lane count of a gathered row
+        int64_t n_blocks[7] = {};
+        int64_t xcd_start[7][9] = {};
     };
     DevSchedule d_rows, d_segs;
     float* side = nullptr;
@@ -160,14 +162,14 @@ size_t layout(cadmm_ctx* c, char* base) {
     c->d_row_comm = b.take<int32_t>(N);
     c->d_perm = b.take<int32_t>(N);
     auto take_schedule = [&](cadmm_ctx::DevSchedule& d, const RowSchedule& rs) {
-        d.ptr = b.take<int64_t>(rs.ptr.size());
-        d.out = b.take<int32_t>(rs.out.size());
-        d.col = b.take<int32_t>(rs.col.size());
-        d.val = b.take<float>(rs.val.size());
-        d.part_lo = b.take<int64_t>(rs.longs.n_parts());
-        d.part_hi = b.take<int64_t>(rs.longs.n_parts());
-        d.long_row = b.take<int32_t>(rs.longs.n_long());
-        d.long_ptr = b.take<int32_t>(rs.longs.n_long() + 1);
+        d.rec = b.take<int4>(rs.rec.size());
+        d.ent = b.take<int2>(rs.ent.size());
+        d.long_row = b.take<int32_t>(rs.n_long());
+        d.long_ptr = b.take<int32_t>(rs.n_long() + 1);
+        for (int l = 0; l < 7; ++l) {
+            d.n_blocks[l] = count_blocks(rs, l);
+            d.blocks[l] = b.take<int4>((size_t)d.n_blocks[l]);
+        }
     };
     take_schedule(c->d_rows, g.row_sched);
     take_schedule(c->d_segs, g.seg_sched);
@@ -187,7 +189,7 @@ size_t layout(cadmm_ctx* c, char* base) {
     c->d_seg_comm = b.take<int32_t>(g.n_seg);
     c->d_seg_pos = b.take<int32_t>(g.n_seg);
     {
-        const int64_t np_ = g.row_sched.longs.n_parts() > g.seg_sched.longs.n_parts() ? g.row_sched.longs.n_parts() : g.seg_sched.longs.n_parts();
+        const int64_t np_ = g.row_sched.n_parts() > g.seg_sched.n_parts() ? g.row_sched.n_parts() : g.seg_sched.n_parts();
         c->side = b.take<float>((size_t)np_ * max_of(c->C, 0, L));
     }
     c->Z.assign(L + 1, nullptr);
@@ -282,15 +284,19 @@ void timed(cadmm_ctx* c, int cls, double bytes, double flops, F body) {
     }
 }
 
-SpmmLong schedule_of(const cadmm_ctx* c, const cadmm_ctx::DevSchedule& d, const RowSchedule& rs) {
-    SpmmLong lg;
-    lg.max_len = kSplitThreshold;
-    lg.n_parts = rs.longs.n_parts(); lg.part_lo = d.part_lo; lg.part_hi = d.part_hi;
-    lg.n_long = rs.longs.n_long(); lg.long_row = d.long_row; lg.long_part_ptr = d.long_ptr;
-    lg.side = c->side;
-    lg.mean_len = (int)((int64_t)rs.col.size() / (rs.n_rows() > 0 ? rs.n_rows() : 1));
-    lg.class_start = rs.class_start;
-    return lg;
+SpmmSchedule schedule_of(const cadmm_ctx* c, const cadmm_ctx::DevSchedule& d, const RowSchedule& rs) {
+    SpmmSchedule sc;
+    sc.n_rows = rs.n_rows();
+    sc.n_parts = rs.n_parts();
+    sc.rec = d.rec; sc.ent = d.ent;
+    sc.n_long = rs.n_long(); sc.long_row = d.long_row; sc.long_part_ptr = d.long_ptr;
+    sc.side = c->side;
+    for (int l = 0; l < 7; ++l) {
+        sc.blocks[l] = d.blocks[l];
+        sc.n_blocks[l] = d.n_blocks[l];
+        for (int k = 0; k <= 8; ++k) sc.xcd_start[l][k] = d.xcd_start[l][k];
+    }
+    return sc;
 }
 
 double spmm_bytes(const cadmm_ctx* c, int64_t out_rows, int width, int extra_reads) {
@@ -319,8 +325,7 @@ SearchParams search_params(const cadmm_ctx* c) {
 void aggregate(cadmm_ctx* c, const float* X, float* Y, int width, const SpmmEpilogue& epi) {
     timed(c, epi.kind ? P_SPMM_GRADZ : P_SPMM, spmm_bytes(c, c->hg.N, width, epi.kind ? 2 : 0),
           2.0 * (double)c->hg.nnz * width, [&] {
-              launch_spmm(c->stream, c->d_rows.ptr, c->d_rows.ptr + 1, c->d_rows.col, c->d_rows.val, X, Y,
-                          c->hg.row_sched.n_rows(), width, epi, schedule_of(c, c->d_rows, c->hg.row_sched), c->d_rows.out);
+              launch_spmm(c->stream, schedule_of(c, c->d_rows, c->hg.row_sched), X, Y, width, epi);
           });
 }
 
@@ -328,8 +333,7 @@ void aggregate(cadmm_ctx* c, const float* X, float* Y, int width, const SpmmEpil
 // (community, row) order: the segments with several entries as a row list, those with one entry as scaled copies.
 void aggregate_segments(cadmm_ctx* c, const float* V, float* P, int width) {
     timed(c, P_SPMM_SEG, spmm_bytes(c, c->hg.n_seg, width, 0), 2.0 * (double)c->hg.nnz * width, [&] {
-        launch_spmm(c->stream, c->d_segs.ptr, c->d_segs.ptr + 1, c->d_segs.col, c->d_segs.val, V, P,
-                    c->hg.seg_sched.n_rows(), width, SpmmEpilogue(), schedule_of(c, c->d_segs, c->hg.seg_sched), c->d_segs.out);
+        launch_spmm(c->stream, schedule_of(c, c->d_segs, c->hg.seg_sched), V, P, width, SpmmEpilogue());
         launch_spmm_single(c->stream, c->d_seg1_pos, c->d_seg1_col, c->d_seg1_val, V, P, (int64_t)c->hg.seg1_pos.size(),
                            width);
     });
@@ -766,16 +770,26 @@ int cadmm_set_workspace(cadmm_ctx* c, void* dev_ptr, size_t bytes) {
     hipStream_t s = c->stream;
     HIP_TRY(c, upload(s, c->d_row_comm, g.row_comm));
     HIP_TRY(c, upload(s, c->d_perm, g.perm));
-    auto upload_schedule = [&](const cadmm_ctx::DevSchedule& d, const RowSchedule& rs) -> hipError_t {
+    auto upload_schedule = [&](cadmm_ctx::DevSchedule& d, const RowSchedule& rs) -> hipError_t {
         hipError_t e;
-        if ((e = upload(s, d.ptr, rs.ptr)) != hipSuccess) return e;
-        if ((e = upload(s, d.out, rs.out)) != hipSuccess) return e;
-        if ((e = upload(s, d.col, rs.col)) != hipSuccess) return e;
-        if ((e = upload(s, d.val, rs.val)) != hipSuccess) return e;
-        if ((e = upload(s, d.part_lo, rs.longs.part_lo)) != hipSuccess) return e;
-        if ((e = upload(s, d.part_hi, rs.longs.part_hi)) != hipSuccess) return e;
-        if ((e = upload(s, d.long_row, rs.longs.long_row)) != hipSuccess) return e;
-        return upload(s, d.long_ptr, rs.longs.long_part_ptr);
+        for (int l = 0; l < 7; ++l) {
+            BlockTable bt;
+            build_block_table(rs, l, bt);
+            static_assert(sizeof(BlockRows) == sizeof(int4), "table entries are read as int4");
+            if ((int64_t)bt.blocks.size() != d.n_blocks[l] || !block_table_ok(rs, l, bt)) return hipErrorInvalidValue;
+            for (int k = 0; k <= 8; ++k) d.xcd_start[l][k] = bt.xcd_start[k];
+            if (!bt.blocks.empty()) {
+                // synchronous with respect to the host buffer: the table is a temporary
+                if ((e = hipMemcpyAsync(d.blocks[l], bt.blocks.data(), bt.blocks.size() * sizeof(BlockRows),
+                                        hipMemcpyHostToDevice, s)) != hipSuccess) return e;
+                if ((e = hipStreamSynchronize(s)) != hipSuccess) return e;
+            }
+        }
+        static_assert(sizeof(RowRecord) == sizeof(int4) && sizeof(EntryPair) == sizeof(int2), "records are read as int4, pairs as int2");
+        if (!rs.rec.empty() && (e = hipMemcpyAsync(d.rec, rs.rec.data(), rs.rec.size() * sizeof(RowRecord), hipMemcpyHostToDevice, s)) != hipSuccess) return e;
+        if ((e = hipMemcpyAsync(d.ent, rs.ent.data(), rs.ent.size() * sizeof(EntryPair), hipMemcpyHostToDevice, s)) != hipSuccess) return e;
+        if ((e = upload(s, d.long_row, rs.long_row)) != hipSuccess) return e;
+        return upload(s, d.long_ptr, rs.long_part_ptr);
     };
     HIP_TRY(c, upload_schedule(c->d_rows, g.row_sched));
     HIP_TRY(c, upload_schedule(c->d_segs, g.seg_sched));
@@ -1112,9 +1126,7 @@ int cadmm_tune(cadmm_ctx* c, const char* key, int32_t value) {
         return CADMM_OK;
     }
     if (std::strcmp(key, "spmm_tile_cols") == 0) { set_spmm_tile_cols(value); return CADMM_OK; }
-    if (std::strcmp(key, "spmm_xcd_remap") == 0) { set_spmm_xcd_remap(value); return CADMM_OK; }
-    if (std::strcmp(key, "spmm_groups_log2") == 0) { set_spmm_groups_log2(value); return CADMM_OK; }
-    if (std::strcmp(key, "spmm_unroll") == 0) { set_spmm_unroll(value); return CADMM_OK; }
+    if (std::strcmp(key, "spmm_xcd_remap") == 0) { set_spmm_xcd_remap(value); drop_graphs(c); return CADMM_OK; }
     return fail(c, CADMM_EINVAL, "unknown tuning key");
 }
 
@@ -1185,18 +1197,28 @@ int cadmm_op_wgrad_noalloc(cadmm_ctx* c, const float* A, const float* G, int64_t
 
 int cadmm_op_calibrate(cadmm_ctx* c, int32_t kind, const float* src, float* dst, int64_t count, int32_t reps,
                        double* rate) {
-    if (!c || !dst || !rate || count < 4 || reps < 1 || (kind != 0 && kind != 1)) return CADMM_EINVAL;
+    if (!c || !dst || !rate || count < 4 || reps < 1 || kind < 0 || kind > 3) return CADMM_EINVAL;
     if (c->device < 0) return fail(c, CADMM_EUNSUPPORTED, "host-only context");
     const int blocks = 2048;
     if (kind == 0 && (!src || count % 4 != 0)) return fail(c, CADMM_EINVAL, "copy needs src and a multiple of four floats");
     if (kind == 1 && count > (1 << 24)) return fail(c, CADMM_EINVAL, "at most 2^24 MFMA steps per launch");
+    if (kind >= 2) {
+        if (!c->has_ws) return fail(c, CADMM_EORDER, "set_workspace first");
+        if (!src || (count != 4 && count != 8 && count != 16 && count != 32 && count != 64 && count != 128 && count != 256))
+            return fail(c, CADMM_EINVAL, "gather calibration needs src and a row width of 4, 8, ... 256 floats");
+    }
     hipEvent_t a = nullptr, b = nullptr;
     HIP_TRY(c, hipEventCreate(&a));
     if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return fail(c, CADMM_EHIP, "hipEventCreate"); }
     double work = 0.0;
     auto once = [&] {
         if (kind == 0) { launch_stream_copy(c->stream, src, dst, count); work += 8.0 * (double)count; }
-        else work += launch_mfma_chain(c->stream, dst, blocks, (int)count);
+        else if (kind == 1) work += launch_mfma_chain(c->stream, dst, blocks, (int)count);
+        else {
+            const RowSchedule& rs = kind == 2 ? c->hg.row_sched : c->hg.seg_sched;
+            work += launch_gather_calibration(c->stream, schedule_of(c, kind == 2 ? c->d_rows : c->d_segs, rs), rs.n_chunks(), src,
+                                              (int)count, dst);
+        }
     };
     once();                                     // untimed first launch
     work = 0.0;
@@ -1209,7 +1231,7 @@ int cadmm_op_calibrate(cadmm_ctx* c, int32_t kind, const float* src, float* dst,
     (void)hipEventDestroy(a);
     (void)hipEventDestroy(b);
     if (e != hipSuccess) return hip_fail(c, e, "op_calibrate");
-    *rate = ms > 0.f ? work / ((double)ms * 1e-3) / (kind == 0 ? 1e9 : 1e12) : 0.0;
+    *rate = ms > 0.f ? work / ((double)ms * 1e-3) / (kind == 1 ? 1e12 : 1e9) : 0.0;
     return check_launch(c, "op_calibrate");
 }
 

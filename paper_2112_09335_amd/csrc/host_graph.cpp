@@ -33,95 +33,205 @@ int stored_class(int64_t len) {
     return kLengthClasses - 1 - k;
 }
 
-// Row r of the list has the entries [lo[r], hi[r]) of col / val and goes to output row out[r] (r if out is null).
+// Row r of the list has the entries [lo[r], hi[r]) of col / val, belongs to group grp[r] (n_groups groups) and goes
+// to output row out[r] (r if out is null).
 void make_schedule(RowSchedule& rs, int64_t nrows, const int64_t* lo, const int64_t* hi, const int32_t* out,
-                   const int32_t* col, const float* val) {
+                   const int32_t* grp, int32_t n_groups, const int32_t* col, const float* val) {
     rs = RowSchedule();
-    int64_t count[kLengthClasses + 1] = {};
-    int64_t n_long = 0, total = 0;
+    // counting sort on (group, class)
+    const size_t nkeys = (size_t)n_groups * kLengthClasses;
+    std::vector<int64_t> count(nkeys + 1, 0);
+    int64_t n_long = 0;
     for (int64_t r = 0; r < nrows; ++r) {
         const int j = stored_class(hi[r] - lo[r]);
-        if (j < 0) ++n_long; else ++count[j + 1];
-        total += hi[r] - lo[r];
+        if (j < 0) ++n_long; else ++count[(size_t)grp[r] * kLengthClasses + j + 1];
     }
-    for (int j = 0; j < kLengthClasses; ++j) count[j + 1] += count[j];
-    for (int j = 0; j <= kLengthClasses; ++j) rs.class_start[j] = count[j];
+    for (size_t k = 0; k < nkeys; ++k) count[k + 1] += count[k];
+    for (size_t k = 0; k < nkeys; ++k)
+        if (count[k + 1] > count[k])
+            rs.runs.push_back({count[k], count[k + 1], (int32_t)(k % kLengthClasses), (int32_t)(k / kLengthClasses)});
     const int64_t n_sched = nrows - n_long;
+    rs.n_sched = n_sched;
     std::vector<int64_t> src((size_t)n_sched);                 // list row of scheduled row i
     std::vector<int64_t> long_src;
     {
-        int64_t cur[kLengthClasses];
-        for (int j = 0; j < kLengthClasses; ++j) cur[j] = count[j];
+        std::vector<int64_t> cur(count.begin(), count.end() - 1);
         for (int64_t r = 0; r < nrows; ++r) {
             const int j = stored_class(hi[r] - lo[r]);
-            if (j < 0) long_src.push_back(r); else src[(size_t)cur[j]++] = r;
+            if (j < 0) long_src.push_back(r); else src[(size_t)cur[(size_t)grp[r] * kLengthClasses + j]++] = r;
         }
     }
-    rs.ptr.assign((size_t)n_sched + 1, 0);
-    rs.out.resize((size_t)n_sched);
+    // records and chunk ranges: chunk 0 is the padding chunk, then the scheduled rows, then the parts of split rows
+    auto chunks_of = [](int64_t len) { return (len + kChunkEntries - 1) / kChunkEntries; };
+    int64_t n_parts = 0;
+    for (int64_t r : long_src) n_parts += (hi[r] - lo[r] + kSplitPart - 1) / kSplitPart;
+    rs.rec.resize((size_t)(n_sched + n_parts));
+    int64_t at = 1;
     for (int64_t i = 0; i < n_sched; ++i) {
         const int64_t r = src[(size_t)i];
-        rs.ptr[(size_t)i + 1] = rs.ptr[(size_t)i] + (hi[r] - lo[r]);
-        rs.out[(size_t)i] = out ? out[r] : (int32_t)r;
+        const int64_t nc = chunks_of(hi[r] - lo[r]);
+        rs.rec[(size_t)i] = {(int32_t)at, (int32_t)(at + nc), out ? out[r] : (int32_t)r, 0};
+        at += nc;
     }
-    rs.col.resize((size_t)total);
-    rs.val.resize((size_t)total);
-    parallel_rows(n_sched, [&](int64_t i0, int64_t i1) {
-        for (int64_t i = i0; i < i1; ++i) {
-            const int64_t r = src[(size_t)i], to = rs.ptr[(size_t)i], n = hi[r] - lo[r];
-            for (int64_t k = 0; k < n; ++k) {
-                rs.col[(size_t)(to + k)] = col[lo[r] + k];
-                rs.val[(size_t)(to + k)] = val[lo[r] + k];
-            }
-        }
-    });
-    int64_t to = rs.ptr[(size_t)n_sched];
-    rs.longs.long_part_ptr.push_back(0);
+    std::vector<int64_t> part_lo, part_hi;                     // entry ranges of the parts in col / val
+    rs.long_part_ptr.push_back(0);
     for (int64_t r : long_src) {
-        const int64_t n = hi[r] - lo[r];
-        for (int64_t k = 0; k < n; ++k) {
-            rs.col[(size_t)(to + k)] = col[lo[r] + k];
-            rs.val[(size_t)(to + k)] = val[lo[r] + k];
+        for (int64_t p = lo[r]; p < hi[r]; p += kSplitPart) {
+            const int64_t p1 = p + kSplitPart < hi[r] ? p + kSplitPart : hi[r];
+            const int64_t nc = chunks_of(p1 - p);
+            const int64_t k = (int64_t)part_lo.size();
+            rs.rec[(size_t)(n_sched + k)] = {(int32_t)at, (int32_t)(at + nc), (int32_t)k, 0};
+            part_lo.push_back(p);
+            part_hi.push_back(p1);
+            at += nc;
         }
-        for (int64_t p = to; p < to + n; p += kSplitPart) {
-            rs.longs.part_lo.push_back(p);
-            rs.longs.part_hi.push_back(p + kSplitPart < to + n ? p + kSplitPart : to + n);
-        }
-        rs.longs.long_row.push_back(out ? out[r] : (int32_t)r);
-        rs.longs.long_part_ptr.push_back((int32_t)rs.longs.part_lo.size());
-        to += n;
+        rs.long_row.push_back(out ? out[r] : (int32_t)r);
+        rs.long_part_ptr.push_back((int32_t)part_lo.size());
     }
+    rs.ent.assign((size_t)at * kChunkEntries, EntryPair{0, 0.f});
+    auto fill = [&](const RowRecord& rec, int64_t p0, int64_t p1) {
+        EntryPair* e = rs.ent.data() + (size_t)rec.chunk0 * kChunkEntries;
+        const int64_t n = p1 - p0, padded = (int64_t)(rec.chunk1 - rec.chunk0) * kChunkEntries;
+        for (int64_t k = 0; k < n; ++k) e[k] = {col[p0 + k], val[p0 + k]};
+        for (int64_t k = n; k < padded; ++k) e[k] = {n > 0 ? col[p0] : 0, 0.f};
+    };
+    parallel_rows(n_sched, [&](int64_t i0, int64_t i1) {
+        for (int64_t i = i0; i < i1; ++i) fill(rs.rec[(size_t)i], lo[src[(size_t)i]], hi[src[(size_t)i]]);
+    });
+    for (int64_t k = 0; k < n_parts; ++k) fill(rs.rec[(size_t)(n_sched + k)], part_lo[(size_t)k], part_hi[(size_t)k]);
 }
 
-// What the aggregation kernel relies on: every scheduled row and every part is an in-range, non-negative entry
-// range, a row sits in the class that bounds its length, outputs are in range.
-bool schedule_ok(const RowSchedule& rs, int64_t n_out) {
-    const int64_t n = rs.n_rows(), total = (int64_t)rs.col.size();
-    if ((int64_t)rs.ptr.size() != n + 1 || rs.val.size() != rs.col.size()) return false;
-    if (rs.class_start[0] != 0 || rs.class_start[kLengthClasses] != n) return false;
-    for (int j = 0; j < kLengthClasses; ++j) {
-        if (rs.class_start[j] > rs.class_start[j + 1]) return false;
-        const int64_t cap = j == 0 ? kSplitThreshold : (int64_t)(4 << (kLengthClasses - 1 - j));
-        for (int64_t i = rs.class_start[j]; i < rs.class_start[j + 1]; ++i) {
-            const int64_t len = rs.ptr[(size_t)i + 1] - rs.ptr[(size_t)i];
-            if (len < 0 || len > cap) return false;
-        }
+// What the aggregation kernels rely on: every record names an in-range, non-empty chunk range past the padding chunk,
+// the chunk ranges tile the entry array in order, the runs tile the scheduled rows and a row sits in a run whose
+// class bounds its length, a part is no longer than kSplitPart, output rows are in range, every column is in range.
+bool schedule_ok(const RowSchedule& rs, int64_t n_out, int64_t n_cols) {
+    const int64_t n = rs.n_rows(), np = rs.n_parts(), nchunks = rs.n_chunks();
+    if (n < 0 || np < 0 || nchunks < 1 || nchunks > INT32_MAX || rs.ent.size() % kChunkEntries != 0) return false;
+    int64_t at = 1;
+    for (int64_t i = 0; i < n + np; ++i) {
+        const RowRecord& r = rs.rec[(size_t)i];
+        if (r.chunk0 != at || r.chunk1 <= r.chunk0 || r.chunk1 > nchunks) return false;
+        if (r.out < 0 || r.out >= (i < n ? n_out : np)) return false;
+        if (i >= n && (int64_t)(r.chunk1 - r.chunk0) * kChunkEntries > kSplitPart) return false;
+        at = r.chunk1;
     }
-    if (n > 0 && (rs.ptr[0] != 0 || rs.ptr[(size_t)n] > total)) return false;
-    for (int64_t i = 0; i < n; ++i)
-        if (rs.out[(size_t)i] < 0 || rs.out[(size_t)i] >= n_out) return false;
-    const LongRows& lr = rs.longs;
-    if (lr.part_lo.size() != lr.part_hi.size() || lr.long_part_ptr.size() != lr.long_row.size() + 1) return false;
-    for (size_t p = 0; p < lr.part_lo.size(); ++p)
-        if (lr.part_lo[p] < 0 || lr.part_lo[p] >= lr.part_hi[p] || lr.part_hi[p] > total ||
-            lr.part_hi[p] - lr.part_lo[p] > kSplitPart) return false;
-    for (size_t i = 0; i < lr.long_row.size(); ++i)
-        if (lr.long_row[i] < 0 || lr.long_row[i] >= n_out || lr.long_part_ptr[i] >= lr.long_part_ptr[i + 1] ||
-            lr.long_part_ptr[i + 1] > (int32_t)lr.part_lo.size()) return false;
+    if (at != nchunks) return false;
+    for (const EntryPair& e : rs.ent)
+        if (e.col < 0 || e.col >= n_cols) return false;
+    int64_t row = 0;
+    for (const ScheduleRun& run : rs.runs) {
+        if (run.row0 != row || run.row1 <= run.row0 || run.cls < 0 || run.cls >= kLengthClasses) return false;
+        const int64_t cap = run.cls == 0 ? kSplitThreshold : (int64_t)(4 << (kLengthClasses - 1 - run.cls));
+        const int64_t cap_chunks = (cap + kChunkEntries - 1) / kChunkEntries;
+        for (int64_t i = run.row0; i < run.row1; ++i)
+            if (rs.rec[(size_t)i].chunk1 - rs.rec[(size_t)i].chunk0 > cap_chunks) return false;
+        row = run.row1;
+    }
+    if (row != n) return false;
+    if (rs.long_part_ptr.size() != rs.long_row.size() + 1) return false;
+    for (size_t i = 0; i < rs.long_row.size(); ++i)
+        if (rs.long_row[i] < 0 || rs.long_row[i] >= n_out || rs.long_part_ptr[i] >= rs.long_part_ptr[i + 1] ||
+            rs.long_part_ptr[i + 1] > (int32_t)np) return false;
+    if (!rs.long_part_ptr.empty() && rs.long_part_ptr.back() != (int32_t)np) return false;
     return true;
 }
 
+// lane groups per row (log2) for the rows of stored class cls when a gathered row takes 2^lpr_log2 lanes
+int groups_log2(int cls, int lpr_log2) {
+    const int g_max = 6 - lpr_log2;
+    if (cls == 0) return g_max;
+    int g = 0;
+    while (g < g_max && (kChunkEntries << g) < (4 << (kLengthClasses - 1 - cls))) ++g;
+    return g;
+}
+
 }  // namespace
+
+int64_t count_blocks(const RowSchedule& rs, int lpr_log2) {
+    int64_t n = (rs.n_parts() + 3) / 4;                 // a part takes a whole wavefront, four per workgroup
+    for (const ScheduleRun& run : rs.runs) {
+        const int64_t per = 4LL << (6 - lpr_log2 - groups_log2(run.cls, lpr_log2));
+        n += (run.row1 - run.row0 + per - 1) / per;
+    }
+    return n;
+}
+
+void build_block_table(const RowSchedule& rs, int lpr_log2, BlockTable& out) {
+    const int64_t n_rows = rs.n_rows(), n_parts = rs.n_parts();
+    const int g_max = 6 - lpr_log2;
+    auto chunks = [&](int64_t i) { return (int64_t)(rs.rec[(size_t)i].chunk1 - rs.rec[(size_t)i].chunk0); };
+    auto trips_for = [](int64_t longest_chunks, int g) { return (int32_t)std::max<int64_t>(1, (longest_chunks + (1LL << g) - 1) >> g); };
+    auto block_of = [&](int64_t r, int64_t r1, int g, double& cost) {
+        int64_t longest = 0, total = 0;
+        for (int64_t i = r; i < r1; ++i) { longest = std::max(longest, chunks(i)); total += chunks(i); }
+        cost = (double)(total * kChunkEntries) + 8.0 * (double)(r1 - r);     // its entries, plus a fixed share per row
+        return BlockRows{(int32_t)r, (int32_t)r1, g, trips_for(longest, g)};
+    };
+    // the parts of split rows, dealt round-robin to the XCDs; they come first in every slice, so that the longest
+    // pieces of work do not form the tail of a launch
+    std::vector<BlockRows> parts[8];
+    double part_cost[8] = {}, total = 0.0, c = 0.0;
+    for (int64_t p = 0, b = 0; p < n_parts; p += 4, ++b) {
+        parts[b & 7].push_back(block_of(n_rows + p, n_rows + std::min(p + 4, n_parts), g_max, c));
+        part_cost[b & 7] += c;
+        total += c;
+    }
+    // the scheduled rows in run order
+    std::vector<BlockRows> rows;
+    std::vector<double> cost;
+    rows.reserve((size_t)count_blocks(rs, lpr_log2));
+    cost.reserve(rows.capacity());
+    for (const ScheduleRun& run : rs.runs) {
+        const int g = groups_log2(run.cls, lpr_log2);
+        const int64_t per = 4LL << (6 - lpr_log2 - g);
+        for (int64_t r = run.row0; r < run.row1; r += per) {
+            rows.push_back(block_of(r, std::min(r + per, run.row1), g, c));
+            cost.push_back(c);
+            total += c;
+        }
+    }
+    // slice k: its parts, then consecutive row workgroups until it holds an eighth of the work
+    out.blocks.clear();
+    out.blocks.reserve(rows.size() + (size_t)((n_parts + 3) / 4));
+    const int64_t nb = (int64_t)rows.size();
+    int64_t b = 0;
+    double done = 0.0;                    // work handed out so far, parts included
+    for (int k = 0; k < 8; ++k) {
+        out.xcd_start[k] = (int64_t)out.blocks.size();
+        out.blocks.insert(out.blocks.end(), parts[k].begin(), parts[k].end());
+        done += part_cost[k];
+        const double want = total * (k + 1) / 8.0;
+        while (b < nb && (k == 7 || done + 0.5 * cost[(size_t)b] < want)) {
+            out.blocks.push_back(rows[(size_t)b]);
+            done += cost[(size_t)b++];
+        }
+    }
+    out.xcd_start[8] = (int64_t)out.blocks.size();
+}
+
+// What the kernels' row mapping relies on: every scheduled row and every part is in exactly one workgroup, no
+// workgroup mixes the two or holds more rows than four wavefronts cover with its lane groups, its trip count covers
+// its longest row, and the XCD slices tile the table.
+bool block_table_ok(const RowSchedule& rs, int lpr_log2, const BlockTable& bt) {
+    const int64_t n_rows = rs.n_rows(), n_parts = rs.n_parts();
+    if (n_rows + n_parts > INT32_MAX) return false;
+    std::vector<BlockRows> sorted(bt.blocks);
+    std::sort(sorted.begin(), sorted.end(), [](const BlockRows& a, const BlockRows& b) { return a.row0 < b.row0; });
+    int64_t at = 0;
+    for (const BlockRows& b : sorted) {
+        if (b.row0 != at || b.row1 <= b.row0 || b.g < 0 || lpr_log2 + b.g > 6 || b.trips < 1) return false;
+        if ((int64_t)b.row1 - b.row0 > (4LL << (6 - lpr_log2 - b.g))) return false;
+        if (b.row0 < n_rows && b.row1 > n_rows) return false;
+        for (int64_t i = b.row0; i < b.row1; ++i)
+            if ((int64_t)(rs.rec[(size_t)i].chunk1 - rs.rec[(size_t)i].chunk0) > ((int64_t)b.trips << b.g)) return false;
+        at = b.row1;
+    }
+    if (at != n_rows + n_parts) return false;
+    if (bt.xcd_start[0] != 0 || bt.xcd_start[8] != (int64_t)bt.blocks.size()) return false;
+    for (int k = 0; k < 8; ++k)
+        if (bt.xcd_start[k] > bt.xcd_start[k + 1]) return false;
+    return true;
+}
 
 std::string build_host_graph(HostGraph& g, int64_t N, int64_t n_edges, const int32_t* src,
                              const int32_t* dst, int32_t M, const int32_t* comm, int chunk_rows) {
@@ -276,10 +386,11 @@ std::string build_host_graph(HostGraph& g, int64_t N, int64_t n_edges, const int
     g.seg_pos.resize((size_t)g.n_seg);
     for (int64_t j = 0; j < g.n_seg; ++j) g.seg_pos[(size_t)g.segc_order[(size_t)j]] = (int32_t)j;
 
-    make_schedule(g.row_sched, N, g.row_ptr.data(), g.row_ptr.data() + 1, nullptr, g.col.data(), g.val.data());
+    make_schedule(g.row_sched, N, g.row_ptr.data(), g.row_ptr.data() + 1, nullptr, g.row_comm.data(), M, g.col.data(),
+                  g.val.data());
     {
         std::vector<int64_t> mlo, mhi;
-        std::vector<int32_t> mpos;
+        std::vector<int32_t> mpos, mgrp;
         for (int64_t j = 0; j < g.n_seg; ++j) {
             const int64_t s = g.segc_order[(size_t)j];
             const int64_t lo = g.seg_ptr[(size_t)s], hi = g.seg_ptr[(size_t)s + 1];
@@ -291,12 +402,22 @@ std::string build_host_graph(HostGraph& g, int64_t N, int64_t n_edges, const int
                 mlo.push_back(lo);
                 mhi.push_back(hi);
                 mpos.push_back((int32_t)j);
+                mgrp.push_back(g.seg_comm[(size_t)s]);
             }
         }
-        make_schedule(g.seg_sched, (int64_t)mpos.size(), mlo.data(), mhi.data(), mpos.data(), g.col.data(), g.val.data());
+        make_schedule(g.seg_sched, (int64_t)mpos.size(), mlo.data(), mhi.data(), mpos.data(), mgrp.data(), M, g.col.data(),
+                      g.val.data());
     }
 
-    if (!schedule_ok(g.row_sched, N) || !schedule_ok(g.seg_sched, g.n_seg)) return "internal error: row schedule";
+    if (!schedule_ok(g.row_sched, N, N) || !schedule_ok(g.seg_sched, g.n_seg, N)) return "internal error: row schedule";
+    for (int l = 0; l < 7; ++l) {
+        BlockTable bt;
+        for (const RowSchedule* rs : {&g.row_sched, &g.seg_sched}) {
+            build_block_table(*rs, l, bt);
+            if (!block_table_ok(*rs, l, bt) || (int64_t)bt.blocks.size() != count_blocks(*rs, l))
+                return "internal error: workgroup table of the aggregation";
+        }
+    }
 
     // reduction chunks: for every community its own rows, then its segments
     g.unit_chunk_ptr.assign(M + 1, 0);

@@ -16,41 +16,39 @@ struct SpmmEpilogue {
     const float* Tl = nullptr;
     float nu = 0.f;
 };
-// Long rows (more than max_len entries) are skipped by the row kernel; their parts are aggregated into
-// `side` (n_parts x width) and added in order by a combine kernel, which also applies the epilogue.
-struct SpmmLong {
-    int max_len = 0;                 // 0 = no splitting
-    int mean_len = 0;                // mean entries per row of the row list (chooses the lane groups per row)
+// Device view of a row list laid out for the aggregation (RowSchedule on the host).  rec[i] = (first chunk, one past
+// the last chunk, output row, 0) of scheduled row i; a chunk is 8 (column, value) pairs of 8 bytes, padded with
+// weight zero, chunk 0 all padding.  Records from n_rows on are the parts of rows that were too long for one lane
+// group: their output row is a row of `side` (n_parts x width), and a combine kernel adds a split row's parts in
+// order and applies the epilogue.
+// blocks[l] / n_blocks[l] / xcd_start[l]: the workgroup -> rows table for 2^l lanes per gathered row (BlockTable).
+struct SpmmSchedule {
+    int64_t n_rows = 0;
     int64_t n_parts = 0;
-    const int64_t* part_lo = nullptr;
-    const int64_t* part_hi = nullptr;
+    const int4* rec = nullptr;
+    const int2* ent = nullptr;
     int64_t n_long = 0;
     const int32_t* long_row = nullptr;
     const int32_t* long_part_ptr = nullptr;
     float* side = nullptr;
-    int xcd_remap = -1;              // 1 / 0: XCD k walks the k-th eighth of the rows / plain order; -1: the global setting
-    // Host array of kSpmmClasses + 1 row indices, or null.  Rows [class_start[j], class_start[j+1]) hold at most
-    // 4 * 2^(kSpmmClasses-1-j) entries each (j = 0: any length up to max_len); each class then gets the lane groups
-    // per row that its rows can fill.  Null: one class, lane groups from mean_len.
-    const int64_t* class_start = nullptr;
+    const int4* blocks[7] = {};
+    int64_t n_blocks[7] = {};
+    int64_t xcd_start[7][9] = {};
 };
-constexpr int kSpmmClasses = 8;
-// Row r of the list goes to row out_index[r] of Y (to row r if out_index is null; the epilogue needs null).
-void launch_spmm(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32_t* col, const float* val,
-                 const float* X, float* Y, int64_t nrows, int width, const SpmmEpilogue& epi,
-                 const SpmmLong& lg, const int32_t* out_index = nullptr);
+void launch_spmm(hipStream_t s, const SpmmSchedule& sched, const float* X, float* Y, int width, const SpmmEpilogue& epi);
 // Y[pos[k], :] = val[k] * X[col[k], :] for k < n: the output rows that have a single entry.
+// calibration: only the gathers of the row list's column stream, rows of `width` floats (4, 8, 16, ... 256) of X;
+// out: 256 floats (never written in practice); returns the bytes the launch asks the memory system for
+double launch_gather_calibration(hipStream_t s, const SpmmSchedule& sc, int64_t n_chunks, const float* X, int width,
+                                 float* out);
 void launch_spmm_single(hipStream_t s, const int32_t* pos, const int32_t* col, const float* val, const float* X,
                         float* Y, int64_t n, int width);
 // columns of the feature matrix handled per launch (0 = all); smaller tiles keep a community's share of
 // the gathered matrix inside one XCD's L2 at the price of re-reading the entries once per tile
 void set_spmm_tile_cols(int cols);
-// 1: inside a length class every XCD walks one contiguous eighth of the rows (default); 0: blocks in plain order
+// 1: every XCD walks one contiguous slice of the workgroup table, whole communities one after the other (default);
+// 0: workgroups in plain table order, which deals consecutive row blocks round-robin to the XCDs
 void set_spmm_xcd_remap(int on);
-// lane groups per output row as a power of two (-1 = from the mean row length)
-void set_spmm_groups_log2(int v);
-// gathers in flight per lane group: 8 (default, single-repeat shapes only) or 4
-void set_spmm_unroll(int v);
 
 // ---------------------------------------------------------------- dense contractions (gemm.hip)
 struct Unit;

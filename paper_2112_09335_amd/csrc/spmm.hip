@@ -3,21 +3,26 @@
 // neighbour community per output row, the "segments").
 //
 // Layout: a row list (the CSR rows, or the (row, community) segments with several entries) laid out by the host
-// for this kernel: rows grouped into length classes, the longest class first and community-contiguous inside a
-// class, with a copy of the column indices and values in that order and the output row of every list row.
-// Features are row-major fp32.
+// for these kernels: rows sorted by (community, length class); one 16-byte record per row (its chunk range and
+// output row); the entries as (column, value) pairs in chunks of eight, padded with weight zero; and a table that
+// names the rows of every workgroup.  Features are row-major fp32.
 //
 // Mapping: a group of LPR lanes (a power of two, up to the 64-lane wavefront) reads one gathered
 // neighbour row with one fully coalesced VEC*4-byte load per lane and keeps VEC*R accumulators per lane.
-// GPR such groups share one output row and take its entries round-robin, eight (or four) entries in flight per
-// group; their partial sums are added by a wavefront-level xor-shuffle reduction.  GPR is chosen per length
-// class so that one trip of the entry loop covers the class's longest row: short rows pack many rows into a
+// GPR such groups share one output row and take its chunks round-robin, one chunk = eight gathers in flight per
+// group and trip; their partial sums are added by a wavefront-level xor-shuffle reduction.  GPR is chosen per run
+// of one length class so that one trip covers the class's longest row: short rows pack many rows into a
 // wavefront, long rows spread over it, and the rows of a wavefront need the same number of trips.
+// What bounds the narrow shapes is the address unit, which takes a wavefront's load instruction four lanes a
+// cycle whatever it loads: so a lane group fetches its chunk with one load of 64 bytes spread over its lanes (one
+// instruction per 128 entries at 16 columns) and hands the pairs round by lane exchanges, instead of one load of
+// four bytes per entry and array.
 // Rows beyond a length threshold (power-law hubs) are cut into parts that run first in the same launch, into a
 // side buffer; a small kernel adds a row's parts in order.  Segments with a single entry are scaled copies of a
 // gathered row and have a kernel of their own.  Everything is order-fixed: no atomics, results are reproducible.
-// The bound is the L2 / fabric traffic of the gathers.  Inside a class XCD k (blockIdx mod 8) walks the k-th
-// contiguous eighth of the rows (a few communities), so that the rows it gathers stay in its L2.
+// XCD k (blockIdx mod 8) walks the k-th slice of the workgroup table, whole communities one after the other with
+// all their length classes, so that the rows of the gathered matrix a community reads are fetched into that XCD's
+// L2 once.
 #include "kernels.h"
 
 namespace cadmm {
@@ -51,49 +56,88 @@ __device__ __forceinline__ void store_vec(float* p, const float (&src)[VEC]) {
     }
 }
 
-// Which rows a workgroup takes: class j covers the rows [row_start[j], row_start[j+1]) with 2^g[j] lane groups per
-// row, in the workgroups [block_start[j], block_start[j+1]) after those of the parts.
-struct ClassMap {
-    int n;
-    int part_g;
-    int g[kSpmmClasses];
-    long long row_start[kSpmmClasses + 1];
-    long long block_start[kSpmmClasses + 1];
+// Slice k of the workgroup table (the workgroups of XCD k) is [start[k], start[k+1]).
+struct XcdMap {
+    long long start[9];
 };
 
-template <int VEC, int R, int EPI, int U>
+template <int S>
+__device__ __forceinline__ int quad_bcast(int v) {       // lane j of every quad gets lane S's value
+    return __builtin_amdgcn_mov_dpp(v, S * 0x55, 0xF, 0xF, true);
+}
+
+// The eight (column, value) pairs of chunk `chunk` for every lane of a lane group of 2^LPRL lanes (LPRL = 3 stands
+// for 8 and more lanes, lpr_log2 then says how many).  The group's lanes share the chunk's 64 bytes among them in
+// as few load instructions as possible and exchange the pairs afterwards.
+template <int LPRL>
+__device__ __forceinline__ void load_chunk(const int2* __restrict__ ent, int64_t chunk, int lpr_log2, int lane,
+                                           int32_t (&c)[8], float (&a)[8]) {
+    const int4* e4 = reinterpret_cast<const int4*>(ent) + chunk * 4;      // a chunk is four 16-byte pieces
+    if constexpr (LPRL == 0) {
+        const int4 q0 = e4[0], q1 = e4[1], q2 = e4[2], q3 = e4[3];
+        c[0] = q0.x; c[1] = q0.z; c[2] = q1.x; c[3] = q1.z; c[4] = q2.x; c[5] = q2.z; c[6] = q3.x; c[7] = q3.z;
+        a[0] = __int_as_float(q0.y); a[1] = __int_as_float(q0.w); a[2] = __int_as_float(q1.y); a[3] = __int_as_float(q1.w);
+        a[4] = __int_as_float(q2.y); a[5] = __int_as_float(q2.w); a[6] = __int_as_float(q3.y); a[7] = __int_as_float(q3.w);
+    } else if constexpr (LPRL == 1) {
+        const int sub = lane & 1;
+        const int4 q0 = e4[2 * sub], q1 = e4[2 * sub + 1];                // pairs 4 sub .. 4 sub + 3
+        const int mine[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int src = (lane & ~1) | (u >> 2);
+            c[u] = __shfl(mine[2 * (u & 3)], src, 64);
+            a[u] = __int_as_float(__shfl(mine[2 * (u & 3) + 1], src, 64));
+        }
+    } else if constexpr (LPRL == 2) {
+        const int4 q = e4[lane & 3];                                      // pairs 2 sub, 2 sub + 1
+        c[0] = quad_bcast<0>(q.x); a[0] = __int_as_float(quad_bcast<0>(q.y));
+        c[1] = quad_bcast<0>(q.z); a[1] = __int_as_float(quad_bcast<0>(q.w));
+        c[2] = quad_bcast<1>(q.x); a[2] = __int_as_float(quad_bcast<1>(q.y));
+        c[3] = quad_bcast<1>(q.z); a[3] = __int_as_float(quad_bcast<1>(q.w));
+        c[4] = quad_bcast<2>(q.x); a[4] = __int_as_float(quad_bcast<2>(q.y));
+        c[5] = quad_bcast<2>(q.z); a[5] = __int_as_float(quad_bcast<2>(q.w));
+        c[6] = quad_bcast<3>(q.x); a[6] = __int_as_float(quad_bcast<3>(q.y));
+        c[7] = quad_bcast<3>(q.z); a[7] = __int_as_float(quad_bcast<3>(q.w));
+    } else {
+        const int base = lane & ~((1 << lpr_log2) - 1);
+        const int2 q = ent[chunk * 8 + (lane & 7)];                       // lane j of the group holds pair j mod 8
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            c[u] = __shfl(q.x, base + u, 64);
+            a[u] = __int_as_float(__shfl(q.y, base + u, 64));
+        }
+    }
+}
+
+// LPRL: lanes per gathered row as a power of two (3 stands for 8 and more, lpr_log2_arg then says how many); R column
+// repeats per lane (more than one only for more than 256 columns, a whole wavefront per gathered row).
+template <int VEC, int R, int EPI, int LPRL>
 __global__ __launch_bounds__(256) void spmm_rows_kernel(
-    const int64_t* __restrict__ lo, const int64_t* __restrict__ hi, const int64_t* __restrict__ part_lo,
-    const int64_t* __restrict__ part_hi, int64_t nrows, int64_t nparts, const int32_t* __restrict__ col,
-    const float* __restrict__ val, const float* __restrict__ X, float* __restrict__ Y, float* __restrict__ side,
-    int width, int lpr_log2, ClassMap cm, int col0, int col1, int max_len, int xcd_remap,
-    const float* __restrict__ Zl, const float* __restrict__ Tl, float nu, const int32_t* __restrict__ out_index,
-    int64_t part_blocks) {
-    // The first part_blocks workgroups (a multiple of 8) take the parts of split rows, the longest pieces of work,
-    // so that they do not form the tail of the launch; then come the workgroups of each length class in turn (each
-    // count a multiple of 8).  Optional XCD-aware renumbering inside a class: XCD k (blockIdx mod 8) walks the
-    // k-th contiguous eighth of its rows.
+    const int4* __restrict__ rec, int64_t nrows, const int2* __restrict__ ent, const float* __restrict__ X,
+    float* __restrict__ Y, float* __restrict__ side, int width, int lpr_log2_arg, const int4* __restrict__ blocks,
+    XcdMap xm, int col0, int col1, int xcd_remap, const float* __restrict__ Zl, const float* __restrict__ Tl, float nu) {
+    // Workgroup b belongs to XCD b mod 8 and takes the (b / 8)-th entry of that XCD's slice of the table (or, without
+    // the XCD-aware numbering, simply entry b).  Records from nrows on are the parts of split rows.
+    const int lpr_log2 = LPRL < 3 ? LPRL : lpr_log2_arg;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    int gpr_log2;
-    int64_t vrow;
-    if ((int64_t)blockIdx.x < part_blocks) {
-        gpr_log2 = cm.part_g;
-        const int span_log2 = lpr_log2 + gpr_log2;      // lanes that share one output row
-        vrow = (((int64_t)blockIdx.x * 4 + wave) << (6 - span_log2)) + (lane >> span_log2);
-        if (vrow >= nparts) return;
-        vrow += nrows;
+    int64_t idx;
+    if (xcd_remap) {
+        const int k = (int)(blockIdx.x & 7);
+        idx = xm.start[k] + (blockIdx.x >> 3);
+        if (idx >= xm.start[k + 1]) return;
     } else {
-        const int64_t b = (int64_t)blockIdx.x - part_blocks;
-        int j = 0;
-        while (j + 1 < cm.n && b >= cm.block_start[j + 1]) ++j;
-        gpr_log2 = cm.g[j];
-        const int span_log2 = lpr_log2 + gpr_log2;
-        int64_t lb = b - cm.block_start[j];
-        if (xcd_remap) lb = (lb & 7) * ((cm.block_start[j + 1] - cm.block_start[j]) >> 3) + (lb >> 3);
-        vrow = cm.row_start[j] + (((lb * 4 + wave) << (6 - span_log2)) + (lane >> span_log2));
-        if (vrow >= cm.row_start[j + 1]) return;        // uniform over the row's lane span
+        idx = blockIdx.x;
+        if (idx >= xm.start[8]) return;
     }
+    const int4 d = blocks[idx];                         // rows [d.x, d.y), 2^d.z lane groups per row
+    const int gpr_log2 = d.z;
+    const int span_log2 = lpr_log2 + gpr_log2;          // lanes that share one output row
+    const int64_t vrow = (int64_t)d.x + ((wave << (6 - span_log2)) + (lane >> span_log2));
+    if (vrow >= d.y) return;                            // uniform over the row's lane span
+    const int4 r = rec[vrow];                           // chunks [r.x, r.y), output row r.z
+    const bool is_part = vrow >= nrows;
+    float* const dst = (is_part ? side : Y) + (int64_t)r.z * (int64_t)width;
     const int lpr = 1 << lpr_log2;
     const int gpr = 1 << gpr_log2;
     const int grp = (lane >> lpr_log2) & (gpr - 1);
@@ -101,83 +145,63 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(
     const int cbase = col0 + sub * VEC;                 // first column of repeat 0
     const int cstride = lpr * VEC;                      // columns between repeats
 
-    int64_t p, e;
-    float* dst;
-    bool is_part = vrow >= nrows;
-    if (!is_part) {
-        p = lo[vrow];
-        e = hi[vrow];
-        if (max_len > 0 && e - p > max_len) return;     // split row: the first workgroups take its parts
-        dst = Y + (out_index ? (int64_t)out_index[vrow] : vrow) * (int64_t)width;
-    } else {
-        p = part_lo[vrow - nrows];
-        e = part_hi[vrow - nrows];
-        dst = side + (vrow - nrows) * (int64_t)width;
-    }
-
     float acc[R][VEC];
 #pragma unroll
-    for (int r = 0; r < R; ++r)
+    for (int q = 0; q < R; ++q)
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) acc[r][v] = 0.f;
-
-    // the groups of a row take entries p+grp, p+grp+gpr, ...; U of them in flight per group.  Every load is
-    // unconditional: a slot past the end of the row reads the row's last entry again with weight zero, and a lane
-    // past the last column reads the last columns again without storing them.  (Loads under a branch would make
-    // the compiler wait for each gather before it issues the next.)
+        for (int v = 0; v < VEC; ++v) acc[q][v] = 0.f;
+    // a lane past the last column reads the last columns again without storing them
     int ccl[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int cc = cbase + r * cstride;
-        ccl[r] = cc < col1 ? cc : col1 - VEC;
+    for (int q = 0; q < R; ++q) {
+        const int cc = cbase + q * cstride;
+        ccl[q] = cc < col1 ? cc : col1 - VEC;
     }
-    for (int64_t q = p + grp; q < e; q += U * gpr) {
-        int32_t c[U];
-        float a[U];
+    // the groups of a row take its chunks grp, grp + gpr, ...: eight gathers in flight per group (four per column
+    // repeat for the wide shapes); the padding of a chunk carries weight zero, so no entry is masked
+    constexpr int UH = (R == 1) ? 8 : 4;
+    for (int ch = r.x + grp; ch < r.y; ch += gpr) {
+        int32_t c[8];
+        float a[8];
+        load_chunk<LPRL>(ent, ch, lpr_log2, lane, c, a);
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t qu = q + u * gpr;
-            const bool ok = qu < e;
-            const int64_t qc = ok ? qu : e - 1;
-            c[u] = col[qc];
-            const float av = val[qc];
-            a[u] = ok ? av : 0.f;
+        for (int h = 0; h < 8 / UH; ++h) {
+            float x[UH][R][VEC];
+#pragma unroll
+            for (int u = 0; u < UH; ++u)
+#pragma unroll
+                for (int q = 0; q < R; ++q) load_vec<VEC>(x[u][q], X + (int64_t)c[UH * h + u] * width + ccl[q]);
+#pragma unroll
+            for (int u = 0; u < UH; ++u)
+#pragma unroll
+                for (int q = 0; q < R; ++q)
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[q][v] = fmaf(a[UH * h + u], x[u][q][v], acc[q][v]);
         }
-        float x[U][R][VEC];
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int r = 0; r < R; ++r) load_vec<VEC>(x[u][r], X + (int64_t)c[u] * width + ccl[r]);
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) acc[r][v] = fmaf(a[u], x[u][r][v], acc[r][v]);
     }
     // wavefront-level reduction across the groups of the row
     for (int off = lpr; off < (lpr << gpr_log2); off <<= 1) {
 #pragma unroll
-        for (int r = 0; r < R; ++r)
+        for (int q = 0; q < R; ++q)
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) acc[r][v] += __shfl_xor(acc[r][v], off, 64);
+            for (int v = 0; v < VEC; ++v) acc[q][v] += __shfl_xor(acc[q][v], off, 64);
     }
     if (grp != 0) return;
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int cc = cbase + r * cstride;
+    for (int q = 0; q < R; ++q) {
+        const int cc = cbase + q * cstride;
         if (cc < col1) {
             if constexpr (EPI == 1) {
                 if (!is_part) {
-                    const int64_t o = (out_index ? (int64_t)out_index[vrow] : vrow) * (int64_t)width + cc;
+                    const int64_t o = (int64_t)r.z * (int64_t)width + cc;
                     float z[VEC], t[VEC];
                     load_vec<VEC>(z, Zl + o);
                     load_vec<VEC>(t, Tl + o);
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) acc[r][v] = nu * (z[v] - fmaxf(t[v], 0.f)) + acc[r][v];
+                    for (int v = 0; v < VEC; ++v) acc[q][v] = nu * (z[v] - fmaxf(t[v], 0.f)) + acc[q][v];
                 }
             }
-            store_vec<VEC>(dst + cc, acc[r]);
+            store_vec<VEC>(dst + cc, acc[q]);
         }
     }
 }
@@ -219,10 +243,43 @@ __global__ __launch_bounds__(256) void spmm_single_kernel(const int32_t* __restr
     }
 }
 
+// Machine calibration for the aggregation: the gathers of a row list and nothing else.  Every lane group takes one
+// chunk of the entry array (the real column stream, in the order the aggregation reads it: XCD k, the workgroups with
+// blockIdx mod 8 = k, walks the k-th eighth front to back), gathers the eight rows the chunk names and adds them up;
+// there are no row records, no reduction across lanes and no result rows (a lane stores only if its sum is a value
+// that does not occur, which keeps the loads alive).  What this reaches is the rate at which the memory system serves
+// this column stream's gathers of 4 * VEC * 2^lpr_log2 bytes.
+template <int LPRL>
+__global__ __launch_bounds__(256) void gather_calibration_kernel(const int2* __restrict__ ent, int64_t n_chunks,
+                                                                 const float* __restrict__ X, int width, int lpr_log2_arg,
+                                                                 float* __restrict__ out) {
+    const int lpr_log2 = LPRL < 3 ? LPRL : lpr_log2_arg;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int k = blockIdx.x & 7;
+    const int64_t per_xcd = (n_chunks + 7) / 8;
+    const int64_t lo = 1 + k * per_xcd, hi = lo + per_xcd < n_chunks ? lo + per_xcd : n_chunks;   // chunk 0 is padding
+    const int groups = 64 >> lpr_log2;
+    const int64_t ch = lo + ((int64_t)(blockIdx.x >> 3) * 4 + wave) * groups + (lane >> lpr_log2);
+    if (ch >= hi) return;                               // uniform over a lane group
+    const int cc = (lane & ((1 << lpr_log2) - 1)) * 4;
+    int32_t c[8];
+    float a[8];
+    load_chunk<LPRL>(ent, ch, lpr_log2, lane, c, a);
+    float x[8][4];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) load_vec<4>(x[u], X + (int64_t)c[u] * width + cc);
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[v] = fmaf(a[u], x[u][v], acc[v]);
+    const float sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    if (sum == 1.2345678e33f) out[threadIdx.x] = sum;
+}
+
 int g_tile_cols = 0;
 int g_xcd_remap = 1;
-int g_gpr_log2 = -1;      // -1: chosen from the mean row length
-int g_unroll = 8;
 
 // Adds the parts of every split row and applies the epilogue.  One wavefront per row: 2^lpr_log2 lanes cover the
 // columns of the tile; where that leaves lanes over, the 64 >> lpr_log2 lane groups take the parts round-robin and
@@ -273,90 +330,53 @@ __global__ __launch_bounds__(64) void spmm_combine_kernel(const float* __restric
 }
 
 template <int VEC, int R>
-void launch_cfg(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32_t* col, const float* val,
-                const float* X, float* Y, int64_t nrows, int width, int lpr_log2, int gpr_log2, int col0, int col1,
-                const SpmmEpilogue& epi, const SpmmLong& lg, bool split, const int32_t* out_index) {
-    const int64_t nparts = split ? lg.n_parts : 0;
-    constexpr int U = (R == 1) ? 8 : 4;              // gathers in flight per lane group when g_unroll allows
-    const bool deep = g_unroll == 8 && R == 1;
-    const int in_flight = deep ? U : 4;
-    const int g_max = 6 - lpr_log2;
-    ClassMap cm;
-    if (lg.class_start && g_gpr_log2 < 0) {
-        // class j holds rows of at most 4 * 2^(kSpmmClasses-1-j) entries (j = 0: up to the split threshold): the
-        // fewest lane groups whose gathers in flight cover such a row in one trip of the entry loop
-        cm.n = kSpmmClasses;
-        for (int j = 0; j < kSpmmClasses; ++j) {
-            int g = 0;
-            if (j == 0) g = g_max;
-            else while (g < g_max && (in_flight << g) < (4 << (kSpmmClasses - 1 - j))) ++g;
-            cm.g[j] = g;
-            cm.row_start[j] = lg.class_start[j];
-        }
-        cm.row_start[kSpmmClasses] = lg.class_start[kSpmmClasses];
-    } else {
-        cm.n = 1;
-        cm.g[0] = gpr_log2;
-        cm.row_start[0] = 0;
-        cm.row_start[1] = nrows;
-    }
-    cm.part_g = (g_gpr_log2 >= 0) ? gpr_log2 : g_max;
-    cm.block_start[0] = 0;
-    for (int j = 0; j < cm.n; ++j) {
-        const int64_t per_block = 4 * (64 >> (lpr_log2 + cm.g[j]));
-        const int64_t n = cm.row_start[j + 1] - cm.row_start[j];
-        cm.block_start[j + 1] = cm.block_start[j] + ((n + per_block - 1) / per_block + 7) / 8 * 8;
-    }
-    for (int j = cm.n; j < kSpmmClasses; ++j) {
-        cm.g[j] = 0;
-        cm.row_start[j + 1] = cm.row_start[cm.n];
-        cm.block_start[j + 1] = cm.block_start[cm.n];
-    }
-    const int64_t part_per_block = 4 * (64 >> (lpr_log2 + cm.part_g));
-    const int64_t part_blocks = ((nparts + part_per_block - 1) / part_per_block + 7) / 8 * 8;
-    const int64_t nb = part_blocks + cm.block_start[cm.n];
+void launch_cfg(hipStream_t s, const SpmmSchedule& sc, const float* X, float* Y, int width, int lpr_log2, int col0,
+                int col1, const SpmmEpilogue& epi) {
+    XcdMap xm;
+    int64_t longest = 0;
+    for (int k = 0; k <= 8; ++k) xm.start[k] = sc.xcd_start[lpr_log2][k];
+    for (int k = 0; k < 8; ++k) longest = xm.start[k + 1] - xm.start[k] > longest ? xm.start[k + 1] - xm.start[k] : longest;
+    const int64_t nb = g_xcd_remap ? 8 * longest : (sc.n_blocks[lpr_log2] + 7) / 8 * 8;
     if (nb <= 0) return;
     dim3 grid((unsigned)nb), block(256);
-    const int xcd_remap = (lg.xcd_remap >= 0) ? lg.xcd_remap : g_xcd_remap;
-    const int max_len = split ? lg.max_len : 0;
-#define CADMM_SPMM(E_, U_, Z_, T_, NU_) hipLaunchKernelGGL((spmm_rows_kernel<VEC, R, E_, U_>), grid, block, 0, s, lo, hi, lg.part_lo, lg.part_hi, nrows, nparts, col, val, X, Y, lg.side, width, lpr_log2, cm, col0, col1, max_len, xcd_remap, Z_, T_, NU_, out_index, part_blocks)
-    if (epi.kind == 1) { if (deep) CADMM_SPMM(1, 8, epi.Zl, epi.Tl, epi.nu); else CADMM_SPMM(1, 4, epi.Zl, epi.Tl, epi.nu); }
-    else { if (deep) CADMM_SPMM(0, 8, nullptr, nullptr, 0.f); else CADMM_SPMM(0, 4, nullptr, nullptr, 0.f); }
-#undef CADMM_SPMM
+#define CADMM_ROWS(L_) do { \
+        if (epi.kind == 1) hipLaunchKernelGGL((spmm_rows_kernel<VEC, R, 1, L_>), grid, block, 0, s, sc.rec, sc.n_rows, sc.ent, X, Y, \
+                                              sc.side, width, lpr_log2, sc.blocks[lpr_log2], xm, col0, col1, g_xcd_remap, epi.Zl, epi.Tl, epi.nu); \
+        else hipLaunchKernelGGL((spmm_rows_kernel<VEC, R, 0, L_>), grid, block, 0, s, sc.rec, sc.n_rows, sc.ent, X, Y, sc.side, width, \
+                                lpr_log2, sc.blocks[lpr_log2], xm, col0, col1, g_xcd_remap, nullptr, nullptr, 0.f); } while (0)
+    if constexpr (R == 1) {
+        if (lpr_log2 == 0) CADMM_ROWS(0);
+        else if (lpr_log2 == 1) CADMM_ROWS(1);
+        else if (lpr_log2 == 2) CADMM_ROWS(2);
+        else CADMM_ROWS(3);
+    } else {
+        CADMM_ROWS(3);                                   // column repeats only occur with a whole wavefront per row
+    }
+#undef CADMM_ROWS
 }
 
 template <int VEC>
-void launch_vec(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32_t* col, const float* val,
-                const float* X, float* Y, int64_t nrows, int width, const SpmmEpilogue& epi, const SpmmLong& lg,
-                const int32_t* out_index) {
+void launch_vec(hipStream_t s, const SpmmSchedule& sc, const float* X, float* Y, int width, const SpmmEpilogue& epi) {
     // column tiles of at most 64 lanes * VEC * 4 repeats; a smaller tile can be requested
     int tile = 64 * VEC * 4;
     if (g_tile_cols > 0 && g_tile_cols < tile) tile = (g_tile_cols + VEC - 1) / VEC * VEC;
-    const bool split = lg.max_len > 0 && lg.n_long > 0;
     for (int col0 = 0; col0 < width; col0 += tile) {
         const int col1 = (width - col0 < tile) ? width : col0 + tile;
         const int lanes_needed = (col1 - col0 + VEC - 1) / VEC;
         int lpr_log2 = 0;
         while ((1 << lpr_log2) < lanes_needed && lpr_log2 < 6) ++lpr_log2;
         const int reps = (lanes_needed + (1 << lpr_log2) - 1) >> lpr_log2;
-        // lane groups per row: as many as the wavefront allows, but only until one trip of the entry loop
-        // (groups x gathers in flight per group) covers a row of mean length
-        int gpr_log2 = 0;
-        const int mean_len = lg.mean_len > 0 ? lg.mean_len : 1;
-        const int in_flight = (reps <= 1) ? g_unroll : 4;
-        while (lpr_log2 + gpr_log2 < 6 && (in_flight << gpr_log2) < mean_len) ++gpr_log2;
-        if (g_gpr_log2 >= 0) gpr_log2 = (lpr_log2 + g_gpr_log2 <= 6) ? g_gpr_log2 : 6 - lpr_log2;
-        if (reps <= 1) launch_cfg<VEC, 1>(s, lo, hi, col, val, X, Y, nrows, width, lpr_log2, gpr_log2, col0, col1, epi, lg, split, out_index);
-        else if (reps <= 2) launch_cfg<VEC, 2>(s, lo, hi, col, val, X, Y, nrows, width, lpr_log2, gpr_log2, col0, col1, epi, lg, split, out_index);
-        else launch_cfg<VEC, 4>(s, lo, hi, col, val, X, Y, nrows, width, lpr_log2, gpr_log2, col0, col1, epi, lg, split, out_index);
-        if (split) {
-            dim3 grid((unsigned)lg.n_long), block(64);
+        if (reps <= 1) launch_cfg<VEC, 1>(s, sc, X, Y, width, lpr_log2, col0, col1, epi);
+        else if (reps <= 2) launch_cfg<VEC, 2>(s, sc, X, Y, width, lpr_log2, col0, col1, epi);
+        else launch_cfg<VEC, 4>(s, sc, X, Y, width, lpr_log2, col0, col1, epi);
+        if (sc.n_long > 0) {
+            dim3 grid((unsigned)sc.n_long), block(64);
             if (epi.kind == 1)
-                hipLaunchKernelGGL((spmm_combine_kernel<VEC, 1>), grid, block, 0, s, lg.side, lg.long_row,
-                                   lg.long_part_ptr, lg.n_long, Y, width, col0, col1, epi.Zl, epi.Tl, epi.nu, lpr_log2);
+                hipLaunchKernelGGL((spmm_combine_kernel<VEC, 1>), grid, block, 0, s, sc.side, sc.long_row,
+                                   sc.long_part_ptr, sc.n_long, Y, width, col0, col1, epi.Zl, epi.Tl, epi.nu, lpr_log2);
             else
-                hipLaunchKernelGGL((spmm_combine_kernel<VEC, 0>), grid, block, 0, s, lg.side, lg.long_row,
-                                   lg.long_part_ptr, lg.n_long, Y, width, col0, col1, nullptr, nullptr, 0.f, lpr_log2);
+                hipLaunchKernelGGL((spmm_combine_kernel<VEC, 0>), grid, block, 0, s, sc.side, sc.long_row,
+                                   sc.long_part_ptr, sc.n_long, Y, width, col0, col1, nullptr, nullptr, 0.f, lpr_log2);
         }
     }
 }
@@ -365,15 +385,24 @@ void launch_vec(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32
 
 void set_spmm_tile_cols(int cols) { g_tile_cols = cols > 0 ? cols : 0; }
 void set_spmm_xcd_remap(int on) { g_xcd_remap = on ? 1 : 0; }
-void set_spmm_groups_log2(int v) { g_gpr_log2 = v; }
-void set_spmm_unroll(int v) { g_unroll = (v == 8) ? 8 : 4; }
 
-void launch_spmm(hipStream_t s, const int64_t* lo, const int64_t* hi, const int32_t* col, const float* val,
-                 const float* X, float* Y, int64_t nrows, int width, const SpmmEpilogue& epi, const SpmmLong& lg,
-                 const int32_t* out_index) {
-    if ((nrows <= 0 && lg.n_parts <= 0) || width <= 0) return;
-    if (width % 4 == 0) launch_vec<4>(s, lo, hi, col, val, X, Y, nrows, width, epi, lg, out_index);
-    else launch_vec<1>(s, lo, hi, col, val, X, Y, nrows, width, epi, lg, out_index);
+double launch_gather_calibration(hipStream_t s, const SpmmSchedule& sc, int64_t n_chunks, const float* X, int width,
+                                 float* out) {
+    int lpr_log2 = 0;
+    while ((4 << lpr_log2) < width) ++lpr_log2;
+    const int64_t per_xcd = (n_chunks + 7) / 8, per_block = 4 * (64 >> lpr_log2);
+    dim3 grid((unsigned)(8 * ((per_xcd + per_block - 1) / per_block))), block(256);
+    if (lpr_log2 == 0) hipLaunchKernelGGL((gather_calibration_kernel<0>), grid, block, 0, s, sc.ent, n_chunks, X, width, lpr_log2, out);
+    else if (lpr_log2 == 1) hipLaunchKernelGGL((gather_calibration_kernel<1>), grid, block, 0, s, sc.ent, n_chunks, X, width, lpr_log2, out);
+    else if (lpr_log2 == 2) hipLaunchKernelGGL((gather_calibration_kernel<2>), grid, block, 0, s, sc.ent, n_chunks, X, width, lpr_log2, out);
+    else hipLaunchKernelGGL((gather_calibration_kernel<3>), grid, block, 0, s, sc.ent, n_chunks, X, width, lpr_log2, out);
+    return (double)(n_chunks - 1) * 8.0 * (8.0 + 4.0 * width);       // the pairs and the rows they name
+}
+
+void launch_spmm(hipStream_t s, const SpmmSchedule& sched, const float* X, float* Y, int width, const SpmmEpilogue& epi) {
+    if ((sched.n_rows <= 0 && sched.n_parts <= 0) || width <= 0) return;
+    if (width % 4 == 0) launch_vec<4>(s, sched, X, Y, width, epi);
+    else launch_vec<1>(s, sched, X, Y, width, epi);
 }
 
 void launch_spmm_single(hipStream_t s, const int32_t* pos, const int32_t* col, const float* val, const float* X,

@@ -48,9 +48,22 @@ def close(name, got, ref, floor=0.0):
 
 
 # A pre-activation counts as tied if its fp64 value is within this many units of the rms of its layer block:
-# 64 fp32 roundings (64 * 2^-24), which covers the rounding of a contraction over a few hundred terms in fp32 and
-# the drift of pre-activations that are carried by update formulas for up to 16 iterations.
-TIE_BAND = 4e-6
+# 16 fp32 roundings (16 * 2^-24), which covers the rounding of a contraction over a few hundred terms in fp32 and
+# the drift of pre-activations that are carried by update formulas for up to 16 iterations.  The largest |T| / rms
+# of a tie seen over all parity cases is 3.7e-7.
+TIE_BAND = 1e-6
+# Entries of a hidden pre-activation that an fp32 implementation may put on the other side of zero, per entry and
+# evaluation: those within its rounding error delta of zero, about 0.8 * delta / rms for a bell-shaped distribution
+# (density 0.4 / rms at zero, both sides), with delta = 3e-7 rms as measured.
+TIE_RATE = 0.8 * 3e-7
+
+
+def expected_ties(N, dims, iters):
+    """Expected number of tied entries in `iters` iterations: an iteration looks at ReLU'(T_l) for l = 1..L-1 in
+    the W step and again, after the W step, for l = 2..L-1 in the Z step of layer l-1."""
+    L = len(dims) - 1
+    entries = sum(N * dims[l] for l in range(1, L)) + sum(N * dims[l] for l in range(2, L))
+    return TIE_RATE * entries * iters
 MAX_TIE_CANDIDATES = 8      # entries inside the band in one iteration; more would make the band unselective
 MAX_TIE_FLIPS = 2           # entries of one iteration allowed to fall on the other side
 

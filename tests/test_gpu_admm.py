@@ -7,16 +7,16 @@ import pytest
 
 from oracle.admm import make_oracle
 from paper_2112_09335_amd import synth
-from parity import compare_iterate, record_case, say, step_with_relu_ties
+from parity import compare_iterate, expected_ties, record_case, say, step_with_relu_ties
 
 pytestmark = pytest.mark.gpu
 
 
 def run_case(w, iters, tag, max_ties=None, tune=None):
     """Per-iteration parity of one workload.  A hidden pre-activation within fp32 rounding of zero (a ReLU tie, see
-    step_with_relu_ties) is accepted only entry by entry, and in at most max_ties iterations of the case: one per
-    case, cases longer than 12 iterations one per 12 iterations started."""
-    max_ties = -(-iters // 12) if max_ties is None else max_ties
+    step_with_relu_ties) is accepted only entry by entry, and in at most max_ties iterations of the case: the number
+    of tied entries expected for its size and length (parity.expected_ties) rounded up, at least one."""
+    max_ties = max(1, int(np.ceil(expected_ties(w.N, w.dims, iters)))) if max_ties is None else max_ties
     from paper_2112_09335_amd import binding
     say(f"[{tag}] N={w.N} M={w.M} dims={w.dims} E={w.E} iters={iters}")
     solver = binding.Solver.from_workload(w, 0)
@@ -37,6 +37,7 @@ def run_case(w, iters, tag, max_ties=None, tune=None):
     finally:
         solver.close()
         record_case(case=tag, N=int(w.N), dims=list(w.dims), iters=iters, iters_done=done, worst=worst, ties=ties,
+                    max_ties=max_ties, expected_ties=expected_ties(w.N, w.dims, iters),
                     ok=bool(done == iters and len(ties) <= max_ties))
     return worst
 

@@ -29,7 +29,7 @@ def test_wgrad_without_allocation_matches_the_workspace_entry_point():
             exact = A.double().T @ G.double()
             assert (got.double() - exact).abs().max().item() <= 1e-4 * exact.abs().max().item()
         # a shape beyond the static scratch is refused before anything is launched
-        A = torch.zeros(256, 4608, device="cuda")
+        A = torch.zeros(256, 5120, device="cuda")
         G = torch.zeros(256, 4096, device="cuda")
         with pytest.raises(binding.CadmmError, match="static scratch"):
             bare.op_wgrad_noalloc(A, G)
