@@ -29,6 +29,14 @@ only oracle <-> GPU agreement and the invariants in the tests hold them):
   * last layer: J FISTA steps of size 1/(rho + c_R) from the current Z_L
     (c_R = 1/2 for cross-entropy, 1 for least squares bounds the Hessian of R);
     a row without label has the exact minimiser  b = c - U/rho  of its quadratic;
+  * fista_mode 1 is FISTA with backtracking (the second form Beck and Teboulle give) on the block subproblem of
+    Z_{L,m} (Eq. 5): one constant L per community and step, started at L = rho in every ADMM iteration (the curvature
+    of the quadratic part, a lower bound of every curvature of the objective), multiplied by eta until
+    F(y - grad/L) <= F(y) - ||grad||^2 / (2L)  (the condition F(p_L(y)) <= Q_L(p_L(y), y) without a non-smooth term;
+    equality up to 1e-12 |F(y)| accepts, so that the rounding of F does not decide a search near the solution),
+    at most max_backtrack multiplications per step, and kept for the later steps of the same solve; a step below
+    resolution (||grad||^2 <= (1e-12 L)^2 ||y||^2) is not taken, as for W and Z; rows without label are outside
+    the sums and take their exact minimiser as in mode 0;
   * dual step with the superscripts as printed (Eq. 2): Z_L^k and p^k (p uses W^{k+1}); dual_form = 1
     selects the usual ADMM dual ascent on the new iterates (Z_L^{k+1}, Z_{L-1}^{k+1}, W_L^{k+1}) instead;
   * updates are Jacobi: W^{k+1} from (W^k, Z^k, U^k); every Z^{k+1}_{l,m} from
@@ -132,9 +140,10 @@ class AdmmOracle:
     STATUS_BACKTRACK_CAP = 1
     STATUS_NONFINITE = 2
     STEP_FLOOR = 1e-12
+    FISTA_SLACK = 1e-12       # the backtracking test of fista_mode 1 accepts up to this relative rounding of F
 
     def __init__(self, graph: OracleGraph, dims, *, nu, rho, tau0, theta0, eta, max_backtrack,
-                 fista_iters, risk=0, dual_form=0, schedule=0, step_policy=0):
+                 fista_iters, risk=0, dual_form=0, schedule=0, step_policy=0, fista_mode=0):
         self.g = graph
         self.M = graph.M
         self.N = graph.N
@@ -156,6 +165,11 @@ class AdmmOracle:
         self.step_policy = int(step_policy)
         if self.step_policy not in (0, 1):
             raise ValueError("step_policy must be 0 (start from the last accepted value) or 1 (from that / eta)")
+        self.fista_mode = int(fista_mode)
+        if self.fista_mode not in (0, 1):
+            raise ValueError("fista_mode must be 0 (constant step) or 1 (backtracking)")
+        self.fista_L = [0.0] * self.M          # L of the last FISTA step per community (mode 1)
+        self.fista_trials = [0] * self.M       # candidates tested in the last solve per community (mode 1)
         self.schedule = int(schedule)
         if self.schedule not in (0, 1):
             raise ValueError("schedule must be 0 (Algorithm 1) or 1 (layer by layer)")
@@ -385,8 +399,64 @@ class AdmmOracle:
         J = self.J if J is None else J
         rows = self.g.rows(m)
         c = sum(p_last[(r, m)] for r in self.g.nbr_and_self(m))
+        if self.fista_mode == 1:
+            return self.fista_block_backtracking(m, self.blk(Zk[self.L], m), c, self.blk(Uk, m), J)
         return fista_rows(self.blk(Zk[self.L], m), c, self.blk(Uk, m), self.Y[rows], self.labelled[rows],
                           self.rho, J, self.risk)
+
+    def fista_block_backtracking(self, m, z0, c, u, J):
+        """FISTA with backtracking on  F(Z) = R(Z, Y_m) + <U_m, Z - c> + rho/2 ||Z - c||^2  over the labelled rows of
+        community m (Appendix A, Eq. 5; F is smooth, so the proximal map is the identity and a step is
+        x = y - grad F(y) / L).  L starts at rho, grows by eta until F(x) <= F(y) - ||grad||^2 / (2L) (up to the
+        rounding slack), and is kept for the later steps.  Rows without label take the exact minimiser c - u/rho of their quadratic."""
+        rows = self.g.rows(m)
+        lab = self.labelled[rows]
+        Y = self.Y[rows][lab]
+        cl, ul = c[lab], u[lab]
+
+        def F(z):
+            return (self.risk_value(z, Y, np.ones(z.shape[0], dtype=bool)) + inner(ul, z - cl)
+                    + 0.5 * self.rho * sqnorm(z - cl))
+
+        def grad(z):
+            return ul + self.rho * (z - cl) + (self.risk_grad(z, Y) if z.shape[0] else 0.0)
+
+        L = self.rho
+        x_prev = z0[lab].copy()
+        yk = x_prev.copy()
+        x = x_prev
+        t = 1.0
+        total = 0
+        for _ in range(J):
+            if yk.shape[0] == 0:
+                break
+            Fy, g = F(yk), grad(yk)
+            gg = sqnorm(g)
+            trials = 0
+            if gg <= (self.STEP_FLOOR * L) ** 2 * sqnorm(yk):     # a step below resolution is not taken
+                x = yk
+                t_next = 0.5 * (1.0 + np.sqrt(1.0 + 4.0 * t * t))
+                yk = x + ((t - 1.0) / t_next) * (x - x_prev)
+                x_prev, t = x, t_next
+                continue
+            while True:
+                x = yk - g / L
+                trials += 1
+                if F(x) <= Fy - gg / (2.0 * L) + self.FISTA_SLACK * abs(Fy):
+                    break
+                if trials > self.max_backtrack:
+                    self.status |= self.STATUS_BACKTRACK_CAP
+                    break
+                L *= self.eta
+            total += trials
+            t_next = 0.5 * (1.0 + np.sqrt(1.0 + 4.0 * t * t))
+            yk = x + ((t - 1.0) / t_next) * (x - x_prev)
+            x_prev, t = x, t_next
+        self.fista_L[m] = L
+        self.fista_trials[m] = total
+        out = (c - u / self.rho).copy()
+        out[lab] = x
+        return out
 
     # ------------------------------------------------------------------ one iteration of Algorithm 1
     def iterate(self, k=1):
@@ -569,7 +639,8 @@ def make_oracle(w, iters=None):
     h = w.hyper
     o = AdmmOracle(g, w.dims, nu=h["nu"], rho=h["rho"], tau0=h["tau0"], theta0=h["theta0"], eta=h["eta"],
                    max_backtrack=h["max_backtrack"], fista_iters=h["fista_iters"], risk=h["risk"],
-                   dual_form=h["dual_form"], schedule=h.get("schedule", 0), step_policy=h.get("step_policy", 0))
+                   dual_form=h["dual_form"], schedule=h.get("schedule", 0), step_policy=h.get("step_policy", 0),
+                   fista_mode=h.get("fista_mode", 0))
     o.set_data(w.X, w.labels)
     o.init(w.W0)
     return o

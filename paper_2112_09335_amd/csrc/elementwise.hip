@@ -879,7 +879,8 @@ void launch_z_trial(hipStream_t s, const ZTrialArgs& a0) {
             else hipLaunchKernelGGL((z_trial_kernel<1, 1, 0>), dim3(a.n_chunks), dim3(256), 0, s, a);
         } else {
             a.ncand = kMaxCand;
-            const int nb = a.n_chunks < kReduceBlocks ? a.n_chunks : kReduceBlocks;
+            // a small grid: such a pass nearly always finds every community done and only has to notice it
+            const int nb = a.n_chunks < kReduceBlocks / 4 ? a.n_chunks : kReduceBlocks / 4;
             if (lr) hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 4, 1>), dim3(nb), dim3(256), 0, s, a);
             else if (v4) hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 4, 0>), dim3(nb), dim3(256), 0, s, a);
             else hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 1, 0>), dim3(nb), dim3(256), 0, s, a);

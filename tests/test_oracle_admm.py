@@ -660,3 +660,108 @@ def test_relu_tie_hook_flips_only_named_entries_inside_the_band_and_is_off_by_de
     finally:
         hook.reset()
     assert np.array_equal(o.grad_phi_W(l, o.W[l], o.Z[0], o.Z[l]), g_plain)
+
+
+# ---------------------------------------------------------------- last layer by FISTA with backtracking (fista_mode 1)
+def test_fista_backtracking_least_squares_finds_the_curvature_and_the_closed_form():
+    """For the least-squares risk the block objective is a quadratic with Hessian (1 + rho) I: the condition
+    F(y - g/L) <= F(y) - ||g||^2 / (2L) holds exactly when L >= 1 + rho, so the search must stop at the first
+    rho eta^i that reaches 1 + rho, in the first step, and the iterates must tend to the closed-form minimiser."""
+    o, _ = tiny_problem(31, risk=1, hyper=dict(fista_mode=1, rho=0.3))
+    p, _ = messages(o, o.W)
+    A = o.g.A.toarray()
+    T = A @ o.Z[o.L - 1] @ o.W[o.L]
+    i = 0
+    while o.rho * o.eta ** i < 1.0 + o.rho:
+        i += 1
+    for m in range(o.M):
+        rows = o.g.rows(m)
+        lab = o.labelled[rows]
+        if not lab.any():
+            continue
+        got1 = o.update_Z_last(m, o.Z, o.U, p[o.L - 1], J=1)
+        assert o.fista_L[m] == pytest.approx(o.rho * o.eta ** i, rel=1e-12) and o.fista_trials[m] == i + 1
+        # the first step from y = Z_L is the plain gradient step of length 1/L
+        z0 = o.Z[o.L][rows]
+        g = o.U[rows] + o.rho * (z0 - T[rows]) + (z0 - o.Y[rows])
+        np.testing.assert_allclose(got1[lab], (z0 - g / o.fista_L[m])[lab], rtol=1e-12, atol=1e-12)
+        want = (o.Y[rows] + o.rho * T[rows] - o.U[rows]) / (1.0 + o.rho)
+        got12 = o.update_Z_last(m, o.Z, o.U, p[o.L - 1], J=12)
+        assert o.fista_trials[m] == 12 + i                        # no growth after the first step
+        got = o.update_Z_last(m, o.Z, o.U, p[o.L - 1], J=40)
+        np.testing.assert_allclose(got[lab], want[lab], rtol=0, atol=1e-6)
+        assert np.abs(got[lab] - want[lab]).max() < np.abs(got12[lab] - want[lab]).max()
+        np.testing.assert_allclose(got[~lab], (T[rows] - o.U[rows] / o.rho)[~lab], rtol=1e-12, atol=1e-12)
+
+
+def test_fista_backtracking_meets_its_condition_with_the_first_L_that_does():
+    """Cross-entropy, every row labelled, one step: with the accepted L the new block satisfies
+    psi(x) <= psi(y) - ||grad||^2 / (2L) on the subproblem's objective (psi_last, pinned to Eq. 1 above), with
+    L / eta it does not, and L is rho times a power of eta."""
+    o, _ = tiny_problem(32, labelled=1.0, hyper=dict(fista_mode=1, rho=0.05))
+    p, _ = messages(o, o.W)
+    A = o.g.A.toarray()
+    T = A @ o.Z[o.L - 1] @ o.W[o.L]
+    searched = 0
+    for m in range(o.M):
+        rows = o.g.rows(m)
+        if rows.stop == rows.start:
+            continue
+        z0 = o.Z[o.L][rows]
+        e = np.exp(z0 - z0.max(axis=1, keepdims=True))
+        g = e / e.sum(axis=1, keepdims=True) - o.Y[rows] + o.U[rows] + o.rho * (z0 - T[rows])
+        x = o.update_Z_last(m, o.Z, o.U, p[o.L - 1], J=1)
+        L = o.fista_L[m]
+        k = np.log(L / o.rho) / np.log(o.eta)
+        assert abs(k - round(k)) < 1e-9 and round(k) == o.fista_trials[m] - 1
+        np.testing.assert_allclose(x, z0 - g / L, rtol=1e-12, atol=1e-12)
+        psi = lambda z: o.psi_last(m, z, o.U, p[o.L - 1])
+        gg = float(np.sum(g * g))
+        assert psi(x) <= psi(z0) - gg / (2 * L) + 1e-12 * abs(psi(z0))
+        if o.fista_trials[m] > 1:
+            searched += 1
+            Lp = L / o.eta
+            assert psi(z0 - g / Lp) > psi(z0) - gg / (2 * Lp)
+    assert searched > 0
+
+
+def test_fista_backtracking_approaches_the_newton_solution_and_stays_below_twice_the_curvature_bound():
+    o, _ = tiny_problem(33, hyper=dict(fista_mode=1))
+    o0, _ = tiny_problem(33, hyper=dict(fista_mode=0))
+    p, _ = messages(o, o.W)
+    A = o.g.A.toarray()
+    T = A @ o.Z[o.L - 1] @ o.W[o.L]
+    for m in range(o.M):
+        rows = o.g.rows(m)
+        lab = o.labelled[rows]
+        if not lab.any():
+            continue
+        b = T[rows] - o.U[rows] / o.rho
+        want = b.copy()
+        for i in np.flatnonzero(lab):
+            z = b[i].copy()
+            y = o.Y[rows][i]
+            for _ in range(200):
+                e = np.exp(z - z.max())
+                q = e / e.sum()
+                grad = q - y + o.rho * (z - b[i])
+                z = z - np.linalg.solve(np.diag(q) - np.outer(q, q) + o.rho * np.eye(z.size), grad)
+            assert np.max(np.abs(grad)) < 1e-12
+            want[i] = z
+        got = o.update_Z_last(m, o.Z, o.U, p[o.L - 1], J=1000)
+        np.testing.assert_allclose(got, want, rtol=0, atol=1e-6)
+        assert o.fista_L[m] <= o.eta * (o.rho + 0.5)             # never beyond the first candidate above the bound
+        # both modes head for the same point
+        np.testing.assert_allclose(o0.update_Z_last(m, o0.Z, o0.U, p[o.L - 1], J=1000), want, rtol=0, atol=1e-6)
+
+
+def test_fista_backtracking_cap_raises_the_status_bit_and_the_sweep_stays_consistent():
+    o, _ = tiny_problem(34, hyper=dict(fista_mode=1, rho=1e-3, max_backtrack=2))
+    o.iterate(1)
+    assert o.status & AdmmOracle.STATUS_BACKTRACK_CAP
+    o, _ = tiny_problem(35, hyper=dict(fista_mode=1))
+    A = o.g.A.toarray()
+    Z0, U0 = copy.deepcopy(o.Z), o.U.copy()
+    o.iterate(1)
+    TL = A @ Z0[o.L - 1] @ o.W[o.L]
+    np.testing.assert_allclose(o.U, U0 + o.rho * (Z0[o.L] - TL), rtol=1e-12, atol=1e-12)     # Eq. 2 is untouched by the mode
