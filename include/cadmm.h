@@ -116,6 +116,11 @@ int  cadmm_get_segment_order(cadmm_ctx* ctx, int64_t* order /* host [n_segments]
  *   Z_l (its communities together), each from the newest values of everything else.
  *   step_policy: 0 = a search for tau_l / theta_{l,m} starts from the value accepted last time, so the
  *   parameters never shrink; 1 = it starts from that value divided by eta, so they can.
+ *   fista_mode: how Z_{L,m} is solved (Appendix A, Eq. 5, "via FISTA"): 0 = fista_iters steps of constant length
+ *   1 / (rho + c_R), c_R = 1/2 (cross-entropy) or 1 (least squares), row by row; 1 = FISTA with backtracking on the block
+ *   Z_{L,m}: one L per community and step, started at rho in every iteration, multiplied by eta until
+ *   F(y - grad/L) <= F(y) - ||grad||^2 / (2L) holds over the labelled rows of the community (at most max_backtrack
+ *   multiplications per step), kept for the later steps of the solve.
  */
 typedef struct {
     int32_t L;
@@ -125,6 +130,7 @@ typedef struct {
     int32_t max_backtrack, fista_iters, dual_form;
     int32_t schedule;
     int32_t step_policy;
+    int32_t fista_mode;
 } cadmm_model;
 int  cadmm_set_model(cadmm_ctx* ctx, const cadmm_model* model);
 
@@ -176,6 +182,9 @@ int  cadmm_get_U(cadmm_ctx* ctx, float* dst);
 /* tau[L], theta[(L-1)*M] (layer-major), n_trials[L + (L-1)*M] and sq_grad[L + (L-1)*M]
  * (squared gradient norms) of the last iteration.  Any pointer may be NULL. */
 int  cadmm_get_steps(cadmm_ctx* ctx, double* tau, double* theta, int32_t* n_trials, double* sq_grad);
+/* fista_mode 1: L[M] = the constant every community's last solve of Z_{L,m} ended with, n_trials[M] = candidates it
+ * tested over all its steps.  Any pointer may be NULL. */
+int  cadmm_get_fista(cadmm_ctx* ctx, double* L, int32_t* n_trials);
 /* Overwrite state (resume / tests).  Any pointer may be NULL (= keep).  W: L host pointers;
  * Z: L host pointers for layers 1..L (caller's node order); U: N x C_L. */
 int  cadmm_set_state(cadmm_ctx* ctx, const float* const* W, const float* const* Z, const float* U,

@@ -23,7 +23,7 @@ EXPORTS = [
     "cadmm_get_Z", "cadmm_get_U", "cadmm_get_steps", "cadmm_set_state", "cadmm_op_aggregate",
     "cadmm_op_aggregate_segments", "cadmm_op_transform", "cadmm_op_wgrad",
     "cadmm_profile", "cadmm_get_profile", "cadmm_profile_class_name", "cadmm_tune", "cadmm_predict",
-    "cadmm_partition", "cadmm_op_calibrate", "cadmm_op_wgrad_noalloc",
+    "cadmm_partition", "cadmm_op_calibrate", "cadmm_op_wgrad_noalloc", "cadmm_get_fista",
 ]
 PROFILE_CLASSES = 19
 
@@ -36,7 +36,8 @@ class _Model(C.Structure):
     _fields_ = [("L", C.c_int32), ("C", C.POINTER(C.c_int32)), ("risk", C.c_int32),
                 ("nu", C.c_float), ("rho", C.c_float), ("tau0", C.c_float), ("theta0", C.c_float),
                 ("eta", C.c_float), ("max_backtrack", C.c_int32), ("fista_iters", C.c_int32),
-                ("dual_form", C.c_int32), ("schedule", C.c_int32), ("step_policy", C.c_int32)]
+                ("dual_form", C.c_int32), ("schedule", C.c_int32), ("step_policy", C.c_int32),
+                ("fista_mode", C.c_int32)]
 
 
 class _Stats(C.Structure):
@@ -83,6 +84,7 @@ def load_library():
     lib.cadmm_get_U.argtypes = [vp, vp]
     lib.cadmm_get_steps.argtypes = [vp, vp, vp, vp, vp]
     lib.cadmm_set_state.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.cadmm_get_fista.argtypes = [vp, vp, vp]
     lib.cadmm_op_aggregate.argtypes = [vp, vp, i32, vp]
     lib.cadmm_op_aggregate_segments.argtypes = [vp, vp, i32, vp]
     lib.cadmm_op_transform.argtypes = [vp, vp, i64, i32, vp, i32, vp]
@@ -201,12 +203,12 @@ class Solver:
 
     # ---- model / workspace / data
     def set_model(self, dims, *, nu, rho, tau0, theta0, eta, max_backtrack, fista_iters, risk=0, dual_form=0,
-                  schedule=0, step_policy=0):
+                  schedule=0, step_policy=0, fista_mode=0):
         self.dims = [int(d) for d in dims]
         self.L = len(self.dims) - 1
         arr = (C.c_int32 * len(self.dims))(*self.dims)
         m = _Model(self.L, arr, risk, nu, rho, tau0, theta0, eta, max_backtrack, fista_iters, dual_form, schedule,
-                   step_policy)
+                   step_policy, fista_mode)
         self._check(self.lib.cadmm_set_model(self.h, C.byref(m)), "cadmm_set_model")
 
     def workspace_bytes(self):
@@ -280,6 +282,13 @@ class Solver:
         self._check(self.lib.cadmm_get_steps(self.h, _ptr(tau), _ptr(theta), _ptr(trials), _ptr(sq)),
                     "cadmm_get_steps")
         return tau, theta, trials, sq
+
+    def get_fista(self):
+        """(L [M], candidates tested [M]) of the last solve of Z_L with backtracking (fista_mode 1)."""
+        L = np.empty(self.M, np.float64)
+        trials = np.empty(self.M, np.int32)
+        self._check(self.lib.cadmm_get_fista(self.h, _ptr(L), _ptr(trials)), "cadmm_get_fista")
+        return L, trials
 
     def set_state(self, W=None, Z=None, U=None, tau=None, theta=None):
         keep = []
@@ -413,7 +422,7 @@ class Solver:
         s.set_model(w.dims, nu=h["nu"], rho=h["rho"], tau0=h["tau0"], theta0=h["theta0"], eta=h["eta"],
                     max_backtrack=h["max_backtrack"], fista_iters=h["fista_iters"], risk=h["risk"],
                     dual_form=h["dual_form"], schedule=h.get("schedule", 0),
-                    step_policy=h.get("step_policy", 0))
+                    step_policy=h.get("step_policy", 0), fista_mode=h.get("fista_mode", 0))
         s.set_workspace()
         s.set_data(w.X, w.labels)
         s.init(w.W0)

@@ -39,7 +39,7 @@ struct cadmm_ctx {
     // (A~ Z_{l-1}) W_l.  Its W-update then needs three aggregations of width C_l, so it pays if
     // 3 C_l < C_{l-1}.  In those layers the slot H[l] holds A~ G_l (N x C_l).
     std::vector<char> agg_first;
-    int risk = 0, max_bt = 60, J = 10, dual_form = 0, schedule = 0, step_policy = 0;
+    int risk = 0, max_bt = 60, J = 10, dual_form = 0, schedule = 0, step_policy = 0, fista_mode = 0;
     bool u_pending = false;      // dual_form 1: the dual step of the last sweep is still to be applied
     float nu = 0, rho = 0, tau0 = 0, theta0 = 0, eta = 2;
     // workspace
@@ -87,6 +87,9 @@ struct cadmm_ctx {
     double* partials = nullptr;
     Unit* unitsW = nullptr;     // [L]
     Unit* unitsZ = nullptr;     // [(L-1) * M]
+    Unit* unitsF = nullptr;     // [M]: the L of the last-layer solve with backtracking (fista_mode 1)
+    float* fistaX = nullptr;    // N x C_L each: x_j and y_j of that solve
+    float* fistaY = nullptr;
     LayerScalars* scalars = nullptr;   // [L+1]
     int32_t* status = nullptr;
     bool base_valid = false, have_prev = false, dual_valid = false;
@@ -225,7 +228,7 @@ size_t layout(cadmm_ctx* c, char* base) {
     c->tn_partial = b.take<float>(tnmax);
     c->tn_partial_floats = tnmax;
     size_t np = (size_t)kReduceBlocks * kMaxCand;
-    const size_t np2 = nch * (kMaxCand + 2);
+    const size_t np2 = nch * (kMaxCand + 3);
     np = np > np2 ? np : np2;
     for (int l = 1; l <= L; ++l) {               // block results of the products that also evaluate a candidate
         const size_t np3 = (size_t)gemm_nn_blocks(N, c->C[l]) * kMaxCand;
@@ -234,6 +237,11 @@ size_t layout(cadmm_ctx* c, char* base) {
     c->partials = b.take<double>(np);
     c->unitsW = b.take<Unit>(L);
     c->unitsZ = b.take<Unit>((size_t)(L - 1) * g.M);
+    c->unitsF = b.take<Unit>((size_t)g.M);
+    if (c->fista_mode == 1) {
+        c->fistaX = b.take<float>(N * c->C[L]);
+        c->fistaY = b.take<float>(N * c->C[L]);
+    }
     c->scalars = b.take<LayerScalars>(L + 1);
     c->status = b.take<int32_t>(4);
     return (b.off + 255) & ~(size_t)255;
@@ -551,6 +559,31 @@ void z_update_hidden(cadmm_ctx* c, int l) {
 void last_layer_update(cadmm_ctx* c) {
     const int L = c->L;
     const int64_t N = c->hg.N;
+    if (c->fista_mode == 1 && c->J > 0) {
+        // FISTA with backtracking on the blocks Z_{L,m}: J + 1 passes over the rows, a device-side search per step
+        FistaArgs a;
+        a.ZL = c->Z[L]; a.U = c->U; a.TL = c->T[L]; a.Xb = c->fistaX; a.Yb = c->fistaY; a.labels = c->d_labels;
+        a.chunk_unit = c->d_chunk_unit; a.chunk_kind = c->d_chunk_kind; a.chunk_begin = c->d_chunk_begin; a.chunk_end = c->d_chunk_end;
+        a.n_chunks = (int32_t)c->hg.chunks.size(); a.unit_chunk_ptr = c->d_unit_chunk_ptr; a.M = c->hg.M;
+        a.CL = c->C[L]; a.risk = c->risk; a.J = c->J; a.update_u = c->dual_form == 0 ? 1 : 0; a.rho = c->rho;
+        a.sp = search_params(c); a.units = c->unitsF; a.partials = c->partials; a.status = c->status;
+        const int more_passes = (c->max_bt + kMaxCand - 1) / kMaxCand;
+        timed(c, P_LAST_LAYER, 4.0 * (double)N * c->C[L] * (3.0 + 7.0 * (c->J - 1) + 6.0) + 4.0 * (double)N * (c->J + 1), 0.0, [&] {
+            double t = 1.0;
+            for (int stage = 0; stage <= c->J; ++stage) {
+                float mom = 0.f;
+                if (stage > 0) {                        // the step taken in this stage is step stage-1
+                    const double tn = 0.5 * (1.0 + std::sqrt(1.0 + 4.0 * t * t));
+                    mom = (float)((t - 1.0) / tn);
+                    t = tn;
+                }
+                launch_fista_stage(c->stream, a, stage, 0, mom);
+                if (stage < c->J)
+                    for (int p = stage == 0 ? 1 : 0; p < more_passes; ++p) launch_fista_stage(c->stream, a, stage, 1, 0.f);
+            }
+        });
+        return;
+    }
     timed(c, P_LAST_LAYER, 4.0 * (5.0 * (double)N * c->C[L] + (double)N), 0.0, [&] {
         launch_last_layer(c->stream, c->Z[L], c->U, c->T[L], c->d_labels, N, c->C[L], c->risk, c->rho, c->J,
                           c->dual_form == 0 ? 1 : 0);
@@ -731,6 +764,7 @@ int cadmm_set_model(cadmm_ctx* c, const cadmm_model* m) {
     if (m->dual_form != 0 && m->dual_form != 1) return fail(c, CADMM_EINVAL, "dual_form must be 0 or 1");
     if (m->schedule != 0 && m->schedule != 1) return fail(c, CADMM_EINVAL, "schedule must be 0 or 1");
     if (m->step_policy != 0 && m->step_policy != 1) return fail(c, CADMM_EINVAL, "step_policy must be 0 or 1");
+    if (m->fista_mode != 0 && m->fista_mode != 1) return fail(c, CADMM_EINVAL, "fista_mode must be 0 or 1");
     c->L = m->L;
     c->C.assign(m->C, m->C + m->L + 1);
     c->risk = m->risk;
@@ -740,6 +774,7 @@ int cadmm_set_model(cadmm_ctx* c, const cadmm_model* m) {
     c->dual_form = m->dual_form;
     c->schedule = m->schedule;
     c->step_policy = m->step_policy;
+    c->fista_mode = m->fista_mode;
     c->agg_first.assign(c->L + 1, 0);
     for (int l = 2; l <= c->L; ++l) c->agg_first[l] = (3 * c->C[l] < c->C[l - 1]) ? 1 : 0;
     c->has_model = true;
@@ -853,6 +888,7 @@ int cadmm_init(cadmm_ctx* c, const float* const* W0) {
     HIP_TRY(c, hipMemsetAsync(c->status, 0, 4 * sizeof(int32_t), s));
     launch_fill_units(s, c->unitsW, L, (double)c->tau0);
     launch_fill_units(s, c->unitsZ, (L - 1) * c->hg.M, (double)c->theta0);
+    launch_fill_units(s, c->unitsF, c->hg.M, (double)c->rho);
     HIP_TRY(c, hipStreamSynchronize(s));                           // W0 host buffers may be freed by the caller
     c->iter = 0;
     c->base_valid = false;
@@ -1018,6 +1054,20 @@ int cadmm_get_steps(cadmm_ctx* c, double* tau, double* theta, int32_t* n_trials,
         if (theta) theta[i] = uz[i].step;
         if (n_trials) n_trials[L + i] = uz[i].ntrials;
         if (sq_grad) sq_grad[L + i] = uz[i].g;
+    }
+    return CADMM_OK;
+}
+
+int cadmm_get_fista(cadmm_ctx* c, double* L, int32_t* n_trials) {
+    if (!c) return CADMM_EINVAL;
+    if (!c->has_init) return fail(c, CADMM_EORDER, "init first");
+    const int M = c->hg.M;
+    std::vector<Unit> u(M);
+    HIP_TRY(c, hipMemcpyAsync(u.data(), c->unitsF, M * sizeof(Unit), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    for (int m = 0; m < M; ++m) {
+        if (L) L[m] = u[m].step;
+        if (n_trials) n_trials[m] = u[m].total + u[m].ntrials;     // the last step's count is not yet added up
     }
     return CADMM_OK;
 }

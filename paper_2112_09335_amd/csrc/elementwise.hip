@@ -47,7 +47,9 @@ __device__ __forceinline__ double block_sum(double v, double* sm) {
     return t;
 }
 
-__device__ __forceinline__ void decide(Unit* u, const double* D, int ncand, SearchParams sp, int32_t* status) {
+// slack: the test accepts up to this much above the bound (0 for the tau and theta searches)
+__device__ __forceinline__ void decide(Unit* u, const double* D, int ncand, SearchParams sp, int32_t* status,
+                                       double slack = 0.0) {
     double step = u->step;
     const double g = u->g;
     int nt = u->ntrials;
@@ -55,7 +57,7 @@ __device__ __forceinline__ void decide(Unit* u, const double* D, int ncand, Sear
         ++nt;
         const double d = D[j];
         if (!(d == d) || fabs(d) > 1.7e308) atomicOr(status, 2);
-        if (d <= -g / (2.0 * step)) { u->step = step; u->ntrials = nt; u->done = 1; return; }
+        if (d <= -g / (2.0 * step) + slack) { u->step = step; u->ntrials = nt; u->done = 1; return; }
         if (nt > sp.max_backtrack) {
             u->step = step; u->ntrials = nt; u->done = 1;
             atomicOr(status, 1);
@@ -762,12 +764,218 @@ __global__ __launch_bounds__(256) void argmax_rows_kernel(const float* __restric
     pred[i] = best;
 }
 
+// ------------------------------------------------------------------------------------------ last layer, FISTA with backtracking
+// See FistaArgs.  2^LPLOG lanes share a node row, four classes per lane, as in last_layer_kernel; a workgroup takes one
+// chunk of rows of one community.  Everything that enters a decision is formed in fp64 from the fp32 state: the
+// gradient g of F(z) = R(z, y) + <u, z - c> + rho/2 ||z - c||^2 at y, and for a candidate L the difference
+// F(y - g/L) - F(y), term by term (the log-sum-exp of both points, the linear and the quadratic terms through
+// x - y = -g/L), so that nothing is lost to the cancellation of two nearly equal values of F.
+constexpr int kFistaStride = kMaxCand + 3;        // per chunk: candidate differences, ||g||^2, ||y||^2, F(y)
+constexpr double kFistaSlack = 1e-12;             // the test accepts up to this relative rounding of F(y)
+
+template <int LPLOG>
+__device__ __forceinline__ double group_sum(double v) {
+#pragma unroll
+    for (int o = 1; o < (1 << LPLOG); o <<= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+template <int LPLOG>
+__device__ __forceinline__ double group_max(double v) {
+#pragma unroll
+    for (int o = 1; o < (1 << LPLOG); o <<= 1) v = fmax(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// log-sum-exp over the row (the lanes of the group hold four entries each; entries past CL are off)
+template <int LPLOG>
+__device__ __forceinline__ double row_lse(const double (&z)[4], const bool (&ok)[4], double (&e)[4], double& se) {
+    double mx = -1.0e300;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) mx = ok[v] ? fmax(mx, z[v]) : mx;
+    mx = group_max<LPLOG>(mx);
+    double s = 0.0;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) { e[v] = ok[v] ? exp(z[v] - mx) : 0.0; s += e[v]; }
+    se = group_sum<LPLOG>(s);
+    return mx + log(se);
+}
+
+template <int LPLOG, int NC>
+__global__ __launch_bounds__(256) void fista_stage_kernel(FistaArgs a, int stage, int more, float mom) {
+    __shared__ double sm[4];
+    constexpr int LP = 1 << LPLOG;
+    if (more) {                                        // a pass of further candidates: only if some search is pending
+        int pending = 0;
+        for (int i = threadIdx.x; i < a.M; i += 256) pending |= (a.units[i].done == 0);
+        if (!__syncthreads_or(pending)) return;
+    }
+    for (int ch = blockIdx.x; ch < a.n_chunks; ch += gridDim.x) {
+        if (a.chunk_kind[ch] != 0) continue;           // only the chunks of rows
+        const Unit* u = a.units + a.chunk_unit[ch];
+        if (more && u->done) continue;
+        const double Lcur = (stage == 0 && !more) ? (double)a.rho : u->step;       // every solve starts from L = rho
+        const bool skipped = stage > 0 && !more && u->skip;
+        const int r0 = a.chunk_begin[ch], r1 = a.chunk_end[ch];
+        double D[NC], sgg = 0.0, syy = 0.0, sF = 0.0;
+#pragma unroll
+        for (int q = 0; q < NC; ++q) D[q] = 0.0;
+        for (int rb = r0; rb < r1; rb += 256 >> LPLOG) {
+            const int row = rb + (threadIdx.x >> LPLOG);
+            const int j0 = (threadIdx.x & (LP - 1)) * 4;
+            const bool act = row < r1;
+            const int64_t base = (int64_t)(act ? row : r0) * a.CL + j0;
+            bool ok[4];
+            double c[4], uu[4], y[4], xo[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                ok[v] = act && (j0 + v < a.CL);
+                c[v] = ok[v] ? (double)a.TL[base + v] : 0.0;
+                uu[v] = ok[v] ? (double)a.U[base + v] : 0.0;
+                // y_{stage-1} and x_{stage-1}; both are Z_L before the first step
+                y[v] = ok[v] ? (double)((stage <= 1 && !more) || stage == 0 ? a.ZL[base + v] : a.Yb[base + v]) : 0.0;
+                xo[v] = ok[v] ? (double)(stage <= 1 ? a.ZL[base + v] : a.Xb[base + v]) : 0.0;
+            }
+            const int lab = act ? a.labels[row] : -1;
+            const bool on = lab >= 0;                  // uniform over the lane group; rows without label are no part of F
+            double e[4], se, g[4];
+            auto gradient = [&](const double (&z)[4], double& lse) {
+                lse = 0.0;
+                if (a.risk == 0) {
+                    lse = row_lse<LPLOG>(z, ok, e, se);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) g[v] = ok[v] ? e[v] / se - ((j0 + v) == lab ? 1.0 : 0.0) : 0.0;
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) g[v] = ok[v] ? z[v] - ((j0 + v) == lab ? 1.0 : 0.0) : 0.0;
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) g[v] = ok[v] ? g[v] + uu[v] + (double)a.rho * (z[v] - c[v]) : 0.0;
+            };
+            double lse_y;
+            if (stage > 0 && !more) {
+                // take step stage-1 from y with the L its search ended with, then the momentum point
+                gradient(y, lse_y);
+                const double invL = skipped ? 0.0 : 1.0 / Lcur;
+                float xn[4], yn[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    xn[v] = (float)(y[v] - g[v] * invL);
+                    yn[v] = xn[v] + mom * (xn[v] - (float)xo[v]);
+                }
+                if (stage < a.J) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (ok[v]) { a.Xb[base + v] = xn[v]; a.Yb[base + v] = yn[v]; }
+                } else {
+                    // last stage: the result, and the dual step of Eq. 2 with the old Z_L
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (ok[v]) {
+                            const float zold = a.ZL[base + v];
+                            a.ZL[base + v] = on ? xn[v] : (float)c[v] - (float)uu[v] / a.rho;
+                            if (a.update_u) a.U[base + v] = (float)uu[v] + a.rho * (zold - (float)c[v]);
+                        }
+                    continue;
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) y[v] = (double)yn[v];
+            }
+            // the search at y: ||g||^2, ||y||^2, F(y), and F(y - g/L) - F(y) for the candidates L = Lcur eta^q
+            gradient(y, lse_y);
+            if (!on) continue;                         // (its lanes still took part in the group reductions above)
+            double gg = 0.0, yy = 0.0, Fy = 0.0, ug = 0.0, gd = 0.0;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                gg += g[v] * g[v];
+                yy += y[v] * y[v];
+                ug += uu[v] * g[v];
+                gd += g[v] * (y[v] - c[v]);
+                const double lin = (j0 + v) == lab ? 1.0 : 0.0;
+                Fy += ok[v] ? uu[v] * (y[v] - c[v]) + 0.5 * (double)a.rho * (y[v] - c[v]) * (y[v] - c[v]) +
+                                  (a.risk == 0 ? -lin * y[v] : 0.5 * (y[v] - lin) * (y[v] - lin)) : 0.0;
+            }
+            const bool lead = (threadIdx.x & (LP - 1)) == 0;
+            if (a.risk == 0 && lead) Fy += lse_y;
+            double gl = 0.0;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) gl += (j0 + v) == lab ? g[v] : 0.0;
+            const double glab = group_sum<LPLOG>(gl);
+            const double gg_row = group_sum<LPLOG>(gg), ug_row = group_sum<LPLOG>(ug), gd_row = group_sum<LPLOG>(gd);
+            sgg += gg; syy += yy; sF += Fy;
+            double Lq = more ? u->step : Lcur;
+#pragma unroll
+            for (int q = 0; q < NC; ++q) {
+                const double inv = 1.0 / Lq;
+                // x - y = -g/L:  <u, x - y> + rho/2 (||x - c||^2 - ||y - c||^2)
+                double d = -inv * ug_row + 0.5 * (double)a.rho * (-2.0 * inv * gd_row + inv * inv * gg_row);
+                if (a.risk == 0) {
+                    double x[4], e2[4], se2;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) x[v] = y[v] - g[v] * inv;
+                    const double lse_x = row_lse<LPLOG>(x, ok, e2, se2);
+                    d += (lse_x - lse_y) + inv * glab;     // R(x) - R(y), with -(x - y)_label = g_label / L
+                } else {
+                    // 1/2 (||x - e||^2 - ||y - e||^2) = sum (x - y) (y - e) + 1/2 ||x - y||^2
+                    double t = 0.0;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) t += ok[v] ? g[v] * (y[v] - ((j0 + v) == lab ? 1.0 : 0.0)) : 0.0;
+                    d += -inv * group_sum<LPLOG>(t) + 0.5 * inv * inv * gg_row;
+                }
+                if (lead) D[q] += d;
+                Lq *= (double)a.sp.eta;
+            }
+        }
+        if (stage == a.J && !more) continue;
+        double* out = a.partials + (int64_t)ch * kFistaStride;
+#pragma unroll
+        for (int q = 0; q < NC; ++q) {
+            const double t = block_sum(D[q], sm);
+            if (threadIdx.x == 0) out[q] = t;
+        }
+        if (!more) {
+            const double t0 = block_sum(sgg, sm), t1 = block_sum(syy, sm), t2 = block_sum(sF, sm);
+            if (threadIdx.x == 0) { out[kMaxCand] = t0; out[kMaxCand + 1] = t1; out[kMaxCand + 2] = t2; }
+        }
+    }
+}
+
+// Takes the decisions of a pass.  first_pass: the searches of stage `stage` begin here (the counters of the finished
+// stage are added up, every solve starts from L = rho), the step floor is applied, then the first candidates are judged.
+__global__ __launch_bounds__(256) void fista_finish_kernel(FistaArgs a, int ncand, int first_pass, int stage) {
+    __shared__ double sm[4];
+    __shared__ double D[kFistaStride];
+    const int unit = blockIdx.x;
+    Unit* u = a.units + unit;
+    if (!first_pass && u->done) return;
+    const int c0 = a.unit_chunk_ptr[unit], c1 = a.unit_chunk_ptr[unit + 1];
+    for (int q = 0; q < kFistaStride; ++q) {
+        if ((q < kMaxCand && q >= ncand) || (q >= kMaxCand && !first_pass)) continue;
+        double s = 0.0;
+        for (int i = c0 + threadIdx.x; i < c1; i += blockDim.x)
+            if (a.chunk_kind[i] == 0) s += a.partials[(int64_t)i * kFistaStride + q];
+        s = block_sum(s, sm);
+        if (threadIdx.x == 0) D[q] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if (first_pass) {
+            if (stage == 0) { u->step = (double)a.rho; u->total = 0; }
+            else u->total += u->ntrials;
+            u->ntrials = 0; u->done = 0; u->skip = 0; u->keep = u->step;
+            floor_test(u, D[kMaxCand], D[kMaxCand + 1]);
+            u->step0 = kFistaSlack * fabs(D[kMaxCand + 2]);       // kept for the passes of further candidates
+            if (u->done) return;
+        }
+        decide(u, D, ncand, a.sp, a.status, u->step0);
+    }
+}
+
 __global__ void fill_units_kernel(Unit* units, int n, double step) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     Unit u;
     u.step = step; u.step0 = step; u.keep = step; u.g = 0.0; u.bnorm = 0.0; u.done = 0; u.skip = 0; u.ntrials = 0;
-    u.spec = 0;
+    u.spec = 0; u.total = 0; u.pad = 0;
     units[i] = u;
 }
 
@@ -926,6 +1134,22 @@ void launch_relu(hipStream_t s, const float* T, float* Z, int64_t count, int app
 
 void launch_argmax_rows(hipStream_t s, const float* T, int32_t* pred, int64_t N, int C) {
     hipLaunchKernelGGL(argmax_rows_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, s, T, pred, N, C);
+}
+
+void launch_fista_stage(hipStream_t s, const FistaArgs& a, int stage, int more, float mom) {
+    if (a.n_chunks <= 0) return;
+    const bool wide = more || stage == 0;              // 16 candidates; else the current L alone
+    const int nb = more ? (a.n_chunks < kReduceBlocks / 4 ? a.n_chunks : kReduceBlocks / 4) : a.n_chunks;
+#define CADMM_FISTA(LG_) do { \
+        if (wide) hipLaunchKernelGGL((fista_stage_kernel<LG_, kMaxCand>), dim3(nb), dim3(256), 0, s, a, stage, more, mom); \
+        else hipLaunchKernelGGL((fista_stage_kernel<LG_, 1>), dim3(nb), dim3(256), 0, s, a, stage, more, mom); } while (0)
+    if (a.CL <= 4) CADMM_FISTA(0);
+    else if (a.CL <= 8) CADMM_FISTA(1);
+    else if (a.CL <= 16) CADMM_FISTA(2);
+    else if (a.CL <= 32) CADMM_FISTA(3);
+    else CADMM_FISTA(4);
+#undef CADMM_FISTA
+    if (stage < a.J) hipLaunchKernelGGL(fista_finish_kernel, dim3(a.M), dim3(256), 0, s, a, wide ? kMaxCand : 1, more ? 0 : 1, stage);
 }
 
 void launch_fill_units(hipStream_t s, Unit* units, int n, double step) {

@@ -109,6 +109,8 @@ struct Unit {
     int32_t skip;      // step below resolution: block stays
     int32_t ntrials;   // candidates tested this iteration
     int32_t spec;      // the previous search accepted its first candidate: a speculative step with step0 is safe
+    int32_t total;     // candidates tested since the counter was cleared (the last-layer solve adds up its steps)
+    int32_t pad;
 };
 
 // Readout scalars of one layer's base evaluation.
@@ -189,6 +191,26 @@ void launch_t_carry(hipStream_t s, float* Tn, const float* P, const int64_t* row
 // update_u = 0 leaves U alone (the dual step is then taken on the new iterates by the next phi_G)
 void launch_last_layer(hipStream_t s, float* ZL, float* U, const float* TL, const int32_t* labels, int64_t N,
                        int CL, int risk, float rho, int J, int update_u);
+// Last layer by FISTA with backtracking on the block subproblem of Z_{L,m} (Appendix A, Eq. 5): one L per community
+// and step, found by the device-side search over the rows of the community (chunk tables of the graph, kind 0).
+// Stage `stage` of `J` steps: stage 0 evaluates 16 candidates L = rho eta^q at y_0 = Z_L; stage j = 1..J-1 takes step
+// j-1 with the L found (x_j = y_{j-1} - grad / L, y_j = x_j + mom (x_j - x_{j-1})) and evaluates the current L at
+// y_j; stage J takes the last step, writes Z_L (rows without label: their exact minimiser) and, with update_u, the dual
+// step of Eq. 2 with the old Z_L.  more = 1 launches a pass of 16 further candidates for the searches not yet done
+// (it returns at once otherwise).  Every stage is followed by the finishing kernel that takes the decisions.
+struct FistaArgs {
+    float* ZL; float* U; const float* TL; float* Xb; float* Yb;      // Xb, Yb: N x CL scratch (x_j and y_j)
+    const int32_t* labels;
+    const int32_t* chunk_unit; const int32_t* chunk_kind; const int32_t* chunk_begin; const int32_t* chunk_end;
+    int32_t n_chunks; const int32_t* unit_chunk_ptr; int32_t M;
+    int CL, risk, J, update_u;
+    float rho;
+    SearchParams sp;
+    Unit* units;           // [M]
+    double* partials;      // [n_chunks * (kMaxCand + 3)]
+    int32_t* status;
+};
+void launch_fista_stage(hipStream_t s, const FistaArgs& a, int stage, int more, float mom);
 void launch_relu(hipStream_t s, const float* T, float* Z, int64_t count, int apply_relu);
 void launch_argmax_rows(hipStream_t s, const float* T, int32_t* pred, int64_t N, int C);
 void launch_fill_units(hipStream_t s, Unit* units, int n, double step);

@@ -46,7 +46,7 @@ class Workload:
 
 DEFAULT_HYPER = dict(nu=1e-3, rho=1e-3, tau0=1e-3, theta0=1e-3, eta=2.0,
                      max_backtrack=60, fista_iters=10, risk=0, dual_form=0, schedule=0,
-                     step_policy=0)
+                     step_policy=0, fista_mode=0)
 
 
 def _dedup_pairs(a: np.ndarray, b: np.ndarray, N: int):

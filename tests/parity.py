@@ -143,4 +143,9 @@ def compare_iterate(solver, orc, tag):
     step_o = np.concatenate([tau_o, theta_o])
     differ = (step_g != step_o) | (tr_g != tr_o)
     assert not np.any(differ & (g_g > 1e-20)), (tag, "steps", step_g[differ], step_o[differ], tr_g[differ], tr_o[differ])
+    if getattr(orc, "fista_mode", 0) == 1 and orc.k > 0:
+        # last layer with backtracking: the constant every community's solve ended with and the candidates it tested
+        L_g, tr_g = solver.get_fista()
+        assert np.array_equal(L_g, np.array(orc.fista_L)), (tag, "fista L", L_g, orc.fista_L)
+        assert np.array_equal(tr_g, np.array(orc.fista_trials, dtype=np.int32)), (tag, "fista trials", tr_g, orc.fista_trials)
     return worst

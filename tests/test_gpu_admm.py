@@ -285,3 +285,59 @@ def test_carried_pre_activations_across_their_refresh():
     run_case(w, 19, "carry/config1/default-period")
     w = synth.config(3, 0.005)
     run_case(w, 18, "carry/config3/default-period")
+
+
+def test_last_layer_by_fista_with_backtracking():
+    """fista_mode 1: Z_{L,m} by FISTA with backtracking on the block (one L per community and step, found on the device);
+    iterates, the L every solve ends with and the number of candidates it tested must match the oracle."""
+    w = synth.config(1, 0.5)
+    w.hyper["fista_mode"] = 1
+    run_case(w, 8, "fista-backtracking/config1")
+    w = synth.config(3, 0.005)                       # three layers, ten classes
+    w.hyper["fista_mode"] = 1
+    run_case(w, 6, "fista-backtracking/config3")
+    w = synth.make_workload("ragged", 11, 1237, 5, [37, 50, 9, 6], 6, 6, graph="sbm", features="gaussian",
+                            avg_degree=6, frac_intra=0.7, labelled_fraction=0.4)
+    w.comm = np.where(w.comm == 3, 4, w.comm).astype(np.int32)      # community 3 is empty; most rows have no label
+    w.hyper["fista_mode"] = 1
+    run_case(w, 5, "fista-backtracking/ragged-ce")
+    w2 = copy.deepcopy(w)
+    w2.hyper["risk"] = 1
+    w2.hyper["dual_form"] = 1
+    run_case(w2, 4, "fista-backtracking/ragged-lsq/dual-form-1")
+    w = synth.config(4, 0.002)                       # 16 classes, 64 communities
+    w.hyper["fista_mode"] = 1
+    run_case(w, 4, "fista-backtracking/config4")
+    # a cap on the multiplications that binds: L cannot reach the curvature, both sides must raise the status bit (the
+    # solve then overshoots and the iteration amplifies rounding within a few iterations, so only two are compared)
+    w.hyper["max_backtrack"] = 6
+    run_case(w, 2, "fista-backtracking/config4/cap")
+    w = synth.make_workload("wide-last", 41, 900, 3, [20, 24, 40], 40, 4, graph="sbm", features="gaussian",
+                            avg_degree=8, frac_intra=0.8)   # 40 classes: sixteen lanes per row
+    w.hyper["fista_mode"] = 1
+    w.hyper["schedule"] = 1
+    run_case(w, 4, "fista-backtracking/40-classes/layer-by-layer")
+
+
+def test_communities_from_the_library_partitioner_feed_the_sweep():
+    """A graph that comes without communities: cadmm_partition (bit-exact against its CPU twin) supplies them, the graph
+    built from them is bit-exact against the oracle's, and the sweep on them matches the oracle iteration by iteration."""
+    from oracle.graph import OracleGraph
+    from oracle.partition import partition as twin_partition
+    from paper_2112_09335_amd import binding
+    w = synth.config(2, 0.1)                          # N = 2000, planted blocks thrown away
+    host = binding.Solver(device=-1)
+    comm = host.partition(w.N, w.src, w.dst, w.M)
+    host.close()
+    assert np.array_equal(comm, np.asarray(twin_partition(w.N, w.src, w.dst, w.M), dtype=np.int32))
+    assert comm.min() >= 0 and comm.max() < w.M and not np.array_equal(comm, w.comm)
+    w.comm = comm
+    s = binding.Solver.from_workload(w, 0)
+    g = s.get_graph()
+    og = OracleGraph(w.N, w.src, w.dst, w.M, w.comm)
+    assert np.array_equal(g["perm"], og.perm) and np.array_equal(g["row_ptr"], og.row_ptr)
+    assert np.array_equal(g["col"], og.col) and np.array_equal(g["val"], og.val.astype(np.float32))
+    assert np.array_equal(g["seg_ptr"], og.seg_ptr) and np.array_equal(g["seg_comm"], og.seg_comm)
+    assert np.array_equal(g["neighbour"], og.neighbour)
+    s.close()
+    run_case(w, 6, "library-partitioner/config2")
