@@ -204,6 +204,8 @@ def main():
     ap.add_argument("--schedule", type=int, default=0, help="0 = Algorithm 1, 1 = layer by layer (serial baseline)")
     ap.add_argument("--step-policy", type=int, default=0, help="0 = step parameters never shrink, 1 = a search "
                     "starts one notch below the last accepted value")
+    ap.add_argument("--fista-mode", type=int, default=0, help="last layer: 0 = FISTA per row with the constant step, "
+                    "1 = FISTA with backtracking on the blocks Z_{L,m}")
     ap.add_argument("--partition", choices=["planted", "builtin"], default="planted",
                     help="communities: the generator's planted blocks, or the library's own partitioner")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink N (debugging only)")
@@ -224,6 +226,7 @@ def main():
     w = synth.config(args.workload, args.scale, args.communities)
     w.hyper["schedule"] = args.schedule
     w.hyper["step_policy"] = args.step_policy
+    w.hyper["fista_mode"] = args.fista_mode
     t_gen = time.perf_counter() - t0
     if args.partition == "builtin":
         t0 = time.perf_counter()
@@ -291,7 +294,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": workload_key, "N": w.N, "communities": w.M,
                    "edges": w.E, "nnz": nnz, "layers": w.L, "widths": w.dims, "scale": args.scale,
-                   "schedule": args.schedule, "step_policy": args.step_policy, "partition": args.partition},
+                   "schedule": args.schedule, "step_policy": args.step_policy, "fista_mode": args.fista_mode,
+                   "partition": args.partition},
         "roofline": None if dominant is None else {k: dominant[k] for k in
                                                    ("bound", "achieved", "peak", "unit", "frac", "traffic")},
         "dominant_kernel": None if dominant is None else dominant["kernel"],

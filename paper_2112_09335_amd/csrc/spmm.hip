@@ -157,6 +157,19 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(
         const int cc = cbase + q * cstride;
         ccl[q] = cc < col1 ? cc : col1 - VEC;
     }
+    // the epilogue's operands (rows of Z_l and T_l at the output row) are asked for before the gathers, so that their
+    // latency is not added at the end of every row
+    float ez[R][VEC], et[R][VEC];
+    if constexpr (EPI == 1) {
+        if (!is_part && grp == 0) {
+#pragma unroll
+            for (int q = 0; q < R; ++q) {
+                const int64_t o = (int64_t)r.z * (int64_t)width + ccl[q];
+                load_vec<VEC>(ez[q], Zl + o);
+                load_vec<VEC>(et[q], Tl + o);
+            }
+        }
+    }
     // the groups of a row take its chunks grp, grp + gpr, ...: eight gathers in flight per group (four per column
     // repeat for the wide shapes); the padding of a chunk carries weight zero, so no entry is masked
     constexpr int UH = (R == 1) ? 8 : 4;
@@ -193,12 +206,8 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(
         if (cc < col1) {
             if constexpr (EPI == 1) {
                 if (!is_part) {
-                    const int64_t o = (int64_t)r.z * (int64_t)width + cc;
-                    float z[VEC], t[VEC];
-                    load_vec<VEC>(z, Zl + o);
-                    load_vec<VEC>(t, Tl + o);
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) acc[q][v] = nu * (z[v] - fmaxf(t[v], 0.f)) + acc[q][v];
+                    for (int v = 0; v < VEC; ++v) acc[q][v] = nu * (ez[q][v] - fmaxf(et[q][v], 0.f)) + acc[q][v];
                 }
             }
             store_vec<VEC>(dst + cc, acc[q]);
