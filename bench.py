@@ -140,6 +140,12 @@ def mfma_leg(steps, warmup):
                        for e in class_entries(prof) if e["bound"] == "mfma"]
             out["paths"]["bf16_split" if split else "fp32"] = dict(gemm_split=split, iterations_per_s=steps / dt,
                                                                   ms_per_step=1e3 * dt / steps, kernels=kernels)
+        # what the matrix cores issue from registers alone on this machine: the ceiling the fractions above are read against
+        out["calibration"] = {
+            "fp32_mfma_TFLOPs": solver.op_calibrate("mfma", 20000, 3),
+            "bf16_mfma_TFLOPs": solver.op_calibrate("mfma_bf16", 20000, 3),
+            "bf16_mfma_TFLOPs_with_6_vector_instructions_each": solver.op_calibrate("mfma_bf16_valu6", 20000, 3),
+        }
     finally:
         solver.tune("gemm_split", 1)
         solver.close()

@@ -236,6 +236,9 @@ int  cadmm_op_wgrad_noalloc(cadmm_ctx* ctx, const float* A, const float* G, int6
  *           src (device, N x count) and added up; no row bounds, no reduction, no result rows.  dst as for kind 1.
  *           rate = GB/s of entry pairs plus gathered rows: what the memory system serves to this access pattern, the
  *           ceiling for cadmm_op_aggregate / _aggregate_segments at that width.  Needs the workspace.
+ *   kind 4: as kind 1 with bf16 MFMAs (32x32x16), the instruction the split products issue; rate = TFLOP/s.
+ *   kind 5 / 6 / 7: as kind 4 with 4 / 6 / 8 independent fp32 vector instructions after every MFMA (the rate still
+ *           counts the MFMA flops only): how much vector work runs beside the matrix cores.
  */
 int  cadmm_op_calibrate(cadmm_ctx* ctx, int32_t kind, const float* src, float* dst, int64_t count, int32_t reps,
                         double* rate);

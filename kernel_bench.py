@@ -7,6 +7,7 @@
 ops:  copy            a plain device copy of 1 GiB (torch), the calibration point for memory counters
       stream          the library's own copy kernel on 1 GiB (cadmm_op_calibrate): what a streaming kernel can reach
       mfma            register-only chains of fp32 MFMAs (cadmm_op_calibrate): what the matrix cores can reach
+      mfma_bf16       the same with bf16 MFMAs; mfma_bf16_valu4 / 6 / 8: with that many vector instructions after each
       gather:W        only the gathers of the row aggregation at width W, no row structure (cadmm_op_calibrate):
                       what the memory system serves to the graph's column stream; gatherseg:W the same for the segments
       aggregate:W     Y = A~ X, X of width W                    (cadmm_op_aggregate)
@@ -64,6 +65,12 @@ def main():
             rate = s.op_calibrate("gather" if kind == "gather" else "gather_segments", W, args.reps)
             print(f"{op:20s} gathers of {4 * W}-byte rows along the real column stream: {rate:8.1f} GB/s requested "
                   f"(pairs + rows) = {rate / (8.0 + 4.0 * W):7.2f} G gathers/s", flush=True)
+            continue
+        if kind.startswith("mfma_bf16"):
+            rate = s.op_calibrate(kind, 20000, args.reps)
+            print(f"{op:20s} bf16 MFMA chains on registers"
+                  + (f" with {kind[-1]} vector instructions after each" if kind != "mfma_bf16" else "")
+                  + f": {rate:7.1f} TFLOP/s ({rate / 2500.0:.3f} of the published 2500)", flush=True)
             continue
         if kind in ("stream", "mfma"):
             if kind == "stream":

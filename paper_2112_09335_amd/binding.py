@@ -347,6 +347,7 @@ class Solver:
 
     def op_calibrate(self, kind, count, reps=5):
         """'copy': GB/s of a plain device copy of `count` floats; 'mfma': TFLOP/s of register-only fp32 MFMA chains;
+        'mfma_bf16': the same with bf16 MFMAs, 'mfma_bf16_valu4/6/8': with that many vector instructions after each;
         'gather' / 'gather_segments': GB/s of the aggregation's gathers alone at a row width of `count` floats."""
         torch = self._torch
         rate = C.c_double()
@@ -360,6 +361,10 @@ class Solver:
         elif kind == "mfma":
             dst = torch.empty(2048 * 256, dtype=torch.float32, device=f"cuda:{self.device}")
             rc = self.lib.cadmm_op_calibrate(self.h, 1, None, C.c_void_p(dst.data_ptr()), count, reps, C.byref(rate))
+        elif kind in ("mfma_bf16", "mfma_bf16_valu4", "mfma_bf16_valu6", "mfma_bf16_valu8"):
+            dst = torch.empty(2048 * 256, dtype=torch.float32, device=f"cuda:{self.device}")
+            code = {"mfma_bf16": 4, "mfma_bf16_valu4": 5, "mfma_bf16_valu6": 6, "mfma_bf16_valu8": 7}[kind]
+            rc = self.lib.cadmm_op_calibrate(self.h, code, None, C.c_void_p(dst.data_ptr()), count, reps, C.byref(rate))
         elif kind in ("gather", "gather_segments"):
             src = torch.randn(self.N, count, dtype=torch.float32, device=f"cuda:{self.device}")
             dst = torch.empty(2048 * 256, dtype=torch.float32, device=f"cuda:{self.device}")

@@ -297,6 +297,7 @@ __global__ __launch_bounds__(256) void gemm_nn_kernel(const float* __restrict__ 
 // v_mfma_f32_32x32x2_f32, at a sixteenth of the cycles per flop.  Operand layout of 32x32x16 (64 lanes): a lane holds
 // A[i = lane%32][k = 8*(lane/32) .. +7] and B[k = 8*(lane/32) .. +7][j = lane%32]; the accumulator as for 32x32x2.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef int intx4 __attribute__((ext_vector_type(4)));        // eight bf16 carried as plain bits
 
 // two fp32 numbers -> their three bf16 parts, each pair packed into one dword (low half = first number)
 __device__ __forceinline__ void split3_pair(float x0, float x1, unsigned& h, unsigned& m, unsigned& l) {
@@ -812,6 +813,46 @@ __global__ __launch_bounds__(256) void mfma_chain_kernel(float* __restrict__ out
     out[(int64_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// Machine calibration: chains of bf16 MFMAs (32x32x16) on registers, four chains per wavefront.  With VALU > 0, that
+// many independent vector instructions (fused multiply-adds on registers of their own) follow every matrix
+// instruction: whether the vector ALU runs beside the matrix cores, and how many instructions fit per matrix instruction.
+template <int VALU>
+__global__ __launch_bounds__(256) void mfma_bf16_chain_kernel(float* __restrict__ out, int iters, float seed) {
+    floatx16 acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    intx4 a, b;
+    a.x = a.y = a.z = a.w = 0x3F803F80 + (int)(threadIdx.x & 7);      // pairs of bf16 near 1
+    b.x = b.y = b.z = b.w = 0x3F003F00;
+    float v[VALU > 0 ? VALU : 1];
+#pragma unroll
+    for (int q = 0; q < (VALU > 0 ? VALU : 1); ++q) v[q] = seed + (float)q;
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc[j],
+                                                             0, 0, 0);
+#pragma unroll
+            for (int q = 0; q < VALU; ++q) v[q] = __builtin_fmaf(v[q], 0.999f, seed);
+            if constexpr (VALU > 0) {
+                // keep each matrix instruction and its vector instructions together in the schedule
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, VALU, 0);     // VALU instructions
+            }
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[j][r];
+#pragma unroll
+    for (int q = 0; q < (VALU > 0 ? VALU : 1); ++q) s += v[q];
+    out[(int64_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 // Machine calibration: dst = src, one float4 per thread and step.
 __global__ __launch_bounds__(256) void stream_copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
                                                           int64_t n4) {
@@ -929,6 +970,14 @@ void launch_gemm_tn(hipStream_t s, const float* A, const float* G, float* out, i
 double launch_mfma_chain(hipStream_t s, float* out, int blocks, int iters) {
     hipLaunchKernelGGL(mfma_chain_kernel, dim3((unsigned)blocks), dim3(256), 0, s, out, iters, 1.0f);
     return (double)blocks * 4.0 * iters * 4.0 * (32.0 * 32.0 * 2.0 * 2.0);      // flops
+}
+
+double launch_mfma_bf16_chain(hipStream_t s, float* out, int blocks, int iters, int valu) {
+    if (valu <= 0) hipLaunchKernelGGL((mfma_bf16_chain_kernel<0>), dim3((unsigned)blocks), dim3(256), 0, s, out, iters, 1.0f);
+    else if (valu <= 4) hipLaunchKernelGGL((mfma_bf16_chain_kernel<4>), dim3((unsigned)blocks), dim3(256), 0, s, out, iters, 1.0f);
+    else if (valu <= 6) hipLaunchKernelGGL((mfma_bf16_chain_kernel<6>), dim3((unsigned)blocks), dim3(256), 0, s, out, iters, 1.0f);
+    else hipLaunchKernelGGL((mfma_bf16_chain_kernel<8>), dim3((unsigned)blocks), dim3(256), 0, s, out, iters, 1.0f);
+    return (double)blocks * 4.0 * iters * 4.0 * (32.0 * 32.0 * 16.0 * 2.0);      // flops
 }
 
 void launch_stream_copy(hipStream_t s, const float* src, float* dst, int64_t count) {

@@ -175,3 +175,5 @@ def test_calibration_kernels_report_a_rate(ctx):
     s, g, torch = ctx
     assert s.op_calibrate("copy", 1 << 22, 3) > 10.0        # GB/s
     assert s.op_calibrate("mfma", 200, 3) > 1.0             # TFLOP/s
+    assert s.op_calibrate("mfma_bf16", 200, 3) > 1.0
+    assert s.op_calibrate("mfma_bf16_valu6", 200, 3) > 1.0
