@@ -163,6 +163,47 @@ def test_readout_and_iteration_properties_at_full_size(full):
         assert val <= base - gsq / (2 * th) + 1e-7 * abs(base), (m, val, base, gsq / (2 * th))
 
 
+def test_last_layer_with_backtracking_at_full_size(full):
+    """fista_mode 1 on the 2,000,000-node workload: the blocks Z_{L,m} of sampled communities against the oracle's
+    block solver run on the library's own state (the oracle handles one community of 31,000 rows in a moment), with
+    the accepted L and the trial count of those communities equal, and Eq. 2 on every row."""
+    from paper_2112_09335_amd import binding
+    w, _, g, torch = full
+    w1 = synth.Workload(w.name, w.N, w.M, w.src, w.dst, w.comm, w.X, w.labels, list(w.dims), w.W0, w.iters,
+                        dict(w.hyper, fista_mode=1))
+    s = binding.Solver.from_workload(w1, 0)
+    try:
+        h = w1.hyper
+        o = AdmmOracle(g, w.dims, nu=h["nu"], rho=h["rho"], tau0=h["tau0"], theta0=h["theta0"], eta=h["eta"],
+                       max_backtrack=h["max_backtrack"], fista_iters=h["fista_iters"], risk=h["risk"], fista_mode=1)
+        o.set_data(w.X, w.labels)
+        L = w.L
+        s.run(2)
+        ZL0 = g.to_new(s.get_Z(L).astype(np.float64))
+        Zp0 = g.to_new(s.get_Z(L - 1).astype(np.float64))
+        U0 = g.to_new(s.get_U().astype(np.float64))
+        s.run(1)
+        assert s.eval()["status"] == 0
+        WL1 = s.get_W(L).astype(np.float64)
+        ZL1 = g.to_new(s.get_Z(L).astype(np.float64))
+        U1 = g.to_new(s.get_U().astype(np.float64))
+        TL = g.A @ (Zp0 @ WL1)
+        say("dual step identity (Eq. 2) with the block solver in place")
+        want = U0 + o.rho * (ZL0 - TL)
+        assert np.abs(U1 - want).max() <= REL * np.abs(want).max()
+        Lgpu, trials_gpu = s.get_fista()
+        for m in (0, 23, 63):
+            say("community", m, "against the oracle's block solver")
+            r = g.rows(m)
+            zref = o.fista_block_backtracking(m, ZL0[r], TL[r], U0[r], o.J)
+            assert np.abs(ZL1[r] - zref).max() <= REL * np.abs(zref).max(), m
+            assert Lgpu[m] == o.fista_L[m] and trials_gpu[m] == o.fista_trials[m], (m, Lgpu[m], o.fista_L[m],
+                                                                                      trials_gpu[m], o.fista_trials[m])
+            assert o.rho <= Lgpu[m] <= o.eta * (o.rho + 0.5)      # cross-entropy: curvature at most rho + 1/2
+    finally:
+        s.close()
+
+
 @pytest.mark.parametrize("index", [3, 5])
 def test_readout_and_dual_step_at_full_size_of_the_other_large_configs(index):
     """Configs 3 (three layers, 32 communities) and 5 (eight layers of 512): after a few iterations the library's
