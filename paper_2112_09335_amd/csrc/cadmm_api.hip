@@ -407,7 +407,7 @@ void carry_T(cadmm_ctx* c, int l) {
     const int Cl = c->C[l];
     timed(c, P_T_CARRY, 4.0 * ((double)c->hg.n_seg * Cl + 2.0 * (double)N * Cl) + 8.0 * (double)c->hg.n_seg, 0.0, [&] {
         launch_t_carry(c->stream, c->T[l], c->Pbuf[(l - 1) & 1], c->d_row_seg_ptr, c->d_seg_comm, c->d_seg_pos, N, Cl,
-                       c->unitsZ + (size_t)(l - 2) * c->hg.M);
+                       c->unitsZ + (size_t)(l - 2) * c->hg.M, c->hg.M);
     });
 }
 

@@ -591,12 +591,20 @@ __global__ __launch_bounds__(256) void z_step_lowrank_kernel(float* __restrict__
 // - sum over the segments (i, c) of P_{(i,c)} / theta_{l,c}  (P = A~_{., c} grad W_{l+1}, already formed for the
 // search).  Applying that keeps T_{l+1} valid for the next iteration without a new aggregation and product.
 constexpr int kCarryBatch = 4;
-template <int VEC>
+constexpr int kCarryUnits = 1024;      // communities whose 1/theta a workgroup keeps in LDS
+// LDSU: the workgroup first copies 1/theta of every community (0 for a skipped step) into LDS, which takes the
+// lookup of a segment's step parameter out of the chain of dependent global loads (row -> segment -> unit).
+template <int VEC, bool LDSU>
 __global__ __launch_bounds__(256) void t_carry_kernel(float* __restrict__ Tn, const float* __restrict__ P,
                                                       const int64_t* __restrict__ row_seg_ptr,
                                                       const int32_t* __restrict__ seg_comm,
                                                       const int32_t* __restrict__ seg_pos, int64_t N, int Cn,
-                                                      const Unit* __restrict__ units) {
+                                                      const Unit* __restrict__ units, int M) {
+    __shared__ double s_inv[LDSU ? kCarryUnits : 1];
+    if constexpr (LDSU) {
+        for (int i = threadIdx.x; i < M; i += 256) s_inv[i] = units[i].skip ? 0.0 : 1.0 / units[i].step;
+        __syncthreads();
+    }
     const int wv = (Cn + VEC - 1) / VEC;
     int cshift = 0;
     while ((1 << cshift) < wv && cshift < 8) ++cshift;
@@ -620,23 +628,25 @@ __global__ __launch_bounds__(256) void t_carry_kernel(float* __restrict__ Tn, co
                     cm[j] = seg_comm[sj];
                     ps[j] = seg_pos[sj];
                 }
-                double st[kCarryBatch];
-                bool use[kCarryBatch];
+                double inv[kCarryBatch];
                 float p[kCarryBatch][VEC];
 #pragma unroll
                 for (int j = 0; j < kCarryBatch; ++j) {
-                    const Unit* u = units + cm[j];
-                    st[j] = u->step;
-                    use[j] = sgm + j < s1 && !u->skip;
+                    if constexpr (LDSU) {
+                        inv[j] = s_inv[cm[j]];
+                    } else {
+                        const Unit* u = units + cm[j];
+                        inv[j] = u->skip ? 0.0 : 1.0 / u->step;
+                    }
+                    if (sgm + j >= s1) inv[j] = 0.0;
                     ldv<VEC>(p[j], P + (int64_t)ps[j] * Cn + cv * VEC);
                 }
 #pragma unroll
                 for (int j = 0; j < kCarryBatch; ++j) {
-                    if (!use[j]) continue;
+                    if (inv[j] == 0.0) continue;          // past the row's end, or a step that was not taken
                     any = true;
-                    const double inv = 1.0 / st[j];
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) acc[v] += (double)p[j][v] * inv;
+                    for (int v = 0; v < VEC; ++v) acc[v] += (double)p[j][v] * inv[j];
                 }
             }
             if (!any) continue;
@@ -1111,10 +1121,12 @@ void launch_z_step_lowrank(hipStream_t s, float* Zl, const float* Tl, const floa
 }
 
 void launch_t_carry(hipStream_t s, float* Tn, const float* P, const int64_t* row_seg_ptr, const int32_t* seg_comm,
-                    const int32_t* seg_pos, int64_t N, int Cn, const Unit* units) {
+                    const int32_t* seg_pos, int64_t N, int Cn, const Unit* units, int M) {
     const int nb = flat_grid(N * (int64_t)Cn * 4);
-    if (Cn % 4 == 0) hipLaunchKernelGGL((t_carry_kernel<4>), dim3(nb), dim3(256), 0, s, Tn, P, row_seg_ptr, seg_comm, seg_pos, N, Cn, units);
-    else hipLaunchKernelGGL((t_carry_kernel<1>), dim3(nb), dim3(256), 0, s, Tn, P, row_seg_ptr, seg_comm, seg_pos, N, Cn, units);
+#define CADMM_CARRY(V_, L_) hipLaunchKernelGGL((t_carry_kernel<V_, L_>), dim3(nb), dim3(256), 0, s, Tn, P, row_seg_ptr, seg_comm, seg_pos, N, Cn, units, M)
+    if (M <= kCarryUnits) { if (Cn % 4 == 0) CADMM_CARRY(4, true); else CADMM_CARRY(1, true); }
+    else { if (Cn % 4 == 0) CADMM_CARRY(4, false); else CADMM_CARRY(1, false); }
+#undef CADMM_CARRY
 }
 
 void launch_last_layer(hipStream_t s, float* ZL, float* U, const float* TL, const int32_t* labels, int64_t N,

@@ -187,7 +187,7 @@ void launch_z_step_lowrank(hipStream_t s, float* Zl, const float* Tl, const floa
 // Tn[i,:] -= sum over the segments (i,c) of row i of P[(i,c),:] / theta_c  (communities whose step was skipped
 // contribute nothing): the pre-activation of the next layer after the Z step, without a new aggregation.
 void launch_t_carry(hipStream_t s, float* Tn, const float* P, const int64_t* row_seg_ptr, const int32_t* seg_comm,
-                    const int32_t* seg_pos, int64_t N, int Cn, const Unit* units);
+                    const int32_t* seg_pos, int64_t N, int Cn, const Unit* units, int M);
 // Last layer (Appendix A, Eq. 5) by J FISTA steps per row, fused with the dual step (Eq. 2):
 //   U_new = U + rho (Z_L - T_L),  Z_L_new = FISTA(start Z_L; c = T_L, U, rho)
 // update_u = 0 leaves U alone (the dual step is then taken on the new iterates by the next phi_G)
