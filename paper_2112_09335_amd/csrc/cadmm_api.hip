@@ -548,9 +548,9 @@ void z_update_hidden(cadmm_ctx* c, int l) {
         });
         timed(c, P_Z_STEP, 4.0 * (3.0 * (double)N * Cl + (double)N + (lowrank ? (double)N * Cn : 0.0)), 0.0, [&] {
             if (lowrank)
-                launch_z_step_lowrank(s, c->Z[l], c->T[l], c->tmpA, c->Wt, c->nu, c->d_row_comm, N, Cl, Cn, units);
+                launch_z_step_lowrank(s, c->Z[l], c->T[l], c->tmpA, c->Wt, c->nu, c->d_row_comm, N, Cl, Cn, units, c->hg.M);
             else
-                launch_z_step(s, c->Z[l], c->tmpB, c->d_row_comm, N, Cl, units);
+                launch_z_step(s, c->Z[l], c->tmpB, c->d_row_comm, N, Cl, units, c->hg.M);
         });
     }
 }

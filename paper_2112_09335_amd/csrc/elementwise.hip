@@ -524,10 +524,19 @@ __global__ __launch_bounds__(256) void z_trial_finish_kernel(ZTrialArgs a) {
     }
 }
 
-template <int VEC>
+constexpr int kStepUnits = 1024;       // communities whose 1/theta a workgroup keeps in LDS
+// Z_{l,m} <- Z_{l,m} - grad / theta_{l,m}.  LDSU: 1/theta of every community (0 where no step is taken) is copied
+// to LDS first and the loads of a row are issued before its community is known: the row's community, then its step
+// parameter, then the data used to be three dependent round trips per row.
+template <int VEC, bool LDSU>
 __global__ __launch_bounds__(256) void z_step_kernel(float* __restrict__ Zl, const float* __restrict__ gradZ,
                                                      const int32_t* __restrict__ row_comm, int64_t N, int Cl,
-                                                     const Unit* __restrict__ units) {
+                                                     const Unit* __restrict__ units, int M) {
+    __shared__ double s_inv[LDSU ? kStepUnits : 1];
+    if constexpr (LDSU) {
+        for (int i = threadIdx.x; i < M; i += 256) s_inv[i] = units[i].skip ? 0.0 : 1.0 / units[i].step;
+        __syncthreads();
+    }
     const int wv = (Cl + VEC - 1) / VEC;
     int cshift = 0;
     while ((1 << cshift) < wv && cshift < 8) ++cshift;
@@ -535,14 +544,16 @@ __global__ __launch_bounds__(256) void z_step_kernel(float* __restrict__ Zl, con
     const int c_first = threadIdx.x & (cp - 1);
     const int64_t r_step = (int64_t)gridDim.x * (256 >> cshift);
     for (int64_t r = (int64_t)blockIdx.x * (256 >> cshift) + (threadIdx.x >> cshift); r < N; r += r_step) {
-        const Unit* u = units + row_comm[r];
-        if (u->skip) continue;
-        const double inv = 1.0 / u->step;
+        const int cm = row_comm[r];
         const int64_t base = r * Cl;
         for (int cv = c_first; cv < wv; cv += cp) {
             float z[VEC], g[VEC];
             ldv<VEC>(z, Zl + base + cv * VEC);
             ldv<VEC>(g, gradZ + base + cv * VEC);
+            double inv;
+            if constexpr (LDSU) inv = s_inv[cm];
+            else inv = units[cm].skip ? 0.0 : 1.0 / units[cm].step;
+            if (inv == 0.0) break;                   // no step for this row's community
 #pragma unroll
             for (int v = 0; v < VEC; ++v) z[v] = (float)((double)z[v] - (double)g[v] * inv);
             stv<VEC>(Zl + base + cv * VEC, z);
@@ -550,40 +561,63 @@ __global__ __launch_bounds__(256) void z_step_kernel(float* __restrict__ Zl, con
     }
 }
 
+// The same step with the gradient rebuilt from its low-rank form (see lowrank_grad); a lane group handles two rows
+// per trip with every load issued before the first use.
+template <bool LDSU>
 __global__ __launch_bounds__(256) void z_step_lowrank_kernel(float* __restrict__ Zl, const float* __restrict__ Tl,
                                                              const float* __restrict__ SG, const float* __restrict__ Wt,
                                                              float nu, const int32_t* __restrict__ row_comm, int64_t N,
-                                                             int Cl, int Cn, const Unit* __restrict__ units) {
+                                                             int Cl, int Cn, const Unit* __restrict__ units, int M) {
+    __shared__ double s_inv[LDSU ? kStepUnits : 1];
+    if constexpr (LDSU) {
+        for (int i = threadIdx.x; i < M; i += 256) s_inv[i] = units[i].skip ? 0.0 : 1.0 / units[i].step;
+        __syncthreads();
+    }
     const int wv = Cl / 4;
     int cshift = 0;
     while ((1 << cshift) < wv && cshift < 8) ++cshift;
     const int c_first = threadIdx.x & ((1 << cshift) - 1);
+    if (c_first >= wv) return;                       // (after the barrier)
     float wt[kLowRankMax][4];
 #pragma unroll
     for (int k = 0; k < kLowRankMax; ++k) {
-        if (k < Cn && c_first < wv) ldv<4>(wt[k], Wt + (int64_t)k * Cl + c_first * 4);
+        if (k < Cn) ldv<4>(wt[k], Wt + (int64_t)k * Cl + c_first * 4);
         else { wt[k][0] = 0.f; wt[k][1] = 0.f; wt[k][2] = 0.f; wt[k][3] = 0.f; }
     }
-    const int64_t r_step = (int64_t)gridDim.x * (256 >> cshift);
-    for (int64_t r = (int64_t)blockIdx.x * (256 >> cshift) + (threadIdx.x >> cshift); r < N; r += r_step) {
-        const Unit* u = units + row_comm[r];
-        if (u->skip || c_first >= wv) continue;
-        const double inv = 1.0 / u->step;
-        float sg[kLowRankMax];
+    constexpr int R = 2;
+    const int64_t rows_per_block = 256 >> cshift;
+    const int64_t r_step = (int64_t)gridDim.x * rows_per_block * R;
+    for (int64_t r0 = ((int64_t)blockIdx.x * R) * rows_per_block + (threadIdx.x >> cshift); r0 < N; r0 += r_step) {
+        int cm[R];
+        float z[R][4], t[R][4], sg[R][kLowRankMax];
 #pragma unroll
-        for (int k4 = 0; k4 < kLowRankMax / 4; ++k4) {
-            float q[4] = {0.f, 0.f, 0.f, 0.f};
-            if (4 * k4 < Cn) ldv<4>(q, SG + r * Cn + 4 * k4);
-            sg[4 * k4] = q[0]; sg[4 * k4 + 1] = q[1]; sg[4 * k4 + 2] = q[2]; sg[4 * k4 + 3] = q[3];
+        for (int q = 0; q < R; ++q) {
+            const int64_t r = r0 + q * rows_per_block;
+            const int64_t rr = r < N ? r : N - 1;    // a row past the end repeats the last one and is not stored
+            cm[q] = row_comm[rr];
+            const int64_t o = rr * Cl + c_first * 4;
+            ldv<4>(z[q], Zl + o);
+            ldv<4>(t[q], Tl + o);
+#pragma unroll
+            for (int k4 = 0; k4 < kLowRankMax / 4; ++k4) {
+                float v[4] = {0.f, 0.f, 0.f, 0.f};
+                if (4 * k4 < Cn) ldv<4>(v, SG + rr * Cn + 4 * k4);
+                sg[q][4 * k4] = v[0]; sg[q][4 * k4 + 1] = v[1]; sg[q][4 * k4 + 2] = v[2]; sg[q][4 * k4 + 3] = v[3];
+            }
         }
-        const int64_t o = r * Cl + c_first * 4;
-        float z[4], t[4], g[4];
-        ldv<4>(z, Zl + o);
-        ldv<4>(t, Tl + o);
-        lowrank_grad(g, z, t, sg, wt, Cn, nu);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) z[v] = (float)((double)z[v] - (double)g[v] * inv);
-        stv<4>(Zl + o, z);
+        for (int q = 0; q < R; ++q) {
+            const int64_t r = r0 + q * rows_per_block;
+            double inv;
+            if constexpr (LDSU) inv = s_inv[cm[q]];
+            else inv = units[cm[q]].skip ? 0.0 : 1.0 / units[cm[q]].step;
+            if (r >= N || inv == 0.0) continue;
+            float g[4];
+            lowrank_grad(g, z[q], t[q], sg[q], wt, Cn, nu);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) z[q][v] = (float)((double)z[q][v] - (double)g[v] * inv);
+            stv<4>(Zl + r * Cl + c_first * 4, z[q]);
+        }
     }
 }
 
@@ -1108,16 +1142,21 @@ void launch_z_trial(hipStream_t s, const ZTrialArgs& a0) {
 }
 
 void launch_z_step(hipStream_t s, float* Zl, const float* gradZ, const int32_t* row_comm, int64_t N, int Cl,
-                   const Unit* units) {
+                   const Unit* units, int M) {
     const int nb = flat_grid(N * (int64_t)Cl);
-    if (Cl % 4 == 0) hipLaunchKernelGGL((z_step_kernel<4>), dim3(nb), dim3(256), 0, s, Zl, gradZ, row_comm, N, Cl, units);
-    else hipLaunchKernelGGL((z_step_kernel<1>), dim3(nb), dim3(256), 0, s, Zl, gradZ, row_comm, N, Cl, units);
+#define CADMM_ZSTEP(V_, L_) hipLaunchKernelGGL((z_step_kernel<V_, L_>), dim3(nb), dim3(256), 0, s, Zl, gradZ, row_comm, N, Cl, units, M)
+    if (M <= kStepUnits) { if (Cl % 4 == 0) CADMM_ZSTEP(4, true); else CADMM_ZSTEP(1, true); }
+    else { if (Cl % 4 == 0) CADMM_ZSTEP(4, false); else CADMM_ZSTEP(1, false); }
+#undef CADMM_ZSTEP
 }
 
 void launch_z_step_lowrank(hipStream_t s, float* Zl, const float* Tl, const float* SG, const float* Wt, float nu,
-                           const int32_t* row_comm, int64_t N, int Cl, int Cn, const Unit* units) {
+                           const int32_t* row_comm, int64_t N, int Cl, int Cn, const Unit* units, int M) {
     const int nb = flat_grid(N * (int64_t)Cl);
-    hipLaunchKernelGGL(z_step_lowrank_kernel, dim3(nb), dim3(256), 0, s, Zl, Tl, SG, Wt, nu, row_comm, N, Cl, Cn, units);
+    if (M <= kStepUnits)
+        hipLaunchKernelGGL((z_step_lowrank_kernel<true>), dim3(nb), dim3(256), 0, s, Zl, Tl, SG, Wt, nu, row_comm, N, Cl, Cn, units, M);
+    else
+        hipLaunchKernelGGL((z_step_lowrank_kernel<false>), dim3(nb), dim3(256), 0, s, Zl, Tl, SG, Wt, nu, row_comm, N, Cl, Cn, units, M);
 }
 
 void launch_t_carry(hipStream_t s, float* Tn, const float* P, const int64_t* row_seg_ptr, const int32_t* seg_comm,

@@ -180,10 +180,10 @@ struct ZTrialArgs {
 void launch_z_trial(hipStream_t s, const ZTrialArgs& a);
 // Z_l[i,:] -= gradZ[i,:] / theta[comm(i)]
 void launch_z_step(hipStream_t s, float* Zl, const float* gradZ, const int32_t* row_comm, int64_t N, int Cl,
-                   const Unit* units);
+                   const Unit* units, int M);
 // the same step with the gradient in its low-rank form nu (Zl - relu(Tl)) + SG Wt (SG: N x Cn, Wt: Cn x Cl)
 void launch_z_step_lowrank(hipStream_t s, float* Zl, const float* Tl, const float* SG, const float* Wt, float nu,
-                           const int32_t* row_comm, int64_t N, int Cl, int Cn, const Unit* units);
+                           const int32_t* row_comm, int64_t N, int Cl, int Cn, const Unit* units, int M);
 // Tn[i,:] -= sum over the segments (i,c) of row i of P[(i,c),:] / theta_c  (communities whose step was skipped
 // contribute nothing): the pre-activation of the next layer after the Z step, without a new aggregation.
 void launch_t_carry(hipStream_t s, float* Tn, const float* P, const int64_t* row_seg_ptr, const int32_t* seg_comm,
