@@ -567,7 +567,8 @@ void last_layer_update(cadmm_ctx* c) {
         a.n_chunks = (int32_t)c->hg.chunks.size(); a.unit_chunk_ptr = c->d_unit_chunk_ptr; a.M = c->hg.M;
         a.CL = c->C[L]; a.risk = c->risk; a.J = c->J; a.update_u = c->dual_form == 0 ? 1 : 0; a.rho = c->rho;
         a.sp = search_params(c); a.units = c->unitsF; a.partials = c->partials; a.status = c->status;
-        const int more_passes = (c->max_bt + kMaxCand - 1) / kMaxCand;
+        // candidates per step: 1 (16 in stage 0), then a pass of 4, then passes of 16 until max_backtrack + 1 are covered
+        const int wide_passes = (c->max_bt + kMaxCand - 1) / kMaxCand;
         timed(c, P_LAST_LAYER, 4.0 * (double)N * c->C[L] * (3.0 + 7.0 * (c->J - 1) + 6.0) + 4.0 * (double)N * (c->J + 1), 0.0, [&] {
             double t = 1.0;
             for (int stage = 0; stage <= c->J; ++stage) {
@@ -578,8 +579,10 @@ void last_layer_update(cadmm_ctx* c) {
                     t = tn;
                 }
                 launch_fista_stage(c->stream, a, stage, 0, mom);
-                if (stage < c->J)
-                    for (int p = stage == 0 ? 1 : 0; p < more_passes; ++p) launch_fista_stage(c->stream, a, stage, 1, 0.f);
+                if (stage < c->J) {
+                    if (stage > 0) launch_fista_stage(c->stream, a, stage, 1, 0.f);
+                    for (int p = stage == 0 ? 1 : 0; p < wide_passes; ++p) launch_fista_stage(c->stream, a, stage, 2, 0.f);
+                }
             }
         });
         return;

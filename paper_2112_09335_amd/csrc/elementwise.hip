@@ -1189,10 +1189,15 @@ void launch_argmax_rows(hipStream_t s, const float* T, int32_t* pred, int64_t N,
 
 void launch_fista_stage(hipStream_t s, const FistaArgs& a, int stage, int more, float mom) {
     if (a.n_chunks <= 0) return;
-    const bool wide = more || stage == 0;              // 16 candidates; else the current L alone
-    const int nb = more ? (a.n_chunks < kReduceBlocks / 4 ? a.n_chunks : kReduceBlocks / 4) : a.n_chunks;
+    // more = 0: the pass that takes the step and tries the first candidate (sixteen at once in stage 0, where L climbs
+    // from rho); more = 1: four further candidates on a full grid (a step usually needs one or two doublings, in many
+    // communities at once); more = 2: sixteen further candidates on a small grid, which usually finds nothing pending
+    const int nc = more == 0 ? (stage == 0 ? kMaxCand : 1) : (more == 1 ? 4 : kMaxCand);
+    const int cap = more == 0 ? a.n_chunks : (more == 1 ? kReduceBlocks : kReduceBlocks / 4);
+    const int nb = a.n_chunks < cap ? a.n_chunks : cap;
 #define CADMM_FISTA(LG_) do { \
-        if (wide) hipLaunchKernelGGL((fista_stage_kernel<LG_, kMaxCand>), dim3(nb), dim3(256), 0, s, a, stage, more, mom); \
+        if (nc == kMaxCand) hipLaunchKernelGGL((fista_stage_kernel<LG_, kMaxCand>), dim3(nb), dim3(256), 0, s, a, stage, more, mom); \
+        else if (nc == 4) hipLaunchKernelGGL((fista_stage_kernel<LG_, 4>), dim3(nb), dim3(256), 0, s, a, stage, more, mom); \
         else hipLaunchKernelGGL((fista_stage_kernel<LG_, 1>), dim3(nb), dim3(256), 0, s, a, stage, more, mom); } while (0)
     if (a.CL <= 4) CADMM_FISTA(0);
     else if (a.CL <= 8) CADMM_FISTA(1);
@@ -1200,7 +1205,7 @@ void launch_fista_stage(hipStream_t s, const FistaArgs& a, int stage, int more, 
     else if (a.CL <= 32) CADMM_FISTA(3);
     else CADMM_FISTA(4);
 #undef CADMM_FISTA
-    if (stage < a.J) hipLaunchKernelGGL(fista_finish_kernel, dim3(a.M), dim3(256), 0, s, a, wide ? kMaxCand : 1, more ? 0 : 1, stage);
+    if (stage < a.J) hipLaunchKernelGGL(fista_finish_kernel, dim3(a.M), dim3(256), 0, s, a, nc, more ? 0 : 1, stage);
 }
 
 void launch_fill_units(hipStream_t s, Unit* units, int n, double step) {
