@@ -197,6 +197,48 @@ def cpu_baseline(index, full_N, full_nnz, communities=None, schedule=0, step_pol
                 scaling_exponent=exponent, extrapolated=not at_full)
 
 
+def full_size_oracle_forms(w, solver, stats):
+    """The oracle's full-graph forms timed at the FULL size of the workload, on the library's own state: Eq. 1 once
+    (`stats_full_graph`: every layer's aggregation, product and penalty) and two evaluations of phi_l per layer (what a
+    W step that accepts its first candidate evaluates besides its gradient).  Not an iteration -- the oracle's iteration
+    works in the message form over M x M community blocks and is far slower -- but a measured full-size anchor next to
+    the extrapolated figure, and a check of the library's readout at the size the benchmark times."""
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+    from oracle.admm import AdmmOracle
+    from oracle.graph import OracleGraph
+    threads = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    threads = max(1, min(threads, int(os.environ.get("OMP_NUM_THREADS", threads))))
+    h = w.hyper
+    with threadpool_limits(limits=threads):
+        t0 = time.perf_counter()
+        g = OracleGraph(w.N, w.src, w.dst, w.M, w.comm, split=False)
+        o = AdmmOracle(g, w.dims, nu=h["nu"], rho=h["rho"], tau0=h["tau0"], theta0=h["theta0"], eta=h["eta"],
+                       max_backtrack=h["max_backtrack"], fista_iters=h["fista_iters"], risk=h["risk"])
+        o.set_data(w.X, w.labels)
+        L = w.L
+        W = [None] + [solver.get_W(l).astype(np.float64) for l in range(1, L + 1)]
+        Z = [o.Z[0]] + [g.to_new(solver.get_Z(l).astype(np.float64)) for l in range(1, L + 1)]
+        U = g.to_new(solver.get_U().astype(np.float64))
+        o.phi_full_graph(1, W[1], Z[0], Z[1], U)          # forms and keeps A~ Z_0, as the library does at set-up
+        t_setup = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        so = o.stats_full_graph(W, Z, U)
+        t_eq1 = time.perf_counter() - t0
+        t_phi = []
+        for l in range(1, L + 1):
+            t0 = time.perf_counter()
+            o.phi_full_graph(l, W[l], Z[l - 1], Z[l], U)
+            o.phi_full_graph(l, W[l], Z[l - 1], Z[l], U)
+            t_phi.append(time.perf_counter() - t0)
+    return dict(what="oracle full-graph forms at full size on the library's state: Eq. 1 once, and two evaluations of "
+                     "phi_l per layer; a lower bound on the CPU time of an iteration, not an iteration",
+                N=w.N, threads=threads, seconds_setup=t_setup, seconds_eq1=t_eq1, seconds_two_phi_per_layer=t_phi,
+                seconds_total=t_eq1 + sum(t_phi), iterations_per_s_upper_bound=1.0 / (t_eq1 + sum(t_phi)),
+                objective_oracle=so["objective"], objective_library=stats["objective"],
+                objective_rel_diff=abs(so["objective"] - stats["objective"]) / abs(so["objective"]))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -219,6 +261,8 @@ def main():
     ap.add_argument("--no-mfma-leg", action="store_true", help="skip the short leg on the GEMM-heavy configuration "
                     "and the fp32-MFMA run of the headline workload")
     ap.add_argument("--mfma-steps", type=int, default=3)
+    ap.add_argument("--no-full-size-oracle", action="store_true", help="skip timing the oracle's full-graph forms at "
+                    "the full size of the workload (about a minute of host work)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding or collectives are part of it); "
@@ -332,6 +376,9 @@ def main():
                                      kernels=[{k: e[k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac",
                                                                  "avg_launch_ms", "share_of_step")}
                                               for e in class_entries(prof0) if e["kernel"].startswith("gemm")])
+    full_forms = None
+    if not args.no_cpu_baseline and not args.no_full_size_oracle and args.scale == 1.0 and args.workload == 4:
+        full_forms = full_size_oracle_forms(w, solver, solver.eval())
     solver.close()
     del solver
     torch.cuda.empty_cache()
@@ -339,6 +386,8 @@ def main():
         out["mfma"] = mfma_leg(args.mfma_steps, 1)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload, w.N, nnz, args.communities, args.schedule, args.step_policy)
+        if full_forms is not None:
+            out["cpu_baseline"]["full_size_full_graph_forms"] = full_forms
     print(json.dumps(out))
 
 
