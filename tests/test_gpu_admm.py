@@ -319,6 +319,14 @@ def test_last_layer_by_fista_with_backtracking():
     run_case(w, 4, "fista-backtracking/40-classes/layer-by-layer")
 
 
+def test_more_communities_than_a_workgroup_keeps_step_parameters_for():
+    """The Z-step and carry kernels keep 1/theta of up to 1024 communities in LDS and look the parameters up in memory
+    beyond that: 1100 communities of a few nodes each, on the low-rank path (two layers) and on the stored-gradient
+    path (three layers)."""
+    run_case(synth.config(4, 0.002, M=1100), 3, "many-communities/config4")       # N = 4000
+    run_case(synth.config(3, 0.008, M=1100), 3, "many-communities/config3")       # N = 1600, three layers
+
+
 def test_communities_from_the_library_partitioner_feed_the_sweep():
     """A graph that comes without communities: cadmm_partition (bit-exact against its CPU twin) supplies them, the graph
     built from them is bit-exact against the oracle's, and the sweep on them matches the oracle iteration by iteration."""
