@@ -13,10 +13,11 @@
 // group and trip; their partial sums are added by a wavefront-level xor-shuffle reduction.  GPR is chosen per run
 // of one length class so that one trip covers the class's longest row: short rows pack many rows into a
 // wavefront, long rows spread over it, and the rows of a wavefront need the same number of trips.
-// What bounds the narrow shapes is the address unit, which takes a wavefront's load instruction four lanes a
-// cycle whatever it loads: so a lane group fetches its chunk with one load of 64 bytes spread over its lanes (one
-// instruction per 128 entries at 16 columns) and hands the pairs round by lane exchanges, instead of one load of
-// four bytes per entry and array.
+// What bounds the narrow shapes (rows of up to 64 bytes) is the rate at which the L2s take 64-byte requests from the
+// L1s, one per gathered row (measured with gather_calibration_kernel below); everything around the gathers is kept
+// out of their way: a lane group fetches its chunk with one load of 64 bytes spread over its lanes (one instruction
+// per 128 entries at 16 columns) and hands the pairs round by lane exchanges, instead of one load of four bytes per
+// entry and array.
 // Rows beyond a length threshold (power-law hubs) are cut into parts that run first in the same launch, into a
 // side buffer; a small kernel adds a row's parts in order.  Segments with a single entry are scaled copies of a
 // gathered row and have a kernel of their own.  Everything is order-fixed: no atomics, results are reproducible.
