@@ -175,6 +175,19 @@ def cpu_baseline(index, full_N, full_nnz, communities=None, schedule=0, step_pol
             orc.iterate(iters)
             dt = time.perf_counter() - t0
             points.append(dict(N=w.N, M=w.M, nnz=orc.g.nnz, iterations=iters, seconds=dt, iterations_per_s=iters / dt))
+    # the smaller sample once more on ONE thread (the oracle is numpy: at these sizes most of its time is the plain
+    # Python loops over communities, which no thread count changes)
+    scale1, _ = ORACLE_SAMPLES[index][0]
+    with threadpool_limits(limits=1):
+        w = synth.config(index, scale1, communities)
+        w.hyper["schedule"] = schedule
+        w.hyper["step_policy"] = step_policy
+        orc = make_oracle(w)
+        orc.iterate(1)
+        t0 = time.perf_counter()
+        orc.iterate(2)
+        single = dict(N=w.N, threads=1, iterations=2, seconds=time.perf_counter() - t0)
+        single["iterations_per_s"] = 2 / single["seconds"]
     a, b = points
     # seconds per iteration = fixed + per_entry * nnz: the fixed part is the per-block overhead of the plain Python loops
     # over communities, the rest grows with the graph
@@ -193,7 +206,7 @@ def cpu_baseline(index, full_N, full_nnz, communities=None, schedule=0, step_pol
                            f"value = 1 / (fixed + per_entry * nnz_full) with fixed = {fixed:.3f} s and per_entry = "
                            f"{per_entry:.3e} s fitted through the two samples (extrapolation to N={full_N}, "
                            f"nnz={full_nnz}); the power law through the same two points has exponent {exponent:.2f}")),
-                samples=points, seconds_per_iteration_fixed=fixed, seconds_per_iteration_per_entry=per_entry,
+                samples=points, single_thread_sample=single, seconds_per_iteration_fixed=fixed, seconds_per_iteration_per_entry=per_entry,
                 scaling_exponent=exponent, extrapolated=not at_full)
 
 
