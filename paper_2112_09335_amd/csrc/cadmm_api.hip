@@ -50,11 +50,9 @@ struct cadmm_ctx {
     int32_t* d_perm = nullptr;
     int32_t* d_seg1_pos = nullptr; int32_t* d_seg1_col = nullptr; float* d_seg1_val = nullptr;
     int32_t* d_segc_row = nullptr;
-    int32_t* d_chunk_unit = nullptr;
-    int32_t* d_chunk_kind = nullptr;
-    int32_t* d_chunk_begin = nullptr;
-    int32_t* d_chunk_end = nullptr;
-    int32_t* d_unit_chunk_ptr = nullptr;
+    // reduction chunk tables of the Z search: [0] many segments per chunk (narrow next layer), [1] few (wide)
+    struct DevChunks { int32_t *unit = nullptr, *kind = nullptr, *begin = nullptr, *end = nullptr, *unit_ptr = nullptr; int32_t n = 0; };
+    DevChunks d_chunks[2];
     int32_t* d_labels = nullptr;
     int32_t* d_pred = nullptr;
     int64_t* d_row_seg_ptr = nullptr;
@@ -180,12 +178,16 @@ size_t layout(cadmm_ctx* c, char* base) {
     c->d_seg1_col = b.take<int32_t>(g.seg1_pos.size());
     c->d_seg1_val = b.take<float>(g.seg1_pos.size());
     c->d_segc_row = b.take<int32_t>(g.n_seg);
-    const size_t nch = g.chunks.size();
-    c->d_chunk_unit = b.take<int32_t>(nch);
-    c->d_chunk_kind = b.take<int32_t>(nch);
-    c->d_chunk_begin = b.take<int32_t>(nch);
-    c->d_chunk_end = b.take<int32_t>(nch);
-    c->d_unit_chunk_ptr = b.take<int32_t>(g.M + 1);
+    const size_t nch = g.chunks.size() > g.chunks_wide.size() ? g.chunks.size() : g.chunks_wide.size();
+    for (int t = 0; t < 2; ++t) {
+        const size_t nt = t == 0 ? g.chunks.size() : g.chunks_wide.size();
+        c->d_chunks[t].unit = b.take<int32_t>(nt);
+        c->d_chunks[t].kind = b.take<int32_t>(nt);
+        c->d_chunks[t].begin = b.take<int32_t>(nt);
+        c->d_chunks[t].end = b.take<int32_t>(nt);
+        c->d_chunks[t].unit_ptr = b.take<int32_t>(g.M + 1);
+        c->d_chunks[t].n = (int32_t)nt;
+    }
     c->d_labels = b.take<int32_t>(N);
     c->d_pred = b.take<int32_t>(N);
     c->d_row_seg_ptr = b.take<int64_t>(N + 1);
@@ -526,10 +528,11 @@ void z_update_hidden(cadmm_ctx* c, int l) {
         aggregate_segments(c, c->tmpV, c->P, Cn);                                    // A~_{r,m} (grad W) per segment
         launch_reset_units(s, units, M, sp);
         ZTrialArgs a;
-        a.chunk_unit = c->d_chunk_unit; a.chunk_kind = c->d_chunk_kind;
-        a.chunk_begin = c->d_chunk_begin; a.chunk_end = c->d_chunk_end;
-        a.n_chunks = (int32_t)c->hg.chunks.size();
-        a.unit_chunk_ptr = c->d_unit_chunk_ptr; a.M = M;
+        const cadmm_ctx::DevChunks& ct = c->d_chunks[Cn > 32 ? 1 : 0];        // a segment's row of P and T_{l+1} has Cn columns
+        a.chunk_unit = ct.unit; a.chunk_kind = ct.kind;
+        a.chunk_begin = ct.begin; a.chunk_end = ct.end;
+        a.n_chunks = ct.n;
+        a.unit_chunk_ptr = ct.unit_ptr; a.M = M;
         a.segc_row = c->d_segc_row;
         a.Zl = c->Z[l]; a.gradZ = lowrank ? nullptr : c->tmpB; a.Tl = c->T[l]; a.Cl = Cl;
         a.SG = c->tmpA; a.Wt = c->Wt;
@@ -563,8 +566,9 @@ void last_layer_update(cadmm_ctx* c) {
         // FISTA with backtracking on the blocks Z_{L,m}: J + 1 passes over the rows, a device-side search per step
         FistaArgs a;
         a.ZL = c->Z[L]; a.U = c->U; a.TL = c->T[L]; a.Xb = c->fistaX; a.Yb = c->fistaY; a.labels = c->d_labels;
-        a.chunk_unit = c->d_chunk_unit; a.chunk_kind = c->d_chunk_kind; a.chunk_begin = c->d_chunk_begin; a.chunk_end = c->d_chunk_end;
-        a.n_chunks = (int32_t)c->hg.chunks.size(); a.unit_chunk_ptr = c->d_unit_chunk_ptr; a.M = c->hg.M;
+        const cadmm_ctx::DevChunks& ct = c->d_chunks[0];                      // only the chunks of rows are used here
+        a.chunk_unit = ct.unit; a.chunk_kind = ct.kind; a.chunk_begin = ct.begin; a.chunk_end = ct.end;
+        a.n_chunks = ct.n; a.unit_chunk_ptr = ct.unit_ptr; a.M = c->hg.M;
         a.CL = c->C[L]; a.risk = c->risk; a.J = c->J; a.update_u = c->dual_form == 0 ? 1 : 0; a.rho = c->rho;
         a.sp = search_params(c); a.units = c->unitsF; a.partials = c->partials; a.status = c->status;
         // candidates per step: 1 (16 in stage 0), then a pass of 4, then passes of 16 until max_backtrack + 1 are covered
@@ -835,13 +839,15 @@ int cadmm_set_workspace(cadmm_ctx* c, void* dev_ptr, size_t bytes) {
     HIP_TRY(c, upload(s, c->d_seg1_col, g.seg1_col));
     HIP_TRY(c, upload(s, c->d_seg1_val, g.seg1_val));
     HIP_TRY(c, upload(s, c->d_segc_row, g.segc_row));
-    std::vector<int32_t> cu, ck, cb, ce;
-    for (const Chunk& ch : g.chunks) { cu.push_back(ch.unit); ck.push_back(ch.kind); cb.push_back(ch.begin); ce.push_back(ch.end); }
-    HIP_TRY(c, upload(s, c->d_chunk_unit, cu));
-    HIP_TRY(c, upload(s, c->d_chunk_kind, ck));
-    HIP_TRY(c, upload(s, c->d_chunk_begin, cb));
-    HIP_TRY(c, upload(s, c->d_chunk_end, ce));
-    HIP_TRY(c, upload(s, c->d_unit_chunk_ptr, g.unit_chunk_ptr));
+    for (int t = 0; t < 2; ++t) {
+        std::vector<int32_t> cu, ck, cb, ce;
+        for (const Chunk& ch : (t == 0 ? g.chunks : g.chunks_wide)) { cu.push_back(ch.unit); ck.push_back(ch.kind); cb.push_back(ch.begin); ce.push_back(ch.end); }
+        HIP_TRY(c, upload(s, c->d_chunks[t].unit, cu));
+        HIP_TRY(c, upload(s, c->d_chunks[t].kind, ck));
+        HIP_TRY(c, upload(s, c->d_chunks[t].begin, cb));
+        HIP_TRY(c, upload(s, c->d_chunks[t].end, ce));
+        HIP_TRY(c, upload(s, c->d_chunks[t].unit_ptr, t == 0 ? g.unit_chunk_ptr : g.unit_chunk_ptr_wide));
+    }
     HIP_TRY(c, upload(s, c->d_row_seg_ptr, g.row_seg_ptr));
     HIP_TRY(c, upload(s, c->d_seg_comm, g.seg_comm));
     HIP_TRY(c, upload(s, c->d_seg_pos, g.seg_pos));

@@ -419,18 +419,23 @@ std::string build_host_graph(HostGraph& g, int64_t N, int64_t n_edges, const int
         }
     }
 
-    // reduction chunks: for every community its own rows, then its segments
-    g.unit_chunk_ptr.assign(M + 1, 0);
-    for (int32_t m = 0; m < M; ++m) {
-        for (int64_t b = g.comm_row_ptr[m]; b < g.comm_row_ptr[m + 1]; b += chunk_rows)
-            g.chunks.push_back({m, 0, (int32_t)b, (int32_t)std::min<int64_t>(b + chunk_rows, g.comm_row_ptr[m + 1])});
-        // a segment carries a row of the next, usually much narrower layer: eight times as many per chunk, so that a
-        // chunk's fixed costs (unit state, block reductions) do not outweigh its pass over memory
-        const int64_t chunk_segs = (int64_t)chunk_rows * 8;
-        for (int64_t b = g.segc_comm_ptr[m]; b < g.segc_comm_ptr[m + 1]; b += chunk_segs)
-            g.chunks.push_back({m, 1, (int32_t)b, (int32_t)std::min<int64_t>(b + chunk_segs, g.segc_comm_ptr[m + 1])});
-        g.unit_chunk_ptr[m + 1] = (int32_t)g.chunks.size();
-    }
+    // reduction chunks: for every community its own rows, then its segments.  A segment carries a row of the next
+    // layer: where that layer is narrow, eight times as many segments as rows go into a chunk, so that a chunk's fixed
+    // costs (unit state, block reductions) do not outweigh its pass over memory; where it is wide, as many as rows, or
+    // the few heavy chunks of a community are what the launch waits for.
+    auto build_chunks = [&](int64_t chunk_segs, std::vector<Chunk>& chunks, std::vector<int32_t>& ptr) {
+        chunks.clear();
+        ptr.assign(M + 1, 0);
+        for (int32_t m = 0; m < M; ++m) {
+            for (int64_t b = g.comm_row_ptr[m]; b < g.comm_row_ptr[m + 1]; b += chunk_rows)
+                chunks.push_back({m, 0, (int32_t)b, (int32_t)std::min<int64_t>(b + chunk_rows, g.comm_row_ptr[m + 1])});
+            for (int64_t b = g.segc_comm_ptr[m]; b < g.segc_comm_ptr[m + 1]; b += chunk_segs)
+                chunks.push_back({m, 1, (int32_t)b, (int32_t)std::min<int64_t>(b + chunk_segs, g.segc_comm_ptr[m + 1])});
+            ptr[m + 1] = (int32_t)chunks.size();
+        }
+    };
+    build_chunks((int64_t)chunk_rows * 8, g.chunks, g.unit_chunk_ptr);
+    build_chunks((int64_t)chunk_rows, g.chunks_wide, g.unit_chunk_ptr_wide);
     return "";
 }
 

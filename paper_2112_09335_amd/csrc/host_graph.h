@@ -101,9 +101,12 @@ struct HostGraph {
     RowSchedule row_sched;              // the CSR rows; output row = the row, group = its community
     RowSchedule seg_sched;              // the segments with several entries; output row = position in the (community, row) order,
                                         // group = the segment's community
-    // reduction chunks for the Z search, grouped by community
+    // reduction chunks for the Z search, grouped by community: many segments per chunk for a narrow next layer ...
     std::vector<Chunk>   chunks;
     std::vector<int32_t> unit_chunk_ptr; // [M+1]
+    // ... and the same with as many segments as rows per chunk, for a wide one
+    std::vector<Chunk>   chunks_wide;
+    std::vector<int32_t> unit_chunk_ptr_wide;
 };
 
 // Returns an empty string on success, an error text otherwise.
