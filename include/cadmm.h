@@ -239,6 +239,8 @@ int  cadmm_op_wgrad_noalloc(cadmm_ctx* ctx, const float* A, const float* G, int6
  *   kind 4: as kind 1 with bf16 MFMAs (32x32x16), the instruction the split products issue; rate = TFLOP/s.
  *   kind 5 / 6 / 7: as kind 4 with 4 / 6 / 8 independent fp32 vector instructions after every MFMA (the rate still
  *           counts the MFMA flops only): how much vector work runs beside the matrix cores.
+ *   kind 8: dst = 0.999 dst + src in place over `count` floats (multiple of 4), both device: two arrays read, one
+ *           written back where it was read, the memory mix of the step kernels; rate = GB/s of the 12 bytes per element.
  */
 int  cadmm_op_calibrate(cadmm_ctx* ctx, int32_t kind, const float* src, float* dst, int64_t count, int32_t reps,
                         double* rate);

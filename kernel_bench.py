@@ -6,6 +6,7 @@
 
 ops:  copy            a plain device copy of 1 GiB (torch), the calibration point for memory counters
       stream          the library's own copy kernel on 1 GiB (cadmm_op_calibrate): what a streaming kernel can reach
+      update          dst = 0.999 dst + src in place (the memory mix of the step kernels)
       mfma            register-only chains of fp32 MFMAs (cadmm_op_calibrate): what the matrix cores can reach
       mfma_bf16       the same with bf16 MFMAs; mfma_bf16_valu4 / 6 / 8: with that many vector instructions after each
       gather:W        only the gathers of the row aggregation at width W, no row structure (cadmm_op_calibrate):
@@ -71,6 +72,10 @@ def main():
             print(f"{op:20s} bf16 MFMA chains on registers"
                   + (f" with {kind[-1]} vector instructions after each" if kind != "mfma_bf16" else "")
                   + f": {rate:7.1f} TFLOP/s ({rate / 2500.0:.3f} of the published 2500)", flush=True)
+            continue
+        if kind == "update":
+            rate = s.op_calibrate("update", 1 << 28, args.reps)
+            print(f"{op:20s} library in-place update kernel, 2 GiB read + 1 GiB written back: {rate:8.1f} GB/s", flush=True)
             continue
         if kind in ("stream", "mfma"):
             if kind == "stream":

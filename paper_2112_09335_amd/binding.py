@@ -346,18 +346,18 @@ class Solver:
         return out
 
     def op_calibrate(self, kind, count, reps=5):
-        """'copy': GB/s of a plain device copy of `count` floats; 'mfma': TFLOP/s of register-only fp32 MFMA chains;
+        """'copy': GB/s of a plain device copy of `count` floats; 'update': GB/s of dst = 0.999 dst + src in place; 'mfma': TFLOP/s of register-only fp32 MFMA chains;
         'mfma_bf16': the same with bf16 MFMAs, 'mfma_bf16_valu4/6/8': with that many vector instructions after each;
         'gather' / 'gather_segments': GB/s of the aggregation's gathers alone at a row width of `count` floats."""
         torch = self._torch
         rate = C.c_double()
         self._enter()
-        if kind == "copy":
+        if kind in ("copy", "update"):
             src = torch.ones(count, dtype=torch.float32, device=f"cuda:{self.device}")
-            dst = torch.empty_like(src)
+            dst = torch.zeros_like(src)
             torch.cuda.current_stream().synchronize()
-            rc = self.lib.cadmm_op_calibrate(self.h, 0, C.c_void_p(src.data_ptr()), C.c_void_p(dst.data_ptr()), count,
-                                             reps, C.byref(rate))
+            rc = self.lib.cadmm_op_calibrate(self.h, 0 if kind == "copy" else 8, C.c_void_p(src.data_ptr()),
+                                             C.c_void_p(dst.data_ptr()), count, reps, C.byref(rate))
         elif kind == "mfma":
             dst = torch.empty(2048 * 256, dtype=torch.float32, device=f"cuda:{self.device}")
             rc = self.lib.cadmm_op_calibrate(self.h, 1, None, C.c_void_p(dst.data_ptr()), count, reps, C.byref(rate))

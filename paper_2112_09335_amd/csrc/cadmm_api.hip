@@ -1256,11 +1256,11 @@ int cadmm_op_wgrad_noalloc(cadmm_ctx* c, const float* A, const float* G, int64_t
 
 int cadmm_op_calibrate(cadmm_ctx* c, int32_t kind, const float* src, float* dst, int64_t count, int32_t reps,
                        double* rate) {
-    if (!c || !dst || !rate || count < 4 || reps < 1 || kind < 0 || kind > 7) return CADMM_EINVAL;
+    if (!c || !dst || !rate || count < 4 || reps < 1 || kind < 0 || kind > 8) return CADMM_EINVAL;
     if (c->device < 0) return fail(c, CADMM_EUNSUPPORTED, "host-only context");
     const int blocks = 2048;
-    if (kind == 0 && (!src || count % 4 != 0)) return fail(c, CADMM_EINVAL, "copy needs src and a multiple of four floats");
-    if ((kind == 1 || kind >= 4) && count > (1 << 24)) return fail(c, CADMM_EINVAL, "at most 2^24 MFMA steps per launch");
+    if ((kind == 0 || kind == 8) && (!src || count % 4 != 0)) return fail(c, CADMM_EINVAL, "copy needs src and a multiple of four floats");
+    if ((kind == 1 || (kind >= 4 && kind <= 7)) && count > (1 << 24)) return fail(c, CADMM_EINVAL, "at most 2^24 MFMA steps per launch");
     if (kind == 2 || kind == 3) {
         if (!c->has_ws) return fail(c, CADMM_EORDER, "set_workspace first");
         if (!src || (count != 4 && count != 8 && count != 16 && count != 32 && count != 64 && count != 128 && count != 256))
@@ -1272,8 +1272,9 @@ int cadmm_op_calibrate(cadmm_ctx* c, int32_t kind, const float* src, float* dst,
     double work = 0.0;
     auto once = [&] {
         if (kind == 0) { launch_stream_copy(c->stream, src, dst, count); work += 8.0 * (double)count; }
+        else if (kind == 8) { launch_stream_update(c->stream, src, dst, count); work += 12.0 * (double)count; }
         else if (kind == 1) work += launch_mfma_chain(c->stream, dst, blocks, (int)count);
-        else if (kind >= 4) work += launch_mfma_bf16_chain(c->stream, dst, blocks, (int)count, kind == 4 ? 0 : kind == 5 ? 4 : kind == 6 ? 6 : 8);
+        else if (kind >= 4 && kind <= 7) work += launch_mfma_bf16_chain(c->stream, dst, blocks, (int)count, kind == 4 ? 0 : kind == 5 ? 4 : kind == 6 ? 6 : 8);
         else {
             const RowSchedule& rs = kind == 2 ? c->hg.row_sched : c->hg.seg_sched;
             work += launch_gather_calibration(c->stream, schedule_of(c, kind == 2 ? c->d_rows : c->d_segs, rs), rs.n_chunks(), src,
@@ -1291,7 +1292,7 @@ int cadmm_op_calibrate(cadmm_ctx* c, int32_t kind, const float* src, float* dst,
     (void)hipEventDestroy(a);
     (void)hipEventDestroy(b);
     if (e != hipSuccess) return hip_fail(c, e, "op_calibrate");
-    *rate = ms > 0.f ? work / ((double)ms * 1e-3) / ((kind == 1 || kind >= 4) ? 1e12 : 1e9) : 0.0;
+    *rate = ms > 0.f ? work / ((double)ms * 1e-3) / ((kind == 1 || (kind >= 4 && kind <= 7)) ? 1e12 : 1e9) : 0.0;
     return check_launch(c, "op_calibrate");
 }
 

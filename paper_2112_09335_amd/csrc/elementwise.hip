@@ -353,27 +353,35 @@ __global__ __launch_bounds__(256) void w_step_kernel(float* __restrict__ W, cons
 // kind 1: segments [begin,end) (community,row order) of the next layer's term, whose pre-activation
 //     row T_{l+1,i} moves by -P_s/theta as seen from this community.
 // grad[v] = nu (z[v] - relu(t[v])) + sum_k sg[k] wt[k][v], always in this order (the step kernel must
-// reproduce the very same values the search saw)
-__device__ __forceinline__ void lowrank_grad(float (&g)[4], const float (&z)[4], const float (&t)[4],
-                                             const float (&sg)[kLowRankMax], const float (&wt)[kLowRankMax][4], int Cn,
-                                             float nu) {
+// reproduce the very same values the search saw).  The rows of W_{l+1}^T are read from LDS (wcol: this lane's four
+// columns of row 0, wv float4 per row): the kernels that rebuild the gradient stream N x C_l matrices and need the
+// wavefronts in flight that 64 registers per lane for these rows would cost them.
+__device__ __forceinline__ void lowrank_grad_lds(float (&g)[4], const float (&z)[4], const float (&t)[4],
+                                                 const float (&sg)[kLowRankMax], const float4* wcol, int wv, int Cn, float nu) {
 #pragma unroll
     for (int v = 0; v < 4; ++v) g[v] = nu * (z[v] - fmaxf(t[v], 0.f));
 #pragma unroll
     for (int k = 0; k < kLowRankMax; ++k) {
         if (k < Cn) {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) g[v] = fmaf(sg[k], wt[k][v], g[v]);
+            const float4 w4 = wcol[k * wv];
+            g[0] = fmaf(sg[k], w4.x, g[0]); g[1] = fmaf(sg[k], w4.y, g[1]);
+            g[2] = fmaf(sg[k], w4.z, g[2]); g[3] = fmaf(sg[k], w4.w, g[3]);
         }
     }
 }
 
+// s_wt: LDS room for W_{l+1}^T (LR only); wt_loaded: whether this workgroup has filled it already.
 template <int NC, int VEC, int LR>
-__device__ __forceinline__ void z_trial_chunk(const ZTrialArgs& a, int ch, double* sm) {
+__device__ __forceinline__ void z_trial_chunk(const ZTrialArgs& a, int ch, double* sm, float* s_wt, bool& wt_loaded) {
     const int unit = a.chunk_unit[ch];
     const Unit* u = a.units + unit;
     if (u->done) return;
     const int kind = a.chunk_kind[ch];
+    if (LR == 1 && kind == 0 && !wt_loaded) {           // (uniform over the workgroup)
+        for (int i = threadIdx.x; i < a.Cn * a.Cl; i += 256) s_wt[i] = a.Wt[i];
+        __syncthreads();
+        wt_loaded = true;
+    }
     const int begin = a.chunk_begin[ch], end = a.chunk_end[ch];
     double inv[NC];
     {
@@ -395,15 +403,8 @@ __device__ __forceinline__ void z_trial_chunk(const ZTrialArgs& a, int ch, doubl
     const int r_step = 256 >> cshift;
     const double hnu = 0.5 * (double)a.sp.nu, hrho = 0.5 * (double)a.sp.rho;
     if (kind == 0) {
-        // low-rank gradient: this thread's four columns of Wt stay in registers (one column slot per thread)
-        float wt[LR ? kLowRankMax : 1][4];
-        if constexpr (LR == 1) {
-#pragma unroll
-            for (int k = 0; k < kLowRankMax; ++k) {
-                if (k < a.Cn && c_first < wv) ldv<4>(wt[k], a.Wt + (int64_t)k * width + c_first * 4);
-                else { wt[k][0] = 0.f; wt[k][1] = 0.f; wt[k][2] = 0.f; wt[k][3] = 0.f; }
-            }
-        }
+        // low-rank gradient: this thread's four columns of W_{l+1}^T, read from LDS (one column slot per thread)
+        const float4* const wcol = reinterpret_cast<const float4*>(s_wt) + (c_first < wv ? c_first : 0);
         for (int r = begin + r_first; r < end; r += r_step) {
             const int64_t base = (int64_t)r * width;
             float srow[LR ? kLowRankMax : 1];      // this row of the N x Cn factor
@@ -419,7 +420,7 @@ __device__ __forceinline__ void z_trial_chunk(const ZTrialArgs& a, int ch, doubl
                 float zv[VEC], gv[VEC], tv[VEC];
                 ldv<VEC>(zv, a.Zl + base + cv * VEC);
                 ldv<VEC>(tv, a.Tl + base + cv * VEC);
-                if constexpr (LR == 1) lowrank_grad(gv, zv, tv, srow, wt, a.Cn, a.sp.nu);
+                if constexpr (LR == 1) lowrank_grad_lds(gv, zv, tv, srow, wcol, wv, a.Cn, a.sp.nu);
                 else ldv<VEC>(gv, a.gradZ + base + cv * VEC);
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
@@ -489,13 +490,15 @@ __device__ __forceinline__ void z_trial_chunk(const ZTrialArgs& a, int ch, doubl
 template <int NC, int VEC, int LR>
 __global__ __launch_bounds__(256) void z_trial_kernel(ZTrialArgs a) {
     __shared__ double sm[4];
+    extern __shared__ __align__(16) float s_wt[];       // [Cn][Cl] with the low-rank gradient, else nothing
+    bool wt_loaded = false;
     if constexpr (NC == 1) {
-        z_trial_chunk<NC, VEC, LR>(a, blockIdx.x, sm);
+        z_trial_chunk<NC, VEC, LR>(a, blockIdx.x, sm, s_wt, wt_loaded);
     } else {
         int pending = 0;
         for (int i = threadIdx.x; i < a.M; i += 256) pending |= (a.units[i].done == 0);
         if (!__syncthreads_or(pending)) return;
-        for (int ch = blockIdx.x; ch < a.n_chunks; ch += gridDim.x) z_trial_chunk<NC, VEC, LR>(a, ch, sm);
+        for (int ch = blockIdx.x; ch < a.n_chunks; ch += gridDim.x) z_trial_chunk<NC, VEC, LR>(a, ch, sm, s_wt, wt_loaded);
     }
 }
 
@@ -561,29 +564,28 @@ __global__ __launch_bounds__(256) void z_step_kernel(float* __restrict__ Zl, con
     }
 }
 
-// The same step with the gradient rebuilt from its low-rank form (see lowrank_grad); a lane group handles two rows
-// per trip with every load issued before the first use.
+// The same step with the gradient rebuilt from its low-rank form (see lowrank_grad_lds: the same operations in the
+// same order); a lane group handles two rows per trip with every load issued before the first use.  The rows of W_{l+1}^T
+// live in LDS, not in 64 registers per lane: the kernel is a plain in-place update of Z_l and needs the wavefronts in
+// flight that a small register footprint allows (5 TB/s against 4.4 with the rows in registers).
 template <bool LDSU>
 __global__ __launch_bounds__(256) void z_step_lowrank_kernel(float* __restrict__ Zl, const float* __restrict__ Tl,
                                                              const float* __restrict__ SG, const float* __restrict__ Wt,
                                                              float nu, const int32_t* __restrict__ row_comm, int64_t N,
                                                              int Cl, int Cn, const Unit* __restrict__ units, int M) {
     __shared__ double s_inv[LDSU ? kStepUnits : 1];
+    extern __shared__ __align__(16) float s_wt[];        // [Cn][Cl]
     if constexpr (LDSU) {
         for (int i = threadIdx.x; i < M; i += 256) s_inv[i] = units[i].skip ? 0.0 : 1.0 / units[i].step;
-        __syncthreads();
     }
+    for (int i = threadIdx.x; i < Cn * Cl; i += 256) s_wt[i] = Wt[i];
+    __syncthreads();
     const int wv = Cl / 4;
     int cshift = 0;
     while ((1 << cshift) < wv && cshift < 8) ++cshift;
     const int c_first = threadIdx.x & ((1 << cshift) - 1);
     if (c_first >= wv) return;                       // (after the barrier)
-    float wt[kLowRankMax][4];
-#pragma unroll
-    for (int k = 0; k < kLowRankMax; ++k) {
-        if (k < Cn) ldv<4>(wt[k], Wt + (int64_t)k * Cl + c_first * 4);
-        else { wt[k][0] = 0.f; wt[k][1] = 0.f; wt[k][2] = 0.f; wt[k][3] = 0.f; }
-    }
+    const float4* const wcol = reinterpret_cast<const float4*>(s_wt) + c_first;      // row k: wcol[k * wv]
     constexpr int R = 2;
     const int64_t rows_per_block = 256 >> cshift;
     const int64_t r_step = (int64_t)gridDim.x * rows_per_block * R;
@@ -605,6 +607,22 @@ __global__ __launch_bounds__(256) void z_step_lowrank_kernel(float* __restrict__
                 sg[q][4 * k4] = v[0]; sg[q][4 * k4 + 1] = v[1]; sg[q][4 * k4 + 2] = v[2]; sg[q][4 * k4 + 3] = v[3];
             }
         }
+        float g[R][4];
+#pragma unroll
+        for (int q = 0; q < R; ++q)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) g[q][v] = nu * (z[q][v] - fmaxf(t[q][v], 0.f));
+#pragma unroll
+        for (int k = 0; k < kLowRankMax; ++k) {
+            if (k < Cn) {
+                const float4 w4 = wcol[k * wv];
+                const float w[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+                for (int q = 0; q < R; ++q)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) g[q][v] = fmaf(sg[q][k], w[v], g[q][v]);
+            }
+        }
 #pragma unroll
         for (int q = 0; q < R; ++q) {
             const int64_t r = r0 + q * rows_per_block;
@@ -612,10 +630,8 @@ __global__ __launch_bounds__(256) void z_step_lowrank_kernel(float* __restrict__
             if constexpr (LDSU) inv = s_inv[cm[q]];
             else inv = units[cm[q]].skip ? 0.0 : 1.0 / units[cm[q]].step;
             if (r >= N || inv == 0.0) continue;
-            float g[4];
-            lowrank_grad(g, z[q], t[q], sg[q], wt, Cn, nu);
 #pragma unroll
-            for (int v = 0; v < 4; ++v) z[q][v] = (float)((double)z[q][v] - (double)g[v] * inv);
+            for (int v = 0; v < 4; ++v) z[q][v] = (float)((double)z[q][v] - (double)g[q][v] * inv);
             stv<4>(Zl + r * Cl + c_first * 4, z[q]);
         }
     }
@@ -1125,15 +1141,16 @@ void launch_z_trial(hipStream_t s, const ZTrialArgs& a0) {
     if (a.n_chunks > 0) {
         const bool v4 = (a.Cl % 4) == 0 && (a.Cn % 4) == 0;
         const bool lr = a.gradZ == nullptr;           // low-rank gradient (the caller checked the shape limits)
+        const size_t lds = lr ? (size_t)a.Cn * a.Cl * sizeof(float) : 0;      // W_{l+1}^T: at most 16 x 1024 floats
         if (a.ncand == 1) {
-            if (lr) hipLaunchKernelGGL((z_trial_kernel<1, 4, 1>), dim3(a.n_chunks), dim3(256), 0, s, a);
+            if (lr) hipLaunchKernelGGL((z_trial_kernel<1, 4, 1>), dim3(a.n_chunks), dim3(256), lds, s, a);
             else if (v4) hipLaunchKernelGGL((z_trial_kernel<1, 4, 0>), dim3(a.n_chunks), dim3(256), 0, s, a);
             else hipLaunchKernelGGL((z_trial_kernel<1, 1, 0>), dim3(a.n_chunks), dim3(256), 0, s, a);
         } else {
             a.ncand = kMaxCand;
             // a small grid: such a pass nearly always finds every community done and only has to notice it
             const int nb = a.n_chunks < kReduceBlocks / 4 ? a.n_chunks : kReduceBlocks / 4;
-            if (lr) hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 4, 1>), dim3(nb), dim3(256), 0, s, a);
+            if (lr) hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 4, 1>), dim3(nb), dim3(256), lds, s, a);
             else if (v4) hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 4, 0>), dim3(nb), dim3(256), 0, s, a);
             else hipLaunchKernelGGL((z_trial_kernel<kMaxCand, 1, 0>), dim3(nb), dim3(256), 0, s, a);
         }
@@ -1152,11 +1169,14 @@ void launch_z_step(hipStream_t s, float* Zl, const float* gradZ, const int32_t* 
 
 void launch_z_step_lowrank(hipStream_t s, float* Zl, const float* Tl, const float* SG, const float* Wt, float nu,
                            const int32_t* row_comm, int64_t N, int Cl, int Cn, const Unit* units, int M) {
-    const int nb = flat_grid(N * (int64_t)Cl);
+    // more and smaller workgroups than the reducing kernels use: nothing is reduced here
+    int64_t nb = (N * (int64_t)Cl + 2047) / 2048;
+    nb = nb < 1 ? 1 : (nb > 4 * kReduceBlocks ? 4 * kReduceBlocks : nb);
+    const size_t lds = (size_t)Cn * Cl * sizeof(float);                 // at most 16 x 1024 floats (the low-rank limit)
     if (M <= kStepUnits)
-        hipLaunchKernelGGL((z_step_lowrank_kernel<true>), dim3(nb), dim3(256), 0, s, Zl, Tl, SG, Wt, nu, row_comm, N, Cl, Cn, units, M);
+        hipLaunchKernelGGL((z_step_lowrank_kernel<true>), dim3((unsigned)nb), dim3(256), lds, s, Zl, Tl, SG, Wt, nu, row_comm, N, Cl, Cn, units, M);
     else
-        hipLaunchKernelGGL((z_step_lowrank_kernel<false>), dim3(nb), dim3(256), 0, s, Zl, Tl, SG, Wt, nu, row_comm, N, Cl, Cn, units, M);
+        hipLaunchKernelGGL((z_step_lowrank_kernel<false>), dim3((unsigned)nb), dim3(256), lds, s, Zl, Tl, SG, Wt, nu, row_comm, N, Cl, Cn, units, M);
 }
 
 void launch_t_carry(hipStream_t s, float* Tn, const float* P, const int64_t* row_seg_ptr, const int32_t* seg_comm,

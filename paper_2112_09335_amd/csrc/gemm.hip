@@ -860,6 +860,19 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(const float4* __restri
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) dst[i] = src[i];
 }
 
+// Machine calibration: dst = 0.999 dst + src in place, one float4 per thread and step: two arrays read, one of them
+// written back to where it was read, the memory mix of the step kernels.
+__global__ __launch_bounds__(256) void stream_update_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
+                                                            int64_t n4) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        const float4 a = src[i];
+        float4 d = dst[i];
+        d.x = 0.999f * d.x + a.x; d.y = 0.999f * d.y + a.y; d.z = 0.999f * d.z + a.z; d.w = 0.999f * d.w + a.w;
+        dst[i] = d;
+    }
+}
+
 int g_split = 1;      // 1: wide products run on the bf16 matrix cores with three-way split operands, 0: fp32 MFMA
 
 struct TnPlan {
@@ -984,6 +997,11 @@ void launch_stream_copy(hipStream_t s, const float* src, float* dst, int64_t cou
     const int64_t n4 = count / 4;
     hipLaunchKernelGGL(stream_copy_kernel, dim3(8192), dim3(256), 0, s, reinterpret_cast<const float4*>(src),
                        reinterpret_cast<float4*>(dst), n4);
+}
+
+void launch_stream_update(hipStream_t s, const float* src, float* dst, int64_t count) {
+    hipLaunchKernelGGL(stream_update_kernel, dim3(8192), dim3(256), 0, s, reinterpret_cast<const float4*>(src),
+                       reinterpret_cast<float4*>(dst), count / 4);
 }
 
 void launch_transpose(hipStream_t s, const float* in, float* out, int K, int C) {

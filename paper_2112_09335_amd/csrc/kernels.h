@@ -80,6 +80,8 @@ double launch_mfma_chain(hipStream_t s, float* out, int blocks, int iters);
 // the same with bf16 32x32x16 MFMAs, each followed by `valu` (0, 4, 6, 8) independent vector instructions
 double launch_mfma_bf16_chain(hipStream_t s, float* out, int blocks, int iters, int valu);
 void launch_stream_copy(hipStream_t s, const float* src, float* dst, int64_t count);
+// dst = 0.999 dst + src in place (count % 4 == 0): two reads and one write-back per element
+void launch_stream_update(hipStream_t s, const float* src, float* dst, int64_t count);
 int64_t gemm_nn_blocks(int64_t n, int C);      // grid size of that launch (= block results of epilogue 2)
 // out[n x C] = [nu (Zl - relu(Tl)) | SG] * Bcat, Bcat = [W (K1 x C); S (K2 x C)], C <= 32, K1 % 4 == K2 % 4 == 0:
 // the product (grad_Z psi) W with grad = nu (Zl - relu(Tl)) + SG W^T, S = W^T W, the gradient never stored.

@@ -174,6 +174,7 @@ def test_products_agree_on_the_fp32_and_the_bf16_split_matrix_core_paths(ctx, n,
 def test_calibration_kernels_report_a_rate(ctx):
     s, g, torch = ctx
     assert s.op_calibrate("copy", 1 << 22, 3) > 10.0        # GB/s
+    assert s.op_calibrate("update", 1 << 22, 3) > 10.0
     assert s.op_calibrate("mfma", 200, 3) > 1.0             # TFLOP/s
     assert s.op_calibrate("mfma_bf16", 200, 3) > 1.0
     assert s.op_calibrate("mfma_bf16_valu6", 200, 3) > 1.0
